@@ -1,0 +1,231 @@
+#!/usr/bin/env python3
+"""Benchmark of the HATA decode-attention hot path on one MI355X.
+
+A "step" is one whole decode step of Alg. 3 of the paper over one batch: hash-encode the
+appended key and the query heads, Hamming-score every cached code, select the budget,
+attend over the selected rows -- one call of hata_decode_step().  Inputs are seeded and
+synthetic, resident in HBM before the timed region.  Consecutive steps rotate over many
+distinct copies ("layers") of the K/V/code caches so that the traffic is HBM traffic and
+not Infinity-Cache hits, as a model with tens of layers does for every token.
+
+Prints ONE JSON line (see the design doc for every field).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=400)
+    ap.add_argument("--warmup", type=int, default=40)
+    ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
+    ap.add_argument("--layers", type=int, default=0, help="distinct cache copies to rotate over (0 = auto)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-dense", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=10.0)
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
+              "--gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+    from paper_2506_02572_amd import hata, synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HATA path has no CPU fallback", file=sys.stderr)
+        sys.exit(1)
+    torch.cuda.set_device(0)
+    dev = torch.device("cuda:0")
+    w = synth.config(int(args.workload[3:]))
+    inp = synth.generate(w)
+    scale = 1.0 / math.sqrt(w.d)
+    n_step_variants = max(1, w.append_steps)
+
+    def dev_bits(a):
+        a = np.ascontiguousarray(a)
+        if a.dtype == np.uint16:
+            a = a.view(np.int16)
+        elif a.dtype == np.uint32:
+            a = a.view(np.int32)
+        return torch.from_numpy(a).to(dev)
+
+    # ---- device buffers: n_layers copies of (K, V, codes)
+    touched = w.algorithmic_bytes()
+    layer_bytes = 2 * inp.K.nbytes + inp.K.nbytes // (w.d * 2) * (w.r // 8)
+    n_layers = args.layers or max(4, min(int(math.ceil((1 << 30) / touched)), int((96 << 30) // layer_bytes)))
+    K0, V0 = dev_bits(inp.K), dev_bits(inp.V)
+    K_all = torch.empty((n_layers,) + tuple(K0.shape), dtype=torch.int16, device=dev)
+    V_all = torch.empty_like(K_all)
+    K_all[:] = K0
+    V_all[:] = V0
+    del K0, V0
+    codes_all = torch.zeros((n_layers, w.B, w.Hkv, w.L_cap, w.W), dtype=torch.int32, device=dev)
+    W_H = dev_bits(inp.W_H)
+    kbud = dev_bits(inp.k)
+    zero = torch.zeros(w.B, dtype=torch.int32, device=dev)
+    # cfg5: the cache grows by one row per step for append_steps steps, then the cycle restarts
+    seq_steps = [dev_bits(inp.seq_len + (t + 1 if w.append_steps else 0)) for t in range(n_step_variants)]
+    q_steps = [dev_bits(inp.q(t)) for t in range(min(n_step_variants, 8))]
+    prefill_len = dev_bits(inp.seq_len + w.append_steps)  # rows a later step appends get codes too
+    out = torch.empty((w.B, w.Hq, w.d), dtype=torch.int16, device=dev)
+    out32 = torch.empty((w.B, w.Hq, w.d), dtype=torch.float32, device=dev)
+    ctx = hata.Context(w.B, w.Hq, w.Hkv, w.d, w.r, w.L_cap, w.k_max)
+    stream = torch.cuda.current_stream()
+
+    def timed(fn, n, warm):
+        for i in range(warm):
+            fn(i)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t0 = time.perf_counter()
+        e0.record(stream)
+        for i in range(n):
+            fn(i)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        wall = (time.perf_counter() - t0) * 1e3
+        return e0.elapsed_time(e1) / n, wall / n  # ms per call (device events, host wall)
+
+    # ---- prefill-side key-code writer (Alg. 1 lines 2-5), every layer once; timed separately
+    max_prefill = int(inp.seq_len.max()) + w.append_steps
+
+    enc_calls = [ctx.prepared("hata_encode_keys", K_all[l], W_H, zero, prefill_len, w.B, max_prefill,
+                              codes_all[l], stream=stream) for l in range(n_layers)]
+
+    def enc(i):
+        enc_calls[i % n_layers]()
+
+    enc_ms, _ = timed(enc, n_layers, 1)
+    enc_keys = int((inp.seq_len + w.append_steps).sum()) * w.Hkv
+    enc_bytes = enc_keys * (w.d * 2 + w.r // 8)
+    enc_flop = 2.0 * enc_keys * w.d * w.r
+
+    # ---- the decode step
+    n_combo = n_layers * n_step_variants // math.gcd(n_layers, n_step_variants)
+    n_combo = min(n_combo, args.steps + args.warmup)
+    step_calls = []
+    for i in range(n_combo):
+        l, t = i % n_layers, i % n_step_variants
+        step_calls.append(ctx.prepared("hata_decode_step", q_steps[t % len(q_steps)], K_all[l], V_all[l],
+                                       W_H, codes_all[l], seq_steps[t], kbud, w.B, True, scale, out,
+                                       out32, stream=stream))
+
+    def step(i):
+        step_calls[i % n_combo]()
+
+    ms_step, ms_wall = timed(step, args.steps, args.warmup)
+    us_step = ms_step * 1e3
+
+    # ---- the dominant kernel alone (Hamming scoring: the largest stream of bytes), same launch
+    qcodes_buf, scores_buf, _ = ctx.hata_step_buffers()
+
+    score_calls = [ctx.prepared("hata_hamming_score", qcodes_buf, codes_all[l], seq_steps[0], w.B,
+                                scores_buf, stream=stream) for l in range(n_layers)]
+
+    def score_only(i):
+        score_calls[i % n_layers]()
+
+    ms_score, _ = timed(score_only, args.steps, args.warmup)
+    code_bytes = int(inp.seq_len.sum() + (w.B if w.append_steps else 0)) * w.Hkv * (w.r // 8)
+    score_gbps = code_bytes / (ms_score * 1e-3) / 1e9
+
+    # ---- dense decode over the whole cache (Eq. 1): the comparison baseline, same shapes
+    dense_us = None
+    if not args.no_dense:
+        dense_calls = [ctx.prepared("hata_dense_decode", q_steps[0], K_all[l], V_all[l], seq_steps[0], w.B,
+                                    scale, out, out32, stream=stream) for l in range(n_layers)]
+
+        def dense(i):
+            dense_calls[i % n_layers]()
+        ms_dense, _ = timed(dense, max(20, args.steps // 8), 5)
+        dense_us = ms_dense * 1e3
+
+    # ---- parity of one step + the oracle timed on this machine's host cores (rank 0, N = 1)
+    cpu = None
+    parity = None
+    if not args.no_cpu_baseline:
+        from oracle import hata_oracle as O
+        seq0 = inp.seq_len + (1 if w.append_steps else 0)
+        # the oracle encodes its own key codes for its own step
+        codes_o, _ = O.encode_keys_batch(inp.K, inp.W_H, np.zeros(w.B, np.int32), seq0, bulk=True)
+        q0 = inp.q(0)
+        t0 = time.perf_counter()
+        ref = O.decode_step(q0, inp.K, inp.V, inp.W_H, codes_o, seq0, inp.k, w.k_max, scale, append=True)
+        t1 = time.perf_counter() - t0
+        reps = int(max(1, min(50, args.cpu_seconds / max(t1, 1e-6))))
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            O.decode_step(q0, inp.K, inp.V, inp.W_H, codes_o, seq0, inp.k, w.k_max, scale, append=True)
+        tn = (time.perf_counter() - t0) / reps
+        cpu = {"value": round(tn * 1e6, 1), "unit": "us/step", "cores": O.num_threads(), "kind": "oracle",
+               "sample": f"{reps} full decode steps of {w.name} (all {w.B * w.Hkv} units, layer 0, step 0)"}
+        # parity of the GPU step on the oracle's codes
+        codes_dev = dev_bits(codes_o)
+        ctx.hata_decode_step(q_steps[0], K_all[0], V_all[0], W_H, codes_dev, seq_steps[0], kbud, w.B, True,
+                             scale, out, out32, stream)
+        torch.cuda.synchronize()
+        _, _, ix = ctx.hata_step_buffers()
+        idx_equal = bool(np.array_equal(ix.cpu().numpy(), ref["idx"]))
+        err = np.abs(out32.cpu().numpy().astype(np.float64) - ref["out"])
+        ok = bool(np.all(err <= 2e-3 + 1e-3 * np.abs(ref["out"])))
+        parity = {"idx_equal": idx_equal, "attn_within_tol": ok, "max_abs_err": float(err.max())}
+
+    alg_bytes = w.algorithmic_bytes(1 if w.append_steps else 0)
+    result = {
+        "metric": "hata_decode_attention_us_per_step",
+        "value": round(us_step, 3),
+        "unit": "us/step",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_step, 6),
+        "higher_is_better": False,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16 K/V/q with fp32 accumulate; u32 codes; fp64 query/append projection",
+        "data": "synthetic",
+        "config": {"workload": w.name, "B": w.B, "Hq": w.Hq, "Hkv": w.Hkv, "d": w.d, "r": w.r,
+                   "L": list(w.L) if len(set(w.L)) > 1 else w.L[0],
+                   "k": list(w.k) if len(set(w.k)) > 1 else w.k[0],
+                   "layers_rotated": n_layers, "append_per_step": True},
+        "achieved_GBps": round(alg_bytes / (us_step * 1e-6) / 1e9, 1),
+        "algorithmic_bytes_per_step": alg_bytes,
+        "step_roofline_frac": round(alg_bytes / (us_step * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4),
+        "host_wall_us_per_step": round(ms_wall * 1e3, 3),
+        "roofline": {"bound": "hbm", "kernel": "score_kernel (hata_hamming_score)",
+                     "achieved": round(score_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": round(score_gbps / HBM_PEAK_GBPS, 4), "traffic": None,
+                     "algorithmic_bytes_per_launch": code_bytes,
+                     "avg_launch_us": round(ms_score * 1e3, 3)},
+        "encode_keys_bulk": {"us_per_layer": round(enc_ms * 1e3, 1), "keys": enc_keys,
+                             "GBps": round(enc_bytes / (enc_ms * 1e-3) / 1e9, 1),
+                             "TFLOPs": round(enc_flop / (enc_ms * 1e-3) / 1e12, 2)},
+        "dense_decode_us": None if dense_us is None else round(dense_us, 2),
+        "speedup_vs_dense": None if dense_us is None else round(dense_us / us_step, 2),
+        "cpu_baseline": cpu,
+        "parity": parity,
+    }
+    print(json.dumps(result))
+    ctx.close()
+
+
+if __name__ == "__main__":
+    main()

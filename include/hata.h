@@ -1,0 +1,152 @@
+/*
+ * hata.h -- C ABI of the MI355X (gfx950) implementation of the HATA decode-attention
+ * hot path: hash-aware top-k attention for one decode step (paper: "HATA: Trainable and
+ * Hardware-Efficient Hash-Aware Top-k Attention", Sec. 3.2 and Sec. 4).
+ *
+ * One decode step (Alg. 3 of the paper), per (sequence, KV head) unit:
+ *   1. HashEncode the query heads and the newly cached key (Alg. 2),
+ *   2. score every cached key code by Hamming distance to the query codes,
+ *      summed over the query heads that share the KV head,
+ *   3. select the k keys with the smallest distance,
+ *   4. run softmax attention over only those k K/V rows.
+ *
+ * General rules of every entry point
+ *   - Every data pointer is a DEVICE pointer owned by the caller unless a comment says
+ *     "host".  The library never allocates or frees device memory: all scratch lives in
+ *     the workspace the caller hands to hata_create().
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only
+ *     enqueue work; they never synchronise the device.  Calls that share one context
+ *     must be issued on one stream (or be otherwise ordered): they share the workspace.
+ *   - Return value: HATA_OK (0) or a negative hata_status.  Nothing is enqueued after a
+ *     validation failure.  No exception or abort crosses this boundary.
+ *   - bf16 tensors are passed as void* to 16-bit patterns (upper half of an IEEE fp32).
+ *   - Per-sequence integers (seq_len, k, start, n_new) are device arrays, read by the
+ *     kernels; the host never waits for them.
+ *
+ * Tensor layouts (B sequences, Hq query heads, Hkv KV heads, G = Hq / Hkv, d = 128,
+ * r hash bits, Wd = r / 32 words, "unit" u = b * Hkv + h):
+ *   q, out    [B, Hq, d]            bf16, contiguous
+ *   out_f32   [B, Hq, d]            fp32, contiguous (optional copy of the un-rounded output)
+ *   K, V      row n of unit (b, h) starts at  base + b*kv_stride_b + h*kv_stride_h + n*kv_stride_n
+ *             (strides in elements; the d values of a row are contiguous; every row 16-byte aligned)
+ *   W_H       [Hkv, d, r]           fp32, contiguous; query head hq uses W_H[hq / G]
+ *   codes     [B, Hkv, L_cap, Wd]   uint32, contiguous; bit j of a code = bit (j % 32) of word j / 32,
+ *             set iff the j-th projection is >= 0
+ *   qcodes    [B, Hq, Wd]           uint32
+ *   scores    [B, Hkv, L_cap]       uint16, Hamming distance summed over the G heads (0 .. G*r)
+ *   idx       [B, Hkv, k_max]       int32, the selected cache rows in ascending order,
+ *                                   entries past min(k[b], seq_len[b]) are -1
+ *   seq_len   [B] int32             number of cached rows of sequence b, INCLUDING the token
+ *                                   appended in this step (Alg. 3 appends before it scores)
+ *   k         [B] int32             token budget of sequence b (clamped to [0, k_max] on device)
+ */
+#ifndef HATA_H
+#define HATA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    HATA_OK = 0,
+    HATA_EINVAL = -1,       /* NULL pointer, B out of range, bad stride/alignment, ... */
+    HATA_EUNSUPPORTED = -2, /* a shape this build has no kernel for */
+    HATA_EWORKSPACE = -3,   /* workspace NULL, misaligned or too small */
+    HATA_EHIP = -4          /* a HIP runtime call failed (launch error, no device, ...) */
+} hata_status;
+
+typedef struct {
+    int32_t B_max;   /* largest batch any call will pass */
+    int32_t Hq;      /* query heads */
+    int32_t Hkv;     /* KV heads; Hq % Hkv == 0, Hq / Hkv <= 16 */
+    int32_t d;       /* head dimension; must be 128 */
+    int32_t r;       /* hash bits; multiple of 32, 32..256; (Hq/Hkv) * r <= 4096 */
+    int32_t L_cap;   /* rows allocated per (sequence, KV head) in K, V and codes */
+    int32_t k_max;   /* largest token budget; 1 <= k_max <= L_cap */
+    int64_t kv_stride_b, kv_stride_h, kv_stride_n; /* K/V strides in elements; stride_n >= d, % 8 == 0 */
+} hata_config;
+
+typedef struct hata_ctx hata_ctx; /* opaque, host memory; owns nothing but its own struct */
+
+/* Static message for a status code (host pointer, never NULL). */
+const char* hata_strerror(int status);
+
+/* Validates `cfg` and writes the workspace size (bytes) a context of that shape needs.
+ * cfg, out: host pointers. */
+int hata_workspace_bytes(const hata_config* cfg, size_t* out);
+
+/* Creates a context.  `workspace` is device memory (256-byte aligned, at least
+ * hata_workspace_bytes() bytes) that stays owned by the caller and must outlive the
+ * context; its control words are cleared here with a synchronous hipMemset on the
+ * current device.  ctx_out, cfg: host pointers. */
+int hata_create(hata_ctx** ctx_out, const hata_config* cfg, void* workspace, size_t workspace_bytes);
+
+/* Frees the host-side context (the workspace is the caller's). */
+int hata_destroy(hata_ctx* ctx);
+
+/*
+ * Key-code writer (Alg. 1 lines 2-5 in bulk; Alg. 3 "Update code cache" for one appended key):
+ *   codes[b, h, n, :] = BitPack(Sign(K[b, h, n, :] . W_H[h]))   for start[b] <= n < start[b] + n_new[b].
+ * `max_new` (host value) is an upper bound of n_new[b] and sizes the launch; rows outside the
+ * range, and rows >= L_cap, are not touched.  Small max_new (<= 8) uses an fp64-accumulating
+ * kernel; larger uses the tiled projection kernel (fp32 accumulation: a bit may differ from an
+ * exact evaluation only where |projection| is below about 1e-5).
+ */
+int hata_encode_keys(hata_ctx* ctx, const void* K, const float* W_H,
+                     const int32_t* start, const int32_t* n_new, int32_t B, int32_t max_new,
+                     uint32_t* codes, void* stream);
+
+/* Query-code writer (Alg. 3 "HashEncode(Q)"): qcodes[b, hq, :] = BitPack(Sign(q[b, hq, :] . W_H[hq / G])).
+ * fp64 accumulation. */
+int hata_encode_query(hata_ctx* ctx, const void* q, const float* W_H, int32_t B,
+                      uint32_t* qcodes, void* stream);
+
+/* Hamming scores (Alg. 3 "Calculate distance in Hamming space", with the aggregation over
+ * query heads sharing a KV cache):
+ *   scores[b, h, n] = sum_{g < G} bitcount(qcodes[b, h*G + g, :] xor codes[b, h, n, :])   for n < seq_len[b].
+ * Entries n >= seq_len[b] are not written. */
+int hata_hamming_score(hata_ctx* ctx, const uint32_t* qcodes, const uint32_t* codes,
+                       const int32_t* seq_len, int32_t B, uint16_t* scores, void* stream);
+
+/* Selection (Alg. 3 "Idx = TopK(S, N)"): the min(k[b], seq_len[b]) rows n < seq_len[b] with the
+ * smallest (scores[n], n) in lexicographic order, i.e. smallest distance first and the lower
+ * row on equal distance; written ascending, the rest of the idx row set to -1.
+ * Scores above G*r are treated as G*r. */
+int hata_topk(hata_ctx* ctx, const uint16_t* scores, const int32_t* seq_len, const int32_t* k,
+              int32_t B, int32_t* idx, void* stream);
+
+/* Attention over the gathered rows (Alg. 3 Gather + Attention; Eq. 2 third line):
+ *   out[b, hq, :] = softmax_t( sm_scale * q[b, hq] . K[b, h, idx_t] ) . V[b, h, idx_t],  h = hq / G,
+ * over the first min(k[b], k_max) entries of idx[b, h, :], skipping negative entries.
+ * The gather is fused: no K_sparse / V_sparse is materialised.  bf16 inputs, fp32 accumulation.
+ * A unit with no valid row gives zeros.  out_f32 may be NULL. */
+int hata_sparse_decode(hata_ctx* ctx, const void* q, const void* K, const void* V,
+                       const int32_t* idx, const int32_t* k, int32_t B, float sm_scale,
+                       void* out, float* out_f32, void* stream);
+
+/* Dense decode attention over the whole cache (Eq. 1), rows 0 .. seq_len[b]-1: the baseline the
+ * sparse path is compared with.  Same numerics and outputs as hata_sparse_decode. */
+int hata_dense_decode(hata_ctx* ctx, const void* q, const void* K, const void* V,
+                      const int32_t* seq_len, int32_t B, float sm_scale,
+                      void* out, float* out_f32, void* stream);
+
+/* One whole decode step in the order of Alg. 3.  The caller has already copied the new K/V row
+ * of each sequence to cache row seq_len[b]-1 (static pre-allocated cache).  If `append` != 0
+ * that row is hash-encoded into `codes` first; then the query is encoded, all seq_len[b] codes
+ * are scored, the budget is selected and attention runs over the selected rows.
+ * Intermediate qcodes / scores / idx live in the workspace (see hata_step_buffers). */
+int hata_decode_step(hata_ctx* ctx, const void* q, const void* K, const void* V, const float* W_H,
+                     uint32_t* codes, const int32_t* seq_len, const int32_t* k, int32_t B,
+                     int32_t append, float sm_scale, void* out, float* out_f32, void* stream);
+
+/* Device pointers of the workspace regions hata_decode_step() writes (layouts as above, sized
+ * for B_max); valid until the workspace is released.  Any output pointer may be NULL. */
+int hata_step_buffers(hata_ctx* ctx, uint32_t** qcodes, uint16_t** scores, int32_t** idx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HATA_H */

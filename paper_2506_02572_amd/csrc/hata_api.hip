@@ -1,0 +1,247 @@
+// C-ABI entry points of libhata: argument validation, workspace carving, launch-shape
+// selection and the stage sequence of one decode step (Alg. 3 of the paper).
+#include <new>
+#include <stdlib.h>
+#include <string.h>
+
+#include "hata_internal.h"
+
+namespace {
+
+constexpr size_t kAlign = 256;
+inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
+
+struct Plan {
+    int G, Wd, NB, NBP, chunk, n_chunks, HT, sparse_rows, sparse_splits, dense_rows, dense_splits;
+    size_t off_qcodes, off_scores, off_idx, off_hist, off_cinfo, off_uinfo, off_partials, total;
+};
+
+int validate_config(const hata_config* f) {
+    if (!f) return HATA_EINVAL;
+    if (f->B_max < 1 || f->Hq < 1 || f->Hkv < 1 || f->L_cap < 1 || f->k_max < 1) return HATA_EINVAL;
+    if (f->Hq % f->Hkv != 0) return HATA_EINVAL;
+    if (f->k_max > f->L_cap) return HATA_EINVAL;
+    if (f->r < 32 || f->r % 32 != 0) return HATA_EINVAL;
+    if (f->kv_stride_n < f->d || f->kv_stride_n % 8 != 0 || f->kv_stride_h % 8 != 0 ||
+        f->kv_stride_b % 8 != 0 || f->kv_stride_h < 0 || f->kv_stride_b < 0)
+        return HATA_EINVAL;
+    if (f->d != 128) return HATA_EUNSUPPORTED;
+    if (f->r > 256) return HATA_EUNSUPPORTED;
+    const int G = f->Hq / f->Hkv;
+    if (G > 16 || (int64_t)G * f->r > 4096) return HATA_EUNSUPPORTED;
+    if ((int64_t)f->B_max * f->Hkv > 65535 || f->B_max > 65535) return HATA_EUNSUPPORTED;
+    return HATA_OK;
+}
+
+// Launch shapes: enough workgroups to cover 256 CUs a few times over, but chunks as large as
+// that allows (fewer partial histograms / attention partials to combine).
+int make_plan(const hata_config* f, Plan* p) {
+    int rc = validate_config(f);
+    if (rc != HATA_OK) return rc;
+    p->G = f->Hq / f->Hkv;
+    p->Wd = f->r / 32;
+    p->NB = p->G * f->r + 1;
+    p->NBP = (p->NB + 7) / 8 * 8;
+    const int64_t units = (int64_t)f->B_max * f->Hkv;
+    const int64_t target_wgs = 768;
+    int chunk = 8192;
+    while (chunk > 1024 && units * ((f->L_cap + chunk - 1) / chunk) < target_wgs) chunk >>= 1;
+    p->chunk = chunk;
+    p->n_chunks = (f->L_cap + chunk - 1) / chunk;
+    if (p->n_chunks > 1024) return HATA_EUNSUPPORTED;  // L_cap above 8M rows
+    const int G = p->G;
+    p->HT = (G % 8 == 0) ? 8 : (G % 5 == 0) ? 5 : (G % 4 == 0) ? 4 : (G % 2 == 0) ? 2 : 1;
+    const int64_t attn_units = units * (G / p->HT);
+    int rows = 256;
+    while (rows > 16 && attn_units * ((f->k_max + rows - 1) / rows) < 512) rows >>= 1;
+    p->sparse_rows = rows;
+    p->sparse_splits = (f->k_max + rows - 1) / rows;
+    int drows = 4096;
+    while (drows > 256 && attn_units * ((f->L_cap + drows - 1) / drows) < 1024) drows >>= 1;
+    p->dense_rows = drows;
+    p->dense_splits = (f->L_cap + drows - 1) / drows;
+    const int max_splits = p->sparse_splits > p->dense_splits ? p->sparse_splits : p->dense_splits;
+
+    size_t o = 0;
+    p->off_qcodes = o;   o = align_up(o + (size_t)f->B_max * f->Hq * p->Wd * 4);
+    p->off_scores = o;   o = align_up(o + (size_t)units * f->L_cap * 2);
+    p->off_idx = o;      o = align_up(o + (size_t)units * f->k_max * 4);
+    p->off_hist = o;     o = align_up(o + (size_t)units * p->n_chunks * p->NBP * 2);
+    p->off_cinfo = o;    o = align_up(o + (size_t)units * p->n_chunks * 2 * 4);
+    p->off_uinfo = o;    o = align_up(o + (size_t)units * 2 * 4);
+    p->off_partials = o; o = align_up(o + (size_t)f->B_max * f->Hq * max_splits * (128 + 2) * 4);
+    p->total = o;
+    return HATA_OK;
+}
+
+inline int check_call(const hata_ctx* c, int B) {
+    if (!c) return HATA_EINVAL;
+    if (B < 1 || B > c->cfg.B_max) return HATA_EINVAL;
+    return HATA_OK;
+}
+inline bool aligned(const void* p, size_t a) { return ((uintptr_t)p % a) == 0; }
+inline int hip_rc(hipError_t e) { return e == hipSuccess ? HATA_OK : HATA_EHIP; }
+
+}  // namespace
+
+extern "C" {
+
+const char* hata_strerror(int status) {
+    switch (status) {
+        case HATA_OK: return "ok";
+        case HATA_EINVAL: return "invalid argument";
+        case HATA_EUNSUPPORTED: return "unsupported shape";
+        case HATA_EWORKSPACE: return "workspace missing, misaligned or too small";
+        case HATA_EHIP: return "HIP runtime error";
+        default: return "unknown status";
+    }
+}
+
+int hata_workspace_bytes(const hata_config* cfg, size_t* out) {
+    if (!out) return HATA_EINVAL;
+    Plan p;
+    int rc = make_plan(cfg, &p);
+    if (rc != HATA_OK) return rc;
+    *out = p.total;
+    return HATA_OK;
+}
+
+int hata_create(hata_ctx** ctx_out, const hata_config* cfg, void* workspace, size_t workspace_bytes) {
+    if (!ctx_out) return HATA_EINVAL;
+    *ctx_out = nullptr;
+    Plan p;
+    int rc = make_plan(cfg, &p);
+    if (rc != HATA_OK) return rc;
+    if (!workspace || !aligned(workspace, kAlign) || workspace_bytes < p.total) return HATA_EWORKSPACE;
+    hata_ctx* c = new (std::nothrow) hata_ctx;
+    if (!c) return HATA_EINVAL;
+    c->cfg = *cfg;
+    c->G = p.G; c->Wd = p.Wd; c->NB = p.NB; c->NBP = p.NBP;
+    c->chunk = p.chunk; c->n_chunks = p.n_chunks; c->HT = p.HT;
+    c->sparse_rows = p.sparse_rows; c->sparse_splits = p.sparse_splits;
+    c->dense_rows = p.dense_rows; c->dense_splits = p.dense_splits;
+    char* w = (char*)workspace;
+    c->qcodes = (uint32_t*)(w + p.off_qcodes);
+    c->scores = (uint16_t*)(w + p.off_scores);
+    c->idx = (int32_t*)(w + p.off_idx);
+    c->chunk_hist = (uint16_t*)(w + p.off_hist);
+    c->chunk_info = (int32_t*)(w + p.off_cinfo);
+    c->unit_info = (int32_t*)(w + p.off_uinfo);
+    c->partials = (float*)(w + p.off_partials);
+    // control words start from a defined state
+    if (hipMemset(c->chunk_info, 0, p.off_partials - p.off_cinfo) != hipSuccess) {
+        delete c;
+        return HATA_EHIP;
+    }
+    *ctx_out = c;
+    return HATA_OK;
+}
+
+int hata_destroy(hata_ctx* ctx) {
+    delete ctx;
+    return HATA_OK;
+}
+
+int hata_encode_keys(hata_ctx* ctx, const void* K, const float* W_H, const int32_t* start,
+                     const int32_t* n_new, int32_t B, int32_t max_new, uint32_t* codes,
+                     void* stream) {
+    int rc = check_call(ctx, B);
+    if (rc != HATA_OK) return rc;
+    if (!K || !W_H || !start || !n_new || !codes) return HATA_EINVAL;
+    if (max_new < 0 || max_new > ctx->cfg.L_cap) return HATA_EINVAL;
+    if (!aligned(K, 16) || !aligned(codes, 16) || !aligned(W_H, 16)) return HATA_EINVAL;
+    if (max_new == 0) return HATA_OK;
+    hipStream_t s = (hipStream_t)stream;
+    if (max_new <= 8)
+        return hip_rc(hata::launch_encode_vectors(ctx, nullptr, nullptr, K, start, n_new, max_new,
+                                                  0, codes, W_H, B, s));
+    return hip_rc(hata::launch_encode_bulk(ctx, K, W_H, start, n_new, B, max_new, codes, s));
+}
+
+int hata_encode_query(hata_ctx* ctx, const void* q, const float* W_H, int32_t B, uint32_t* qcodes,
+                      void* stream) {
+    int rc = check_call(ctx, B);
+    if (rc != HATA_OK) return rc;
+    if (!q || !W_H || !qcodes) return HATA_EINVAL;
+    if (!aligned(q, 16) || !aligned(qcodes, 4) || !aligned(W_H, 16)) return HATA_EINVAL;
+    return hip_rc(hata::launch_encode_vectors(ctx, q, qcodes, nullptr, nullptr, nullptr, 0, 0,
+                                              nullptr, W_H, B, (hipStream_t)stream));
+}
+
+int hata_hamming_score(hata_ctx* ctx, const uint32_t* qcodes, const uint32_t* codes,
+                       const int32_t* seq_len, int32_t B, uint16_t* scores, void* stream) {
+    int rc = check_call(ctx, B);
+    if (rc != HATA_OK) return rc;
+    if (!qcodes || !codes || !seq_len || !scores) return HATA_EINVAL;
+    if (!aligned(qcodes, 4) || !aligned(codes, 16) || !aligned(scores, 2)) return HATA_EINVAL;
+    // the chunk histograms are written too (into the workspace): the launch is the very one the
+    // fused decode step makes
+    return hip_rc(hata::launch_score(ctx, qcodes, codes, seq_len, B, scores, true,
+                                     (hipStream_t)stream));
+}
+
+int hata_topk(hata_ctx* ctx, const uint16_t* scores, const int32_t* seq_len, const int32_t* k,
+              int32_t B, int32_t* idx, void* stream) {
+    int rc = check_call(ctx, B);
+    if (rc != HATA_OK) return rc;
+    if (!scores || !seq_len || !k || !idx) return HATA_EINVAL;
+    if (!aligned(scores, 2) || !aligned(idx, 4)) return HATA_EINVAL;
+    return hip_rc(hata::launch_topk(ctx, scores, seq_len, k, B, idx, false, (hipStream_t)stream));
+}
+
+int hata_sparse_decode(hata_ctx* ctx, const void* q, const void* K, const void* V,
+                       const int32_t* idx, const int32_t* k, int32_t B, float sm_scale, void* out,
+                       float* out_f32, void* stream) {
+    int rc = check_call(ctx, B);
+    if (rc != HATA_OK) return rc;
+    if (!q || !K || !V || !idx || !k || !out) return HATA_EINVAL;
+    if (!aligned(q, 16) || !aligned(K, 16) || !aligned(V, 16) || !aligned(out, 2)) return HATA_EINVAL;
+    return hip_rc(hata::launch_attention(ctx, false, q, K, V, idx, k, B, sm_scale, out, out_f32,
+                                         (hipStream_t)stream));
+}
+
+int hata_dense_decode(hata_ctx* ctx, const void* q, const void* K, const void* V,
+                      const int32_t* seq_len, int32_t B, float sm_scale, void* out, float* out_f32,
+                      void* stream) {
+    int rc = check_call(ctx, B);
+    if (rc != HATA_OK) return rc;
+    if (!q || !K || !V || !seq_len || !out) return HATA_EINVAL;
+    if (!aligned(q, 16) || !aligned(K, 16) || !aligned(V, 16) || !aligned(out, 2)) return HATA_EINVAL;
+    return hip_rc(hata::launch_attention(ctx, true, q, K, V, nullptr, seq_len, B, sm_scale, out,
+                                         out_f32, (hipStream_t)stream));
+}
+
+int hata_decode_step(hata_ctx* ctx, const void* q, const void* K, const void* V, const float* W_H,
+                     uint32_t* codes, const int32_t* seq_len, const int32_t* k, int32_t B,
+                     int32_t append, float sm_scale, void* out, float* out_f32, void* stream) {
+    int rc = check_call(ctx, B);
+    if (rc != HATA_OK) return rc;
+    if (!q || !K || !V || !W_H || !codes || !seq_len || !k || !out) return HATA_EINVAL;
+    if (!aligned(q, 16) || !aligned(K, 16) || !aligned(V, 16) || !aligned(codes, 16) ||
+        !aligned(W_H, 16) || !aligned(out, 2))
+        return HATA_EINVAL;
+    hipStream_t s = (hipStream_t)stream;
+    // Alg. 3: HashEncode(Q), HashEncode(K_new) and the code-cache update, in one launch
+    hipError_t e = hata::launch_encode_vectors(ctx, q, ctx->qcodes, append ? K : nullptr, seq_len,
+                                               nullptr, 1, 1, codes, W_H, B, s);
+    if (e != hipSuccess) return HATA_EHIP;
+    // Hamming distances of every cached code (the new one included) + chunk histograms
+    e = hata::launch_score(ctx, ctx->qcodes, codes, seq_len, B, ctx->scores, true, s);
+    if (e != hipSuccess) return HATA_EHIP;
+    // TopK(S, N)
+    e = hata::launch_topk(ctx, ctx->scores, seq_len, k, B, ctx->idx, true, s);
+    if (e != hipSuccess) return HATA_EHIP;
+    // attention over the selected rows, gather fused
+    e = hata::launch_attention(ctx, false, q, K, V, ctx->idx, k, B, sm_scale, out, out_f32, s);
+    return hip_rc(e);
+}
+
+int hata_step_buffers(hata_ctx* ctx, uint32_t** qcodes, uint16_t** scores, int32_t** idx) {
+    if (!ctx) return HATA_EINVAL;
+    if (qcodes) *qcodes = ctx->qcodes;
+    if (scores) *scores = ctx->scores;
+    if (idx) *idx = ctx->idx;
+    return HATA_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,151 @@
+// HashEncode kernels (Alg. 2 of the paper): codes = BitPack(Sign(x . W_H)).
+//
+//   encode_vectors_kernel  one workgroup per vector (query heads, appended keys);
+//                          fp64 accumulation, so the sign agrees with an exact
+//                          evaluation unless |projection| is below ~1e-13.
+//   encode_bulk_kernel     64 keys per workgroup, fp32 accumulation (prefill, Alg. 1 l.2-5).
+#include "hata_device.h"
+#include "hata_internal.h"
+
+namespace hata {
+
+// Bit j of a code goes to word j/32, bit position j%32; bit = (projection >= 0).
+__global__ __launch_bounds__(256) void encode_vectors_kernel(
+    const uint16_t* __restrict__ q, uint32_t* __restrict__ qcodes, int nq_blocks,
+    const uint16_t* __restrict__ K, const int32_t* __restrict__ start,
+    const int32_t* __restrict__ n_new, int max_new, int from_seq_len,
+    uint32_t* __restrict__ codes, const float* __restrict__ W_H,
+    int Hq, int Hkv, int G, int r, int Wd, int L_cap,
+    int64_t sb, int64_t sh, int64_t sn) {
+    __shared__ float xs[HATA_D];
+    __shared__ double part[256];
+    const int tid = threadIdx.x;
+    int blk = blockIdx.x;
+    const uint16_t* x;
+    uint32_t* dst;
+    int h;
+    if (blk < nq_blocks) {
+        const int hq = blk % Hq;
+        h = hq / G;
+        x = q + (int64_t)blk * HATA_D;
+        dst = qcodes + (int64_t)blk * Wd;
+    } else {
+        blk -= nq_blocks;
+        const int t = blk % max_new;
+        const int u = blk / max_new;
+        const int b = u / Hkv;
+        h = u % Hkv;
+        int n, cnt;
+        if (from_seq_len) { n = start[b] - 1; cnt = 1; }
+        else { n = start[b] + t; cnt = n_new[b]; }
+        if (t >= cnt || n < 0 || n >= L_cap) return;  // uniform over the workgroup
+        x = K + b * sb + h * sh + n * sn;
+        dst = codes + ((int64_t)u * L_cap + n) * Wd;
+    }
+    if (tid < HATA_D) xs[tid] = __uint_as_float((uint32_t)x[tid] << 16);
+    __syncthreads();
+    const int parts = 256 / r;                    // r <= 256
+    const int per = (HATA_D + parts - 1) / parts; // channels per part
+    const int j = tid % r, p = tid / r;
+    double acc = 0.0;
+    if (p < parts) {
+        const float* w = W_H + (int64_t)h * HATA_D * r + j;
+        const int i0 = p * per;
+        const int i1 = min(HATA_D, i0 + per);
+        for (int i = i0; i < i1; ++i) acc += (double)xs[i] * (double)w[(int64_t)i * r];
+    }
+    part[tid] = acc;
+    __syncthreads();
+    bool bit = false;
+    if (tid < r) {
+        double y = 0.0;
+        for (int pp = 0; pp < parts; ++pp) y += part[pp * r + tid];
+        bit = (y >= 0.0);
+    }
+    const unsigned long long mask = __ballot(bit);
+    const int wave = tid >> 6;
+    if ((tid & 63) == 0 && wave * 64 < r) {
+        dst[2 * wave] = (uint32_t)mask;
+        if (2 * wave + 1 < Wd) dst[2 * wave + 1] = (uint32_t)(mask >> 32);
+    }
+}
+
+// 64 keys per workgroup; thread = (key, word group).  The word group is uniform over a
+// wave, so the W_H reads are wave-uniform.  grid = (tiles, Hkv, B).
+__global__ __launch_bounds__(256) void encode_bulk_kernel(
+    const uint16_t* __restrict__ K, const float* __restrict__ W_H,
+    const int32_t* __restrict__ start, const int32_t* __restrict__ n_new,
+    uint32_t* __restrict__ codes, int Hkv, int r, int Wd, int L_cap,
+    int64_t sb, int64_t sh, int64_t sn) {
+    __shared__ float xs[64][HATA_D + 1];
+    const int tid = threadIdx.x;
+    const int h = blockIdx.y, b = blockIdx.z;
+    const int first = start[b];
+    const int cnt = n_new[b];
+    const int t0 = blockIdx.x * 64;
+    if (t0 >= cnt) return;
+    const int64_t u = (int64_t)b * Hkv + h;
+    // stage the tile: 16 lanes per row, 16 B (8 bf16) per lane
+    for (int it = 0; it < 4; ++it) {
+        const int row = it * 16 + (tid >> 4);
+        const int n = first + t0 + row;
+        const int sub = tid & 15;
+        uint4 v = make_uint4(0, 0, 0, 0);
+        if (t0 + row < cnt && n >= 0 && n < L_cap)
+            v = *reinterpret_cast<const uint4*>(K + b * sb + h * sh + (int64_t)n * sn + sub * 8);
+        float* dstp = &xs[row][sub * 8];
+        dstp[0] = bf16_lo(v.x); dstp[1] = bf16_hi(v.x);
+        dstp[2] = bf16_lo(v.y); dstp[3] = bf16_hi(v.y);
+        dstp[4] = bf16_lo(v.z); dstp[5] = bf16_hi(v.z);
+        dstp[6] = bf16_lo(v.w); dstp[7] = bf16_hi(v.w);
+    }
+    __syncthreads();
+    const int key = tid & 63;
+    const int n = first + t0 + key;
+    const bool live = (t0 + key < cnt) && n >= 0 && n < L_cap;
+    const int wg = __builtin_amdgcn_readfirstlane(tid >> 6);
+    for (int w = wg; w < Wd; w += 4) {
+        float acc[32];
+#pragma unroll
+        for (int c = 0; c < 32; ++c) acc[c] = 0.f;
+        const float* wp = W_H + (int64_t)h * HATA_D * r + w * 32;
+        for (int i = 0; i < HATA_D; ++i) {
+            const float xv = xs[key][i];
+#pragma unroll
+            for (int c = 0; c < 32; ++c) acc[c] = fmaf(xv, wp[(int64_t)i * r + c], acc[c]);
+        }
+        uint32_t word = 0;
+#pragma unroll
+        for (int c = 0; c < 32; ++c) word |= (acc[c] >= 0.f ? 1u : 0u) << c;
+        if (live) codes[(u * L_cap + n) * Wd + w] = word;
+    }
+}
+
+hipError_t launch_encode_vectors(const hata_ctx* c, const void* q, uint32_t* qcodes,
+                                 const void* K, const int32_t* start, const int32_t* n_new,
+                                 int max_new, int from_seq_len, uint32_t* codes,
+                                 const float* W_H, int B, hipStream_t s) {
+    const hata_config& f = c->cfg;
+    const int nq = q ? B * f.Hq : 0;
+    const int nk = K ? B * f.Hkv * max_new : 0;
+    if (nq + nk == 0) return hipSuccess;
+    hipLaunchKernelGGL(encode_vectors_kernel, dim3(nq + nk), dim3(256), 0, s,
+                       (const uint16_t*)q, qcodes, nq, (const uint16_t*)K, start, n_new,
+                       max_new > 0 ? max_new : 1, from_seq_len, codes, W_H, f.Hq, f.Hkv, c->G,
+                       f.r, c->Wd, f.L_cap, f.kv_stride_b, f.kv_stride_h, f.kv_stride_n);
+    return hipGetLastError();
+}
+
+hipError_t launch_encode_bulk(const hata_ctx* c, const void* K, const float* W_H,
+                              const int32_t* start, const int32_t* n_new, int B, int max_new,
+                              uint32_t* codes, hipStream_t s) {
+    const hata_config& f = c->cfg;
+    const int tiles = (max_new + 63) / 64;
+    if (tiles <= 0 || B <= 0) return hipSuccess;
+    hipLaunchKernelGGL(encode_bulk_kernel, dim3(tiles, f.Hkv, B), dim3(256), 0, s,
+                       (const uint16_t*)K, W_H, start, n_new, codes, f.Hkv, f.r, c->Wd, f.L_cap,
+                       f.kv_stride_b, f.kv_stride_h, f.kv_stride_n);
+    return hipGetLastError();
+}
+
+}  // namespace hata

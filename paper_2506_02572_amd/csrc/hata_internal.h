@@ -1,0 +1,50 @@
+// Host-side internals of libhata: the context and the per-stage launchers.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/hata.h"
+
+struct hata_ctx {
+    hata_config cfg;
+    int G;            // query heads per KV head
+    int Wd;           // 32-bit words per code
+    int NB;           // number of score values: G*r + 1
+    int NBP;          // NB rounded up to a multiple of 8 (row pitch of the chunk histograms)
+    int chunk;        // cached keys handled by one scoring / selection workgroup
+    int n_chunks;     // ceil(L_cap / chunk)
+    int HT;           // query heads of a group handled together by one attention workgroup
+    int sparse_rows;  // selected rows per attention workgroup
+    int sparse_splits;
+    int dense_rows;   // cache rows per dense-attention workgroup
+    int dense_splits;
+    // regions of the caller's workspace
+    uint32_t* qcodes;      // [B_max, Hq, Wd]
+    uint16_t* scores;      // [B_max, Hkv, L_cap]
+    int32_t* idx;          // [B_max, Hkv, k_max]
+    uint16_t* chunk_hist;  // [B_max*Hkv, n_chunks, NBP]
+    int32_t* chunk_info;   // [B_max*Hkv, n_chunks, 2] = {output offset, ties taken}
+    int32_t* unit_info;    // [B_max*Hkv, 2] = {threshold, selected count}
+    float* partials;       // [B_max*Hq, max(sparse_splits, dense_splits), d + 2]
+};
+
+namespace hata {
+
+// every launcher returns hipGetLastError() of its launches
+hipError_t launch_encode_vectors(const hata_ctx* c, const void* q, uint32_t* qcodes,
+                                 const void* K, const int32_t* start, const int32_t* n_new,
+                                 int max_new, int from_seq_len, uint32_t* codes,
+                                 const float* W_H, int B, hipStream_t s);
+hipError_t launch_encode_bulk(const hata_ctx* c, const void* K, const float* W_H,
+                              const int32_t* start, const int32_t* n_new, int B, int max_new,
+                              uint32_t* codes, hipStream_t s);
+hipError_t launch_score(const hata_ctx* c, const uint32_t* qcodes, const uint32_t* codes,
+                        const int32_t* seq_len, int B, uint16_t* scores, bool with_hist,
+                        hipStream_t s);
+hipError_t launch_topk(const hata_ctx* c, const uint16_t* scores, const int32_t* seq_len,
+                       const int32_t* k, int B, int32_t* idx, bool have_hist, hipStream_t s);
+hipError_t launch_attention(const hata_ctx* c, bool dense, const void* q, const void* K,
+                            const void* V, const int32_t* idx, const int32_t* count_src, int B,
+                            float sm_scale, void* out, float* out_f32, hipStream_t s);
+
+}  // namespace hata

@@ -1,0 +1,223 @@
+"""Thin ctypes binding of ``libhata.so`` (the C ABI declared in ``include/hata.h``).
+
+Argument marshalling only: every step of the path runs in the HIP kernels behind the
+C ABI.  torch is used for device memory and the stream handle, nothing else.  There is
+no CPU fallback: if the library is missing or a call fails, an exception is raised.
+Function names match the C entry points.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libhata.so")
+
+EXPORTS = (
+    "hata_strerror", "hata_workspace_bytes", "hata_create", "hata_destroy", "hata_encode_keys",
+    "hata_encode_query", "hata_hamming_score", "hata_topk", "hata_sparse_decode",
+    "hata_dense_decode", "hata_decode_step", "hata_step_buffers",
+)
+
+
+class HataError(RuntimeError):
+    pass
+
+
+class hata_config(ctypes.Structure):
+    _fields_ = [
+        ("B_max", ctypes.c_int32), ("Hq", ctypes.c_int32), ("Hkv", ctypes.c_int32),
+        ("d", ctypes.c_int32), ("r", ctypes.c_int32), ("L_cap", ctypes.c_int32),
+        ("k_max", ctypes.c_int32),
+        ("kv_stride_b", ctypes.c_int64), ("kv_stride_h", ctypes.c_int64),
+        ("kv_stride_n", ctypes.c_int64),
+    ]
+
+
+_lib = None
+_vp = ctypes.c_void_p
+_i32 = ctypes.c_int32
+
+
+def load_library(build_if_missing: bool = True) -> ctypes.CDLL:
+    """Load libhata.so (building it with hipcc first only if no built library exists)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    # torch ships its own HIP runtime with the same soname as the system one; importing torch
+    # first makes libhata.so bind to that runtime, so both see the same device allocations.
+    import torch  # noqa: F401
+    if not os.path.exists(LIB_PATH):
+        if not build_if_missing:
+            raise HataError(f"{LIB_PATH} is not built; run paper_2506_02572_amd/build.py")
+        from . import build as _build
+        _build.build(force=True)
+    lib = ctypes.CDLL(LIB_PATH)
+    lib.hata_strerror.restype = ctypes.c_char_p
+    lib.hata_strerror.argtypes = [ctypes.c_int]
+    lib.hata_workspace_bytes.argtypes = [ctypes.POINTER(hata_config), ctypes.POINTER(ctypes.c_size_t)]
+    lib.hata_create.argtypes = [ctypes.POINTER(_vp), ctypes.POINTER(hata_config), _vp, ctypes.c_size_t]
+    lib.hata_destroy.argtypes = [_vp]
+    lib.hata_encode_keys.argtypes = [_vp, _vp, _vp, _vp, _vp, _i32, _i32, _vp, _vp]
+    lib.hata_encode_query.argtypes = [_vp, _vp, _vp, _i32, _vp, _vp]
+    lib.hata_hamming_score.argtypes = [_vp, _vp, _vp, _vp, _i32, _vp, _vp]
+    lib.hata_topk.argtypes = [_vp, _vp, _vp, _vp, _i32, _vp, _vp]
+    lib.hata_sparse_decode.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _i32, ctypes.c_float, _vp, _vp, _vp]
+    lib.hata_dense_decode.argtypes = [_vp, _vp, _vp, _vp, _vp, _i32, ctypes.c_float, _vp, _vp, _vp]
+    lib.hata_decode_step.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32,
+                                     ctypes.c_float, _vp, _vp, _vp]
+    lib.hata_step_buffers.argtypes = [_vp, ctypes.POINTER(_vp), ctypes.POINTER(_vp), ctypes.POINTER(_vp)]
+    for name in EXPORTS:
+        if name != "hata_strerror":
+            getattr(lib, name).restype = ctypes.c_int
+    _lib = lib
+    return lib
+
+
+def strerror(status: int) -> str:
+    return load_library().hata_strerror(int(status)).decode()
+
+
+def _check(status: int, what: str) -> None:
+    if status != 0:
+        raise HataError(f"{what} failed: {strerror(status)} ({status})")
+
+
+def _ptr(t):
+    """Device pointer of a torch tensor (or None)."""
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise HataError("expected a device tensor")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream=None):
+    import torch
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+@dataclass
+class Shape:
+    B_max: int
+    Hq: int
+    Hkv: int
+    d: int
+    r: int
+    L_cap: int
+    k_max: int
+
+
+class Context:
+    """Owns a hata_ctx and the torch-allocated workspace it points into."""
+
+    def __init__(self, B_max, Hq, Hkv, d, r, L_cap, k_max, kv_strides=None, device="cuda:0"):
+        import torch
+        lib = load_library()
+        if not torch.cuda.is_available():
+            raise HataError("no GPU visible: the HATA path has no CPU fallback")
+        self.shape = Shape(B_max, Hq, Hkv, d, r, L_cap, k_max)
+        if kv_strides is None:
+            kv_strides = (Hkv * L_cap * d, L_cap * d, d)
+        self.cfg = hata_config(B_max, Hq, Hkv, d, r, L_cap, k_max, *kv_strides)
+        nbytes = ctypes.c_size_t(0)
+        _check(lib.hata_workspace_bytes(ctypes.byref(self.cfg), ctypes.byref(nbytes)),
+               "hata_workspace_bytes")
+        self.device = torch.device(device)
+        self.workspace = torch.empty(nbytes.value + 256, dtype=torch.uint8, device=self.device)
+        base = self.workspace.data_ptr()
+        self._ws_ptr = (base + 255) // 256 * 256
+        self._h = ctypes.c_void_p(None)
+        with torch.cuda.device(self.device):
+            _check(lib.hata_create(ctypes.byref(self._h), ctypes.byref(self.cfg),
+                                   ctypes.c_void_p(self._ws_ptr), nbytes.value), "hata_create")
+        self.workspace_bytes = nbytes.value
+
+    def close(self):
+        if getattr(self, "_h", None) is not None and self._h.value:
+            load_library().hata_destroy(self._h)
+            self._h = ctypes.c_void_p(None)
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    # ---- entry points (same names as the C ABI) ----
+    def hata_encode_keys(self, K, W_H, start, n_new, B, max_new, codes, stream=None):
+        _check(load_library().hata_encode_keys(self._h, _ptr(K), _ptr(W_H), _ptr(start), _ptr(n_new),
+                                               B, max_new, _ptr(codes), _stream(stream)),
+               "hata_encode_keys")
+
+    def hata_encode_query(self, q, W_H, B, qcodes, stream=None):
+        _check(load_library().hata_encode_query(self._h, _ptr(q), _ptr(W_H), B, _ptr(qcodes),
+                                                _stream(stream)), "hata_encode_query")
+
+    def hata_hamming_score(self, qcodes, codes, seq_len, B, scores, stream=None):
+        _check(load_library().hata_hamming_score(self._h, _ptr(qcodes), _ptr(codes), _ptr(seq_len), B,
+                                                 _ptr(scores), _stream(stream)), "hata_hamming_score")
+
+    def hata_topk(self, scores, seq_len, k, B, idx, stream=None):
+        _check(load_library().hata_topk(self._h, _ptr(scores), _ptr(seq_len), _ptr(k), B, _ptr(idx),
+                                        _stream(stream)), "hata_topk")
+
+    def hata_sparse_decode(self, q, K, V, idx, k, B, sm_scale, out, out_f32=None, stream=None):
+        _check(load_library().hata_sparse_decode(self._h, _ptr(q), _ptr(K), _ptr(V), _ptr(idx), _ptr(k),
+                                                 B, sm_scale, _ptr(out), _ptr(out_f32),
+                                                 _stream(stream)), "hata_sparse_decode")
+
+    def hata_dense_decode(self, q, K, V, seq_len, B, sm_scale, out, out_f32=None, stream=None):
+        _check(load_library().hata_dense_decode(self._h, _ptr(q), _ptr(K), _ptr(V), _ptr(seq_len), B,
+                                                sm_scale, _ptr(out), _ptr(out_f32), _stream(stream)),
+               "hata_dense_decode")
+
+    def hata_decode_step(self, q, K, V, W_H, codes, seq_len, k, B, append, sm_scale, out,
+                         out_f32=None, stream=None):
+        _check(load_library().hata_decode_step(self._h, _ptr(q), _ptr(K), _ptr(V), _ptr(W_H),
+                                               _ptr(codes), _ptr(seq_len), _ptr(k), B,
+                                               1 if append else 0, sm_scale, _ptr(out),
+                                               _ptr(out_f32), _stream(stream)), "hata_decode_step")
+
+    def prepared(self, name, *args, stream=None):
+        """Marshal the arguments of entry point ``name`` once and return a zero-argument callable
+        that issues exactly that C call (for launch loops where per-call marshalling would
+        dominate).  Tensor arguments must stay alive as long as the callable is used."""
+        fn = getattr(load_library(), name)
+        cargs = [self._h]
+        for a in args:
+            if a is None or hasattr(a, "data_ptr"):
+                cargs.append(_ptr(a))
+            elif isinstance(a, bool):
+                cargs.append(1 if a else 0)
+            else:
+                cargs.append(a)
+        cargs.append(_stream(stream))
+        cargs = tuple(cargs)
+
+        def call():
+            rc = fn(*cargs)
+            if rc != 0:
+                _check(rc, name)
+        return call
+
+    def hata_step_buffers(self):
+        """torch views (no copy) of the workspace regions hata_decode_step writes:
+        (qcodes int32 [B_max,Hq,Wd], scores int16 [B_max,Hkv,L_cap], idx int32 [B_max,Hkv,k_max])."""
+        import torch
+        qc, sc, ix = ctypes.c_void_p(), ctypes.c_void_p(), ctypes.c_void_p()
+        _check(load_library().hata_step_buffers(self._h, ctypes.byref(qc), ctypes.byref(sc),
+                                                ctypes.byref(ix)), "hata_step_buffers")
+        s = self.shape
+        base = self.workspace.data_ptr()
+
+        def view(ptr, nbytes, dtype, shape):
+            off = ptr.value - base
+            return self.workspace[off:off + nbytes].view(dtype).view(*shape)
+
+        Wd = s.r // 32
+        return (view(qc, s.B_max * s.Hq * Wd * 4, torch.int32, (s.B_max, s.Hq, Wd)),
+                view(sc, s.B_max * s.Hkv * s.L_cap * 2, torch.int16, (s.B_max, s.Hkv, s.L_cap)),
+                view(ix, s.B_max * s.Hkv * s.k_max * 4, torch.int32, (s.B_max, s.Hkv, s.k_max)))

@@ -1,0 +1,65 @@
+"""The C-ABI library loads without a GPU and exports every symbol include/hata.h declares;
+host-side validation (no kernel launch) behaves as the header says."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2506_02572_amd import hata
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "hata.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(hata_[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported_and_bound():
+    lib = hata.load_library()
+    names = declared_symbols()
+    assert len(names) >= 12
+    for n in names:
+        assert hasattr(lib, n), f"{n} declared in hata.h but not exported by libhata.so"
+    assert sorted(hata.EXPORTS) == names
+
+
+def test_strerror_and_workspace_validation():
+    lib = hata.load_library()
+    assert hata.strerror(0) == "ok"
+    for code in (-1, -2, -3, -4, -99):
+        assert hata.strerror(code)
+    n = ctypes.c_size_t(0)
+    good = hata.hata_config(1, 32, 8, 128, 128, 32768, 512, 8 * 32768 * 128, 32768 * 128, 128)
+    assert lib.hata_workspace_bytes(ctypes.byref(good), ctypes.byref(n)) == 0
+    # scores (2 B/key) + chunk histograms + idx + partials: well under 4 MB for this shape
+    assert 8 * 32768 * 2 < n.value < 4 << 20
+    bad = [
+        hata.hata_config(1, 32, 8, 64, 128, 32768, 512, 1, 1, 128),         # d != 128
+        hata.hata_config(1, 32, 7, 128, 128, 32768, 512, 1 << 20, 1 << 20, 128),  # Hq % Hkv
+        hata.hata_config(1, 32, 8, 128, 100, 32768, 512, 1 << 20, 1 << 20, 128),  # r % 32
+        hata.hata_config(1, 32, 8, 128, 128, 256, 512, 1 << 20, 1 << 20, 128),    # k_max > L_cap
+        hata.hata_config(1, 32, 8, 128, 128, 32768, 512, 1 << 20, 1 << 20, 100),  # row stride < d
+        hata.hata_config(0, 32, 8, 128, 128, 32768, 512, 1 << 20, 1 << 20, 128),  # B_max < 1
+    ]
+    for cfg in bad:
+        assert lib.hata_workspace_bytes(ctypes.byref(cfg), ctypes.byref(n)) < 0
+    assert lib.hata_workspace_bytes(None, ctypes.byref(n)) == -1
+    # create refuses a missing workspace before touching the device
+    h = ctypes.c_void_p()
+    assert lib.hata_create(ctypes.byref(h), ctypes.byref(good), None, 0) == -3
+    assert not h.value
+    # calls on a NULL context are rejected, nothing is launched
+    assert lib.hata_encode_query(None, None, None, 1, None, None) == -1
+    assert lib.hata_decode_step(None, None, None, None, None, None, None, None, 1, 0, 1.0, None, None, None) == -1
+    assert lib.hata_destroy(None) == 0
+
+
+def test_binding_has_no_cpu_fallback():
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("GPU present")
+    with pytest.raises(hata.HataError):
+        hata.Context(1, 32, 8, 128, 128, 2048, 128)
