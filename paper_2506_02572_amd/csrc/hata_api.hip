@@ -13,7 +13,7 @@ inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
 struct Plan {
     int G, Wd, NB, NBP, chunk, n_chunks, HT, sparse_rows, sparse_splits, dense_rows, dense_splits;
-    size_t off_qcodes, off_scores, off_idx, off_hist, off_cinfo, off_uinfo, off_partials, total;
+    size_t off_qcodes, off_scores, off_idx, off_hist, off_cinfo, off_uinfo, off_ucnt, off_acnt, off_partials, total;
 };
 
 int validate_config(const hata_config* f) {
@@ -67,8 +67,10 @@ int make_plan(const hata_config* f, Plan* p) {
     p->off_scores = o;   o = align_up(o + (size_t)units * f->L_cap * 2);
     p->off_idx = o;      o = align_up(o + (size_t)units * f->k_max * 4);
     p->off_hist = o;     o = align_up(o + (size_t)units * p->n_chunks * p->NBP * 2);
-    p->off_cinfo = o;    o = align_up(o + (size_t)units * p->n_chunks * 2 * 4);
+    p->off_cinfo = o;    o = align_up(o + (size_t)units * (p->n_chunks + 1) * 2 * 4);
     p->off_uinfo = o;    o = align_up(o + (size_t)units * 2 * 4);
+    p->off_ucnt = o;     o = align_up(o + (size_t)units * 4);
+    p->off_acnt = o;     o = align_up(o + (size_t)f->B_max * f->Hq * 4);
     p->off_partials = o; o = align_up(o + (size_t)f->B_max * f->Hq * max_splits * (128 + 2) * 4);
     p->total = o;
     return HATA_OK;
@@ -127,8 +129,10 @@ int hata_create(hata_ctx** ctx_out, const hata_config* cfg, void* workspace, siz
     c->chunk_hist = (uint16_t*)(w + p.off_hist);
     c->chunk_info = (int32_t*)(w + p.off_cinfo);
     c->unit_info = (int32_t*)(w + p.off_uinfo);
+    c->unit_counter = (uint32_t*)(w + p.off_ucnt);
+    c->attn_counter = (uint32_t*)(w + p.off_acnt);
     c->partials = (float*)(w + p.off_partials);
-    // control words start from a defined state
+    // control words and the self-resetting arrival counters start from zero
     if (hipMemset(c->chunk_info, 0, p.off_partials - p.off_cinfo) != hipSuccess) {
         delete c;
         return HATA_EHIP;
@@ -174,9 +178,8 @@ int hata_hamming_score(hata_ctx* ctx, const uint32_t* qcodes, const uint32_t* co
     if (rc != HATA_OK) return rc;
     if (!qcodes || !codes || !seq_len || !scores) return HATA_EINVAL;
     if (!aligned(qcodes, 4) || !aligned(codes, 16) || !aligned(scores, 2)) return HATA_EINVAL;
-    // the chunk histograms are written too (into the workspace): the launch is the very one the
-    // fused decode step makes
-    return hip_rc(hata::launch_score(ctx, qcodes, codes, seq_len, B, scores, true,
+    // the chunk histograms are written too (into the workspace), as in the fused decode step
+    return hip_rc(hata::launch_score(ctx, qcodes, codes, seq_len, B, scores, nullptr,
                                      (hipStream_t)stream));
 }
 
@@ -186,7 +189,7 @@ int hata_topk(hata_ctx* ctx, const uint16_t* scores, const int32_t* seq_len, con
     if (rc != HATA_OK) return rc;
     if (!scores || !seq_len || !k || !idx) return HATA_EINVAL;
     if (!aligned(scores, 2) || !aligned(idx, 4)) return HATA_EINVAL;
-    return hip_rc(hata::launch_topk(ctx, scores, seq_len, k, B, idx, false, (hipStream_t)stream));
+    return hip_rc(hata::launch_topk(ctx, scores, seq_len, k, B, idx, (hipStream_t)stream));
 }
 
 int hata_sparse_decode(hata_ctx* ctx, const void* q, const void* K, const void* V,
@@ -196,8 +199,8 @@ int hata_sparse_decode(hata_ctx* ctx, const void* q, const void* K, const void* 
     if (rc != HATA_OK) return rc;
     if (!q || !K || !V || !idx || !k || !out) return HATA_EINVAL;
     if (!aligned(q, 16) || !aligned(K, 16) || !aligned(V, 16) || !aligned(out, 2)) return HATA_EINVAL;
-    return hip_rc(hata::launch_attention(ctx, false, q, K, V, idx, k, B, sm_scale, out, out_f32,
-                                         (hipStream_t)stream));
+    return hip_rc(hata::launch_attention(ctx, 0, q, K, V, const_cast<int32_t*>(idx), k, nullptr, B,
+                                         sm_scale, out, out_f32, (hipStream_t)stream));
 }
 
 int hata_dense_decode(hata_ctx* ctx, const void* q, const void* K, const void* V,
@@ -207,8 +210,8 @@ int hata_dense_decode(hata_ctx* ctx, const void* q, const void* K, const void* V
     if (rc != HATA_OK) return rc;
     if (!q || !K || !V || !seq_len || !out) return HATA_EINVAL;
     if (!aligned(q, 16) || !aligned(K, 16) || !aligned(V, 16) || !aligned(out, 2)) return HATA_EINVAL;
-    return hip_rc(hata::launch_attention(ctx, true, q, K, V, nullptr, seq_len, B, sm_scale, out,
-                                         out_f32, (hipStream_t)stream));
+    return hip_rc(hata::launch_attention(ctx, 1, q, K, V, nullptr, seq_len, seq_len, B, sm_scale,
+                                         out, out_f32, (hipStream_t)stream));
 }
 
 int hata_decode_step(hata_ctx* ctx, const void* q, const void* K, const void* V, const float* W_H,
@@ -225,14 +228,12 @@ int hata_decode_step(hata_ctx* ctx, const void* q, const void* K, const void* V,
     hipError_t e = hata::launch_encode_vectors(ctx, q, ctx->qcodes, append ? K : nullptr, seq_len,
                                                nullptr, 1, 1, codes, W_H, B, s);
     if (e != hipSuccess) return HATA_EHIP;
-    // Hamming distances of every cached code (the new one included) + chunk histograms
-    e = hata::launch_score(ctx, ctx->qcodes, codes, seq_len, B, ctx->scores, true, s);
+    // Hamming distances of every cached code (the new one included), chunk histograms, and --
+    // by the last workgroup of each unit -- the selection threshold and chunk offsets
+    e = hata::launch_score(ctx, ctx->qcodes, codes, seq_len, B, ctx->scores, k, s);
     if (e != hipSuccess) return HATA_EHIP;
-    // TopK(S, N)
-    e = hata::launch_topk(ctx, ctx->scores, seq_len, k, B, ctx->idx, true, s);
-    if (e != hipSuccess) return HATA_EHIP;
-    // attention over the selected rows, gather fused
-    e = hata::launch_attention(ctx, false, q, K, V, ctx->idx, k, B, sm_scale, out, out_f32, s);
+    // TopK(S, N) compaction fused with the attention over the selected rows (gather fused too)
+    e = hata::launch_attention(ctx, 2, q, K, V, ctx->idx, k, seq_len, B, sm_scale, out, out_f32, s);
     return hip_rc(e);
 }
 

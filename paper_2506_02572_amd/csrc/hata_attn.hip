@@ -2,13 +2,23 @@
 // the gather fused into the attention kernel; Eq. 2 third line, scale of Eq. 1), and the
 // dense variant over the whole cache (Eq. 1) that serves as the comparison baseline.
 //
+// One kernel template, three row sources:
+//   ROWS_IDX     rows come from an index list in memory            (hata_sparse_decode)
+//   ROWS_DENSE   rows 0 .. seq_len-1                               (hata_dense_decode)
+//   ROWS_SELECT  rows are selected on the fly from the stored scores, the unit threshold and
+//                the per-chunk offsets (ordered compaction of just the chunks that hold this
+//                workgroup's slice of the index list); the index list is written as a
+//                by-product                                         (hata_decode_step)
+//
 // Split over the rows: every workgroup handles a slice of a unit's rows for HT query heads of
 // the group at once (each K/V row is read once for all of them), keeps an online-softmax
-// state per wave, and writes one partial (max, sum, weighted V) per query head; a small merge
-// kernel combines the partials.  A row is 256 B = 16 lanes x 128-bit, so a wave reads four
-// whole rows per load instruction.  bf16 inputs, fp32 softmax and accumulation.
+// state per wave, and writes one partial (max, sum, weighted V) per query head; the last
+// workgroup of a (unit, head tile) to finish merges the partials and writes the output, so no
+// separate merge launch is needed.  A row is 256 B = 16 lanes x 128-bit, so a wave reads
+// four whole rows per load instruction.  bf16 inputs, fp32 softmax and accumulation.
 #include "hata_device.h"
 #include "hata_internal.h"
+#include "hata_select.h"
 
 namespace hata {
 
@@ -20,44 +30,138 @@ __device__ __forceinline__ float dot2_bf16(uint32_t a, uint32_t b, float c) {
 }
 
 #define HATA_NEG_INF (-__builtin_huge_valf())
-
 // partial layout per (query head, split): [0] = running max (log2 domain), [1] = sum, [2..2+d) = acc
 #define HATA_PSTRIDE (HATA_D + 2)
+#define HATA_MAX_ROWS_PER_WG 256
+
+enum { ROWS_IDX = 0, ROWS_DENSE = 1, ROWS_SELECT = 2 };
+
+struct AttnArgs {
+    const uint16_t* q;
+    const uint16_t* K;
+    const uint16_t* V;
+    const int32_t* idx_in;      // ROWS_IDX
+    int32_t* idx_out;           // ROWS_SELECT
+    const int32_t* count_src;   // ROWS_IDX: k[B]; ROWS_DENSE: seq_len[B]
+    const uint16_t* scores;     // ROWS_SELECT ...
+    const int32_t* seq_len;
+    const int32_t* chunk_info;
+    const int32_t* unit_info;
+    int chunk, n_chunks;
+    float* partials;
+    uint32_t* counter;
+    uint16_t* out;
+    float* out_f32;
+    int Hq, Hkv, G, L_cap, k_max, rows_per_wg, n_splits;
+    int64_t sb, sh, sn;
+    float scale_log2;
+};
+
+__device__ __forceinline__ float block_reduce_max_256(float v, float* lds4) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+    if ((threadIdx.x & 63) == 0) lds4[threadIdx.x >> 6] = v;
+    __syncthreads();
+    v = fmaxf(fmaxf(lds4[0], lds4[1]), fmaxf(lds4[2], lds4[3]));
+    __syncthreads();
+    return v;
+}
+__device__ __forceinline__ float block_reduce_sum_256(float v, float* lds4) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    if ((threadIdx.x & 63) == 0) lds4[threadIdx.x >> 6] = v;
+    __syncthreads();
+    v = lds4[0] + lds4[1] + lds4[2] + lds4[3];
+    __syncthreads();
+    return v;
+}
 
 // grid = (splits, Hkv * (G / HT), B); 256 threads = 4 waves; lane = (row group rg = lane / 16,
 // sub = lane % 16 -> elements [8 sub, 8 sub + 8) of a row).
-template <int HT, bool DENSE>
-__global__ __launch_bounds__(256) void attn_partial_kernel(
-    const uint16_t* __restrict__ q, const uint16_t* __restrict__ K,
-    const uint16_t* __restrict__ V, const int32_t* __restrict__ idx,
-    const int32_t* __restrict__ count_src, float* __restrict__ partials,
-    int Hq, int Hkv, int G, int L_cap, int k_max, int rows_per_wg, int n_splits,
-    int64_t sb, int64_t sh, int64_t sn, float scale_log2) {
+template <int HT, int MODE>
+__global__ __launch_bounds__(256) void attn_kernel(const AttnArgs a) {
     __shared__ float sm_m[4][HT];
     __shared__ float sm_l[4][HT];
     __shared__ float sm_acc[4][HT][HATA_D];
+    __shared__ int s_rows[MODE == ROWS_SELECT ? HATA_MAX_ROWS_PER_WG : 1];
+    __shared__ uint32_t scan4[4];
+    __shared__ float red4[4];
+    __shared__ int s_clo, s_chi, s_last;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int sub = lane & 15, rg = lane >> 4;
     const int split = blockIdx.x;
-    const int tiles_per_group = G / HT;
-    const int h = blockIdx.y / tiles_per_group;
-    const int ht = blockIdx.y % tiles_per_group;
+    const int tiles = a.G / HT;
+    const int h = blockIdx.y / tiles;
+    const int ht = blockIdx.y % tiles;
     const int b = blockIdx.z;
-    const int count = DENSE ? clampi(count_src[b], 0, L_cap) : clampi(count_src[b], 0, k_max);
-    const int row_begin = split * rows_per_wg;
-    if (row_begin >= count) return;
-    const int row_end = min(row_begin + rows_per_wg, count);
-    const int64_t u = (int64_t)b * Hkv + h;
-    const int hq0 = h * G + ht * HT;
-    const uint16_t* Kb = K + b * sb + h * sh;
-    const uint16_t* Vb = V + b * sb + h * sh;
-    const int32_t* ip = DENSE ? nullptr : idx + u * k_max;
+    const int64_t u = (int64_t)b * a.Hkv + h;
+    const int hq0 = h * a.G + ht * HT;
+    int count;
+    if (MODE == ROWS_DENSE) count = clampi(a.count_src[b], 0, a.L_cap);
+    else if (MODE == ROWS_IDX) count = clampi(a.count_src[b], 0, a.k_max);
+    else count = clampi(a.unit_info[u * 2 + 1], 0, a.k_max);
+    const int row_begin = split * a.rows_per_wg;
+    if (MODE == ROWS_SELECT && ht == 0) {
+        // slots of the index list past the selected count hold -1
+        const int p0 = max(count, row_begin), p1 = min(row_begin + a.rows_per_wg, a.k_max);
+        for (int p = p0 + tid; p < p1; p += 256) a.idx_out[u * a.k_max + p] = -1;
+    }
+    if (row_begin >= count) {
+        if (count == 0 && split == 0) {  // no row at all: the output is zero
+            for (int i = tid; i < HT * HATA_D; i += 256) {
+                const int64_t o = ((int64_t)b * a.Hq + hq0) * HATA_D + i;
+                a.out[o] = 0;
+                if (a.out_f32) a.out_f32[o] = 0.f;
+            }
+        }
+        return;
+    }
+    const int row_end = min(row_begin + a.rows_per_wg, count);
+    const uint16_t* Kb = a.K + b * a.sb + h * a.sh;
+    const uint16_t* Vb = a.V + b * a.sb + h * a.sh;
+    const int32_t* ip = (MODE == ROWS_IDX) ? a.idx_in + u * a.k_max : nullptr;
+
+    if constexpr (MODE == ROWS_SELECT) {
+        // ordered compaction of the chunks that hold positions [row_begin, row_end)
+        const int L = clampi(a.seq_len[b], 0, a.L_cap);
+        const int nc = (L + a.chunk - 1) / a.chunk;
+        const int T = a.unit_info[u * 2 + 0];
+        const int32_t* ci = a.chunk_info + u * (a.n_chunks + 1) * 2;
+        if (tid == 0) { s_clo = nc; s_chi = -1; }
+        __syncthreads();
+        for (int c = tid; c < nc; c += 256) {
+            const int o0 = ci[2 * c], o1 = ci[2 * c + 2];
+            if (o0 < row_end && o1 > row_begin) { atomicMin(&s_clo, c); atomicMax(&s_chi, c); }
+        }
+        __syncthreads();
+        const int c_lo = s_clo, c_hi = s_chi;
+        const uint16_t* sp = a.scores + u * a.L_cap;
+        int32_t* io = a.idx_out + u * a.k_max;
+        for (int c = c_lo; c <= c_hi; ++c) {
+            const int off = ci[2 * c], take = ci[2 * c + 1];
+            if (ci[2 * c + 2] == off) continue;
+            const int base = c * a.chunk;
+            const int end = min(base + a.chunk, L);
+            uint32_t run_lt = 0, run_eq = 0;
+            for (int n0 = base; n0 < end; n0 += 1024) {
+                if (off + (int)run_lt + (int)min(run_eq, (uint32_t)take) >= row_end) break;
+                compact_block_1024(sp, n0, end, T, off, take, run_lt, run_eq, scan4,
+                                   [&](int pos, int n) {
+                                       if (pos >= row_begin && pos < row_end) {
+                                           s_rows[pos - row_begin] = n;
+                                           if (ht == 0) io[pos] = n;
+                                       }
+                                   });
+            }
+        }
+        __syncthreads();
+    }
 
     // this lane's 8 query elements of each head, kept as packed bf16 pairs
     uint32_t qr[HT][4];
 #pragma unroll
     for (int g = 0; g < HT; ++g) {
-        uint4 v = *reinterpret_cast<const uint4*>(q + ((int64_t)b * Hq + hq0 + g) * HATA_D + sub * 8);
+        const uint4 v = *reinterpret_cast<const uint4*>(a.q + ((int64_t)b * a.Hq + hq0 + g) * HATA_D + sub * 8);
         qr[g][0] = v.x; qr[g][1] = v.y; qr[g][2] = v.z; qr[g][3] = v.w;
     }
     float m_run[HT], l_run[HT], acc[HT][8];
@@ -77,12 +181,16 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(
             const int row = tile + it * 16 + wave * 4 + rg;
             ok[it] = row < row_end;
             int n = 0;
-            if (ok[it]) n = DENSE ? row : ip[row];
-            ok[it] = ok[it] && n >= 0 && n < L_cap;
+            if (ok[it]) {
+                if (MODE == ROWS_DENSE) n = row;
+                else if (MODE == ROWS_IDX) n = ip[row];
+                else n = s_rows[row - row_begin];
+            }
+            ok[it] = ok[it] && n >= 0 && n < a.L_cap;
             kv[it] = make_uint4(0, 0, 0, 0);
             vv[it] = make_uint4(0, 0, 0, 0);
             if (ok[it]) {
-                const int64_t o = (int64_t)n * sn + sub * 8;
+                const int64_t o = (int64_t)n * a.sn + sub * 8;
                 kv[it] = *reinterpret_cast<const uint4*>(Kb + o);
                 vv[it] = *reinterpret_cast<const uint4*>(Vb + o);
             }
@@ -103,7 +211,7 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(
                 d += __shfl_xor(d, 2, 64);
                 d += __shfl_xor(d, 4, 64);
                 d += __shfl_xor(d, 8, 64);
-                s[it][g] = ok[it] ? d * scale_log2 : HATA_NEG_INF;
+                s[it][g] = ok[it] ? d * a.scale_log2 : HATA_NEG_INF;
                 m_tile[g] = fmaxf(m_tile[g], s[it][g]);
             }
         }
@@ -155,87 +263,108 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(
         }
     }
     __syncthreads();
-    // combine the four waves and write the partial: thread -> (head, channel)
+    const int ns = (count + a.rows_per_wg - 1) / a.rows_per_wg;  // workgroups that contribute
+    // combine the four waves: thread -> (head, channel)
     for (int i = tid; i < HT * HATA_D; i += 256) {
         const int g = i / HATA_D, ch = i % HATA_D;
         const float m0 = sm_m[0][g], m1 = sm_m[1][g], m2 = sm_m[2][g], m3 = sm_m[3][g];
         const float M = fmaxf(fmaxf(m0, m1), fmaxf(m2, m3));
-        float a = 0.f, l = 0.f;
+        float av = 0.f, l = 0.f;
         if (M != HATA_NEG_INF) {
             const float f0 = exp2f(m0 - M), f1 = exp2f(m1 - M), f2 = exp2f(m2 - M), f3 = exp2f(m3 - M);
-            a = f0 * sm_acc[0][g][ch] + f1 * sm_acc[1][g][ch] + f2 * sm_acc[2][g][ch] + f3 * sm_acc[3][g][ch];
+            av = f0 * sm_acc[0][g][ch] + f1 * sm_acc[1][g][ch] + f2 * sm_acc[2][g][ch] + f3 * sm_acc[3][g][ch];
             l = f0 * sm_l[0][g] + f1 * sm_l[1][g] + f2 * sm_l[2][g] + f3 * sm_l[3][g];
         }
-        float* pp = partials + (((int64_t)b * Hq + hq0 + g) * n_splits + split) * HATA_PSTRIDE;
-        pp[2 + ch] = a;
-        if (ch == 0) { pp[0] = M; pp[1] = l; }
-    }
-}
-
-// grid = B*Hq, 128 threads (one per channel)
-__global__ __launch_bounds__(128) void attn_merge_kernel(
-    const float* __restrict__ partials, const int32_t* __restrict__ count_src,
-    uint16_t* __restrict__ out, float* __restrict__ out_f32, int Hq, int count_cap,
-    int rows_per_wg, int n_splits) {
-    const int ch = threadIdx.x;
-    const int bh = blockIdx.x;
-    const int b = bh / Hq;
-    const int count = clampi(count_src[b], 0, count_cap);
-    const int ns = (count + rows_per_wg - 1) / rows_per_wg;
-    const float* pp = partials + (int64_t)bh * n_splits * HATA_PSTRIDE;
-    float M = HATA_NEG_INF;
-    for (int s = 0; s < ns; ++s) M = fmaxf(M, pp[s * HATA_PSTRIDE]);
-    float a = 0.f, l = 0.f;
-    if (M != HATA_NEG_INF) {
-        for (int s = 0; s < ns; ++s) {
-            const float f = exp2f(pp[s * HATA_PSTRIDE] - M);
-            a = fmaf(f, pp[s * HATA_PSTRIDE + 2 + ch], a);
-            l = fmaf(f, pp[s * HATA_PSTRIDE + 1], l);
+        if (ns == 1) {  // single slice: this is the result
+            const float o = l > 0.f ? av / l : 0.f;
+            const int64_t oo = ((int64_t)b * a.Hq + hq0 + g) * HATA_D + ch;
+            a.out[oo] = (uint16_t)f32_to_bf16(o);
+            if (a.out_f32) a.out_f32[oo] = o;
+        } else {
+            float* pp = a.partials + (((int64_t)b * a.Hq + hq0 + g) * a.n_splits + split) * HATA_PSTRIDE;
+            st_dev(pp + 2 + ch, av);
+            if (ch == 0) { st_dev(pp, M); st_dev(pp + 1, l); }
         }
     }
-    const float o = l > 0.f ? a / l : 0.f;
-    out[(int64_t)bh * HATA_D + ch] = (uint16_t)f32_to_bf16(o);
-    if (out_f32) out_f32[(int64_t)bh * HATA_D + ch] = o;
+    if (ns == 1) return;
+    // count the finished slices; the last workgroup merges them (partials are written with
+    // write-through stores and read back with device-coherent loads)
+    wait_stores();
+    __syncthreads();
+    if (tid == 0) {
+        uint32_t* cnt = a.counter + u * tiles + ht;
+        const uint32_t done = atomicAdd(cnt, 1u);
+        const int last = (done == (uint32_t)(ns - 1));
+        if (last) *cnt = 0;
+        s_last = last;
+    }
+    __syncthreads();
+    if (!s_last) return;
+    for (int g = 0; g < HT; ++g) {
+        const float* pp = a.partials + ((int64_t)b * a.Hq + hq0 + g) * a.n_splits * HATA_PSTRIDE;
+        float m_loc = HATA_NEG_INF;
+        for (int s2 = tid; s2 < ns; s2 += 256) m_loc = fmaxf(m_loc, ld_dev(pp + s2 * HATA_PSTRIDE));
+        const float M = block_reduce_max_256(m_loc, red4);
+        float l_loc = 0.f;
+        if (M != HATA_NEG_INF)
+            for (int s2 = tid; s2 < ns; s2 += 256)
+                l_loc += exp2f(ld_dev(pp + s2 * HATA_PSTRIDE) - M) * ld_dev(pp + s2 * HATA_PSTRIDE + 1);
+        const float Lsum = block_reduce_sum_256(l_loc, red4);
+        // threads 0..127 take even slices, 128..255 odd slices of channel tid % 128
+        const int ch = tid & 127, half = tid >> 7;
+        float av = 0.f;
+        if (M != HATA_NEG_INF)
+            for (int s2 = half; s2 < ns; s2 += 2)
+                av = fmaf(exp2f(ld_dev(pp + s2 * HATA_PSTRIDE) - M), ld_dev(pp + s2 * HATA_PSTRIDE + 2 + ch), av);
+        if (half == 1) sm_acc[0][0][ch] = av;
+        __syncthreads();
+        if (half == 0) {
+            av += sm_acc[0][0][ch];
+            const float o = Lsum > 0.f ? av / Lsum : 0.f;
+            const int64_t oo = ((int64_t)b * a.Hq + hq0 + g) * HATA_D + ch;
+            a.out[oo] = (uint16_t)f32_to_bf16(o);
+            if (a.out_f32) a.out_f32[oo] = o;
+        }
+        __syncthreads();
+    }
 }
 
 template <int HT>
-static void launch_partial(const hata_ctx* c, bool dense, const void* q, const void* K,
-                           const void* V, const int32_t* idx, const int32_t* count_src, int B,
-                           float scale_log2, hipStream_t s) {
-    const hata_config& f = c->cfg;
-    const int rows = dense ? c->dense_rows : c->sparse_rows;
-    const int splits = dense ? c->dense_splits : c->sparse_splits;
-    const dim3 grid(splits, f.Hkv * (c->G / HT), B);
-    if (dense)
-        hipLaunchKernelGGL((attn_partial_kernel<HT, true>), grid, dim3(256), 0, s,
-                           (const uint16_t*)q, (const uint16_t*)K, (const uint16_t*)V, idx,
-                           count_src, c->partials, f.Hq, f.Hkv, c->G, f.L_cap, f.k_max, rows,
-                           splits, f.kv_stride_b, f.kv_stride_h, f.kv_stride_n, scale_log2);
-    else
-        hipLaunchKernelGGL((attn_partial_kernel<HT, false>), grid, dim3(256), 0, s,
-                           (const uint16_t*)q, (const uint16_t*)K, (const uint16_t*)V, idx,
-                           count_src, c->partials, f.Hq, f.Hkv, c->G, f.L_cap, f.k_max, rows,
-                           splits, f.kv_stride_b, f.kv_stride_h, f.kv_stride_n, scale_log2);
+static void launch_mode(int mode, const AttnArgs& a, dim3 grid, hipStream_t s) {
+    switch (mode) {
+        case ROWS_DENSE: hipLaunchKernelGGL((attn_kernel<HT, ROWS_DENSE>), grid, dim3(256), 0, s, a); break;
+        case ROWS_SELECT: hipLaunchKernelGGL((attn_kernel<HT, ROWS_SELECT>), grid, dim3(256), 0, s, a); break;
+        default: hipLaunchKernelGGL((attn_kernel<HT, ROWS_IDX>), grid, dim3(256), 0, s, a); break;
+    }
 }
 
-hipError_t launch_attention(const hata_ctx* c, bool dense, const void* q, const void* K,
-                            const void* V, const int32_t* idx, const int32_t* count_src, int B,
-                            float sm_scale, void* out, float* out_f32, hipStream_t s) {
+// mode 0: rows from idx (count from k); 1: dense (count from seq_len); 2: select on the fly
+// from the workspace's scores / thresholds (idx is written)
+hipError_t launch_attention(const hata_ctx* c, int mode, const void* q, const void* K,
+                            const void* V, int32_t* idx, const int32_t* count_src,
+                            const int32_t* seq_len, int B, float sm_scale, void* out,
+                            float* out_f32, hipStream_t s) {
     const hata_config& f = c->cfg;
-    const float scale_log2 = sm_scale * 1.4426950408889634f;
+    AttnArgs a;
+    a.q = (const uint16_t*)q; a.K = (const uint16_t*)K; a.V = (const uint16_t*)V;
+    a.idx_in = idx; a.idx_out = idx; a.count_src = count_src;
+    a.scores = c->scores; a.seq_len = seq_len; a.chunk_info = c->chunk_info;
+    a.unit_info = c->unit_info; a.chunk = c->chunk; a.n_chunks = c->n_chunks;
+    a.partials = c->partials; a.counter = c->attn_counter;
+    a.out = (uint16_t*)out; a.out_f32 = out_f32;
+    a.Hq = f.Hq; a.Hkv = f.Hkv; a.G = c->G; a.L_cap = f.L_cap; a.k_max = f.k_max;
+    const bool dense = (mode == ROWS_DENSE);
+    a.rows_per_wg = dense ? c->dense_rows : c->sparse_rows;
+    a.n_splits = dense ? c->dense_splits : c->sparse_splits;
+    a.sb = f.kv_stride_b; a.sh = f.kv_stride_h; a.sn = f.kv_stride_n;
+    a.scale_log2 = sm_scale * 1.4426950408889634f;
     switch (c->HT) {
-        case 8: launch_partial<8>(c, dense, q, K, V, idx, count_src, B, scale_log2, s); break;
-        case 5: launch_partial<5>(c, dense, q, K, V, idx, count_src, B, scale_log2, s); break;
-        case 4: launch_partial<4>(c, dense, q, K, V, idx, count_src, B, scale_log2, s); break;
-        case 2: launch_partial<2>(c, dense, q, K, V, idx, count_src, B, scale_log2, s); break;
-        default: launch_partial<1>(c, dense, q, K, V, idx, count_src, B, scale_log2, s); break;
+        case 8: launch_mode<8>(mode, a, dim3(a.n_splits, f.Hkv * (c->G / 8), B), s); break;
+        case 5: launch_mode<5>(mode, a, dim3(a.n_splits, f.Hkv * (c->G / 5), B), s); break;
+        case 4: launch_mode<4>(mode, a, dim3(a.n_splits, f.Hkv * (c->G / 4), B), s); break;
+        case 2: launch_mode<2>(mode, a, dim3(a.n_splits, f.Hkv * (c->G / 2), B), s); break;
+        default: launch_mode<1>(mode, a, dim3(a.n_splits, f.Hkv * c->G, B), s); break;
     }
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(attn_merge_kernel, dim3(B * f.Hq), dim3(128), 0, s, c->partials, count_src,
-                       (uint16_t*)out, out_f32, f.Hq, dense ? f.L_cap : f.k_max,
-                       dense ? c->dense_rows : c->sparse_rows,
-                       dense ? c->dense_splits : c->sparse_splits);
     return hipGetLastError();
 }
 

@@ -10,7 +10,10 @@
 namespace hata {
 
 // Bit j of a code goes to word j/32, bit position j%32; bit = (projection >= 0).
-__global__ __launch_bounds__(256) void encode_vectors_kernel(
+// 1024 threads = (column j, part p): every thread sums 128 / parts channels with all its W_H
+// loads in flight at once, so the kernel costs about one memory round trip.
+#define HATA_ENC_THREADS 1024
+__global__ __launch_bounds__(HATA_ENC_THREADS) void encode_vectors_kernel(
     const uint16_t* __restrict__ q, uint32_t* __restrict__ qcodes, int nq_blocks,
     const uint16_t* __restrict__ K, const int32_t* __restrict__ start,
     const int32_t* __restrict__ n_new, int max_new, int from_seq_len,
@@ -18,7 +21,7 @@ __global__ __launch_bounds__(256) void encode_vectors_kernel(
     int Hq, int Hkv, int G, int r, int Wd, int L_cap,
     int64_t sb, int64_t sh, int64_t sn) {
     __shared__ float xs[HATA_D];
-    __shared__ double part[256];
+    __shared__ double part[HATA_ENC_THREADS];
     const int tid = threadIdx.x;
     int blk = blockIdx.x;
     const uint16_t* x;
@@ -42,18 +45,25 @@ __global__ __launch_bounds__(256) void encode_vectors_kernel(
         x = K + b * sb + h * sh + n * sn;
         dst = codes + ((int64_t)u * L_cap + n) * Wd;
     }
+    const int parts = HATA_ENC_THREADS / r;       // r <= 256 -> parts >= 4
+    const int per = (HATA_D + parts - 1) / parts; // channels per part (<= 32)
+    const int j = tid % r, p = tid / r;
+    // issue the weight loads before waiting for x
+    float wv[32];
+    const int i0 = p * per;
+    const bool active = p < parts;
+    {
+        const float* w = W_H + (int64_t)h * HATA_D * r + j;
+#pragma unroll
+        for (int t = 0; t < 32; ++t)
+            wv[t] = (active && t < per && i0 + t < HATA_D) ? w[(int64_t)(i0 + t) * r] : 0.f;
+    }
     if (tid < HATA_D) xs[tid] = __uint_as_float((uint32_t)x[tid] << 16);
     __syncthreads();
-    const int parts = 256 / r;                    // r <= 256
-    const int per = (HATA_D + parts - 1) / parts; // channels per part
-    const int j = tid % r, p = tid / r;
     double acc = 0.0;
-    if (p < parts) {
-        const float* w = W_H + (int64_t)h * HATA_D * r + j;
-        const int i0 = p * per;
-        const int i1 = min(HATA_D, i0 + per);
-        for (int i = i0; i < i1; ++i) acc += (double)xs[i] * (double)w[(int64_t)i * r];
-    }
+#pragma unroll
+    for (int t = 0; t < 32; ++t)
+        if (t < per && i0 + t < HATA_D) acc += (double)xs[i0 + t] * (double)wv[t];
     part[tid] = acc;
     __syncthreads();
     bool bit = false;
@@ -129,7 +139,7 @@ hipError_t launch_encode_vectors(const hata_ctx* c, const void* q, uint32_t* qco
     const int nq = q ? B * f.Hq : 0;
     const int nk = K ? B * f.Hkv * max_new : 0;
     if (nq + nk == 0) return hipSuccess;
-    hipLaunchKernelGGL(encode_vectors_kernel, dim3(nq + nk), dim3(256), 0, s,
+    hipLaunchKernelGGL(encode_vectors_kernel, dim3(nq + nk), dim3(HATA_ENC_THREADS), 0, s,
                        (const uint16_t*)q, qcodes, nq, (const uint16_t*)K, start, n_new,
                        max_new > 0 ? max_new : 1, from_seq_len, codes, W_H, f.Hq, f.Hkv, c->G,
                        f.r, c->Wd, f.L_cap, f.kv_stride_b, f.kv_stride_h, f.kv_stride_n);

@@ -23,8 +23,10 @@ struct hata_ctx {
     uint16_t* scores;      // [B_max, Hkv, L_cap]
     int32_t* idx;          // [B_max, Hkv, k_max]
     uint16_t* chunk_hist;  // [B_max*Hkv, n_chunks, NBP]
-    int32_t* chunk_info;   // [B_max*Hkv, n_chunks, 2] = {output offset, ties taken}
+    int32_t* chunk_info;   // [B_max*Hkv, n_chunks + 1, 2] = {output offset, ties taken}
     int32_t* unit_info;    // [B_max*Hkv, 2] = {threshold, selected count}
+    uint32_t* unit_counter;  // [B_max*Hkv] scored chunks of a unit (self-resetting)
+    uint32_t* attn_counter;  // [B_max*Hq] finished attention slices (self-resetting)
     float* partials;       // [B_max*Hq, max(sparse_splits, dense_splits), d + 2]
 };
 
@@ -39,12 +41,14 @@ hipError_t launch_encode_bulk(const hata_ctx* c, const void* K, const float* W_H
                               const int32_t* start, const int32_t* n_new, int B, int max_new,
                               uint32_t* codes, hipStream_t s);
 hipError_t launch_score(const hata_ctx* c, const uint32_t* qcodes, const uint32_t* codes,
-                        const int32_t* seq_len, int B, uint16_t* scores, bool with_hist,
+                        const int32_t* seq_len, int B, uint16_t* scores, const int32_t* kbud,
                         hipStream_t s);
 hipError_t launch_topk(const hata_ctx* c, const uint16_t* scores, const int32_t* seq_len,
-                       const int32_t* k, int B, int32_t* idx, bool have_hist, hipStream_t s);
-hipError_t launch_attention(const hata_ctx* c, bool dense, const void* q, const void* K,
-                            const void* V, const int32_t* idx, const int32_t* count_src, int B,
-                            float sm_scale, void* out, float* out_f32, hipStream_t s);
+                       const int32_t* k, int B, int32_t* idx, hipStream_t s);
+// mode: 0 = rows from idx, 1 = dense, 2 = select on the fly (writes idx)
+hipError_t launch_attention(const hata_ctx* c, int mode, const void* q, const void* K,
+                            const void* V, int32_t* idx, const int32_t* count_src,
+                            const int32_t* seq_len, int B, float sm_scale, void* out,
+                            float* out_f32, hipStream_t s);
 
 }  // namespace hata

@@ -6,8 +6,12 @@
 // the G query codes are wave-uniform and sit in scalar registers.  Optionally the
 // workgroup also histograms its chunk's scores in LDS and writes the histogram out, which
 // is what the selection stage needs (a counting select over the <= G*r+1 score values).
+// In the fused decode step (SELECT = true) the workgroup that scores the LAST chunk of a unit
+// to finish goes on to compute the unit's selection threshold and the per-chunk output
+// offsets, so no separate launch is needed for that.
 #include "hata_device.h"
 #include "hata_internal.h"
+#include "hata_select.h"
 
 namespace hata {
 
@@ -36,21 +40,65 @@ __device__ __forceinline__ CodeVec<WD> load_code(const uint32_t* p) {
     return c;
 }
 
+// LDS histogram (NB words) -> the chunk's row of uint16 counts, two bins per write-through store
+__device__ __forceinline__ void write_chunk_hist(uint16_t* hp, const uint32_t* hist, int NB, int NBP) {
+    uint32_t* hp32 = reinterpret_cast<uint32_t*>(hp);
+    for (int i = threadIdx.x; i < NBP / 2; i += 256) {
+        const uint32_t lo = (2 * i < NB) ? hist[2 * i] : 0u;
+        const uint32_t hi = (2 * i + 1 < NB) ? hist[2 * i + 1] : 0u;
+        st_dev(hp32 + i, lo | (hi << 16));
+    }
+}
+
 // grid = (n_chunks, Hkv, B), 256 threads.  WD words per code, G heads per group.
-template <int WD, int G>
+// Tail of a scoring workgroup in the fused step: publish the chunk histogram, count the unit's
+// finished chunks, and let the last one compute the unit's threshold.  `hist` (NB words of LDS)
+// is reused as the total histogram.
+__device__ __forceinline__ void finish_unit(
+    int64_t u, int nc, int keff, const uint16_t* __restrict__ chunk_hist_u, int NB, int NBP,
+    int n_chunks, int32_t* __restrict__ chunk_info, int32_t* __restrict__ unit_info,
+    uint32_t* __restrict__ unit_counter, uint32_t* hist, ThresholdLds& S, int* flag) {
+    wait_stores();    // this thread's write-through histogram stores have completed
+    __syncthreads();  // ... and so have those of the whole workgroup
+    if (threadIdx.x == 0) {
+        const uint32_t done = atomicAdd(&unit_counter[u], 1u);
+        const int last = (done == (uint32_t)(nc - 1));
+        if (last) unit_counter[u] = 0;  // ready for the next launch
+        *flag = last;
+    }
+    __syncthreads();
+    if (!*flag) return;
+    // the other workgroups' histograms are read with device-coherent loads
+    unit_threshold<true>(chunk_hist_u, nc, keff, NB, NBP, chunk_info + u * (n_chunks + 1) * 2,
+                   unit_info + u * 2, hist, S);
+}
+
+template <int WD, int G, bool SELECT>
 __global__ __launch_bounds__(256) void score_kernel(
     const uint32_t* __restrict__ qcodes, const uint32_t* __restrict__ codes,
     const int32_t* __restrict__ seq_len, uint16_t* __restrict__ scores,
     uint16_t* __restrict__ chunk_hist, int Hq, int Hkv, int L_cap, int chunk, int n_chunks,
-    int NB, int NBP) {
+    int NB, int NBP, const int32_t* __restrict__ kbud, int k_max,
+    int32_t* __restrict__ chunk_info, int32_t* __restrict__ unit_info,
+    uint32_t* __restrict__ unit_counter) {
     extern __shared__ uint32_t hist[];  // NB bins when chunk_hist != nullptr
+    __shared__ ThresholdLds S;
+    __shared__ int last_flag;
     const int tid = threadIdx.x;
     const int c = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
     const int L = clampi(seq_len[b], 0, L_cap);
     const int base = c * chunk;
-    if (base >= L) return;
-    const int end = min(base + chunk, L);
     const int64_t u = (int64_t)b * Hkv + h;
+    if (base >= L) {
+        if (SELECT && L == 0 && c == 0 && tid == 0) {  // empty sequence: nothing selected
+            unit_info[u * 2 + 0] = 0;
+            unit_info[u * 2 + 1] = 0;
+            chunk_info[u * (n_chunks + 1) * 2 + 0] = 0;
+            chunk_info[u * (n_chunks + 1) * 2 + 1] = 0;
+        }
+        return;
+    }
+    const int end = min(base + chunk, L);
     const bool do_hist = chunk_hist != nullptr;
     if (do_hist) {
         for (int i = tid; i < NB; i += 256) hist[i] = 0;
@@ -90,8 +138,12 @@ __global__ __launch_bounds__(256) void score_kernel(
     }
     if (do_hist) {
         __syncthreads();
-        uint16_t* hp = chunk_hist + (u * n_chunks + c) * NBP;
-        for (int i = tid; i < NB; i += 256) hp[i] = (uint16_t)hist[i];
+        write_chunk_hist(chunk_hist + (u * n_chunks + c) * NBP, hist, NB, NBP);
+    }
+    if constexpr (SELECT) {
+        const int keff = min(clampi(kbud[b], 0, k_max), L);
+        finish_unit(u, (L + chunk - 1) / chunk, keff, chunk_hist + u * n_chunks * NBP, NB, NBP,
+                    n_chunks, chunk_info, unit_info, unit_counter, hist, S, &last_flag);
     }
 }
 
@@ -100,19 +152,29 @@ __global__ __launch_bounds__(256) void score_kernel_generic(
     const uint32_t* __restrict__ qcodes, const uint32_t* __restrict__ codes,
     const int32_t* __restrict__ seq_len, uint16_t* __restrict__ scores,
     uint16_t* __restrict__ chunk_hist, int Hq, int Hkv, int G, int WD, int L_cap, int chunk,
-    int n_chunks, int NB, int NBP) {
+    int n_chunks, int NB, int NBP, int select, const int32_t* __restrict__ kbud, int k_max,
+    int32_t* __restrict__ chunk_info, int32_t* __restrict__ unit_info,
+    uint32_t* __restrict__ unit_counter) {
     extern __shared__ uint32_t hist[];
     __shared__ uint32_t qc[16 * 8];
+    __shared__ ThresholdLds S;
+    __shared__ int last_flag;
     const int tid = threadIdx.x;
     const int c = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
     const int L = clampi(seq_len[b], 0, L_cap);
     const int base = c * chunk;
-    if (base >= L) return;
-    const int end = min(base + chunk, L);
     const int64_t u = (int64_t)b * Hkv + h;
-    const bool do_hist = chunk_hist != nullptr;
-    if (do_hist)
-        for (int i = tid; i < NB; i += 256) hist[i] = 0;
+    if (base >= L) {
+        if (select && L == 0 && c == 0 && tid == 0) {
+            unit_info[u * 2 + 0] = 0;
+            unit_info[u * 2 + 1] = 0;
+            chunk_info[u * (n_chunks + 1) * 2 + 0] = 0;
+            chunk_info[u * (n_chunks + 1) * 2 + 1] = 0;
+        }
+        return;
+    }
+    const int end = min(base + chunk, L);
+    for (int i = tid; i < NB; i += 256) hist[i] = 0;
     if (tid < G * WD) qc[tid] = qcodes[((int64_t)b * Hq + (int64_t)h * G) * WD + tid];
     __syncthreads();
     const uint32_t* cp = codes + u * L_cap * WD;
@@ -124,45 +186,56 @@ __global__ __launch_bounds__(256) void score_kernel_generic(
             for (int g = 0; g < G; ++g) s += __popc(qc[g * WD + w] ^ kw);
         }
         sp[n] = (uint16_t)s;
-        if (do_hist) atomicAdd(&hist[s], 1u);
+        atomicAdd(&hist[s], 1u);
     }
-    if (do_hist) {
-        __syncthreads();
-        uint16_t* hp = chunk_hist + (u * n_chunks + c) * NBP;
-        for (int i = tid; i < NB; i += 256) hp[i] = (uint16_t)hist[i];
+    __syncthreads();
+    write_chunk_hist(chunk_hist + (u * n_chunks + c) * NBP, hist, NB, NBP);
+    if (select) {
+        const int keff = min(clampi(kbud[b], 0, k_max), L);
+        finish_unit(u, (L + chunk - 1) / chunk, keff, chunk_hist + u * n_chunks * NBP, NB, NBP,
+                    n_chunks, chunk_info, unit_info, unit_counter, hist, S, &last_flag);
     }
 }
 
 template <int WD, int G>
 static void launch_t(const hata_ctx* c, const uint32_t* qcodes, const uint32_t* codes,
-                     const int32_t* seq_len, int B, uint16_t* scores, uint16_t* hist,
+                     const int32_t* seq_len, int B, uint16_t* scores, const int32_t* kbud,
                      hipStream_t s) {
     const hata_config& f = c->cfg;
-    const size_t lds = hist ? (size_t)c->NB * 4 : 0;
-    hipLaunchKernelGGL((score_kernel<WD, G>), dim3(c->n_chunks, f.Hkv, B), dim3(256), lds, s,
-                       qcodes, codes, seq_len, scores, hist, f.Hq, f.Hkv, f.L_cap, c->chunk,
-                       c->n_chunks, c->NB, c->NBP);
+    const size_t lds = (size_t)c->NB * 4;
+    const dim3 grid(c->n_chunks, f.Hkv, B);
+    if (kbud)
+        hipLaunchKernelGGL((score_kernel<WD, G, true>), grid, dim3(256), lds, s, qcodes, codes,
+                           seq_len, scores, c->chunk_hist, f.Hq, f.Hkv, f.L_cap, c->chunk,
+                           c->n_chunks, c->NB, c->NBP, kbud, f.k_max, c->chunk_info,
+                           c->unit_info, c->unit_counter);
+    else
+        hipLaunchKernelGGL((score_kernel<WD, G, false>), grid, dim3(256), lds, s, qcodes, codes,
+                           seq_len, scores, c->chunk_hist, f.Hq, f.Hkv, f.L_cap, c->chunk,
+                           c->n_chunks, c->NB, c->NBP, kbud, f.k_max, c->chunk_info,
+                           c->unit_info, c->unit_counter);
 }
 
+// kbud == nullptr: scores (+ chunk histograms) only.  kbud != nullptr: the fused-step variant,
+// which also leaves the unit thresholds and chunk offsets of the selection in the workspace.
 hipError_t launch_score(const hata_ctx* c, const uint32_t* qcodes, const uint32_t* codes,
-                        const int32_t* seq_len, int B, uint16_t* scores, bool with_hist,
+                        const int32_t* seq_len, int B, uint16_t* scores, const int32_t* kbud,
                         hipStream_t s) {
     const hata_config& f = c->cfg;
-    uint16_t* hist = with_hist ? c->chunk_hist : nullptr;
     const int key = c->Wd * 100 + c->G;
     switch (key) {
-#define HATA_CASE(WD, GG) case WD * 100 + GG: launch_t<WD, GG>(c, qcodes, codes, seq_len, B, scores, hist, s); break;
+#define HATA_CASE(WD, GG) case WD * 100 + GG: launch_t<WD, GG>(c, qcodes, codes, seq_len, B, scores, kbud, s); break;
         HATA_CASE(4, 1) HATA_CASE(4, 2) HATA_CASE(4, 4) HATA_CASE(4, 5) HATA_CASE(4, 8)
         HATA_CASE(8, 1) HATA_CASE(8, 2) HATA_CASE(8, 4) HATA_CASE(8, 5) HATA_CASE(8, 8)
         HATA_CASE(2, 1) HATA_CASE(2, 4) HATA_CASE(2, 8)
         HATA_CASE(1, 1) HATA_CASE(1, 4) HATA_CASE(1, 8)
 #undef HATA_CASE
-        default: {
-            const size_t lds = hist ? (size_t)c->NB * 4 : 0;
-            hipLaunchKernelGGL(score_kernel_generic, dim3(c->n_chunks, f.Hkv, B), dim3(256), lds,
-                               s, qcodes, codes, seq_len, scores, hist, f.Hq, f.Hkv, c->G, c->Wd,
-                               f.L_cap, c->chunk, c->n_chunks, c->NB, c->NBP);
-        }
+        default:
+            hipLaunchKernelGGL(score_kernel_generic, dim3(c->n_chunks, f.Hkv, B), dim3(256),
+                               (size_t)c->NB * 4, s, qcodes, codes, seq_len, scores, c->chunk_hist,
+                               f.Hq, f.Hkv, c->G, c->Wd, f.L_cap, c->chunk, c->n_chunks, c->NB,
+                               c->NBP, kbud ? 1 : 0, kbud, f.k_max, c->chunk_info, c->unit_info,
+                               c->unit_counter);
     }
     return hipGetLastError();
 }
