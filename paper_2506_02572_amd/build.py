@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libhata.so")
 SOURCES = ["hata_api.hip", "hata_encode.hip", "hata_score.hip", "hata_topk.hip", "hata_attn.hip"]
-HEADERS = ["hata_device.h", "hata_internal.h", os.path.join("..", "..", "include", "hata.h")]
+HEADERS = ["hata_device.h", "hata_internal.h", "hata_select.h", "hata_trace.h", os.path.join("..", "..", "include", "hata.h")]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
@@ -26,10 +26,12 @@ def stale() -> bool:
     return any(os.path.getmtime(d) > t for d in deps)
 
 
-def build(force: bool = True, verbose: bool = False) -> str:
+def build(force: bool = True, verbose: bool = False, trace: bool = False) -> str:
+    """trace=True adds the in-kernel timestamp hooks of hata_trace.h (tuning builds only)."""
     if not force and not stale():
         return LIB
-    cmd = [HIPCC] + FLAGS + [os.path.join(CSRC, s) for s in SOURCES] + ["-o", LIB]
+    extra = ["-DHATA_TRACE", "-fgpu-rdc"] if trace else []
+    cmd = [HIPCC] + FLAGS + extra + [os.path.join(CSRC, s) for s in SOURCES] + ["-o", LIB]
     if verbose:
         print(" ".join(cmd), flush=True)
     res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
@@ -42,5 +44,5 @@ def build(force: bool = True, verbose: bool = False) -> str:
 
 
 if __name__ == "__main__":
-    build(force=True, verbose=True)
+    build(force=True, verbose=True, trace="--trace" in sys.argv)
     print(LIB)

@@ -5,6 +5,14 @@
 #include <string.h>
 
 #include "hata_internal.h"
+#include "hata_trace.h"
+
+#ifdef HATA_TRACE
+__device__ unsigned long long g_hata_trace[64];
+extern "C" int hata_debug_trace(unsigned long long* host_out) {
+    return (int)hipMemcpyFromSymbol(host_out, HIP_SYMBOL(g_hata_trace), sizeof(unsigned long long) * 64);
+}
+#endif
 
 namespace {
 
@@ -13,7 +21,7 @@ inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
 struct Plan {
     int G, Wd, NB, NBP, chunk, n_chunks, HT, sparse_rows, sparse_splits, dense_rows, dense_splits;
-    size_t off_qcodes, off_scores, off_idx, off_hist, off_cinfo, off_uinfo, off_ucnt, off_acnt, off_partials, total;
+    size_t off_qcodes, off_scores, off_idx, off_hist, off_cinfo, off_uinfo, off_ucnt, off_acnt, off_uhist, off_partials, total;
 };
 
 int validate_config(const hata_config* f) {
@@ -43,9 +51,12 @@ int make_plan(const hata_config* f, Plan* p) {
     p->NB = p->G * f->r + 1;
     p->NBP = (p->NB + 7) / 8 * 8;
     const int64_t units = (int64_t)f->B_max * f->Hkv;
-    const int64_t target_wgs = 768;
-    int chunk = 8192;
+    // one scoring workgroup per CU at least, chunks of at most 4096 keys (larger only if the
+    // cache is so long that a unit would otherwise exceed 1024 chunks)
+    const int64_t target_wgs = 256;
+    int chunk = 4096;
     while (chunk > 1024 && units * ((f->L_cap + chunk - 1) / chunk) < target_wgs) chunk >>= 1;
+    while (chunk < 8192 && (f->L_cap + chunk - 1) / chunk > 1024) chunk <<= 1;
     p->chunk = chunk;
     p->n_chunks = (f->L_cap + chunk - 1) / chunk;
     if (p->n_chunks > 1024) return HATA_EUNSUPPORTED;  // L_cap above 8M rows
@@ -57,7 +68,7 @@ int make_plan(const hata_config* f, Plan* p) {
     p->sparse_rows = rows;
     p->sparse_splits = (f->k_max + rows - 1) / rows;
     int drows = 4096;
-    while (drows > 256 && attn_units * ((f->L_cap + drows - 1) / drows) < 1024) drows >>= 1;
+    while (drows > 512 && attn_units * ((f->L_cap + drows - 1) / drows) < 512) drows >>= 1;
     p->dense_rows = drows;
     p->dense_splits = (f->L_cap + drows - 1) / drows;
     const int max_splits = p->sparse_splits > p->dense_splits ? p->sparse_splits : p->dense_splits;
@@ -71,6 +82,7 @@ int make_plan(const hata_config* f, Plan* p) {
     p->off_uinfo = o;    o = align_up(o + (size_t)units * 2 * 4);
     p->off_ucnt = o;     o = align_up(o + (size_t)units * 4);
     p->off_acnt = o;     o = align_up(o + (size_t)f->B_max * f->Hq * 4);
+    p->off_uhist = o;    o = align_up(o + (size_t)units * p->NB * 4);
     p->off_partials = o; o = align_up(o + (size_t)f->B_max * f->Hq * max_splits * (128 + 2) * 4);
     p->total = o;
     return HATA_OK;
@@ -131,6 +143,7 @@ int hata_create(hata_ctx** ctx_out, const hata_config* cfg, void* workspace, siz
     c->unit_info = (int32_t*)(w + p.off_uinfo);
     c->unit_counter = (uint32_t*)(w + p.off_ucnt);
     c->attn_counter = (uint32_t*)(w + p.off_acnt);
+    c->unit_hist = (uint32_t*)(w + p.off_uhist);
     c->partials = (float*)(w + p.off_partials);
     // control words and the self-resetting arrival counters start from zero
     if (hipMemset(c->chunk_info, 0, p.off_partials - p.off_cinfo) != hipSuccess) {

@@ -19,6 +19,7 @@
 #include "hata_device.h"
 #include "hata_internal.h"
 #include "hata_select.h"
+#include "hata_trace.h"
 
 namespace hata {
 
@@ -57,25 +58,6 @@ struct AttnArgs {
     float scale_log2;
 };
 
-__device__ __forceinline__ float block_reduce_max_256(float v, float* lds4) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
-    if ((threadIdx.x & 63) == 0) lds4[threadIdx.x >> 6] = v;
-    __syncthreads();
-    v = fmaxf(fmaxf(lds4[0], lds4[1]), fmaxf(lds4[2], lds4[3]));
-    __syncthreads();
-    return v;
-}
-__device__ __forceinline__ float block_reduce_sum_256(float v, float* lds4) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
-    if ((threadIdx.x & 63) == 0) lds4[threadIdx.x >> 6] = v;
-    __syncthreads();
-    v = lds4[0] + lds4[1] + lds4[2] + lds4[3];
-    __syncthreads();
-    return v;
-}
-
 // grid = (splits, Hkv * (G / HT), B); 256 threads = 4 waves; lane = (row group rg = lane / 16,
 // sub = lane % 16 -> elements [8 sub, 8 sub + 8) of a row).
 template <int HT, int MODE>
@@ -85,7 +67,6 @@ __global__ __launch_bounds__(256) void attn_kernel(const AttnArgs a) {
     __shared__ float sm_acc[4][HT][HATA_D];
     __shared__ int s_rows[MODE == ROWS_SELECT ? HATA_MAX_ROWS_PER_WG : 1];
     __shared__ uint32_t scan4[4];
-    __shared__ float red4[4];
     __shared__ int s_clo, s_chi, s_last;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int sub = lane & 15, rg = lane >> 4;
@@ -96,6 +77,9 @@ __global__ __launch_bounds__(256) void attn_kernel(const AttnArgs a) {
     const int b = blockIdx.z;
     const int64_t u = (int64_t)b * a.Hkv + h;
     const int hq0 = h * a.G + ht * HT;
+#define TA(i) HATA_TRACE_AT(i, MODE == ROWS_SELECT && u == 0 && ht == 0 && split == 0)
+#define TL(i) HATA_TRACE_AT(i, MODE == ROWS_SELECT && u == 0 && ht == 0)
+    TA(20);
     int count;
     if (MODE == ROWS_DENSE) count = clampi(a.count_src[b], 0, a.L_cap);
     else if (MODE == ROWS_IDX) count = clampi(a.count_src[b], 0, a.k_max);
@@ -127,6 +111,7 @@ __global__ __launch_bounds__(256) void attn_kernel(const AttnArgs a) {
         const int nc = (L + a.chunk - 1) / a.chunk;
         const int T = a.unit_info[u * 2 + 0];
         const int32_t* ci = a.chunk_info + u * (a.n_chunks + 1) * 2;
+        TA(21);
         if (tid == 0) { s_clo = nc; s_chi = -1; }
         __syncthreads();
         for (int c = tid; c < nc; c += 256) {
@@ -135,6 +120,7 @@ __global__ __launch_bounds__(256) void attn_kernel(const AttnArgs a) {
         }
         __syncthreads();
         const int c_lo = s_clo, c_hi = s_chi;
+        TA(22);
         const uint16_t* sp = a.scores + u * a.L_cap;
         int32_t* io = a.idx_out + u * a.k_max;
         for (int c = c_lo; c <= c_hi; ++c) {
@@ -142,21 +128,17 @@ __global__ __launch_bounds__(256) void attn_kernel(const AttnArgs a) {
             if (ci[2 * c + 2] == off) continue;
             const int base = c * a.chunk;
             const int end = min(base + a.chunk, L);
-            uint32_t run_lt = 0, run_eq = 0;
-            for (int n0 = base; n0 < end; n0 += 1024) {
-                if (off + (int)run_lt + (int)min(run_eq, (uint32_t)take) >= row_end) break;
-                compact_block_1024(sp, n0, end, T, off, take, run_lt, run_eq, scan4,
-                                   [&](int pos, int n) {
-                                       if (pos >= row_begin && pos < row_end) {
-                                           s_rows[pos - row_begin] = n;
-                                           if (ht == 0) io[pos] = n;
-                                       }
-                                   });
-            }
+            compact_chunk_any(a.chunk / 256, sp, base, end, T, off, take, scan4,
+                              [&](int pos, int n) {
+                                  if (pos >= row_begin && pos < row_end) {
+                                      s_rows[pos - row_begin] = n;
+                                      if (ht == 0) io[pos] = n;
+                                  }
+                              });
         }
         __syncthreads();
     }
-
+    TA(23);
     // this lane's 8 query elements of each head, kept as packed bf16 pairs
     uint32_t qr[HT][4];
 #pragma unroll
@@ -243,6 +225,7 @@ __global__ __launch_bounds__(256) void attn_kernel(const AttnArgs a) {
             }
         }
     }
+    TA(24);
     // combine the four row groups of the wave (all share m_run)
 #pragma unroll
     for (int g = 0; g < HT; ++g) {
@@ -289,7 +272,9 @@ __global__ __launch_bounds__(256) void attn_kernel(const AttnArgs a) {
     if (ns == 1) return;
     // count the finished slices; the last workgroup merges them (partials are written with
     // write-through stores and read back with device-coherent loads)
+    TA(25);
     wait_stores();
+    TA(26);
     __syncthreads();
     if (tid == 0) {
         uint32_t* cnt = a.counter + u * tiles + ht;
@@ -299,34 +284,49 @@ __global__ __launch_bounds__(256) void attn_kernel(const AttnArgs a) {
         s_last = last;
     }
     __syncthreads();
+    TA(27);
     if (!s_last) return;
-    for (int g = 0; g < HT; ++g) {
+    TL(30);
+    // thread -> (head, channel); online merge over the slices, 8 slices of loads in flight at once
+    for (int i = tid; i < HT * HATA_D; i += 256) {
+        const int g = i / HATA_D, ch = i % HATA_D;
         const float* pp = a.partials + ((int64_t)b * a.Hq + hq0 + g) * a.n_splits * HATA_PSTRIDE;
-        float m_loc = HATA_NEG_INF;
-        for (int s2 = tid; s2 < ns; s2 += 256) m_loc = fmaxf(m_loc, ld_dev(pp + s2 * HATA_PSTRIDE));
-        const float M = block_reduce_max_256(m_loc, red4);
-        float l_loc = 0.f;
-        if (M != HATA_NEG_INF)
-            for (int s2 = tid; s2 < ns; s2 += 256)
-                l_loc += exp2f(ld_dev(pp + s2 * HATA_PSTRIDE) - M) * ld_dev(pp + s2 * HATA_PSTRIDE + 1);
-        const float Lsum = block_reduce_sum_256(l_loc, red4);
-        // threads 0..127 take even slices, 128..255 odd slices of channel tid % 128
-        const int ch = tid & 127, half = tid >> 7;
-        float av = 0.f;
-        if (M != HATA_NEG_INF)
-            for (int s2 = half; s2 < ns; s2 += 2)
-                av = fmaf(exp2f(ld_dev(pp + s2 * HATA_PSTRIDE) - M), ld_dev(pp + s2 * HATA_PSTRIDE + 2 + ch), av);
-        if (half == 1) sm_acc[0][0][ch] = av;
-        __syncthreads();
-        if (half == 0) {
-            av += sm_acc[0][0][ch];
-            const float o = Lsum > 0.f ? av / Lsum : 0.f;
-            const int64_t oo = ((int64_t)b * a.Hq + hq0 + g) * HATA_D + ch;
-            a.out[oo] = (uint16_t)f32_to_bf16(o);
-            if (a.out_f32) a.out_f32[oo] = o;
+        float M = HATA_NEG_INF, Lsum = 0.f, A = 0.f;
+        for (int s0 = 0; s0 < ns; s0 += 8) {
+            float m[8], l[8], av[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                // unconditional loads (clamped slice) so that all 24 are in flight together
+                const bool ok = s0 + j < ns;
+                const float* p = pp + (int64_t)min(s0 + j, ns - 1) * HATA_PSTRIDE;
+                const float mj = ld_dev(p), lj = ld_dev(p + 1), aj = ld_dev(p + 2 + ch);
+                m[j] = ok ? mj : HATA_NEG_INF;
+                l[j] = ok ? lj : 0.f;
+                av[j] = ok ? aj : 0.f;
+            }
+            float mb = m[0];
+#pragma unroll
+            for (int j = 1; j < 8; ++j) mb = fmaxf(mb, m[j]);
+            const float Mn = fmaxf(M, mb);
+            if (Mn == HATA_NEG_INF) continue;
+            const float sc = exp2f(M - Mn);
+            A *= sc; Lsum *= sc;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const float w = exp2f(m[j] - Mn);
+                A = fmaf(w, av[j], A);
+                Lsum = fmaf(w, l[j], Lsum);
+            }
+            M = Mn;
         }
-        __syncthreads();
+        const float o = Lsum > 0.f ? A / Lsum : 0.f;
+        const int64_t oo = ((int64_t)b * a.Hq + hq0 + g) * HATA_D + ch;
+        a.out[oo] = (uint16_t)f32_to_bf16(o);
+        if (a.out_f32) a.out_f32[oo] = o;
     }
+    TL(31);
+#undef TA
+#undef TL
 }
 
 template <int HT>

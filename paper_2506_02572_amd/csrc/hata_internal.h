@@ -26,6 +26,7 @@ struct hata_ctx {
     int32_t* chunk_info;   // [B_max*Hkv, n_chunks + 1, 2] = {output offset, ties taken}
     int32_t* unit_info;    // [B_max*Hkv, 2] = {threshold, selected count}
     uint32_t* unit_counter;  // [B_max*Hkv] scored chunks of a unit (self-resetting)
+    uint32_t* unit_hist;     // [B_max*Hkv, NB] total histogram of a unit (self-clearing)
     uint32_t* attn_counter;  // [B_max*Hq] finished attention slices (self-resetting)
     float* partials;       // [B_max*Hq, max(sparse_splits, dense_splits), d + 2]
 };

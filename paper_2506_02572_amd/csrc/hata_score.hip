@@ -12,6 +12,7 @@
 #include "hata_device.h"
 #include "hata_internal.h"
 #include "hata_select.h"
+#include "hata_trace.h"
 
 namespace hata {
 
@@ -57,8 +58,17 @@ __device__ __forceinline__ void write_chunk_hist(uint16_t* hp, const uint32_t* h
 __device__ __forceinline__ void finish_unit(
     int64_t u, int nc, int keff, const uint16_t* __restrict__ chunk_hist_u, int NB, int NBP,
     int n_chunks, int32_t* __restrict__ chunk_info, int32_t* __restrict__ unit_info,
-    uint32_t* __restrict__ unit_counter, uint32_t* hist, ThresholdLds& S, int* flag) {
-    wait_stores();    // this thread's write-through histogram stores have completed
+    uint32_t* __restrict__ unit_counter, uint32_t* __restrict__ unit_hist, uint32_t* hist,
+    ThresholdLds& S, int* flag) {
+    HATA_TRACE_AT(2, u == 0);
+    // add this chunk's histogram to the unit's total (only occupied bins)
+    for (int i = threadIdx.x; i < NB; i += 256) {
+        const uint32_t hv = hist[i];
+        if (hv) atomicAdd(&unit_hist[u * NB + i], hv);
+    }
+    HATA_TRACE_AT(3, u == 0);
+    wait_stores();    // this thread's write-through stores and atomics have completed
+    HATA_TRACE_AT(4, u == 0);
     __syncthreads();  // ... and so have those of the whole workgroup
     if (threadIdx.x == 0) {
         const uint32_t done = atomicAdd(&unit_counter[u], 1u);
@@ -68,9 +78,11 @@ __device__ __forceinline__ void finish_unit(
     }
     __syncthreads();
     if (!*flag) return;
+    HATA_TRACE_AT(5, u == 0);
     // the other workgroups' histograms are read with device-coherent loads
-    unit_threshold<true>(chunk_hist_u, nc, keff, NB, NBP, chunk_info + u * (n_chunks + 1) * 2,
+    unit_threshold<true>(chunk_hist_u, unit_hist + u * NB, nc, keff, NB, NBP, chunk_info + u * (n_chunks + 1) * 2,
                    unit_info + u * 2, hist, S);
+    HATA_TRACE_AT(6, u == 0);
 }
 
 template <int WD, int G, bool SELECT>
@@ -80,7 +92,7 @@ __global__ __launch_bounds__(256) void score_kernel(
     uint16_t* __restrict__ chunk_hist, int Hq, int Hkv, int L_cap, int chunk, int n_chunks,
     int NB, int NBP, const int32_t* __restrict__ kbud, int k_max,
     int32_t* __restrict__ chunk_info, int32_t* __restrict__ unit_info,
-    uint32_t* __restrict__ unit_counter) {
+    uint32_t* __restrict__ unit_counter, uint32_t* __restrict__ unit_hist) {
     extern __shared__ uint32_t hist[];  // NB bins when chunk_hist != nullptr
     __shared__ ThresholdLds S;
     __shared__ int last_flag;
@@ -99,6 +111,7 @@ __global__ __launch_bounds__(256) void score_kernel(
         return;
     }
     const int end = min(base + chunk, L);
+    HATA_TRACE_AT(0, SELECT && u == 0 && c == 0);
     const bool do_hist = chunk_hist != nullptr;
     if (do_hist) {
         for (int i = tid; i < NB; i += 256) hist[i] = 0;
@@ -114,7 +127,7 @@ __global__ __launch_bounds__(256) void score_kernel(
 
     const uint32_t* cp = codes + u * L_cap * WD;
     uint16_t* sp = scores + u * L_cap;
-    constexpr int UNR = 4;
+    constexpr int UNR = (WD <= 4) ? 8 : 4;  // 128 B of codes in flight per lane
     for (int n0 = base + tid; n0 < end; n0 += 256 * UNR) {
         CodeVec<WD> kc[UNR];
 #pragma unroll
@@ -136,6 +149,7 @@ __global__ __launch_bounds__(256) void score_kernel(
             }
         }
     }
+    HATA_TRACE_AT(1, SELECT && u == 0 && c == 0);
     if (do_hist) {
         __syncthreads();
         write_chunk_hist(chunk_hist + (u * n_chunks + c) * NBP, hist, NB, NBP);
@@ -143,7 +157,7 @@ __global__ __launch_bounds__(256) void score_kernel(
     if constexpr (SELECT) {
         const int keff = min(clampi(kbud[b], 0, k_max), L);
         finish_unit(u, (L + chunk - 1) / chunk, keff, chunk_hist + u * n_chunks * NBP, NB, NBP,
-                    n_chunks, chunk_info, unit_info, unit_counter, hist, S, &last_flag);
+                    n_chunks, chunk_info, unit_info, unit_counter, unit_hist, hist, S, &last_flag);
     }
 }
 
@@ -154,7 +168,7 @@ __global__ __launch_bounds__(256) void score_kernel_generic(
     uint16_t* __restrict__ chunk_hist, int Hq, int Hkv, int G, int WD, int L_cap, int chunk,
     int n_chunks, int NB, int NBP, int select, const int32_t* __restrict__ kbud, int k_max,
     int32_t* __restrict__ chunk_info, int32_t* __restrict__ unit_info,
-    uint32_t* __restrict__ unit_counter) {
+    uint32_t* __restrict__ unit_counter, uint32_t* __restrict__ unit_hist) {
     extern __shared__ uint32_t hist[];
     __shared__ uint32_t qc[16 * 8];
     __shared__ ThresholdLds S;
@@ -193,7 +207,7 @@ __global__ __launch_bounds__(256) void score_kernel_generic(
     if (select) {
         const int keff = min(clampi(kbud[b], 0, k_max), L);
         finish_unit(u, (L + chunk - 1) / chunk, keff, chunk_hist + u * n_chunks * NBP, NB, NBP,
-                    n_chunks, chunk_info, unit_info, unit_counter, hist, S, &last_flag);
+                    n_chunks, chunk_info, unit_info, unit_counter, unit_hist, hist, S, &last_flag);
     }
 }
 
@@ -208,12 +222,12 @@ static void launch_t(const hata_ctx* c, const uint32_t* qcodes, const uint32_t* 
         hipLaunchKernelGGL((score_kernel<WD, G, true>), grid, dim3(256), lds, s, qcodes, codes,
                            seq_len, scores, c->chunk_hist, f.Hq, f.Hkv, f.L_cap, c->chunk,
                            c->n_chunks, c->NB, c->NBP, kbud, f.k_max, c->chunk_info,
-                           c->unit_info, c->unit_counter);
+                           c->unit_info, c->unit_counter, c->unit_hist);
     else
         hipLaunchKernelGGL((score_kernel<WD, G, false>), grid, dim3(256), lds, s, qcodes, codes,
                            seq_len, scores, c->chunk_hist, f.Hq, f.Hkv, f.L_cap, c->chunk,
                            c->n_chunks, c->NB, c->NBP, kbud, f.k_max, c->chunk_info,
-                           c->unit_info, c->unit_counter);
+                           c->unit_info, c->unit_counter, c->unit_hist);
 }
 
 // kbud == nullptr: scores (+ chunk histograms) only.  kbud != nullptr: the fused-step variant,
@@ -235,7 +249,7 @@ hipError_t launch_score(const hata_ctx* c, const uint32_t* qcodes, const uint32_
                                (size_t)c->NB * 4, s, qcodes, codes, seq_len, scores, c->chunk_hist,
                                f.Hq, f.Hkv, c->G, c->Wd, f.L_cap, c->chunk, c->n_chunks, c->NB,
                                c->NBP, kbud ? 1 : 0, kbud, f.k_max, c->chunk_info, c->unit_info,
-                               c->unit_counter);
+                               c->unit_counter, c->unit_hist);
     }
     return hipGetLastError();
 }

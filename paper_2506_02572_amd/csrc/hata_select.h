@@ -8,6 +8,7 @@
 // and the index list comes out ascending.  No atomic decides an output position.
 #pragma once
 #include "hata_device.h"
+#include "hata_trace.h"
 
 namespace hata {
 
@@ -16,7 +17,7 @@ namespace hata {
 // LDS a workgroup needs to run unit_threshold()
 struct ThresholdLds {
     uint32_t scan4[4];
-    int T, need;
+    int T, need, bmin;
     uint32_t c_lt[HATA_MAX_CHUNKS];
     uint32_t c_eq[HATA_MAX_CHUNKS];
 };
@@ -25,45 +26,78 @@ struct ThresholdLds {
 //   unit_info[u]       = {T, keff}: keys with score < T are all selected, keff = min(k, L)
 //   chunk_info[u][c]   = {first output position of chunk c, ties (score == T) chunk c may take},
 //                        c = 0 .. nc (entry nc = {keff, 0} closes the list)
-// from the nc chunk histograms of the unit (`hp`, pitch NBP, uint16 counts).
-// COHERENT: the histograms were written by other workgroups of this launch (device-coherent loads).
-// `tot` is NB words of LDS.  Must be called by all 256 threads.
-template <bool COHERENT>
-__device__ __forceinline__ uint2 load_bins4(const uint16_t* p) {
-    if constexpr (COHERENT) return ld_dev_u2(p);
-    else return *reinterpret_cast<const uint2*>(p);
-}
+// from the nc chunk histograms of the unit (`hp`, pitch NBP, uint16 counts) and -- FUSED -- the
+// unit's total histogram `unit_hist` (NB words) that the scoring workgroups of this launch
+// accumulated with atomics; it is read with device-coherent loads and cleared for the next
+// launch.  Not FUSED: the total is summed from the chunk rows.  `tot` is NB words of LDS.
+// Must be called by all 256 threads.
+//
+// Only the few 8-bin columns between the lowest occupied score and T matter for the per-chunk
+// counts (the selected keys are the low tail of the distribution), so the second pass reads
+// just those columns of every chunk row.
+struct Bins8 { uint32_t w[4]; };  // 8 uint16 counts
 
 template <bool COHERENT>
-__device__ __forceinline__ void unit_threshold(
-    const uint16_t* __restrict__ hp, int nc, int keff, int NB, int NBP,
-    int32_t* __restrict__ chunk_info_u, int32_t* __restrict__ unit_info_u, uint32_t* tot,
-    ThresholdLds& S) {
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    // total histogram: thread -> 4 consecutive bins (one 8-byte load per chunk)
-    const int ncol = NBP / 4;
-    for (int col = tid; col < ncol; col += 256) {
-        uint32_t a0 = 0, a1 = 0, a2 = 0, a3 = 0;
-        const uint16_t* p = hp + col * 4;
-#pragma unroll 8
-        for (int c = 0; c < nc; ++c) {
-            const uint2 v = load_bins4<COHERENT>(p + (int64_t)c * NBP);
-            a0 += v.x & 0xffffu; a1 += v.x >> 16;
-            a2 += v.y & 0xffffu; a3 += v.y >> 16;
-        }
-        const int b0 = col * 4;
-        if (b0 + 0 < NB) tot[b0 + 0] = a0;
-        if (b0 + 1 < NB) tot[b0 + 1] = a1;
-        if (b0 + 2 < NB) tot[b0 + 2] = a2;
-        if (b0 + 3 < NB) tot[b0 + 3] = a3;
+__device__ __forceinline__ Bins8 load_bins8(const uint16_t* p) {
+    Bins8 r;
+    if constexpr (COHERENT) {
+        const uint2 a = ld_dev_u2(p), b = ld_dev_u2(p + 4);
+        r.w[0] = a.x; r.w[1] = a.y; r.w[2] = b.x; r.w[3] = b.y;
+    } else {
+        const uint4 v = *reinterpret_cast<const uint4*>(p);
+        r.w[0] = v.x; r.w[1] = v.y; r.w[2] = v.z; r.w[3] = v.w;
     }
-    if (tid == 0) { S.T = (keff > 0) ? NB : 0; S.need = 0; }
+    return r;
+}
+__device__ __forceinline__ uint32_t bin_of(const Bins8& v, int e) {
+    const uint32_t w = v.w[e >> 1];
+    return (e & 1) ? (w >> 16) : (w & 0xffffu);
+}
+
+template <bool FUSED>
+__device__ __forceinline__ void unit_threshold(
+    const uint16_t* __restrict__ hp, uint32_t* __restrict__ unit_hist_u, int nc, int keff, int NB,
+    int NBP, int32_t* __restrict__ chunk_info_u, int32_t* __restrict__ unit_info_u, uint32_t* tot,
+    ThresholdLds& S) {
+    const int tid = threadIdx.x;
+    if (tid == 0) { S.T = (keff > 0) ? NB : 0; S.need = 0; S.bmin = NB; }
+    for (int c = tid; c < nc; c += 256) { S.c_lt[c] = 0; S.c_eq[c] = 0; }
+    // total histogram of the unit
+    if constexpr (FUSED) {
+        for (int i0 = tid; i0 < NB; i0 += 256 * 4) {
+            uint32_t x[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j)  // clamped index: unconditional loads, all in flight
+                x[j] = __hip_atomic_load(unit_hist_u + min(i0 + j * 256, NB - 1), __ATOMIC_RELAXED,
+                                         __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int i = i0 + j * 256;
+                if (i < NB) {
+                    tot[i] = x[j];
+                    if (x[j]) unit_hist_u[i] = 0;  // left clean for the next launch
+                }
+            }
+        }
+    } else {
+        for (int i = tid; i < NB; i += 256) {
+            uint32_t t = 0;
+            for (int c = 0; c < nc; ++c) t += hp[(int64_t)c * NBP + i];
+            tot[i] = t;
+        }
+    }
     __syncthreads();
-    // T = smallest score value whose inclusive prefix count reaches keff
+    HATA_TRACE_AT(10, FUSED);
+    // T = smallest score value whose inclusive prefix count reaches keff; bmin = lowest occupied score
     const int seg = (NB + 255) / 256;
     const int s0 = tid * seg, s1 = min(NB, s0 + seg);
     uint32_t local = 0;
-    for (int i = s0; i < s1; ++i) local += tot[i];
+    int first_nz = NB;
+    for (int i = s1 - 1; i >= s0; --i) {
+        local += tot[i];
+        if (tot[i]) first_nz = i;
+    }
+    if (first_nz < NB) atomicMin(&S.bmin, first_nz);
     uint32_t total;
     const uint32_t before = block_excl_scan_256(local, S.scan4, &total);
     if (keff > 0 && before < (uint32_t)keff && before + local >= (uint32_t)keff) {
@@ -75,30 +109,39 @@ __device__ __forceinline__ void unit_threshold(
     }
     __syncthreads();
     const int T = S.T, need = S.need;
-    // per chunk: keys below T and keys equal to T (one wave per chunk, 4 bins per lane and load)
-    for (int c = wave; c < nc; c += 4) {
-        const uint16_t* row = hp + (int64_t)c * NBP;
-        uint32_t lt = 0;
-        for (int col = lane; col * 4 < T; col += 64) {
-            const uint2 v = load_bins4<COHERENT>(row + col * 4);
-            const int b0 = col * 4;
-            lt += (b0 + 0 < T ? v.x & 0xffffu : 0u) + (b0 + 1 < T ? v.x >> 16 : 0u);
-            lt += (b0 + 2 < T ? v.y & 0xffffu : 0u) + (b0 + 3 < T ? v.y >> 16 : 0u);
-        }
+    HATA_TRACE_AT(11, FUSED);
+    // per chunk: keys below T and keys equal to T, from columns [bmin / 8, T / 8] of its row
+    if (T < NB) {
+        const int col0 = min(S.bmin, T) / 8;
+        const int ncols = T / 8 - col0 + 1;
+        const int items = nc * ncols;
+        for (int i0 = tid; i0 < items; i0 += 256 * 4) {
+            Bins8 x[4];
 #pragma unroll
-        for (int o = 32; o > 0; o >>= 1) lt += __shfl_xor(lt, o, 64);
-        if (lane == 0) {
-            uint32_t eq = 0;
-            if (T < NB) {
-                const uint2 v = load_bins4<COHERENT>(row + (T & ~3));
-                const uint32_t w = (T & 2) ? v.y : v.x;
-                eq = (T & 1) ? (w >> 16) : (w & 0xffffu);
+            for (int j = 0; j < 4; ++j) {
+                const int i = min(i0 + j * 256, items - 1);
+                const int c = i / ncols, col = col0 + (i - c * ncols);
+                x[j] = load_bins8<FUSED>(hp + (int64_t)c * NBP + col * 8);
             }
-            S.c_lt[c] = lt;
-            S.c_eq[c] = eq;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int i = i0 + j * 256;
+                if (i < items) {
+                    const int c = i / ncols, col = col0 + (i - c * ncols);
+                    uint32_t lt = 0;
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        const uint32_t cnt = bin_of(x[j], e);
+                        lt += (col * 8 + e < T) ? cnt : 0u;
+                        if (col * 8 + e == T) S.c_eq[c] = cnt;  // one item per chunk holds bin T
+                    }
+                    if (lt) atomicAdd(&S.c_lt[c], lt);
+                }
+            }
         }
     }
     __syncthreads();
+    HATA_TRACE_AT(12, FUSED);
     // ordered offsets: ties are granted to chunks in cache order.  thread t owns chunks
     // [t*cpt, (t+1)*cpt)
     const int cpt = (nc + 255) / 256;
@@ -136,36 +179,41 @@ __device__ __forceinline__ void unit_threshold(
     }
 }
 
-// Ordered compaction of one block of 1024 consecutive keys [n0, n0 + 1024) by 256 threads
-// (4 keys each).  `run_lt`, `run_eq` count the selected-below-T and equal-to-T keys of the
-// chunk seen before this block; they are advanced.  For every selected key, emit(pos, n) is
-// called with pos = its position in the unit's index list.  Must be called by all 256 threads.
-template <typename Emit>
-__device__ __forceinline__ void compact_block_1024(
-    const uint16_t* __restrict__ sp, int n0, int L, int T, int off, int take,
-    uint32_t& run_lt, uint32_t& run_eq, uint32_t* scan4, Emit emit) {
+// Ordered compaction of one whole chunk of 256 * KPT consecutive keys [n0, n0 + 256*KPT) by 256
+// threads (KPT consecutive keys each, all score loads in flight together).  For every selected
+// key, emit(pos, n) is called with pos = its position in the unit's index list.
+// Must be called by all 256 threads.
+template <int KPT, typename Emit>
+__device__ __forceinline__ void compact_chunk(
+    const uint16_t* __restrict__ sp, int n0, int L, int T, int off, int take, uint32_t* scan4,
+    Emit emit) {
     const int tid = threadIdx.x;
-    const int n = n0 + tid * 4;
-    uint32_t sv[4];
-    if (n + 4 <= L && (reinterpret_cast<uintptr_t>(sp + n) & 7) == 0) {
-        const uint2 v = *reinterpret_cast<const uint2*>(sp + n);
-        sv[0] = v.x & 0xffffu; sv[1] = v.x >> 16; sv[2] = v.y & 0xffffu; sv[3] = v.y >> 16;
+    const int n = n0 + tid * KPT;
+    uint32_t sv[KPT];
+    if (n + KPT <= L && (reinterpret_cast<uintptr_t>(sp + n) & 7) == 0) {
+#pragma unroll
+        for (int i = 0; i < KPT / 4; ++i) {
+            const uint2 v = reinterpret_cast<const uint2*>(sp + n)[i];
+            sv[4 * i + 0] = v.x & 0xffffu; sv[4 * i + 1] = v.x >> 16;
+            sv[4 * i + 2] = v.y & 0xffffu; sv[4 * i + 3] = v.y >> 16;
+        }
     } else {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) sv[i] = (n + i < L) ? (uint32_t)sp[n + i] : 0xffffffffu;
+        for (int i = 0; i < KPT; ++i) sv[i] = (n + i < L) ? (uint32_t)sp[n + i] : 0xffffffffu;
     }
     uint32_t lt = 0, eq = 0;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < KPT; ++i) {
         const bool live = n + i < L;
         lt += (live && (int)sv[i] < T) ? 1u : 0u;
         eq += (live && (int)sv[i] == T) ? 1u : 0u;
     }
     uint32_t total;
     const uint32_t before = block_excl_scan_256(lt | (eq << 16), scan4, &total);
-    uint32_t lt_b = run_lt + (before & 0xffffu), eq_b = run_eq + (before >> 16);
+    uint32_t lt_b = before & 0xffffu, eq_b = before >> 16;
+    if (lt == 0 && (eq == 0 || eq_b >= (uint32_t)take)) return;  // nothing of this thread is selected
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < KPT; ++i) {
         const bool live = n + i < L;
         if (live && (int)sv[i] < T) {
             emit(off + (int)lt_b + (int)min(eq_b, (uint32_t)take), n + i);
@@ -175,8 +223,19 @@ __device__ __forceinline__ void compact_block_1024(
             ++eq_b;
         }
     }
-    run_lt += total & 0xffffu;
-    run_eq += total >> 16;
+}
+
+// chunk = 256 * kpt keys, kpt in {4, 8, 16, 32}
+template <typename Emit>
+__device__ __forceinline__ void compact_chunk_any(
+    int kpt, const uint16_t* __restrict__ sp, int n0, int L, int T, int off, int take,
+    uint32_t* scan4, Emit emit) {
+    switch (kpt) {
+        case 4: compact_chunk<4>(sp, n0, L, T, off, take, scan4, emit); break;
+        case 8: compact_chunk<8>(sp, n0, L, T, off, take, scan4, emit); break;
+        case 16: compact_chunk<16>(sp, n0, L, T, off, take, scan4, emit); break;
+        default: compact_chunk<32>(sp, n0, L, T, off, take, scan4, emit); break;
+    }
 }
 
 }  // namespace hata

@@ -43,7 +43,7 @@ __global__ __launch_bounds__(256) void threshold_kernel(
     const int L = clampi(seq_len[b], 0, L_cap);
     const int keff = min(clampi(kbud[b], 0, k_max), L);
     const int nc = (L + chunk - 1) / chunk;
-    unit_threshold<false>(chunk_hist + (int64_t)u * n_chunks * NBP, nc, keff, NB, NBP,
+    unit_threshold<false>(chunk_hist + (int64_t)u * n_chunks * NBP, nullptr, nc, keff, NB, NBP,
                    chunk_info + (int64_t)u * (n_chunks + 1) * 2, unit_info + u * 2, tot, S);
 }
 
@@ -68,11 +68,9 @@ __global__ __launch_bounds__(256) void compact_kernel(
     const int off = ci[0], take = ci[1];
     if (ci[2] == off) return;  // nothing selected in this chunk
     const uint16_t* sp = scores + u * L_cap;
-    uint32_t run_lt = 0, run_eq = 0;
     const int end = min(base + chunk, L);
-    for (int n0 = base; n0 < end; n0 += 1024)
-        compact_block_1024(sp, n0, end, T, off, take, run_lt, run_eq, scan4,
-                           [&](int pos, int n) { if (pos < k_max) out[pos] = n; });
+    compact_chunk_any(chunk / 256, sp, base, end, T, off, take, scan4,
+                      [&](int pos, int n) { if (pos < k_max) out[pos] = n; });
 }
 
 hipError_t launch_topk(const hata_ctx* c, const uint16_t* scores, const int32_t* seq_len,
