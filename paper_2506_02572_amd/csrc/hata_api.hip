@@ -65,10 +65,13 @@ int make_plan(const hata_config* f, Plan* p) {
     const int64_t attn_units = units * (G / p->HT);
     int rows = 256;
     while (rows > 16 && attn_units * ((f->k_max + rows - 1) / rows) < 512) rows >>= 1;
+    while (rows < 256 && (f->k_max + rows - 1) / rows > 256) rows <<= 1;
     p->sparse_rows = rows;
     p->sparse_splits = (f->k_max + rows - 1) / rows;
+    if (p->sparse_splits > 256) return HATA_EUNSUPPORTED;  // budget above 65536 rows
     int drows = 4096;
     while (drows > 512 && attn_units * ((f->L_cap + drows - 1) / drows) < 512) drows >>= 1;
+    while ((f->L_cap + drows - 1) / drows > 256) drows <<= 1;  // the merge handles <= 256 slices
     p->dense_rows = drows;
     p->dense_splits = (f->L_cap + drows - 1) / drows;
     const int max_splits = p->sparse_splits > p->dense_splits ? p->sparse_splits : p->dense_splits;

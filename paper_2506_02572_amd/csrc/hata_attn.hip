@@ -189,18 +189,14 @@ __global__ __launch_bounds__(256) void attn_kernel(const AttnArgs a) {
                 d = dot2_bf16(qr[g][1], kv[it].y, d);
                 d = dot2_bf16(qr[g][2], kv[it].z, d);
                 d = dot2_bf16(qr[g][3], kv[it].w, d);
-                d += __shfl_xor(d, 1, 64);
-                d += __shfl_xor(d, 2, 64);
-                d += __shfl_xor(d, 4, 64);
-                d += __shfl_xor(d, 8, 64);
+                d = row_sum16(d);
                 s[it][g] = ok[it] ? d * a.scale_log2 : HATA_NEG_INF;
                 m_tile[g] = fmaxf(m_tile[g], s[it][g]);
             }
         }
 #pragma unroll
         for (int g = 0; g < HT; ++g) {
-            m_tile[g] = fmaxf(m_tile[g], __shfl_xor(m_tile[g], 16, 64));
-            m_tile[g] = fmaxf(m_tile[g], __shfl_xor(m_tile[g], 32, 64));
+            m_tile[g] = rows_max4(m_tile[g]);
             const float m_new = fmaxf(m_run[g], m_tile[g]);
             // m_new == -inf only while no valid row has been seen: keep the state untouched
             const float alpha = (m_new == HATA_NEG_INF) ? 1.f : exp2f(m_run[g] - m_new);
@@ -229,13 +225,9 @@ __global__ __launch_bounds__(256) void attn_kernel(const AttnArgs a) {
     // combine the four row groups of the wave (all share m_run)
 #pragma unroll
     for (int g = 0; g < HT; ++g) {
-        l_run[g] += __shfl_xor(l_run[g], 16, 64);
-        l_run[g] += __shfl_xor(l_run[g], 32, 64);
+        l_run[g] = rows_sum4(l_run[g]);
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            acc[g][e] += __shfl_xor(acc[g][e], 16, 64);
-            acc[g][e] += __shfl_xor(acc[g][e], 32, 64);
-        }
+        for (int e = 0; e < 8; ++e) acc[g][e] = rows_sum4(acc[g][e]);
     }
     if (rg == 0) {
 #pragma unroll
@@ -287,42 +279,66 @@ __global__ __launch_bounds__(256) void attn_kernel(const AttnArgs a) {
     TA(27);
     if (!s_last) return;
     TL(30);
-    // thread -> (head, channel); online merge over the slices, 8 slices of loads in flight at once
-    for (int i = tid; i < HT * HATA_D; i += 256) {
+    // Merge.  Every load of the merge is issued before the first wait: each thread pulls the
+    // first 16 slices of its NO output channels into registers (later slices, ns > 16, batch by
+    // batch), while one wave per head turns the (max, sum) pairs of the slices into normalised
+    // weights w[g][s] = exp2(m_s - M) / sum_s' exp2(m_s' - M) l_s' in LDS.
+    constexpr int NO = (HT * HATA_D + 255) / 256;  // outputs (head, channel) per thread
+    float* sm_w = &sm_acc[0][0][0];                // [HT][nsp], nsp <= 256
+    const int nsp = (ns + 3) & ~3;
+    float av[NO][16];
+#pragma unroll
+    for (int r = 0; r < NO; ++r) {
+        const int i = min(tid + 256 * r, HT * HATA_D - 1);
         const int g = i / HATA_D, ch = i % HATA_D;
+        const float* pp = a.partials + ((int64_t)b * a.Hq + hq0 + g) * a.n_splits * HATA_PSTRIDE + 2 + ch;
+#pragma unroll
+        for (int j = 0; j < 16; ++j) av[r][j] = ld_dev(pp + (int64_t)min(j, ns - 1) * HATA_PSTRIDE);
+    }
+    for (int g = wave; g < HT; g += 4) {
         const float* pp = a.partials + ((int64_t)b * a.Hq + hq0 + g) * a.n_splits * HATA_PSTRIDE;
-        float M = HATA_NEG_INF, Lsum = 0.f, A = 0.f;
-        for (int s0 = 0; s0 < ns; s0 += 8) {
-            float m[8], l[8], av[8];
-#pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                // unconditional loads (clamped slice) so that all 24 are in flight together
-                const bool ok = s0 + j < ns;
-                const float* p = pp + (int64_t)min(s0 + j, ns - 1) * HATA_PSTRIDE;
-                const float mj = ld_dev(p), lj = ld_dev(p + 1), aj = ld_dev(p + 2 + ch);
-                m[j] = ok ? mj : HATA_NEG_INF;
-                l[j] = ok ? lj : 0.f;
-                av[j] = ok ? aj : 0.f;
-            }
-            float mb = m[0];
-#pragma unroll
-            for (int j = 1; j < 8; ++j) mb = fmaxf(mb, m[j]);
-            const float Mn = fmaxf(M, mb);
-            if (Mn == HATA_NEG_INF) continue;
-            const float sc = exp2f(M - Mn);
-            A *= sc; Lsum *= sc;
-#pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const float w = exp2f(m[j] - Mn);
-                A = fmaf(w, av[j], A);
-                Lsum = fmaf(w, l[j], Lsum);
-            }
-            M = Mn;
+        float m_loc = HATA_NEG_INF;
+        for (int s2 = lane; s2 < ns; s2 += 64) m_loc = fmaxf(m_loc, ld_dev(pp + (int64_t)s2 * HATA_PSTRIDE));
+        const float M = wave_max64(m_loc);
+        float l_loc = 0.f;
+        for (int s2 = lane; s2 < ns; s2 += 64) {
+            const float w = (M == HATA_NEG_INF) ? 0.f : exp2f(ld_dev(pp + (int64_t)s2 * HATA_PSTRIDE) - M);
+            sm_w[g * nsp + s2] = w;
+            l_loc = fmaf(w, ld_dev(pp + (int64_t)s2 * HATA_PSTRIDE + 1), l_loc);
         }
-        const float o = Lsum > 0.f ? A / Lsum : 0.f;
-        const int64_t oo = ((int64_t)b * a.Hq + hq0 + g) * HATA_D + ch;
-        a.out[oo] = (uint16_t)f32_to_bf16(o);
-        if (a.out_f32) a.out_f32[oo] = o;
+        const float Lsum = wave_sum64(l_loc);
+        const float inv = Lsum > 0.f ? 1.f / Lsum : 0.f;
+        for (int s2 = lane; s2 < nsp; s2 += 64) sm_w[g * nsp + s2] = (s2 < ns) ? sm_w[g * nsp + s2] * inv : 0.f;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int r = 0; r < NO; ++r) {
+        const int i = tid + 256 * r;
+        if (i < HT * HATA_D) {
+            const int g = i / HATA_D, ch = i % HATA_D;
+            const float4* w4 = reinterpret_cast<const float4*>(sm_w + g * nsp);
+            float A = 0.f;
+#pragma unroll
+            for (int j4 = 0; j4 < 4; ++j4) {
+                if (j4 * 4 < nsp) {  // weights of slices >= ns are zero
+                    const float4 w = w4[j4];
+                    A = fmaf(w.x, av[r][4 * j4], A); A = fmaf(w.y, av[r][4 * j4 + 1], A);
+                    A = fmaf(w.z, av[r][4 * j4 + 2], A); A = fmaf(w.w, av[r][4 * j4 + 3], A);
+                }
+            }
+            const float* pp = a.partials + ((int64_t)b * a.Hq + hq0 + g) * a.n_splits * HATA_PSTRIDE + 2 + ch;
+            for (int s0 = 16; s0 < ns; s0 += 16) {
+                float bv[16];
+#pragma unroll
+                for (int j = 0; j < 16; ++j) bv[j] = ld_dev(pp + (int64_t)min(s0 + j, ns - 1) * HATA_PSTRIDE);
+#pragma unroll
+                for (int j = 0; j < 16; ++j)
+                    if (s0 + j < ns) A = fmaf(sm_w[g * nsp + s0 + j], bv[j], A);
+            }
+            const int64_t oo = ((int64_t)b * a.Hq + hq0 + g) * HATA_D + ch;
+            a.out[oo] = (uint16_t)f32_to_bf16(A);
+            if (a.out_f32) a.out_f32[oo] = A;
+        }
     }
     TL(31);
 #undef TA

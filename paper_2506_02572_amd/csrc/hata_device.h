@@ -41,6 +41,56 @@ __device__ __forceinline__ void wait_stores() { asm volatile("s_waitcnt vmcnt(0)
 
 __device__ __forceinline__ int clampi(int v, int lo, int hi) { return v < lo ? lo : (v > hi ? hi : v); }
 
+// ---- cross-lane reductions in the VALU (no LDS traffic) ----
+// A wave is 4 rows of 16 lanes.  row_sum16: every lane gets the sum over its row (DPP quad
+// permutes and row mirrors).  xor16 / xor32 exchanges use the lane-swap instructions: with both
+// operands equal to v, swapping the odd rows of one copy with the even rows of the other leaves
+// {v[row ^ 1 ... even source], v[odd source]}, whose sum (or max) is the all-reduce over row
+// pairs; likewise for the two 32-lane halves.
+#define HATA_DPP(v, ctrl) \
+    __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, (v)), (ctrl), 0xf, 0xf, true))
+__device__ __forceinline__ float row_sum16(float v) {
+    v += HATA_DPP(v, 0xB1);   // quad_perm [1,0,3,2]
+    v += HATA_DPP(v, 0x4E);   // quad_perm [2,3,0,1]
+    v += HATA_DPP(v, 0x141);  // row_half_mirror
+    v += HATA_DPP(v, 0x140);  // row_mirror
+    return v;
+}
+// (written as inline asm: the instruction rewrites BOTH of its registers, and the compiler
+// builtin of this toolchain returns the first register for both results; the s_nop cover the
+// VALU-write -> lane-swap read hazard the compiler would otherwise handle)
+__device__ __forceinline__ float row_max16(float v) {
+    v = fmaxf(v, HATA_DPP(v, 0xB1));
+    v = fmaxf(v, HATA_DPP(v, 0x4E));
+    v = fmaxf(v, HATA_DPP(v, 0x141));
+    v = fmaxf(v, HATA_DPP(v, 0x140));
+    return v;
+}
+__device__ __forceinline__ void swap16(float v, float& a, float& b) {
+    a = v; b = v;
+    asm volatile("s_nop 1\n\tv_permlane16_swap_b32 %0, %1\n\ts_nop 1" : "+v"(a), "+v"(b));
+}
+__device__ __forceinline__ void swap32(float v, float& a, float& b) {
+    a = v; b = v;
+    asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1\n\ts_nop 1" : "+v"(a), "+v"(b));
+}
+// all-reduce over the 4 rows of the wave (lane-wise): every lane gets the sum / max of the four
+// lanes with the same position in their row
+__device__ __forceinline__ float rows_sum4(float v) {
+    float a, b;
+    swap16(v, a, b); v = a + b;
+    swap32(v, a, b); return a + b;
+}
+__device__ __forceinline__ float rows_max4(float v) {
+    float a, b;
+    swap16(v, a, b); v = fmaxf(a, b);
+    swap32(v, a, b); return fmaxf(a, b);
+}
+
+// all-reduce over the whole wave
+__device__ __forceinline__ float wave_sum64(float v) { return rows_sum4(row_sum16(v)); }
+__device__ __forceinline__ float wave_max64(float v) { return rows_max4(row_max16(v)); }
+
 // wave-level inclusive scan (sum) over 64 lanes
 __device__ __forceinline__ uint32_t wave_incl_scan(uint32_t v) {
     const int lane = threadIdx.x & 63;

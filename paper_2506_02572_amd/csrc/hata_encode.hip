@@ -80,6 +80,80 @@ __global__ __launch_bounds__(HATA_ENC_THREADS) void encode_vectors_kernel(
     }
 }
 
+// One workgroup per (sequence, KV head) unit: the G query heads of the group and, optionally,
+// the key appended in this step share one pass over W_H[h] (each weight is loaded once and used
+// for every vector).  1024 threads = (column j, part p); fp64 accumulation; the partial sums of
+// the parts are combined in a fixed order, so the result is deterministic.
+// grid = B * Hkv.  R = hash bits (128 or 256).
+template <int R>
+__global__ __launch_bounds__(HATA_ENC_THREADS) void encode_unit_kernel(
+    const uint16_t* __restrict__ q, uint32_t* __restrict__ qcodes,
+    const uint16_t* __restrict__ K, const int32_t* __restrict__ seq_len, int append,
+    uint32_t* __restrict__ codes, const float* __restrict__ W_H,
+    int Hq, int Hkv, int G, int L_cap, int64_t sb, int64_t sh, int64_t sn) {
+    constexpr int PARTS = HATA_ENC_THREADS / R;
+    constexpr int PER = HATA_D / PARTS;
+    constexpr int WD = R / 32;
+    constexpr int VG = 4;  // vectors reduced per round
+    __shared__ float xs[17][HATA_D];
+    __shared__ double part[PARTS][VG][R];
+    const int tid = threadIdx.x;
+    const int u = blockIdx.x;
+    const int b = u / Hkv, h = u % Hkv;
+    const int j = tid % R, p = tid / R;
+    // weights first: PER independent loads per thread
+    float wv[PER];
+    {
+        const float* w = W_H + (int64_t)h * HATA_D * R + (int64_t)p * PER * R + j;
+#pragma unroll
+        for (int t = 0; t < PER; ++t) wv[t] = w[(int64_t)t * R];
+    }
+    int n_key = -1;
+    if (append) {
+        n_key = seq_len[b] - 1;
+        if (n_key < 0 || n_key >= L_cap) n_key = -1;
+    }
+    const int nv = G + (n_key >= 0 ? 1 : 0);
+    for (int i = tid; i < nv * HATA_D; i += HATA_ENC_THREADS) {
+        const int v = i / HATA_D, ch = i % HATA_D;
+        const uint16_t* x = (v < G) ? q + ((int64_t)b * Hq + (int64_t)h * G + v) * HATA_D
+                                    : K + b * sb + h * sh + (int64_t)n_key * sn;
+        xs[v][ch] = __uint_as_float((uint32_t)x[ch] << 16);
+    }
+    __syncthreads();
+    for (int v0 = 0; v0 < nv; v0 += VG) {
+        double acc[VG];
+#pragma unroll
+        for (int i = 0; i < VG; ++i) acc[i] = 0.0;
+#pragma unroll
+        for (int t = 0; t < PER; ++t) {
+            const double wd = (double)wv[t];
+#pragma unroll
+            for (int i = 0; i < VG; ++i)  // rows past nv are read (stale LDS) but never used
+                acc[i] += (double)xs[min(v0 + i, 16)][p * PER + t] * wd;
+        }
+#pragma unroll
+        for (int i = 0; i < VG; ++i) part[p][i][j] = acc[i];
+        __syncthreads();
+        if (tid < VG * R) {
+            const int i = tid / R;  // uniform over a wave (R >= 64)
+            const int v = v0 + i;
+            double y = 0.0;
+#pragma unroll
+            for (int pp = 0; pp < PARTS; ++pp) y += part[pp][i][j];
+            const unsigned long long mask = __ballot(y >= 0.0);
+            if ((tid & 63) == 0 && v < nv) {
+                uint32_t* dst = (v < G) ? qcodes + ((int64_t)b * Hq + (int64_t)h * G + v) * WD
+                                        : codes + ((int64_t)u * L_cap + n_key) * WD;
+                const int w0 = (j >> 6) * 2;
+                dst[w0] = (uint32_t)mask;
+                dst[w0 + 1] = (uint32_t)(mask >> 32);
+            }
+        }
+        __syncthreads();
+    }
+}
+
 // 64 keys per workgroup; thread = (key, word group).  The word group is uniform over a
 // wave, so the W_H reads are wave-uniform.  grid = (tiles, Hkv, B).
 __global__ __launch_bounds__(256) void encode_bulk_kernel(
@@ -136,6 +210,21 @@ hipError_t launch_encode_vectors(const hata_ctx* c, const void* q, uint32_t* qco
                                  int max_new, int from_seq_len, uint32_t* codes,
                                  const float* W_H, int B, hipStream_t s) {
     const hata_config& f = c->cfg;
+    // queries (+ the key at seq_len - 1) of a unit in one workgroup when a kernel for r exists
+    if (q && (!K || from_seq_len) && c->G <= 16 && (f.r == 128 || f.r == 256)) {
+        const int append = K ? 1 : 0;
+        if (f.r == 128)
+            hipLaunchKernelGGL((encode_unit_kernel<128>), dim3(B * f.Hkv), dim3(HATA_ENC_THREADS), 0, s,
+                               (const uint16_t*)q, qcodes, (const uint16_t*)K, start, append, codes,
+                               W_H, f.Hq, f.Hkv, c->G, f.L_cap, f.kv_stride_b, f.kv_stride_h,
+                               f.kv_stride_n);
+        else
+            hipLaunchKernelGGL((encode_unit_kernel<256>), dim3(B * f.Hkv), dim3(HATA_ENC_THREADS), 0, s,
+                               (const uint16_t*)q, qcodes, (const uint16_t*)K, start, append, codes,
+                               W_H, f.Hq, f.Hkv, c->G, f.L_cap, f.kv_stride_b, f.kv_stride_h,
+                               f.kv_stride_n);
+        return hipGetLastError();
+    }
     const int nq = q ? B * f.Hq : 0;
     const int nk = K ? B * f.Hkv * max_new : 0;
     if (nq + nk == 0) return hipSuccess;

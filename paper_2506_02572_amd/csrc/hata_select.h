@@ -87,7 +87,7 @@ __device__ __forceinline__ void unit_threshold(
         }
     }
     __syncthreads();
-    HATA_TRACE_AT(10, FUSED);
+    HATA_TRACE_AT(10, FUSED && blockIdx.y == 0 && blockIdx.z == 0);
     // T = smallest score value whose inclusive prefix count reaches keff; bmin = lowest occupied score
     const int seg = (NB + 255) / 256;
     const int s0 = tid * seg, s1 = min(NB, s0 + seg);
@@ -109,7 +109,7 @@ __device__ __forceinline__ void unit_threshold(
     }
     __syncthreads();
     const int T = S.T, need = S.need;
-    HATA_TRACE_AT(11, FUSED);
+    HATA_TRACE_AT(11, FUSED && blockIdx.y == 0 && blockIdx.z == 0);
     // per chunk: keys below T and keys equal to T, from columns [bmin / 8, T / 8] of its row
     if (T < NB) {
         const int col0 = min(S.bmin, T) / 8;
@@ -141,7 +141,7 @@ __device__ __forceinline__ void unit_threshold(
         }
     }
     __syncthreads();
-    HATA_TRACE_AT(12, FUSED);
+    HATA_TRACE_AT(12, FUSED && blockIdx.y == 0 && blockIdx.z == 0);
     // ordered offsets: ties are granted to chunks in cache order.  thread t owns chunks
     // [t*cpt, (t+1)*cpt)
     const int cpt = (nc + 255) / 256;
@@ -171,6 +171,7 @@ __device__ __forceinline__ void unit_threshold(
             eqb += S.c_eq[c];
         }
     }
+    HATA_TRACE_AT(13, FUSED && blockIdx.y == 0 && blockIdx.z == 0);
     if (tid == 0) {
         chunk_info_u[nc * 2 + 0] = keff;
         chunk_info_u[nc * 2 + 1] = 0;
