@@ -25,6 +25,16 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBPS = 8000.0
 
+# HBM bytes per launch of the scoring kernel, from the rocprofv3 --pmc runs summarised in
+# profiles/score_kernel_hbm_traffic.md: FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0 (factors from a plain
+# 256 MiB copy in the same runs).  None = not measured for that workload.
+SCORE_KERNEL_TRAFFIC_BYTES = {
+    "cfg2_llama3_8b_32k": 5080269,
+    "cfg3_batched_ragged": 45563085,
+    "cfg4_long_128k_r256": 36281549,
+    "cfg5_gqa8_append": 39114752,
+}
+
 
 def parse():
     ap = argparse.ArgumentParser()
@@ -36,6 +46,9 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=10.0)
+    ap.add_argument("--pmc-probe", action="store_true",
+                    help="run only a known-size copy kernel and the scoring kernel (for rocprofv3 --pmc "
+                         "FETCH_SIZE / WRITE_SIZE runs that calibrate and measure HBM traffic)")
     return ap.parse_args()
 
 
@@ -117,6 +130,28 @@ def main():
     enc_keys = int((inp.seq_len + w.append_steps).sum()) * w.Hkv
     enc_bytes = enc_keys * (w.d * 2 + w.r // 8)
     enc_flop = 2.0 * enc_keys * w.d * w.r
+
+    if args.pmc_probe:
+        # a plain copy of known size (reads and writes COPY_BYTES each) calibrates the counters;
+        # then the scoring launch, the same call the roofline leg times
+        COPY_BYTES = 256 << 20
+        src = torch.empty(COPY_BYTES // 4, dtype=torch.int32, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        qcodes_buf, scores_buf, _ = ctx.hata_step_buffers()
+        ctx.hata_encode_query(q_steps[0], W_H, w.B, qcodes_buf, stream)
+        torch.cuda.synchronize()
+        for i in range(10):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        for i in range(40):
+            ctx.hata_hamming_score(qcodes_buf, codes_all[i % n_layers], seq_steps[0], w.B, scores_buf, stream)
+        torch.cuda.synchronize()
+        code_bytes = int(inp.seq_len.sum() + (w.B if w.append_steps else 0)) * w.Hkv * (w.r // 8)
+        print(json.dumps({"pmc_probe": True, "workload": w.name, "copy_bytes_each_way": COPY_BYTES,
+                          "score_code_bytes": code_bytes,
+                          "score_write_bytes": code_bytes // (w.r // 8) * 2}))
+        ctx.close()
+        return
 
     # ---- the decode step
     n_combo = n_layers * n_step_variants // math.gcd(n_layers, n_step_variants)
@@ -212,7 +247,8 @@ def main():
         "host_wall_us_per_step": round(ms_wall * 1e3, 3),
         "roofline": {"bound": "hbm", "kernel": "score_kernel (hata_hamming_score)",
                      "achieved": round(score_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": round(score_gbps / HBM_PEAK_GBPS, 4), "traffic": None,
+                     "frac": round(score_gbps / HBM_PEAK_GBPS, 4),
+                     "traffic": SCORE_KERNEL_TRAFFIC_BYTES.get(w.name),
                      "algorithmic_bytes_per_launch": code_bytes,
                      "avg_launch_us": round(ms_score * 1e3, 3)},
         "encode_keys_bulk": {"us_per_layer": round(enc_ms * 1e3, 1), "keys": enc_keys,
