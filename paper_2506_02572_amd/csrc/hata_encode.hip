@@ -205,6 +205,133 @@ __global__ __launch_bounds__(256) void encode_bulk_kernel(
     }
 }
 
+// ---------------------------------------------------------------------------------------
+// Prefill key-code writer on the matrix cores (Alg. 1 l.2-5: K_H = HashEncode(K)).
+//
+// The projection [keys, 128] x [128, r] is a dense contraction, so it runs on MFMA
+// (v_mfma_f32_32x32x16_bf16).  K is bf16 already; the fp32 weights are split exactly into
+// three bf16 planes (hi + mid + lo carries all 24 mantissa bits), every bf16 x bf16 product is
+// exact in fp32, and only the fp32 accumulation rounds (~1e-6 relative) -- which is what keeps
+// the sign bits equal to an exact evaluation outside a |projection| < ~1e-5 band.
+//
+// Mapping: M = 32 hash columns (wave w owns columns [32 w, 32 w + 32), i.e. code word w),
+// N = 32 keys, K = channels.  A wave keeps its weight fragments (3 planes x 8 channel steps) in
+// registers for the whole launch; key rows are staged through LDS 128 at a time with coalesced
+// 128-bit loads (next stage prefetched into registers) and read back in the operand layout
+// (lane = key, 16 B of consecutive channels).  In the 32x32 result a lane holds 16 hash columns of
+// ONE key, so the sign bits are packed inside the lane and joined with the other half-wave.
+// grid = (key blocks, Hkv, B); R / 32 waves per workgroup.
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
+typedef __attribute__((ext_vector_type(16))) float f32x16_t;
+#define HATA_MFMA_STAGE 128   // keys per LDS stage
+#define HATA_MFMA_PITCH 136   // LDS row pitch in bf16 elements (272 B: rows shift by 4 banks)
+
+__device__ __forceinline__ uint32_t bf16_rne_bits(float f) { return f32_to_bf16(f); }
+
+template <int R>
+__global__ __launch_bounds__(R * 2) void encode_mfma_kernel(
+    const uint16_t* __restrict__ K, const float* __restrict__ W_H,
+    const int32_t* __restrict__ start, const int32_t* __restrict__ n_new,
+    uint32_t* __restrict__ codes, int Hkv, int L_cap, int keys_per_wg,
+    int64_t sb, int64_t sh, int64_t sn) {
+    constexpr int THREADS = R * 2;
+    constexpr int WD = R / 32;
+    constexpr int ROWS_PER_IT = THREADS / 16;              // rows staged per load instruction
+    constexpr int NIT = HATA_MFMA_STAGE / ROWS_PER_IT;     // load instructions per stage and thread
+    __shared__ __attribute__((aligned(16))) uint16_t tile[HATA_MFMA_STAGE * HATA_MFMA_PITCH];
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int m = lane & 31, half = lane >> 5;
+    const int h = blockIdx.y, b = blockIdx.z;
+    const int first = start[b];
+    const int cnt = min(n_new[b], L_cap - first);
+    const int kb0 = blockIdx.x * keys_per_wg;
+    if (first < 0 || kb0 >= cnt) return;
+    const int kb1 = min(kb0 + keys_per_wg, cnt);
+    const int64_t u = (int64_t)b * Hkv + h;
+    const uint16_t* Kb = K + b * sb + h * sh + (int64_t)first * sn;
+    uint32_t* cb = codes + (u * L_cap + first) * WD;
+
+    // weight fragments: a[plane][kk] holds W_H[h][kk*16 + 8*half + e][32 w + m], e = 0..7
+    bf16x8_t afrag[3][8];
+    {
+        const float* wp = W_H + (int64_t)h * HATA_D * R + w * 32 + m;
+#pragma unroll
+        for (int kk = 0; kk < 8; ++kk) {
+            uint32_t hi[4], mid[4], lo[4];
+#pragma unroll
+            for (int e2 = 0; e2 < 4; ++e2) {
+                uint32_t ph[2], pm[2], pl[2];
+#pragma unroll
+                for (int q = 0; q < 2; ++q) {
+                    const float wv = wp[(int64_t)(kk * 16 + 8 * half + 2 * e2 + q) * R];
+                    ph[q] = bf16_rne_bits(wv);
+                    const float r1 = wv - __uint_as_float(ph[q] << 16);
+                    pm[q] = bf16_rne_bits(r1);
+                    const float r2 = r1 - __uint_as_float(pm[q] << 16);
+                    pl[q] = bf16_rne_bits(r2);
+                }
+                hi[e2] = ph[0] | (ph[1] << 16);
+                mid[e2] = pm[0] | (pm[1] << 16);
+                lo[e2] = pl[0] | (pl[1] << 16);
+            }
+            afrag[0][kk] = __builtin_bit_cast(bf16x8_t, make_uint4(hi[0], hi[1], hi[2], hi[3]));
+            afrag[1][kk] = __builtin_bit_cast(bf16x8_t, make_uint4(mid[0], mid[1], mid[2], mid[3]));
+            afrag[2][kk] = __builtin_bit_cast(bf16x8_t, make_uint4(lo[0], lo[1], lo[2], lo[3]));
+        }
+    }
+
+    // stage loader: thread -> (row = it * ROWS_PER_IT + tid / 16, 16-byte piece tid % 16)
+    const int lrow = tid >> 4, lsub = tid & 15;
+    uint4 pre[NIT];
+    auto load_stage = [&](int k0) {
+#pragma unroll
+        for (int it = 0; it < NIT; ++it) {
+            const int key = k0 + it * ROWS_PER_IT + lrow;
+            pre[it] = make_uint4(0, 0, 0, 0);
+            if (key < kb1) pre[it] = *reinterpret_cast<const uint4*>(Kb + (int64_t)key * sn + lsub * 8);
+        }
+    };
+    load_stage(kb0);
+    for (int k0 = kb0; k0 < kb1; k0 += HATA_MFMA_STAGE) {
+        __syncthreads();  // the previous stage has been consumed
+#pragma unroll
+        for (int it = 0; it < NIT; ++it)
+            *reinterpret_cast<uint4*>(&tile[(it * ROWS_PER_IT + lrow) * HATA_MFMA_PITCH + lsub * 8]) = pre[it];
+        __syncthreads();
+        if (k0 + HATA_MFMA_STAGE < kb1) load_stage(k0 + HATA_MFMA_STAGE);  // overlaps the MFMAs below
+
+        f32x16_t acc[4];
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[t][i] = 0.f;
+#pragma unroll
+        for (int kk = 0; kk < 8; ++kk) {
+            bf16x8_t bfrag[4];
+#pragma unroll
+            for (int t = 0; t < 4; ++t)
+                bfrag[t] = *reinterpret_cast<const bf16x8_t*>(
+                    &tile[(t * 32 + m) * HATA_MFMA_PITCH + kk * 16 + 8 * half]);
+#pragma unroll
+            for (int p = 0; p < 3; ++p)
+#pragma unroll
+                for (int t = 0; t < 4; ++t)
+                    acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(afrag[p][kk], bfrag[t], acc[t], 0, 0, 0);
+        }
+        // sign bits: this lane holds hash columns 8*(i/4) + 4*half + i%4 of key t*32 + m
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            uint32_t word = 0;
+#pragma unroll
+            for (int i = 0; i < 16; ++i)
+                word |= (acc[t][i] >= 0.f ? 1u : 0u) << (8 * (i / 4) + 4 * half + (i % 4));
+            word |= (uint32_t)__shfl_xor((int)word, 32, 64);
+            const int key = k0 + t * 32 + m;
+            if (half == 0 && key < kb1) cb[(int64_t)key * WD + w] = word;
+        }
+    }
+}
+
 hipError_t launch_encode_vectors(const hata_ctx* c, const void* q, uint32_t* qcodes,
                                  const void* K, const int32_t* start, const int32_t* n_new,
                                  int max_new, int from_seq_len, uint32_t* codes,
@@ -239,8 +366,23 @@ hipError_t launch_encode_bulk(const hata_ctx* c, const void* K, const float* W_H
                               const int32_t* start, const int32_t* n_new, int B, int max_new,
                               uint32_t* codes, hipStream_t s) {
     const hata_config& f = c->cfg;
+    if (max_new <= 0 || B <= 0) return hipSuccess;
+    if (f.r == 128 || f.r == 256) {
+        // key blocks of 512..4096 keys: at least ~512 workgroups when the prefill is long enough
+        int kpw = 4096;
+        while (kpw > 512 && (int64_t)((max_new + kpw - 1) / kpw) * f.Hkv * B < 512) kpw >>= 1;
+        const dim3 grid((max_new + kpw - 1) / kpw, f.Hkv, B);
+        if (f.r == 128)
+            hipLaunchKernelGGL((encode_mfma_kernel<128>), grid, dim3(256), 0, s, (const uint16_t*)K,
+                               W_H, start, n_new, codes, f.Hkv, f.L_cap, kpw, f.kv_stride_b,
+                               f.kv_stride_h, f.kv_stride_n);
+        else
+            hipLaunchKernelGGL((encode_mfma_kernel<256>), grid, dim3(512), 0, s, (const uint16_t*)K,
+                               W_H, start, n_new, codes, f.Hkv, f.L_cap, kpw, f.kv_stride_b,
+                               f.kv_stride_h, f.kv_stride_n);
+        return hipGetLastError();
+    }
     const int tiles = (max_new + 63) / 64;
-    if (tiles <= 0 || B <= 0) return hipSuccess;
     hipLaunchKernelGGL(encode_bulk_kernel, dim3(tiles, f.Hkv, B), dim3(256), 0, s,
                        (const uint16_t*)K, W_H, start, n_new, codes, f.Hkv, f.r, c->Wd, f.L_cap,
                        f.kv_stride_b, f.kv_stride_h, f.kv_stride_n);
