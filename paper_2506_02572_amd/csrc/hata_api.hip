@@ -57,6 +57,12 @@ int make_plan(const hata_config* f, Plan* p) {
     int chunk = 4096;
     while (chunk > 1024 && units * ((f->L_cap + chunk - 1) / chunk) < target_wgs) chunk >>= 1;
     while (chunk < 8192 && (f->L_cap + chunk - 1) / chunk > 1024) chunk <<= 1;
+    // tuning overrides (launch-shape sweeps): HATA_TUNE_CHUNK in {1024,2048,4096,8192},
+    // HATA_TUNE_ROWS in {16..256, power of two}; invalid values are ignored
+    if (const char* e = getenv("HATA_TUNE_CHUNK")) {
+        const int v = atoi(e);
+        if ((v == 1024 || v == 2048 || v == 4096 || v == 8192) && (f->L_cap + v - 1) / v <= 1024) chunk = v;
+    }
     p->chunk = chunk;
     p->n_chunks = (f->L_cap + chunk - 1) / chunk;
     if (p->n_chunks > 1024) return HATA_EUNSUPPORTED;  // L_cap above 8M rows
@@ -65,6 +71,10 @@ int make_plan(const hata_config* f, Plan* p) {
     const int64_t attn_units = units * (G / p->HT);
     int rows = 256;
     while (rows > 16 && attn_units * ((f->k_max + rows - 1) / rows) < 512) rows >>= 1;
+    if (const char* e = getenv("HATA_TUNE_ROWS")) {
+        const int v = atoi(e);
+        if (v >= 16 && v <= 256 && (v & (v - 1)) == 0) rows = v;
+    }
     while (rows < 256 && (f->k_max + rows - 1) / rows > 256) rows <<= 1;
     p->sparse_rows = rows;
     p->sparse_splits = (f->k_max + rows - 1) / rows;

@@ -31,6 +31,9 @@ __device__ __forceinline__ float dot2_bf16(uint32_t a, uint32_t b, float c) {
 }
 
 #define HATA_NEG_INF (-__builtin_huge_valf())
+// 2^x for x <= 0 in one instruction (v_exp_f32, ~1 ulp; results below the normal range flush to 0,
+// which is what a vanishing softmax weight should do; 2^-inf = 0)
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 // partial layout per (query head, split): [0] = running max (log2 domain), [1] = sum, [2..2+d) = acc
 #define HATA_PSTRIDE (HATA_D + 2)
 #define HATA_MAX_ROWS_PER_WG 256
@@ -199,7 +202,7 @@ __global__ __launch_bounds__(256) void attn_kernel(const AttnArgs a) {
             m_tile[g] = rows_max4(m_tile[g]);
             const float m_new = fmaxf(m_run[g], m_tile[g]);
             // m_new == -inf only while no valid row has been seen: keep the state untouched
-            const float alpha = (m_new == HATA_NEG_INF) ? 1.f : exp2f(m_run[g] - m_new);
+            const float alpha = (m_new == HATA_NEG_INF) ? 1.f : fast_exp2(m_run[g] - m_new);
             l_run[g] *= alpha;
 #pragma unroll
             for (int e = 0; e < 8; ++e) acc[g][e] *= alpha;
@@ -214,7 +217,7 @@ __global__ __launch_bounds__(256) void attn_kernel(const AttnArgs a) {
             vf[6] = bf16_lo(vv[it].w); vf[7] = bf16_hi(vv[it].w);
 #pragma unroll
             for (int g = 0; g < HT; ++g) {
-                const float p = ok[it] ? exp2f(s[it][g] - m_run[g]) : 0.f;
+                const float p = ok[it] ? fast_exp2(s[it][g] - m_run[g]) : 0.f;
                 l_run[g] += p;
 #pragma unroll
                 for (int e = 0; e < 8; ++e) acc[g][e] = fmaf(p, vf[e], acc[g][e]);
@@ -246,7 +249,7 @@ __global__ __launch_bounds__(256) void attn_kernel(const AttnArgs a) {
         const float M = fmaxf(fmaxf(m0, m1), fmaxf(m2, m3));
         float av = 0.f, l = 0.f;
         if (M != HATA_NEG_INF) {
-            const float f0 = exp2f(m0 - M), f1 = exp2f(m1 - M), f2 = exp2f(m2 - M), f3 = exp2f(m3 - M);
+            const float f0 = fast_exp2(m0 - M), f1 = fast_exp2(m1 - M), f2 = fast_exp2(m2 - M), f3 = fast_exp2(m3 - M);
             av = f0 * sm_acc[0][g][ch] + f1 * sm_acc[1][g][ch] + f2 * sm_acc[2][g][ch] + f3 * sm_acc[3][g][ch];
             l = f0 * sm_l[0][g] + f1 * sm_l[1][g] + f2 * sm_l[2][g] + f3 * sm_l[3][g];
         }
@@ -302,7 +305,7 @@ __global__ __launch_bounds__(256) void attn_kernel(const AttnArgs a) {
         const float M = wave_max64(m_loc);
         float l_loc = 0.f;
         for (int s2 = lane; s2 < ns; s2 += 64) {
-            const float w = (M == HATA_NEG_INF) ? 0.f : exp2f(ld_dev(pp + (int64_t)s2 * HATA_PSTRIDE) - M);
+            const float w = (M == HATA_NEG_INF) ? 0.f : fast_exp2(ld_dev(pp + (int64_t)s2 * HATA_PSTRIDE) - M);
             sm_w[g * nsp + s2] = w;
             l_loc = fmaf(w, ld_dev(pp + (int64_t)s2 * HATA_PSTRIDE + 1), l_loc);
         }
