@@ -205,7 +205,7 @@ def main():
         t0 = time.perf_counter()
         ref = O.decode_step(q0, inp.K, inp.V, inp.W_H, codes_o, seq0, inp.k, w.k_max, scale, append=True)
         t1 = time.perf_counter() - t0
-        reps = int(max(1, min(50, args.cpu_seconds / max(t1, 1e-6))))
+        reps = int(max(1, min(5000, args.cpu_seconds / max(t1, 1e-6))))
         t0 = time.perf_counter()
         for _ in range(reps):
             O.decode_step(q0, inp.K, inp.V, inp.W_H, codes_o, seq0, inp.k, w.k_max, scale, append=True)
