@@ -108,6 +108,15 @@ __global__ __launch_bounds__(256) void attn_kernel(const AttnArgs a) {
     const uint16_t* Vb = a.V + b * a.sb + h * a.sh;
     const int32_t* ip = (MODE == ROWS_IDX) ? a.idx_in + u * a.k_max : nullptr;
 
+    // this lane's 8 query elements of each head, kept as packed bf16 pairs (loaded
+    // first: nothing below depends on them until the rows are known)
+    uint32_t qr[HT][4];
+#pragma unroll
+    for (int g = 0; g < HT; ++g) {
+        const uint4 v = *reinterpret_cast<const uint4*>(a.q + ((int64_t)b * a.Hq + hq0 + g) * HATA_D + sub * 8);
+        qr[g][0] = v.x; qr[g][1] = v.y; qr[g][2] = v.z; qr[g][3] = v.w;
+    }
+
     if constexpr (MODE == ROWS_SELECT) {
         // ordered compaction of the chunks that hold positions [row_begin, row_end)
         const int L = clampi(a.seq_len[b], 0, a.L_cap);
@@ -142,13 +151,6 @@ __global__ __launch_bounds__(256) void attn_kernel(const AttnArgs a) {
         __syncthreads();
     }
     TA(23);
-    // this lane's 8 query elements of each head, kept as packed bf16 pairs
-    uint32_t qr[HT][4];
-#pragma unroll
-    for (int g = 0; g < HT; ++g) {
-        const uint4 v = *reinterpret_cast<const uint4*>(a.q + ((int64_t)b * a.Hq + hq0 + g) * HATA_D + sub * 8);
-        qr[g][0] = v.x; qr[g][1] = v.y; qr[g][2] = v.z; qr[g][3] = v.w;
-    }
     float m_run[HT], l_run[HT], acc[HT][8];
 #pragma unroll
     for (int g = 0; g < HT; ++g) {

@@ -91,14 +91,18 @@ __device__ __forceinline__ float rows_max4(float v) {
 __device__ __forceinline__ float wave_sum64(float v) { return rows_sum4(row_sum16(v)); }
 __device__ __forceinline__ float wave_max64(float v) { return rows_max4(row_max16(v)); }
 
-// wave-level inclusive scan (sum) over 64 lanes
+// wave-level inclusive scan (sum) over 64 lanes, in the VALU: Hillis-Steele inside each row of
+// 16 lanes with DPP row shifts, then the row totals are carried across rows with the two
+// row-broadcast controls (lane 15 of a row into the next row; lane 31 into the upper half)
+#define HATA_DPP_U(v, ctrl, rows) \
+    (uint32_t)__builtin_amdgcn_update_dpp(0, (int)(v), (ctrl), (rows), 0xf, false)
 __device__ __forceinline__ uint32_t wave_incl_scan(uint32_t v) {
-    const int lane = threadIdx.x & 63;
-#pragma unroll
-    for (int o = 1; o < 64; o <<= 1) {
-        uint32_t t = __shfl_up(v, o, 64);
-        if (lane >= o) v += t;
-    }
+    v += HATA_DPP_U(v, 0x111, 0xf);  // row_shr:1
+    v += HATA_DPP_U(v, 0x112, 0xf);  // row_shr:2
+    v += HATA_DPP_U(v, 0x114, 0xf);  // row_shr:4
+    v += HATA_DPP_U(v, 0x118, 0xf);  // row_shr:8
+    v += HATA_DPP_U(v, 0x142, 0xa);  // row_bcast:15 into rows 1 and 3
+    v += HATA_DPP_U(v, 0x143, 0xc);  // row_bcast:31 into rows 2 and 3
     return v;
 }
 
