@@ -19,23 +19,11 @@
 #include "hata_device.h"
 #include "hata_internal.h"
 #include "hata_select.h"
+#include "hata_attn_core.h"
 #include "hata_trace.h"
 
 namespace hata {
 
-typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
-
-__device__ __forceinline__ float dot2_bf16(uint32_t a, uint32_t b, float c) {
-    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, a),
-                                           __builtin_bit_cast(bf16x2_t, b), c, false);
-}
-
-#define HATA_NEG_INF (-__builtin_huge_valf())
-// 2^x for x <= 0 in one instruction (v_exp_f32, ~1 ulp; results below the normal range flush to 0,
-// which is what a vanishing softmax weight should do; 2^-inf = 0)
-__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
-// partial layout per (query head, split): [0] = running max (log2 domain), [1] = sum, [2..2+d) = acc
-#define HATA_PSTRIDE (HATA_D + 2)
 #define HATA_MAX_ROWS_PER_WG 256
 
 enum { ROWS_IDX = 0, ROWS_DENSE = 1, ROWS_SELECT = 2 };
@@ -61,18 +49,14 @@ struct AttnArgs {
     float scale_log2;
 };
 
-// grid = (splits, Hkv * (G / HT), B); 256 threads = 4 waves; lane = (row group rg = lane / 16,
-// sub = lane % 16 -> elements [8 sub, 8 sub + 8) of a row).
+// grid = (splits, Hkv * (G / HT), B); 256 threads.
 template <int HT, int MODE>
 __global__ __launch_bounds__(256) void attn_kernel(const AttnArgs a) {
-    __shared__ float sm_m[4][HT];
-    __shared__ float sm_l[4][HT];
-    __shared__ float sm_acc[4][HT][HATA_D];
+    __shared__ __attribute__((aligned(16))) AttnLds<HT> S;
     __shared__ int s_rows[MODE == ROWS_SELECT ? HATA_MAX_ROWS_PER_WG : 1];
     __shared__ uint32_t scan4[4];
     __shared__ int s_clo, s_chi, s_last;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int sub = lane & 15, rg = lane >> 4;
+    const int tid = threadIdx.x;
     const int split = blockIdx.x;
     const int tiles = a.G / HT;
     const int h = blockIdx.y / tiles;
@@ -88,6 +72,8 @@ __global__ __launch_bounds__(256) void attn_kernel(const AttnArgs a) {
     else if (MODE == ROWS_IDX) count = clampi(a.count_src[b], 0, a.k_max);
     else count = clampi(a.unit_info[u * 2 + 1], 0, a.k_max);
     const int row_begin = split * a.rows_per_wg;
+    uint16_t* outp = a.out + ((int64_t)b * a.Hq + hq0) * HATA_D;
+    float* outp32 = a.out_f32 ? a.out_f32 + ((int64_t)b * a.Hq + hq0) * HATA_D : nullptr;
     if (MODE == ROWS_SELECT && ht == 0) {
         // slots of the index list past the selected count hold -1
         const int p0 = max(count, row_begin), p1 = min(row_begin + a.rows_per_wg, a.k_max);
@@ -96,9 +82,8 @@ __global__ __launch_bounds__(256) void attn_kernel(const AttnArgs a) {
     if (row_begin >= count) {
         if (count == 0 && split == 0) {  // no row at all: the output is zero
             for (int i = tid; i < HT * HATA_D; i += 256) {
-                const int64_t o = ((int64_t)b * a.Hq + hq0) * HATA_D + i;
-                a.out[o] = 0;
-                if (a.out_f32) a.out_f32[o] = 0.f;
+                outp[i] = 0;
+                if (outp32) outp32[i] = 0.f;
             }
         }
         return;
@@ -107,15 +92,9 @@ __global__ __launch_bounds__(256) void attn_kernel(const AttnArgs a) {
     const uint16_t* Kb = a.K + b * a.sb + h * a.sh;
     const uint16_t* Vb = a.V + b * a.sb + h * a.sh;
     const int32_t* ip = (MODE == ROWS_IDX) ? a.idx_in + u * a.k_max : nullptr;
-
-    // this lane's 8 query elements of each head, kept as packed bf16 pairs (loaded
-    // first: nothing below depends on them until the rows are known)
+    // query fragments first: nothing below depends on them until the rows are known
     uint32_t qr[HT][4];
-#pragma unroll
-    for (int g = 0; g < HT; ++g) {
-        const uint4 v = *reinterpret_cast<const uint4*>(a.q + ((int64_t)b * a.Hq + hq0 + g) * HATA_D + sub * 8);
-        qr[g][0] = v.x; qr[g][1] = v.y; qr[g][2] = v.z; qr[g][3] = v.w;
-    }
+    attn_load_q<HT>(a.q + ((int64_t)b * a.Hq + hq0) * HATA_D, qr);
 
     if constexpr (MODE == ROWS_SELECT) {
         // ordered compaction of the chunks that hold positions [row_begin, row_end)
@@ -151,127 +130,22 @@ __global__ __launch_bounds__(256) void attn_kernel(const AttnArgs a) {
         __syncthreads();
     }
     TA(23);
-    float m_run[HT], l_run[HT], acc[HT][8];
-#pragma unroll
-    for (int g = 0; g < HT; ++g) {
-        m_run[g] = HATA_NEG_INF; l_run[g] = 0.f;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) acc[g][e] = 0.f;
-    }
-
-    constexpr int IT = 4;  // 4 iterations x 16 rows = 64 rows per tile
-    for (int tile = row_begin; tile < row_end; tile += 16 * IT) {
-        uint4 kv[IT], vv[IT];
-        bool ok[IT];
-#pragma unroll
-        for (int it = 0; it < IT; ++it) {
-            const int row = tile + it * 16 + wave * 4 + rg;
-            ok[it] = row < row_end;
-            int n = 0;
-            if (ok[it]) {
-                if (MODE == ROWS_DENSE) n = row;
-                else if (MODE == ROWS_IDX) n = ip[row];
-                else n = s_rows[row - row_begin];
-            }
-            ok[it] = ok[it] && n >= 0 && n < a.L_cap;
-            kv[it] = make_uint4(0, 0, 0, 0);
-            vv[it] = make_uint4(0, 0, 0, 0);
-            if (ok[it]) {
-                const int64_t o = (int64_t)n * a.sn + sub * 8;
-                kv[it] = *reinterpret_cast<const uint4*>(Kb + o);
-                vv[it] = *reinterpret_cast<const uint4*>(Vb + o);
-            }
-        }
-        float s[IT][HT];
-        float m_tile[HT];
-#pragma unroll
-        for (int g = 0; g < HT; ++g) m_tile[g] = HATA_NEG_INF;
-#pragma unroll
-        for (int it = 0; it < IT; ++it) {
-#pragma unroll
-            for (int g = 0; g < HT; ++g) {
-                float d = dot2_bf16(qr[g][0], kv[it].x, 0.f);
-                d = dot2_bf16(qr[g][1], kv[it].y, d);
-                d = dot2_bf16(qr[g][2], kv[it].z, d);
-                d = dot2_bf16(qr[g][3], kv[it].w, d);
-                d = row_sum16(d);
-                s[it][g] = ok[it] ? d * a.scale_log2 : HATA_NEG_INF;
-                m_tile[g] = fmaxf(m_tile[g], s[it][g]);
-            }
-        }
-#pragma unroll
-        for (int g = 0; g < HT; ++g) {
-            m_tile[g] = rows_max4(m_tile[g]);
-            const float m_new = fmaxf(m_run[g], m_tile[g]);
-            // m_new == -inf only while no valid row has been seen: keep the state untouched
-            const float alpha = (m_new == HATA_NEG_INF) ? 1.f : fast_exp2(m_run[g] - m_new);
-            l_run[g] *= alpha;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) acc[g][e] *= alpha;
-            m_run[g] = m_new;
-        }
-#pragma unroll
-        for (int it = 0; it < IT; ++it) {
-            float vf[8];
-            vf[0] = bf16_lo(vv[it].x); vf[1] = bf16_hi(vv[it].x);
-            vf[2] = bf16_lo(vv[it].y); vf[3] = bf16_hi(vv[it].y);
-            vf[4] = bf16_lo(vv[it].z); vf[5] = bf16_hi(vv[it].z);
-            vf[6] = bf16_lo(vv[it].w); vf[7] = bf16_hi(vv[it].w);
-#pragma unroll
-            for (int g = 0; g < HT; ++g) {
-                const float p = ok[it] ? fast_exp2(s[it][g] - m_run[g]) : 0.f;
-                l_run[g] += p;
-#pragma unroll
-                for (int e = 0; e < 8; ++e) acc[g][e] = fmaf(p, vf[e], acc[g][e]);
-            }
-        }
-    }
+    attn_rows<HT>(qr, Kb, Vb, a.sn, a.L_cap, row_begin, row_end, a.scale_log2,
+                  [&](int row) {
+                      if (MODE == ROWS_DENSE) return row;
+                      if (MODE == ROWS_IDX) return (int)ip[row];
+                      return s_rows[row - row_begin];
+                  }, S);
     TA(24);
-    // combine the four row groups of the wave (all share m_run)
-#pragma unroll
-    for (int g = 0; g < HT; ++g) {
-        l_run[g] = rows_sum4(l_run[g]);
-#pragma unroll
-        for (int e = 0; e < 8; ++e) acc[g][e] = rows_sum4(acc[g][e]);
-    }
-    if (rg == 0) {
-#pragma unroll
-        for (int g = 0; g < HT; ++g) {
-            if (sub == 0) { sm_m[wave][g] = m_run[g]; sm_l[wave][g] = l_run[g]; }
-#pragma unroll
-            for (int e = 0; e < 8; ++e) sm_acc[wave][g][sub * 8 + e] = acc[g][e];
-        }
-    }
-    __syncthreads();
     const int ns = (count + a.rows_per_wg - 1) / a.rows_per_wg;  // workgroups that contribute
-    // combine the four waves: thread -> (head, channel)
-    for (int i = tid; i < HT * HATA_D; i += 256) {
-        const int g = i / HATA_D, ch = i % HATA_D;
-        const float m0 = sm_m[0][g], m1 = sm_m[1][g], m2 = sm_m[2][g], m3 = sm_m[3][g];
-        const float M = fmaxf(fmaxf(m0, m1), fmaxf(m2, m3));
-        float av = 0.f, l = 0.f;
-        if (M != HATA_NEG_INF) {
-            const float f0 = fast_exp2(m0 - M), f1 = fast_exp2(m1 - M), f2 = fast_exp2(m2 - M), f3 = fast_exp2(m3 - M);
-            av = f0 * sm_acc[0][g][ch] + f1 * sm_acc[1][g][ch] + f2 * sm_acc[2][g][ch] + f3 * sm_acc[3][g][ch];
-            l = f0 * sm_l[0][g] + f1 * sm_l[1][g] + f2 * sm_l[2][g] + f3 * sm_l[3][g];
-        }
-        if (ns == 1) {  // single slice: this is the result
-            const float o = l > 0.f ? av / l : 0.f;
-            const int64_t oo = ((int64_t)b * a.Hq + hq0 + g) * HATA_D + ch;
-            a.out[oo] = (uint16_t)f32_to_bf16(o);
-            if (a.out_f32) a.out_f32[oo] = o;
-        } else {
-            float* pp = a.partials + (((int64_t)b * a.Hq + hq0 + g) * a.n_splits + split) * HATA_PSTRIDE;
-            st_dev(pp + 2 + ch, av);
-            if (ch == 0) { st_dev(pp, M); st_dev(pp + 1, l); }
-        }
-    }
+    const int64_t head_stride = (int64_t)a.n_splits * HATA_PSTRIDE;
+    float* part0 = a.partials + ((int64_t)b * a.Hq + hq0) * head_stride;
+    attn_emit<HT>(S, ns == 1, outp, outp32, part0 + (int64_t)split * HATA_PSTRIDE, head_stride);
     if (ns == 1) return;
     // count the finished slices; the last workgroup merges them (partials are written with
     // write-through stores and read back with device-coherent loads)
     TA(25);
     wait_stores();
-    TA(26);
     __syncthreads();
     if (tid == 0) {
         uint32_t* cnt = a.counter + u * tiles + ht;
@@ -284,67 +158,7 @@ __global__ __launch_bounds__(256) void attn_kernel(const AttnArgs a) {
     TA(27);
     if (!s_last) return;
     TL(30);
-    // Merge.  Every load of the merge is issued before the first wait: each thread pulls the
-    // first 16 slices of its NO output channels into registers (later slices, ns > 16, batch by
-    // batch), while one wave per head turns the (max, sum) pairs of the slices into normalised
-    // weights w[g][s] = exp2(m_s - M) / sum_s' exp2(m_s' - M) l_s' in LDS.
-    constexpr int NO = (HT * HATA_D + 255) / 256;  // outputs (head, channel) per thread
-    float* sm_w = &sm_acc[0][0][0];                // [HT][nsp], nsp <= 256
-    const int nsp = (ns + 3) & ~3;
-    float av[NO][16];
-#pragma unroll
-    for (int r = 0; r < NO; ++r) {
-        const int i = min(tid + 256 * r, HT * HATA_D - 1);
-        const int g = i / HATA_D, ch = i % HATA_D;
-        const float* pp = a.partials + ((int64_t)b * a.Hq + hq0 + g) * a.n_splits * HATA_PSTRIDE + 2 + ch;
-#pragma unroll
-        for (int j = 0; j < 16; ++j) av[r][j] = ld_dev(pp + (int64_t)min(j, ns - 1) * HATA_PSTRIDE);
-    }
-    for (int g = wave; g < HT; g += 4) {
-        const float* pp = a.partials + ((int64_t)b * a.Hq + hq0 + g) * a.n_splits * HATA_PSTRIDE;
-        float m_loc = HATA_NEG_INF;
-        for (int s2 = lane; s2 < ns; s2 += 64) m_loc = fmaxf(m_loc, ld_dev(pp + (int64_t)s2 * HATA_PSTRIDE));
-        const float M = wave_max64(m_loc);
-        float l_loc = 0.f;
-        for (int s2 = lane; s2 < ns; s2 += 64) {
-            const float w = (M == HATA_NEG_INF) ? 0.f : fast_exp2(ld_dev(pp + (int64_t)s2 * HATA_PSTRIDE) - M);
-            sm_w[g * nsp + s2] = w;
-            l_loc = fmaf(w, ld_dev(pp + (int64_t)s2 * HATA_PSTRIDE + 1), l_loc);
-        }
-        const float Lsum = wave_sum64(l_loc);
-        const float inv = Lsum > 0.f ? 1.f / Lsum : 0.f;
-        for (int s2 = lane; s2 < nsp; s2 += 64) sm_w[g * nsp + s2] = (s2 < ns) ? sm_w[g * nsp + s2] * inv : 0.f;
-    }
-    __syncthreads();
-#pragma unroll
-    for (int r = 0; r < NO; ++r) {
-        const int i = tid + 256 * r;
-        if (i < HT * HATA_D) {
-            const int g = i / HATA_D, ch = i % HATA_D;
-            const float4* w4 = reinterpret_cast<const float4*>(sm_w + g * nsp);
-            float A = 0.f;
-#pragma unroll
-            for (int j4 = 0; j4 < 4; ++j4) {
-                if (j4 * 4 < nsp) {  // weights of slices >= ns are zero
-                    const float4 w = w4[j4];
-                    A = fmaf(w.x, av[r][4 * j4], A); A = fmaf(w.y, av[r][4 * j4 + 1], A);
-                    A = fmaf(w.z, av[r][4 * j4 + 2], A); A = fmaf(w.w, av[r][4 * j4 + 3], A);
-                }
-            }
-            const float* pp = a.partials + ((int64_t)b * a.Hq + hq0 + g) * a.n_splits * HATA_PSTRIDE + 2 + ch;
-            for (int s0 = 16; s0 < ns; s0 += 16) {
-                float bv[16];
-#pragma unroll
-                for (int j = 0; j < 16; ++j) bv[j] = ld_dev(pp + (int64_t)min(s0 + j, ns - 1) * HATA_PSTRIDE);
-#pragma unroll
-                for (int j = 0; j < 16; ++j)
-                    if (s0 + j < ns) A = fmaf(sm_w[g * nsp + s0 + j], bv[j], A);
-            }
-            const int64_t oo = ((int64_t)b * a.Hq + hq0 + g) * HATA_D + ch;
-            a.out[oo] = (uint16_t)f32_to_bf16(A);
-            if (a.out_f32) a.out_f32[oo] = A;
-        }
-    }
+    attn_merge<HT>(S, part0, head_stride, ns, outp, outp32);
     TL(31);
 #undef TA
 #undef TL

@@ -1,0 +1,245 @@
+// Device-side core of decode attention over a list of cache rows (Alg. 3 of the paper: Gather +
+// Attention with the gather fused; Eq. 2 third line, scale of Eq. 1), shared by the stand-alone
+// attention kernels and the cooperative decode-step kernel.
+//
+// A workgroup of 256 threads (4 waves) handles a slice of a unit's rows for HT query heads of the
+// group at once, so each K/V row is read once for all of them.  A row is 256 B = 16 lanes x 128-bit:
+// lane = (row group rg = lane / 16, sub = lane % 16 -> elements [8 sub, 8 sub + 8) of a row), a wave
+// reads four whole rows per load instruction.  q.k uses v_dot2_f32_bf16; reductions over the 16
+// lanes of a row use DPP, over the 4 row groups the lane-swap instructions.  Every wave keeps its
+// own online-softmax state (no workgroup barrier inside the row loop); the four states are combined
+// through LDS at the end.  bf16 inputs, fp32 softmax and accumulation.
+#pragma once
+#include "hata_device.h"
+
+namespace hata {
+
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+
+__device__ __forceinline__ float dot2_bf16(uint32_t a, uint32_t b, float c) {
+    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, a),
+                                           __builtin_bit_cast(bf16x2_t, b), c, false);
+}
+
+#define HATA_NEG_INF (-__builtin_huge_valf())
+// 2^x for x <= 0 in one instruction (v_exp_f32, ~1 ulp; results below the normal range flush to 0,
+// which is what a vanishing softmax weight should do; 2^-inf = 0)
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+// partial layout per (query head, slice): [0] = running max (log2 domain), [1] = sum, [2..2+d) = acc
+#define HATA_PSTRIDE (HATA_D + 2)
+
+template <int HT>
+struct AttnLds {
+    float m[4][HT];
+    float l[4][HT];
+    float acc[4][HT][HATA_D];  // reused by the merge for the slice weights
+};
+
+// this lane's 8 query elements of each of the HT heads starting at q0 (packed bf16 pairs)
+template <int HT>
+__device__ __forceinline__ void attn_load_q(const uint16_t* __restrict__ q0, uint32_t (&qr)[HT][4]) {
+    const int sub = threadIdx.x & 15;
+#pragma unroll
+    for (int g = 0; g < HT; ++g) {
+        const uint4 v = *reinterpret_cast<const uint4*>(q0 + (int64_t)g * HATA_D + sub * 8);
+        qr[g][0] = v.x; qr[g][1] = v.y; qr[g][2] = v.z; qr[g][3] = v.w;
+    }
+}
+
+// Attention of the HT heads over rows [row_begin, row_end): row_of(row) gives the cache row (< 0 or
+// >= L_cap: skipped).  On return (after a workgroup barrier) S holds the four waves' states.
+// Must be called by all 256 threads.
+template <int HT, typename RowOf>
+__device__ __forceinline__ void attn_rows(
+    const uint32_t (&qr)[HT][4], const uint16_t* __restrict__ Kb, const uint16_t* __restrict__ Vb,
+    int64_t sn, int L_cap, int row_begin, int row_end, float scale_log2, RowOf row_of,
+    AttnLds<HT>& S) {
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int sub = lane & 15, rg = lane >> 4;
+    float m_run[HT], l_run[HT], acc[HT][8];
+#pragma unroll
+    for (int g = 0; g < HT; ++g) {
+        m_run[g] = HATA_NEG_INF; l_run[g] = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[g][e] = 0.f;
+    }
+    constexpr int IT = 4;  // 4 iterations x 16 rows = 64 rows per tile
+    for (int tile = row_begin; tile < row_end; tile += 16 * IT) {
+        uint4 kv[IT], vv[IT];
+        bool ok[IT];
+#pragma unroll
+        for (int it = 0; it < IT; ++it) {
+            const int row = tile + it * 16 + wave * 4 + rg;
+            ok[it] = row < row_end;
+            int n = 0;
+            if (ok[it]) n = row_of(row);
+            ok[it] = ok[it] && n >= 0 && n < L_cap;
+            kv[it] = make_uint4(0, 0, 0, 0);
+            vv[it] = make_uint4(0, 0, 0, 0);
+            if (ok[it]) {
+                const int64_t o = (int64_t)n * sn + sub * 8;
+                kv[it] = *reinterpret_cast<const uint4*>(Kb + o);
+                vv[it] = *reinterpret_cast<const uint4*>(Vb + o);
+            }
+        }
+        float s[IT][HT];
+        float m_tile[HT];
+#pragma unroll
+        for (int g = 0; g < HT; ++g) m_tile[g] = HATA_NEG_INF;
+#pragma unroll
+        for (int it = 0; it < IT; ++it) {
+#pragma unroll
+            for (int g = 0; g < HT; ++g) {
+                float d = dot2_bf16(qr[g][0], kv[it].x, 0.f);
+                d = dot2_bf16(qr[g][1], kv[it].y, d);
+                d = dot2_bf16(qr[g][2], kv[it].z, d);
+                d = dot2_bf16(qr[g][3], kv[it].w, d);
+                d = row_sum16(d);
+                s[it][g] = ok[it] ? d * scale_log2 : HATA_NEG_INF;
+                m_tile[g] = fmaxf(m_tile[g], s[it][g]);
+            }
+        }
+#pragma unroll
+        for (int g = 0; g < HT; ++g) {
+            m_tile[g] = rows_max4(m_tile[g]);
+            const float m_new = fmaxf(m_run[g], m_tile[g]);
+            // m_new == -inf only while no valid row has been seen: keep the state untouched
+            const float alpha = (m_new == HATA_NEG_INF) ? 1.f : fast_exp2(m_run[g] - m_new);
+            l_run[g] *= alpha;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc[g][e] *= alpha;
+            m_run[g] = m_new;
+        }
+#pragma unroll
+        for (int it = 0; it < IT; ++it) {
+            float vf[8];
+            vf[0] = bf16_lo(vv[it].x); vf[1] = bf16_hi(vv[it].x);
+            vf[2] = bf16_lo(vv[it].y); vf[3] = bf16_hi(vv[it].y);
+            vf[4] = bf16_lo(vv[it].z); vf[5] = bf16_hi(vv[it].z);
+            vf[6] = bf16_lo(vv[it].w); vf[7] = bf16_hi(vv[it].w);
+#pragma unroll
+            for (int g = 0; g < HT; ++g) {
+                const float p = ok[it] ? fast_exp2(s[it][g] - m_run[g]) : 0.f;
+                l_run[g] += p;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) acc[g][e] = fmaf(p, vf[e], acc[g][e]);
+            }
+        }
+    }
+    // combine the four row groups of the wave (all share m_run)
+#pragma unroll
+    for (int g = 0; g < HT; ++g) {
+        l_run[g] = rows_sum4(l_run[g]);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[g][e] = rows_sum4(acc[g][e]);
+    }
+    if (rg == 0) {
+#pragma unroll
+        for (int g = 0; g < HT; ++g) {
+            if (sub == 0) { S.m[wave][g] = m_run[g]; S.l[wave][g] = l_run[g]; }
+#pragma unroll
+            for (int e = 0; e < 8; ++e) S.acc[wave][g][sub * 8 + e] = acc[g][e];
+        }
+    }
+    __syncthreads();
+}
+
+// Combine the four wave states in S (thread -> (head, channel)).  final: write the attention
+// output of head g to out[g * 128 + ch]; otherwise write the slice's partial (max, sum, acc) for
+// head g at part + g * head_stride with write-through stores.
+template <int HT>
+__device__ __forceinline__ void attn_emit(
+    const AttnLds<HT>& S, bool final, uint16_t* __restrict__ out, float* __restrict__ out_f32,
+    float* __restrict__ part, int64_t head_stride) {
+    for (int i = threadIdx.x; i < HT * HATA_D; i += 256) {
+        const int g = i / HATA_D, ch = i % HATA_D;
+        const float m0 = S.m[0][g], m1 = S.m[1][g], m2 = S.m[2][g], m3 = S.m[3][g];
+        const float M = fmaxf(fmaxf(m0, m1), fmaxf(m2, m3));
+        float av = 0.f, l = 0.f;
+        if (M != HATA_NEG_INF) {
+            const float f0 = fast_exp2(m0 - M), f1 = fast_exp2(m1 - M), f2 = fast_exp2(m2 - M), f3 = fast_exp2(m3 - M);
+            av = f0 * S.acc[0][g][ch] + f1 * S.acc[1][g][ch] + f2 * S.acc[2][g][ch] + f3 * S.acc[3][g][ch];
+            l = f0 * S.l[0][g] + f1 * S.l[1][g] + f2 * S.l[2][g] + f3 * S.l[3][g];
+        }
+        if (final) {
+            const float o = l > 0.f ? av / l : 0.f;
+            out[i] = (uint16_t)f32_to_bf16(o);
+            if (out_f32) out_f32[i] = o;
+        } else {
+            float* pp = part + g * head_stride;
+            st_dev(pp + 2 + ch, av);
+            if (ch == 0) { st_dev(pp, M); st_dev(pp + 1, l); }
+        }
+    }
+}
+
+// Merge ns slices (written by other workgroups of this launch with attn_emit) into the output of
+// the HT heads: part0 = partial of head 0, slice 0; slices are HATA_PSTRIDE apart, heads
+// head_stride apart.  Every load is issued before the first wait: each thread pulls the first 16
+// slices of its NO output channels into registers (later slices batch by batch) while one wave per
+// head turns the (max, sum) pairs into normalised weights in LDS (S.acc is reused; ns <= 256).
+// Must be called by all 256 threads, after a barrier that follows the last use of S.
+template <int HT>
+__device__ __forceinline__ void attn_merge(
+    AttnLds<HT>& S, const float* __restrict__ part0, int64_t head_stride, int ns,
+    uint16_t* __restrict__ out, float* __restrict__ out_f32) {
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    constexpr int NO = (HT * HATA_D + 255) / 256;  // outputs (head, channel) per thread
+    float* sm_w = &S.acc[0][0][0];                 // [HT][nsp]
+    const int nsp = (ns + 3) & ~3;
+    float av[NO][16];
+#pragma unroll
+    for (int r = 0; r < NO; ++r) {
+        const int i = min(tid + 256 * r, HT * HATA_D - 1);
+        const int g = i / HATA_D, ch = i % HATA_D;
+        const float* pp = part0 + g * head_stride + 2 + ch;
+#pragma unroll
+        for (int j = 0; j < 16; ++j) av[r][j] = ld_dev(pp + (int64_t)min(j, ns - 1) * HATA_PSTRIDE);
+    }
+    for (int g = wave; g < HT; g += 4) {
+        const float* pp = part0 + g * head_stride;
+        float m_loc = HATA_NEG_INF;
+        for (int s2 = lane; s2 < ns; s2 += 64) m_loc = fmaxf(m_loc, ld_dev(pp + (int64_t)s2 * HATA_PSTRIDE));
+        const float M = wave_max64(m_loc);
+        float l_loc = 0.f;
+        for (int s2 = lane; s2 < ns; s2 += 64) {
+            const float w = (M == HATA_NEG_INF) ? 0.f : fast_exp2(ld_dev(pp + (int64_t)s2 * HATA_PSTRIDE) - M);
+            sm_w[g * nsp + s2] = w;
+            l_loc = fmaf(w, ld_dev(pp + (int64_t)s2 * HATA_PSTRIDE + 1), l_loc);
+        }
+        const float Lsum = wave_sum64(l_loc);
+        const float inv = Lsum > 0.f ? 1.f / Lsum : 0.f;
+        for (int s2 = lane; s2 < nsp; s2 += 64) sm_w[g * nsp + s2] = (s2 < ns) ? sm_w[g * nsp + s2] * inv : 0.f;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int r = 0; r < NO; ++r) {
+        const int i = tid + 256 * r;
+        if (i < HT * HATA_D) {
+            const int g = i / HATA_D, ch = i % HATA_D;
+            const float4* w4 = reinterpret_cast<const float4*>(sm_w + g * nsp);
+            float A = 0.f;
+#pragma unroll
+            for (int j4 = 0; j4 < 4; ++j4) {
+                if (j4 * 4 < nsp) {  // weights of slices >= ns are zero
+                    const float4 w = w4[j4];
+                    A = fmaf(w.x, av[r][4 * j4], A); A = fmaf(w.y, av[r][4 * j4 + 1], A);
+                    A = fmaf(w.z, av[r][4 * j4 + 2], A); A = fmaf(w.w, av[r][4 * j4 + 3], A);
+                }
+            }
+            const float* pp = part0 + g * head_stride + 2 + ch;
+            for (int s0 = 16; s0 < ns; s0 += 16) {
+                float bv[16];
+#pragma unroll
+                for (int j = 0; j < 16; ++j) bv[j] = ld_dev(pp + (int64_t)min(s0 + j, ns - 1) * HATA_PSTRIDE);
+#pragma unroll
+                for (int j = 0; j < 16; ++j)
+                    if (s0 + j < ns) A = fmaf(sm_w[g * nsp + s0 + j], bv[j], A);
+            }
+            out[i] = (uint16_t)f32_to_bf16(A);
+            if (out_f32) out_f32[i] = A;
+        }
+    }
+}
+
+}  // namespace hata
