@@ -21,7 +21,7 @@ inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
 struct Plan {
     int G, Wd, NB, NBP, chunk, n_chunks, HT, sparse_rows, sparse_splits, dense_rows, dense_splits;
-    size_t off_qcodes, off_scores, off_idx, off_hist, off_cinfo, off_uinfo, off_ucnt, off_acnt, off_uhist, off_partials, total;
+    size_t off_qcodes, off_scores, off_idx, off_hist, off_cinfo, off_uinfo, off_ucnt, off_acnt, off_uflag, off_err, off_uhist, off_partials, total;
 };
 
 int validate_config(const hata_config* f) {
@@ -84,7 +84,8 @@ int make_plan(const hata_config* f, Plan* p) {
     while ((f->L_cap + drows - 1) / drows > 256) drows <<= 1;  // the merge handles <= 256 slices
     p->dense_rows = drows;
     p->dense_splits = (f->L_cap + drows - 1) / drows;
-    const int max_splits = p->sparse_splits > p->dense_splits ? p->sparse_splits : p->dense_splits;
+    int max_splits = p->sparse_splits > p->dense_splits ? p->sparse_splits : p->dense_splits;
+    if (p->n_chunks > max_splits) max_splits = p->n_chunks;  // the cooperative step: one slice per chunk
 
     size_t o = 0;
     p->off_qcodes = o;   o = align_up(o + (size_t)f->B_max * f->Hq * p->Wd * 4);
@@ -95,6 +96,8 @@ int make_plan(const hata_config* f, Plan* p) {
     p->off_uinfo = o;    o = align_up(o + (size_t)units * 2 * 4);
     p->off_ucnt = o;     o = align_up(o + (size_t)units * 4);
     p->off_acnt = o;     o = align_up(o + (size_t)f->B_max * f->Hq * 4);
+    p->off_uflag = o;    o = align_up(o + (size_t)units * 4);
+    p->off_err = o;      o = align_up(o + 4);
     p->off_uhist = o;    o = align_up(o + (size_t)units * p->NB * 4);
     p->off_partials = o; o = align_up(o + (size_t)f->B_max * f->Hq * max_splits * (128 + 2) * 4);
     p->total = o;
@@ -157,12 +160,19 @@ int hata_create(hata_ctx** ctx_out, const hata_config* cfg, void* workspace, siz
     c->unit_counter = (uint32_t*)(w + p.off_ucnt);
     c->attn_counter = (uint32_t*)(w + p.off_acnt);
     c->unit_hist = (uint32_t*)(w + p.off_uhist);
+    c->unit_flag = (uint32_t*)(w + p.off_uflag);
+    c->error_word = (uint32_t*)(w + p.off_err);
+    c->epoch = 0;
+    c->coop_capacity = 0;
     c->partials = (float*)(w + p.off_partials);
     // control words and the self-resetting arrival counters start from zero
     if (hipMemset(c->chunk_info, 0, p.off_partials - p.off_cinfo) != hipSuccess) {
         delete c;
         return HATA_EHIP;
     }
+    c->coop_capacity = hata::coop_capacity(c);
+    if (const char* e = getenv("HATA_TUNE_PATH"))
+        if (atoi(e) == 3) c->coop_capacity = 0;  // tuning: force the three-launch step
     *ctx_out = c;
     return HATA_OK;
 }
@@ -254,8 +264,15 @@ int hata_decode_step(hata_ctx* ctx, const void* q, const void* K, const void* V,
     hipError_t e = hata::launch_encode_vectors(ctx, q, ctx->qcodes, append ? K : nullptr, seq_len,
                                                nullptr, 1, 1, codes, W_H, B, s);
     if (e != hipSuccess) return HATA_EHIP;
-    // Hamming distances of every cached code (the new one included), chunk histograms, and --
-    // by the last workgroup of each unit -- the selection threshold and chunk offsets
+    // Cooperative path: scoring, selection and attention in ONE launch (workgroups of a unit wait
+    // for the unit's threshold inside the kernel), when every workgroup can be resident at once.
+    if ((int64_t)ctx->n_chunks * ctx->cfg.Hkv * B <= ctx->coop_capacity && ctx->n_chunks <= 256) {
+        e = hata::launch_coop_step(ctx, q, K, V, codes, seq_len, k, B, sm_scale, out, out_f32, s);
+        if (e == hipSuccess) return HATA_OK;
+        if (e != hipErrorNotSupported) return HATA_EHIP;
+    }
+    // Three-launch path.  Hamming distances of every cached code (the new one included), chunk
+    // histograms, and -- by the last workgroup of each unit -- the selection threshold and offsets
     e = hata::launch_score(ctx, ctx->qcodes, codes, seq_len, B, ctx->scores, k, s);
     if (e != hipSuccess) return HATA_EHIP;
     // TopK(S, N) compaction fused with the attention over the selected rows (gather fused too)

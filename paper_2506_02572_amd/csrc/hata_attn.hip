@@ -130,7 +130,7 @@ __global__ __launch_bounds__(256) void attn_kernel(const AttnArgs a) {
         __syncthreads();
     }
     TA(23);
-    attn_rows<HT>(qr, Kb, Vb, a.sn, a.L_cap, row_begin, row_end, a.scale_log2,
+    attn_rows<HT, 4>(qr, Kb, Vb, a.sn, a.L_cap, row_begin, row_end, a.scale_log2,
                   [&](int row) {
                       if (MODE == ROWS_DENSE) return row;
                       if (MODE == ROWS_IDX) return (int)ip[row];

@@ -49,7 +49,8 @@ __device__ __forceinline__ void attn_load_q(const uint16_t* __restrict__ q0, uin
 // Attention of the HT heads over rows [row_begin, row_end): row_of(row) gives the cache row (< 0 or
 // >= L_cap: skipped).  On return (after a workgroup barrier) S holds the four waves' states.
 // Must be called by all 256 threads.
-template <int HT, typename RowOf>
+// IT: 16-row load iterations per tile (a tile of 16 IT rows is in flight per workgroup).
+template <int HT, int IT, typename RowOf>
 __device__ __forceinline__ void attn_rows(
     const uint32_t (&qr)[HT][4], const uint16_t* __restrict__ Kb, const uint16_t* __restrict__ Vb,
     int64_t sn, int L_cap, int row_begin, int row_end, float scale_log2, RowOf row_of,
@@ -63,7 +64,6 @@ __device__ __forceinline__ void attn_rows(
 #pragma unroll
         for (int e = 0; e < 8; ++e) acc[g][e] = 0.f;
     }
-    constexpr int IT = 4;  // 4 iterations x 16 rows = 64 rows per tile
     for (int tile = row_begin; tile < row_end; tile += 16 * IT) {
         uint4 kv[IT], vv[IT];
         bool ok[IT];

@@ -1,0 +1,337 @@
+// Cooperative decode step: Hamming scoring, top-k selection and attention over the selected rows
+// (Alg. 3 of the paper from "Calculate distance in Hamming space" to the sparse attention output)
+// in ONE launch.
+//
+// grid = (n_chunks, Hkv, B); the workgroup of (unit u, chunk c)
+//   1. scores its chunk of cached key codes (as score_kernel does), keeps the scores in LDS,
+//      publishes the chunk histogram and adds it to the unit histogram, then ARRIVES at the unit;
+//   2. the last workgroup of the unit to arrive computes the unit's threshold and the ordered
+//      chunk offsets (unit_threshold) and publishes an epoch flag; the others WAIT for that flag;
+//   3. compacts its own chunk (ordered, from the LDS scores) -- writing its part of Idx -- and
+//      attends over exactly the rows it selected, for all query heads of the group;
+//   4. writes its partial (max, sum, weighted V); the last workgroup of the unit to finish merges.
+// So the scores never make a round trip through memory for the selection, and the only serial
+// pieces are the two last-arriver tails.
+//
+// The wait in step 2 needs every workgroup of a unit to be running; the host launches this kernel
+// only when the whole grid can be resident at once.  The wait is bounded anyway: a workgroup that
+// gives up sets the context's error word and runs to its end, so every wave always terminates.
+#include "hata_attn_core.h"
+#include "hata_device.h"
+#include "hata_internal.h"
+#include "hata_select.h"
+#include "hata_trace.h"
+
+namespace hata {
+
+#define HATA_COOP_MAX_CHUNK 4096
+#define HATA_COOP_SPIN_LIMIT (1 << 18)
+
+struct CoopArgs {
+    const uint16_t* q;
+    const uint16_t* K;
+    const uint16_t* V;
+    const uint32_t* qcodes;
+    const uint32_t* codes;
+    const int32_t* seq_len;
+    const int32_t* kbud;
+    uint16_t* scores;
+    int32_t* idx;
+    uint16_t* chunk_hist;
+    int32_t* chunk_info;
+    int32_t* unit_info;
+    uint32_t* unit_counter;
+    uint32_t* unit_hist;
+    uint32_t* unit_flag;
+    uint32_t* attn_counter;
+    uint32_t* error_word;
+    float* partials;
+    uint16_t* out;
+    float* out_f32;
+    int Hq, Hkv, L_cap, k_max, chunk, n_chunks, NB, NBP;
+    int64_t sb, sh, sn;
+    float scale_log2;
+    uint32_t epoch;
+};
+
+template <int WD>
+struct CodeW { uint32_t w[WD]; };
+
+template <int WD>
+__device__ __forceinline__ CodeW<WD> coop_load_code(const uint32_t* p) {
+    CodeW<WD> c;
+#pragma unroll
+    for (int i = 0; i < WD / 4; ++i) {
+        const uint4 v = reinterpret_cast<const uint4*>(p)[i];
+        c.w[4 * i] = v.x; c.w[4 * i + 1] = v.y; c.w[4 * i + 2] = v.z; c.w[4 * i + 3] = v.w;
+    }
+    return c;
+}
+
+// WD in {4, 8} (r = 128, 256); G in {1, 2, 4, 5, 8} (all heads of the group in one attention tile)
+template <int WD, int G>
+__global__ __launch_bounds__(256, 3) void decode_step_coop_kernel(const CoopArgs a) {
+    extern __shared__ uint32_t hist[];  // NB words: chunk histogram, later the unit's total
+    __shared__ ThresholdLds TS;
+    __shared__ __attribute__((aligned(16))) AttnLds<G> S;
+    __shared__ __attribute__((aligned(16))) uint16_t s_sc[HATA_COOP_MAX_CHUNK];  // chunk scores, later the selected rows (offsets in the chunk)
+    __shared__ uint32_t scan4[4];
+    __shared__ int s_flag;
+    const int tid = threadIdx.x;
+    const int c = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+    const int64_t u = (int64_t)b * a.Hkv + h;
+    const int L = clampi(a.seq_len[b], 0, a.L_cap);
+    const int base = c * a.chunk;
+    const int hq0 = h * G;
+    uint16_t* outp = a.out + ((int64_t)b * a.Hq + hq0) * HATA_D;
+    float* outp32 = a.out_f32 ? a.out_f32 + ((int64_t)b * a.Hq + hq0) * HATA_D : nullptr;
+    if (base >= L) {
+        if (L == 0 && c == 0) {  // empty sequence: nothing selected, zero output
+            for (int i = tid; i < G * HATA_D; i += 256) {
+                outp[i] = 0;
+                if (outp32) outp32[i] = 0.f;
+            }
+            for (int p = tid; p < a.k_max; p += 256) a.idx[u * a.k_max + p] = -1;
+        }
+        return;
+    }
+#define TC(i) HATA_TRACE_AT(i, u == 0 && c == 0)
+#define TU(i) HATA_TRACE_AT(i, u == 0)
+    TC(40);
+    const int end = min(base + a.chunk, L);
+    const int nc = (L + a.chunk - 1) / a.chunk;
+    const int keff = min(clampi(a.kbud[b], 0, a.k_max), L);
+    // ---- 1. score the chunk
+    for (int i = tid; i < a.NB; i += 256) hist[i] = 0;
+    uint32_t qc[G][WD];
+    {
+        const uint32_t* qp = a.qcodes + ((int64_t)b * a.Hq + hq0) * WD;
+#pragma unroll
+        for (int g = 0; g < G; ++g)
+#pragma unroll
+            for (int w = 0; w < WD; ++w) qc[g][w] = __builtin_amdgcn_readfirstlane(qp[g * WD + w]);
+    }
+    __syncthreads();
+    {
+        const uint32_t* cp = a.codes + u * a.L_cap * WD;
+        uint16_t* sp = a.scores + u * a.L_cap;
+        constexpr int UNR = (WD <= 4) ? 8 : 4;
+        for (int n0 = base + tid; n0 < end; n0 += 256 * UNR) {
+            CodeW<WD> kc[UNR];
+#pragma unroll
+            for (int j = 0; j < UNR; ++j) {
+                const int n = n0 + j * 256;
+                if (n < end) kc[j] = coop_load_code<WD>(cp + (int64_t)n * WD);
+            }
+#pragma unroll
+            for (int j = 0; j < UNR; ++j) {
+                const int n = n0 + j * 256;
+                if (n < end) {
+                    uint32_t s = 0;
+#pragma unroll
+                    for (int g = 0; g < G; ++g)
+#pragma unroll
+                        for (int w = 0; w < WD; ++w) s += __popc(qc[g][w] ^ kc[j].w[w]);
+                    sp[n] = (uint16_t)s;
+                    s_sc[n - base] = (uint16_t)s;
+                    atomicAdd(&hist[s], 1u);
+                }
+            }
+        }
+    }
+    __syncthreads();
+    TC(41);
+    // ---- 2. publish the histogram, arrive at the unit, threshold by the last arriver
+    {
+        uint32_t* hp32 = reinterpret_cast<uint32_t*>(a.chunk_hist + (u * a.n_chunks + c) * a.NBP);
+        for (int i = tid; i < a.NBP / 2; i += 256) {
+            const uint32_t lo = (2 * i < a.NB) ? hist[2 * i] : 0u;
+            const uint32_t hi = (2 * i + 1 < a.NB) ? hist[2 * i + 1] : 0u;
+            st_dev(hp32 + i, lo | (hi << 16));
+        }
+        for (int i = tid; i < a.NB; i += 256) {
+            const uint32_t hv = hist[i];
+            if (hv) atomicAdd(&a.unit_hist[u * a.NB + i], hv);
+        }
+    }
+    TC(42);
+    wait_stores();
+    __syncthreads();
+    TC(43);
+    if (tid == 0) {
+        const uint32_t done = atomicAdd(&a.unit_counter[u], 1u);
+        const int last = (done == (uint32_t)(nc - 1));
+        if (last) a.unit_counter[u] = 0;
+        s_flag = last;
+    }
+    __syncthreads();
+    int32_t* ci_u = a.chunk_info + u * (a.n_chunks + 1) * 2;
+    TC(44);
+    if (s_flag) {
+        TU(51);
+        unit_threshold<true>(a.chunk_hist + u * a.n_chunks * a.NBP, a.unit_hist + u * a.NB, nc, keff,
+                             a.NB, a.NBP, ci_u, a.unit_info + u * 2, hist, TS);
+        wait_stores();
+        __syncthreads();
+        if (tid == 0) st_dev(a.unit_flag + u, a.epoch);
+        TU(52);
+    } else {
+        if (tid == 0) {
+            int budget = HATA_COOP_SPIN_LIMIT;
+            while (__hip_atomic_load(a.unit_flag + u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != a.epoch &&
+                   --budget > 0)
+                __builtin_amdgcn_s_sleep(1);
+            if (budget <= 0) a.error_word[0] = 1u;  // gave up: results of this launch are invalid
+        }
+        __syncthreads();
+    }
+    TC(45);
+    // the unit's threshold and this chunk's offsets (device-coherent loads)
+    const int T = (int)__hip_atomic_load(reinterpret_cast<uint32_t*>(a.unit_info + u * 2), __ATOMIC_RELAXED,
+                                         __HIP_MEMORY_SCOPE_AGENT);
+    const uint2 ci0 = ld_dev_u2(ci_u + 2 * c);
+    const uint2 ci1 = ld_dev_u2(ci_u + 2 * c + 2);
+    const int off = clampi((int)ci0.x, 0, a.k_max), take = (int)ci0.y;
+    const int cnt = clampi((int)ci1.x - off, 0, min(a.chunk, a.k_max - off));
+
+    // ---- 3. ordered compaction of the own chunk from the LDS scores
+    int32_t* io = a.idx + u * a.k_max;
+    if (c == 0)
+        for (int p = keff + tid; p < a.k_max; p += 256) io[p] = -1;
+    {
+        const int kpt = a.chunk / 256;  // consecutive keys per thread
+        const int n_first = tid * kpt;  // offset in the chunk
+        // this thread's scores (kpt <= 16 consecutive uint16), read once with 8-byte LDS loads
+        uint32_t sv[16];
+#pragma unroll
+        for (int i4 = 0; i4 < 4; ++i4) {
+            if (i4 * 4 < kpt) {
+                const uint2 v = *reinterpret_cast<const uint2*>(&s_sc[n_first + i4 * 4]);
+                sv[4 * i4 + 0] = v.x & 0xffffu; sv[4 * i4 + 1] = v.x >> 16;
+                sv[4 * i4 + 2] = v.y & 0xffffu; sv[4 * i4 + 3] = v.y >> 16;
+            } else {
+                sv[4 * i4 + 0] = sv[4 * i4 + 1] = sv[4 * i4 + 2] = sv[4 * i4 + 3] = 0xffffffffu;
+            }
+        }
+        uint32_t lt = 0, eq = 0;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const bool live = i < kpt && base + n_first + i < end;
+            lt += (live && (int)sv[i] < T) ? 1u : 0u;
+            eq += (live && (int)sv[i] == T) ? 1u : 0u;
+        }
+        uint32_t total;
+        const uint32_t before = block_excl_scan_256(lt | (eq << 16), scan4, &total);
+        uint32_t lt_b = before & 0xffffu, eq_b = before >> 16;
+        // which of this thread's keys are selected, decided before the buffer is reused
+        uint32_t sel_mask = 0;  // bit i: key i of this thread is selected
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const bool live = i < kpt && base + n_first + i < end;
+            if (live && (int)sv[i] < T) sel_mask |= 1u << i;
+            else if (live && (int)sv[i] == T) { if (eq_b < (uint32_t)take) sel_mask |= 1u << i; ++eq_b; }
+        }
+        eq_b = before >> 16;
+        __syncthreads();  // every thread has read its scores: s_sc now becomes the row list
+        uint32_t r = lt_b + min(eq_b, (uint32_t)take);  // local rank of the thread's first selected key
+        for (int i = 0; i < kpt; ++i) {
+            if (sel_mask & (1u << i)) {
+                if (r < (uint32_t)cnt) {
+                    s_sc[r] = (uint16_t)(n_first + i);
+                    io[off + r] = base + n_first + i;
+                }
+                ++r;
+            }
+        }
+    }
+    __syncthreads();
+    TC(46);
+    // ---- 4. attention over the rows this chunk contributes
+    const uint16_t* Kb = a.K + b * a.sb + h * a.sh;
+    const uint16_t* Vb = a.V + b * a.sb + h * a.sh;
+    uint32_t qr[G][4];  // in flight together with the first K/V rows
+    attn_load_q<G>(a.q + ((int64_t)b * a.Hq + hq0) * HATA_D, qr);
+    // 8 heads share the registers with the rest of this kernel: 32-row tiles keep it spill-free
+    attn_rows<G, (G >= 8 ? 2 : 4)>(qr, Kb, Vb, a.sn, a.L_cap, 0, cnt, a.scale_log2,
+                 [&](int row) { return base + (int)s_sc[row]; }, S);
+    TC(47);
+    const int64_t head_stride = (int64_t)a.n_chunks * HATA_PSTRIDE;
+    float* part0 = a.partials + ((int64_t)b * a.Hq + hq0) * head_stride;
+    attn_emit<G>(S, nc == 1, outp, outp32, part0 + (int64_t)c * HATA_PSTRIDE, head_stride);
+    if (nc == 1) return;
+    TC(48);
+    wait_stores();
+    __syncthreads();
+    if (tid == 0) {
+        uint32_t* cntp = a.attn_counter + u;
+        const uint32_t done = atomicAdd(cntp, 1u);
+        const int last = (done == (uint32_t)(nc - 1));
+        if (last) *cntp = 0;
+        s_flag = last;
+    }
+    __syncthreads();
+    TC(49);
+    if (!s_flag) return;
+    TU(53);
+    attn_merge<G>(S, part0, head_stride, nc, outp, outp32);
+    TU(54);
+#undef TC
+#undef TU
+}
+
+template <int WD, int G>
+static const void* coop_fn() { return (const void*)&decode_step_coop_kernel<WD, G>; }
+
+static const void* coop_kernel_for(int Wd, int G) {
+    switch (Wd * 100 + G) {
+        case 401: return coop_fn<4, 1>();
+        case 402: return coop_fn<4, 2>();
+        case 404: return coop_fn<4, 4>();
+        case 405: return coop_fn<4, 5>();
+        case 408: return coop_fn<4, 8>();
+        case 801: return coop_fn<8, 1>();
+        case 802: return coop_fn<8, 2>();
+        case 804: return coop_fn<8, 4>();
+        case 805: return coop_fn<8, 5>();
+        case 808: return coop_fn<8, 8>();
+        default: return nullptr;
+    }
+}
+
+// how many workgroups of this context's cooperative kernel fit on the device at once
+int coop_capacity(const hata_ctx* c) {
+    const void* fn = coop_kernel_for(c->Wd, c->G);
+    if (!fn || c->chunk > HATA_COOP_MAX_CHUNK) return 0;
+    int per_cu = 0, dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return 0;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, 256, (size_t)c->NB * 4) != hipSuccess) return 0;
+    return per_cu * cus;
+}
+
+hipError_t launch_coop_step(hata_ctx* c, const void* q, const void* K, const void* V,
+                            const uint32_t* codes, const int32_t* seq_len, const int32_t* k, int B,
+                            float sm_scale, void* out, float* out_f32, hipStream_t s) {
+    const hata_config& f = c->cfg;
+    const void* fn = coop_kernel_for(c->Wd, c->G);
+    if (!fn || c->chunk > HATA_COOP_MAX_CHUNK) return hipErrorNotSupported;
+    CoopArgs a;
+    a.q = (const uint16_t*)q; a.K = (const uint16_t*)K; a.V = (const uint16_t*)V;
+    a.qcodes = c->qcodes; a.codes = codes; a.seq_len = seq_len; a.kbud = k;
+    a.scores = c->scores; a.idx = c->idx; a.chunk_hist = c->chunk_hist;
+    a.chunk_info = c->chunk_info; a.unit_info = c->unit_info; a.unit_counter = c->unit_counter;
+    a.unit_hist = c->unit_hist; a.unit_flag = c->unit_flag; a.attn_counter = c->attn_counter;
+    a.error_word = c->error_word; a.partials = c->partials;
+    a.out = (uint16_t*)out; a.out_f32 = out_f32;
+    a.Hq = f.Hq; a.Hkv = f.Hkv; a.L_cap = f.L_cap; a.k_max = f.k_max; a.chunk = c->chunk;
+    a.n_chunks = c->n_chunks; a.NB = c->NB; a.NBP = c->NBP;
+    a.sb = f.kv_stride_b; a.sh = f.kv_stride_h; a.sn = f.kv_stride_n;
+    a.scale_log2 = sm_scale * 1.4426950408889634f;
+    c->epoch += 1;
+    if (c->epoch == 0) c->epoch = 1;  // 0 is the cleared state of the flags
+    a.epoch = c->epoch;
+    void* args[] = {(void*)&a};
+    return hipLaunchKernel(fn, dim3(c->n_chunks, f.Hkv, B), dim3(256), args, (size_t)c->NB * 4, s);
+}
+
+}  // namespace hata

@@ -28,6 +28,10 @@ struct hata_ctx {
     uint32_t* unit_counter;  // [B_max*Hkv] scored chunks of a unit (self-resetting)
     uint32_t* unit_hist;     // [B_max*Hkv, NB] total histogram of a unit (self-clearing)
     uint32_t* attn_counter;  // [B_max*Hq] finished attention slices (self-resetting)
+    uint32_t* unit_flag;     // [B_max*Hkv] epoch at which a unit's threshold was published (cooperative step)
+    uint32_t* error_word;    // [1] set by a cooperative launch that gave up waiting
+    uint32_t epoch;          // launch counter of the cooperative step
+    int coop_capacity;       // workgroups of the cooperative kernel that can be resident at once (0 = unusable)
     float* partials;       // [B_max*Hq, max(sparse_splits, dense_splits), d + 2]
 };
 
@@ -51,5 +55,12 @@ hipError_t launch_attention(const hata_ctx* c, int mode, const void* q, const vo
                             const void* V, int32_t* idx, const int32_t* count_src,
                             const int32_t* seq_len, int B, float sm_scale, void* out,
                             float* out_f32, hipStream_t s);
+
+// score + select + attend in one cooperative launch; returns hipErrorNotSupported if this shape
+// has no cooperative kernel
+hipError_t launch_coop_step(hata_ctx* c, const void* q, const void* K, const void* V,
+                            const uint32_t* codes, const int32_t* seq_len, const int32_t* k, int B,
+                            float sm_scale, void* out, float* out_f32, hipStream_t s);
+int coop_capacity(const hata_ctx* c);
 
 }  // namespace hata

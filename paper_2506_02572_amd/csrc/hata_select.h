@@ -165,18 +165,19 @@ __device__ __forceinline__ void unit_threshold(
         for (int c = c0; c < c1; ++c) {
             const uint32_t can = (uint32_t)need > eqb ? (uint32_t)need - eqb : 0u;
             const uint32_t take = min(can, S.c_eq[c]);
-            chunk_info_u[c * 2 + 0] = (int32_t)off;
-            chunk_info_u[c * 2 + 1] = (int32_t)take;
+            st_dev(reinterpret_cast<uint32_t*>(chunk_info_u) + c * 2 + 0, off);
+            st_dev(reinterpret_cast<uint32_t*>(chunk_info_u) + c * 2 + 1, take);
             off += S.c_lt[c] + take;
             eqb += S.c_eq[c];
         }
     }
     HATA_TRACE_AT(13, FUSED && blockIdx.y == 0 && blockIdx.z == 0);
     if (tid == 0) {
-        chunk_info_u[nc * 2 + 0] = keff;
-        chunk_info_u[nc * 2 + 1] = 0;
-        unit_info_u[0] = T;
-        unit_info_u[1] = keff;
+        // (write-through: a cooperative launch reads these from other workgroups right away)
+        st_dev(reinterpret_cast<uint32_t*>(chunk_info_u) + nc * 2 + 0, (uint32_t)keff);
+        st_dev(reinterpret_cast<uint32_t*>(chunk_info_u) + nc * 2 + 1, 0u);
+        st_dev(reinterpret_cast<uint32_t*>(unit_info_u) + 0, (uint32_t)T);
+        st_dev(reinterpret_cast<uint32_t*>(unit_info_u) + 1, (uint32_t)keff);
     }
 }
 
