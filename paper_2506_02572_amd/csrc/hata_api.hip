@@ -53,7 +53,7 @@ int make_plan(const hata_config* f, Plan* p) {
     const int64_t units = (int64_t)f->B_max * f->Hkv;
     // one scoring workgroup per CU at least, chunks of at most 4096 keys (larger only if the
     // cache is so long that a unit would otherwise exceed 1024 chunks)
-    const int64_t target_wgs = 256;
+    const int64_t target_wgs = 128;
     int chunk = 4096;
     while (chunk > 1024 && units * ((f->L_cap + chunk - 1) / chunk) < target_wgs) chunk >>= 1;
     while (chunk < 8192 && (f->L_cap + chunk - 1) / chunk > 1024) chunk <<= 1;
@@ -96,7 +96,7 @@ int make_plan(const hata_config* f, Plan* p) {
     p->off_uinfo = o;    o = align_up(o + (size_t)units * 2 * 4);
     p->off_ucnt = o;     o = align_up(o + (size_t)units * 4);
     p->off_acnt = o;     o = align_up(o + (size_t)f->B_max * f->Hq * 4);
-    p->off_uflag = o;    o = align_up(o + (size_t)units * 4);
+    p->off_uflag = o;    o = align_up(o + (size_t)units * p->n_chunks * 2 * 8);
     p->off_err = o;      o = align_up(o + 4);
     p->off_uhist = o;    o = align_up(o + (size_t)units * p->NB * 4);
     p->off_partials = o; o = align_up(o + (size_t)f->B_max * f->Hq * max_splits * (128 + 2) * 4);
@@ -160,7 +160,7 @@ int hata_create(hata_ctx** ctx_out, const hata_config* cfg, void* workspace, siz
     c->unit_counter = (uint32_t*)(w + p.off_ucnt);
     c->attn_counter = (uint32_t*)(w + p.off_acnt);
     c->unit_hist = (uint32_t*)(w + p.off_uhist);
-    c->unit_flag = (uint32_t*)(w + p.off_uflag);
+    c->coop_rec = (unsigned long long*)(w + p.off_uflag);
     c->error_word = (uint32_t*)(w + p.off_err);
     c->epoch = 0;
     c->coop_capacity = 0;

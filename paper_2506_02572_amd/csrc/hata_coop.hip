@@ -42,7 +42,7 @@ struct CoopArgs {
     int32_t* unit_info;
     uint32_t* unit_counter;
     uint32_t* unit_hist;
-    uint32_t* unit_flag;
+    unsigned long long* rec;
     uint32_t* attn_counter;
     uint32_t* error_word;
     float* partials;
@@ -77,6 +77,7 @@ __global__ __launch_bounds__(256, 3) void decode_step_coop_kernel(const CoopArgs
     __shared__ __attribute__((aligned(16))) uint16_t s_sc[HATA_COOP_MAX_CHUNK];  // chunk scores, later the selected rows (offsets in the chunk)
     __shared__ uint32_t scan4[4];
     __shared__ int s_flag;
+    __shared__ uint32_t s_rec[2];
     const int tid = threadIdx.x;
     const int c = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
     const int64_t u = (int64_t)b * a.Hkv + h;
@@ -166,33 +167,35 @@ __global__ __launch_bounds__(256, 3) void decode_step_coop_kernel(const CoopArgs
     }
     __syncthreads();
     int32_t* ci_u = a.chunk_info + u * (a.n_chunks + 1) * 2;
+    unsigned long long* rec_u = a.rec + u * a.n_chunks * 2;
     TC(44);
     if (s_flag) {
         TU(51);
         unit_threshold<true>(a.chunk_hist + u * a.n_chunks * a.NBP, a.unit_hist + u * a.NB, nc, keff,
-                             a.NB, a.NBP, ci_u, a.unit_info + u * 2, hist, TS);
-        wait_stores();
-        __syncthreads();
-        if (tid == 0) st_dev(a.unit_flag + u, a.epoch);
+                             a.NB, a.NBP, ci_u, a.unit_info + u * 2, hist, TS, rec_u, a.epoch);
         TU(52);
-    } else {
-        if (tid == 0) {
-            int budget = HATA_COOP_SPIN_LIMIT;
-            while (__hip_atomic_load(a.unit_flag + u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != a.epoch &&
-                   --budget > 0)
-                __builtin_amdgcn_s_sleep(1);
-            if (budget <= 0) a.error_word[0] = 1u;  // gave up: results of this launch are invalid
-        }
-        __syncthreads();
     }
+    // every workgroup (the last arriver too) picks up its chunk's record: two words that carry
+    // this launch's epoch once the threshold of the unit has been published
+    if (tid == 0) {
+        int budget = HATA_COOP_SPIN_LIMIT;
+        unsigned long long r0, r1;
+        for (;;) {
+            r0 = __hip_atomic_load(rec_u + 2 * c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            r1 = __hip_atomic_load(rec_u + 2 * c + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (((uint32_t)(r0 >> 32) == a.epoch && (uint32_t)(r1 >> 32) == a.epoch) || --budget <= 0) break;
+            __builtin_amdgcn_s_sleep(1);
+        }
+        if (budget <= 0) { a.error_word[0] = 1u; r0 = 0; r1 = 0; }  // gave up: this launch's results are invalid
+        s_rec[0] = (uint32_t)r0;
+        s_rec[1] = (uint32_t)r1;
+    }
+    __syncthreads();
     TC(45);
-    // the unit's threshold and this chunk's offsets (device-coherent loads)
-    const int T = (int)__hip_atomic_load(reinterpret_cast<uint32_t*>(a.unit_info + u * 2), __ATOMIC_RELAXED,
-                                         __HIP_MEMORY_SCOPE_AGENT);
-    const uint2 ci0 = ld_dev_u2(ci_u + 2 * c);
-    const uint2 ci1 = ld_dev_u2(ci_u + 2 * c + 2);
-    const int off = clampi((int)ci0.x, 0, a.k_max), take = (int)ci0.y;
-    const int cnt = clampi((int)ci1.x - off, 0, min(a.chunk, a.k_max - off));
+    const int off = clampi((int)(s_rec[0] >> 13), 0, a.k_max);
+    const int cnt = clampi((int)(s_rec[0] & 0x1fffu), 0, min(a.chunk, a.k_max - off));
+    const int take = (int)(s_rec[1] >> 13);
+    const int T = (int)(s_rec[1] & 0x1fffu);
 
     // ---- 3. ordered compaction of the own chunk from the LDS scores
     int32_t* io = a.idx + u * a.k_max;
@@ -320,7 +323,7 @@ hipError_t launch_coop_step(hata_ctx* c, const void* q, const void* K, const voi
     a.qcodes = c->qcodes; a.codes = codes; a.seq_len = seq_len; a.kbud = k;
     a.scores = c->scores; a.idx = c->idx; a.chunk_hist = c->chunk_hist;
     a.chunk_info = c->chunk_info; a.unit_info = c->unit_info; a.unit_counter = c->unit_counter;
-    a.unit_hist = c->unit_hist; a.unit_flag = c->unit_flag; a.attn_counter = c->attn_counter;
+    a.unit_hist = c->unit_hist; a.rec = c->coop_rec; a.attn_counter = c->attn_counter;
     a.error_word = c->error_word; a.partials = c->partials;
     a.out = (uint16_t*)out; a.out_f32 = out_f32;
     a.Hq = f.Hq; a.Hkv = f.Hkv; a.L_cap = f.L_cap; a.k_max = f.k_max; a.chunk = c->chunk;

@@ -28,7 +28,7 @@ struct hata_ctx {
     uint32_t* unit_counter;  // [B_max*Hkv] scored chunks of a unit (self-resetting)
     uint32_t* unit_hist;     // [B_max*Hkv, NB] total histogram of a unit (self-clearing)
     uint32_t* attn_counter;  // [B_max*Hq] finished attention slices (self-resetting)
-    uint32_t* unit_flag;     // [B_max*Hkv] epoch at which a unit's threshold was published (cooperative step)
+    unsigned long long* coop_rec;  // [B_max*Hkv, n_chunks, 2] epoch-stamped chunk records (cooperative step)
     uint32_t* error_word;    // [1] set by a cooperative launch that gave up waiting
     uint32_t epoch;          // launch counter of the cooperative step
     int coop_capacity;       // workgroups of the cooperative kernel that can be resident at once (0 = unusable)

@@ -58,7 +58,7 @@ template <bool FUSED>
 __device__ __forceinline__ void unit_threshold(
     const uint16_t* __restrict__ hp, uint32_t* __restrict__ unit_hist_u, int nc, int keff, int NB,
     int NBP, int32_t* __restrict__ chunk_info_u, int32_t* __restrict__ unit_info_u, uint32_t* tot,
-    ThresholdLds& S) {
+    ThresholdLds& S, unsigned long long* __restrict__ rec_u = nullptr, uint32_t epoch = 0) {
     const int tid = threadIdx.x;
     if (tid == 0) { S.T = (keff > 0) ? NB : 0; S.need = 0; S.bmin = NB; }
     for (int c = tid; c < nc; c += 256) { S.c_lt[c] = 0; S.c_eq[c] = 0; }
@@ -89,22 +89,28 @@ __device__ __forceinline__ void unit_threshold(
     __syncthreads();
     HATA_TRACE_AT(10, FUSED && blockIdx.y == 0 && blockIdx.z == 0);
     // T = smallest score value whose inclusive prefix count reaches keff; bmin = lowest occupied score
+    // thread t owns bins [t*seg, (t+1)*seg), seg <= 17 (NB <= 4097), held in registers
     const int seg = (NB + 255) / 256;
-    const int s0 = tid * seg, s1 = min(NB, s0 + seg);
+    const int s0 = tid * seg;
+    uint32_t tv[17];
     uint32_t local = 0;
     int first_nz = NB;
-    for (int i = s1 - 1; i >= s0; --i) {
-        local += tot[i];
-        if (tot[i]) first_nz = i;
+#pragma unroll
+    for (int i = 16; i >= 0; --i) {
+        tv[i] = (i < seg && s0 + i < NB) ? tot[s0 + i] : 0u;
+        local += tv[i];
+        if (tv[i]) first_nz = s0 + i;
     }
     if (first_nz < NB) atomicMin(&S.bmin, first_nz);
     uint32_t total;
     const uint32_t before = block_excl_scan_256(local, S.scan4, &total);
     if (keff > 0 && before < (uint32_t)keff && before + local >= (uint32_t)keff) {
         uint32_t run = before;
-        for (int i = s0; i < s1; ++i) {
-            if (run + tot[i] >= (uint32_t)keff) { S.T = i; S.need = keff - (int)run; break; }
-            run += tot[i];
+        bool found = false;
+#pragma unroll
+        for (int i = 0; i < 17; ++i) {
+            if (!found && run + tv[i] >= (uint32_t)keff) { S.T = s0 + i; S.need = keff - (int)run; found = true; }
+            run += tv[i];
         }
     }
     __syncthreads();
@@ -167,6 +173,16 @@ __device__ __forceinline__ void unit_threshold(
             const uint32_t take = min(can, S.c_eq[c]);
             st_dev(reinterpret_cast<uint32_t*>(chunk_info_u) + c * 2 + 0, off);
             st_dev(reinterpret_cast<uint32_t*>(chunk_info_u) + c * 2 + 1, take);
+            if (rec_u) {
+                // two self-validating words per chunk (each carries the launch epoch in its upper
+                // half, so a waiting workgroup needs no separate flag): {off, selected count} and
+                // {ties granted, T}
+                const uint32_t cnt_c = S.c_lt[c] + take;
+                __hip_atomic_store(rec_u + 2 * c, ((unsigned long long)epoch << 32) | (off << 13) | cnt_c,
+                                   __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __hip_atomic_store(rec_u + 2 * c + 1, ((unsigned long long)epoch << 32) | (take << 13) | (uint32_t)T,
+                                   __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
             off += S.c_lt[c] + take;
             eqb += S.c_eq[c];
         }
