@@ -88,29 +88,28 @@ __device__ __forceinline__ void unit_threshold(
     }
     __syncthreads();
     HATA_TRACE_AT(10, FUSED && blockIdx.y == 0 && blockIdx.z == 0);
-    // T = smallest score value whose inclusive prefix count reaches keff; bmin = lowest occupied score
-    // thread t owns bins [t*seg, (t+1)*seg), seg <= 17 (NB <= 4097), held in registers
-    const int seg = (NB + 255) / 256;
-    const int s0 = tid * seg;
-    uint32_t tv[17];
-    uint32_t local = 0;
-    int first_nz = NB;
-#pragma unroll
-    for (int i = 16; i >= 0; --i) {
-        tv[i] = (i < seg && s0 + i < NB) ? tot[s0 + i] : 0u;
-        local += tv[i];
-        if (tv[i]) first_nz = s0 + i;
-    }
-    if (first_nz < NB) atomicMin(&S.bmin, first_nz);
-    uint32_t total;
-    const uint32_t before = block_excl_scan_256(local, S.scan4, &total);
-    if (keff > 0 && before < (uint32_t)keff && before + local >= (uint32_t)keff) {
-        uint32_t run = before;
-        bool found = false;
-#pragma unroll
-        for (int i = 0; i < 17; ++i) {
-            if (!found && run + tv[i] >= (uint32_t)keff) { S.T = s0 + i; S.need = keff - (int)run; found = true; }
-            run += tv[i];
+    // T = smallest score value whose inclusive prefix count reaches keff; bmin = lowest occupied
+    // score.  One wave does it (lane l owns bins [l*seg, (l+1)*seg)): a wave scan needs no barrier.
+    if (tid < 64) {
+        const int seg = (NB + 63) / 64;
+        const int s0 = tid * seg, s1 = min(NB, s0 + seg);
+        uint32_t local = 0;
+        int first_nz = NB;
+        for (int i = s1 - 1; i >= s0; --i) {
+            const uint32_t v = tot[i];
+            local += v;
+            if (v) first_nz = i;
+        }
+        if (first_nz < NB) atomicMin(&S.bmin, first_nz);
+        const uint32_t incl = wave_incl_scan(local);
+        const uint32_t before = incl - local;
+        if (keff > 0 && before < (uint32_t)keff && incl >= (uint32_t)keff) {
+            uint32_t run = before;
+            for (int i = s0; i < s1; ++i) {
+                const uint32_t v = tot[i];
+                if (run + v >= (uint32_t)keff) { S.T = i; S.need = keff - (int)run; break; }
+                run += v;
+            }
         }
     }
     __syncthreads();
@@ -148,25 +147,24 @@ __device__ __forceinline__ void unit_threshold(
     }
     __syncthreads();
     HATA_TRACE_AT(12, FUSED && blockIdx.y == 0 && blockIdx.z == 0);
-    // ordered offsets: ties are granted to chunks in cache order.  thread t owns chunks
-    // [t*cpt, (t+1)*cpt)
-    const int cpt = (nc + 255) / 256;
-    const int c0 = min(nc, tid * cpt), c1 = min(nc, c0 + cpt);
-    uint32_t eq_loc = 0;
-    for (int c = c0; c < c1; ++c) eq_loc += S.c_eq[c];
-    uint32_t eq_before = block_excl_scan_256(eq_loc, S.scan4, &total);
-    uint32_t sel_loc = 0;
-    {
-        uint32_t eqb = eq_before;
-        for (int c = c0; c < c1; ++c) {
-            const uint32_t can = (uint32_t)need > eqb ? (uint32_t)need - eqb : 0u;
-            const uint32_t take = min(can, S.c_eq[c]);
-            sel_loc += S.c_lt[c] + take;
-            eqb += S.c_eq[c];
+    // ordered offsets: ties are granted to chunks in cache order.  One wave: lane l owns chunks
+    // [l*cpl, (l+1)*cpl); two wave scans (ties seen so far, then selected so far), no barrier.
+    if (tid < 64) {
+        const int cpl = (nc + 63) / 64;
+        const int c0 = min(nc, tid * cpl), c1 = min(nc, c0 + cpl);
+        uint32_t eq_loc = 0;
+        for (int c = c0; c < c1; ++c) eq_loc += S.c_eq[c];
+        const uint32_t eq_before = wave_incl_scan(eq_loc) - eq_loc;
+        uint32_t sel_loc = 0;
+        {
+            uint32_t eqb = eq_before;
+            for (int c = c0; c < c1; ++c) {
+                const uint32_t can = (uint32_t)need > eqb ? (uint32_t)need - eqb : 0u;
+                sel_loc += S.c_lt[c] + min(can, S.c_eq[c]);
+                eqb += S.c_eq[c];
+            }
         }
-    }
-    uint32_t off = block_excl_scan_256(sel_loc, S.scan4, &total);
-    {
+        uint32_t off = wave_incl_scan(sel_loc) - sel_loc;
         uint32_t eqb = eq_before;
         for (int c = c0; c < c1; ++c) {
             const uint32_t can = (uint32_t)need > eqb ? (uint32_t)need - eqb : 0u;
