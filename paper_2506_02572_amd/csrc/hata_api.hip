@@ -21,7 +21,7 @@ inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
 struct Plan {
     int G, Wd, NB, NBP, chunk, n_chunks, HT, sparse_rows, sparse_splits, dense_rows, dense_splits;
-    size_t off_qcodes, off_scores, off_idx, off_hist, off_cinfo, off_uinfo, off_ucnt, off_acnt, off_uflag, off_err, off_uhist, off_partials, total;
+    size_t off_qcodes, off_scores, off_idx, off_hist, off_cinfo, off_uinfo, off_ucnt, off_acnt, off_uflag, off_qrec, off_err, off_uhist, off_partials, total;
 };
 
 int validate_config(const hata_config* f) {
@@ -97,6 +97,7 @@ int make_plan(const hata_config* f, Plan* p) {
     p->off_ucnt = o;     o = align_up(o + (size_t)units * 4);
     p->off_acnt = o;     o = align_up(o + (size_t)f->B_max * f->Hq * 4);
     p->off_uflag = o;    o = align_up(o + (size_t)units * p->n_chunks * 2 * 8);
+    p->off_qrec = o;     o = align_up(o + (size_t)f->B_max * f->Hq * p->Wd * 8);
     p->off_err = o;      o = align_up(o + 4);
     p->off_uhist = o;    o = align_up(o + (size_t)units * p->NB * 4);
     p->off_partials = o; o = align_up(o + (size_t)f->B_max * f->Hq * max_splits * (128 + 2) * 4);
@@ -161,6 +162,7 @@ int hata_create(hata_ctx** ctx_out, const hata_config* cfg, void* workspace, siz
     c->attn_counter = (uint32_t*)(w + p.off_acnt);
     c->unit_hist = (uint32_t*)(w + p.off_uhist);
     c->coop_rec = (unsigned long long*)(w + p.off_uflag);
+    c->coop_qrec = (unsigned long long*)(w + p.off_qrec);
     c->error_word = (uint32_t*)(w + p.off_err);
     c->epoch = 0;
     c->coop_capacity = 0;
@@ -260,17 +262,19 @@ int hata_decode_step(hata_ctx* ctx, const void* q, const void* K, const void* V,
         !aligned(W_H, 16) || !aligned(out, 2))
         return HATA_EINVAL;
     hipStream_t s = (hipStream_t)stream;
+    // Cooperative path: encoding, scoring, selection and attention in ONE launch (workgroups of a
+    // unit wait for the unit's threshold inside the kernel), when every workgroup can be resident
+    // at once.
+    if ((int64_t)ctx->n_chunks * ctx->cfg.Hkv * B <= ctx->coop_capacity && ctx->n_chunks <= 256) {
+        hipError_t e = hata::launch_coop_step(ctx, q, K, V, W_H, codes, append, seq_len, k, B,
+                                              sm_scale, out, out_f32, s);
+        if (e == hipSuccess) return HATA_OK;
+        if (e != hipErrorNotSupported) return HATA_EHIP;
+    }
     // Alg. 3: HashEncode(Q), HashEncode(K_new) and the code-cache update, in one launch
     hipError_t e = hata::launch_encode_vectors(ctx, q, ctx->qcodes, append ? K : nullptr, seq_len,
                                                nullptr, 1, 1, codes, W_H, B, s);
     if (e != hipSuccess) return HATA_EHIP;
-    // Cooperative path: scoring, selection and attention in ONE launch (workgroups of a unit wait
-    // for the unit's threshold inside the kernel), when every workgroup can be resident at once.
-    if ((int64_t)ctx->n_chunks * ctx->cfg.Hkv * B <= ctx->coop_capacity && ctx->n_chunks <= 256) {
-        e = hata::launch_coop_step(ctx, q, K, V, codes, seq_len, k, B, sm_scale, out, out_f32, s);
-        if (e == hipSuccess) return HATA_OK;
-        if (e != hipErrorNotSupported) return HATA_EHIP;
-    }
     // Three-launch path.  Hamming distances of every cached code (the new one included), chunk
     // histograms, and -- by the last workgroup of each unit -- the selection threshold and offsets
     e = hata::launch_score(ctx, ctx->qcodes, codes, seq_len, B, ctx->scores, k, s);

@@ -3,6 +3,8 @@
 // in ONE launch.
 //
 // grid = (n_chunks, Hkv, B); the workgroup of (unit u, chunk c)
+//   0. hash-encodes its share of the unit's query vectors, publishes the code words and collects
+//      the others' (the owner of the appended row also encodes that key);
 //   1. scores its chunk of cached key codes (as score_kernel does), keeps the scores in LDS,
 //      publishes the chunk histogram and adds it to the unit histogram, then ARRIVES at the unit;
 //   2. the last workgroup of the unit to arrive computes the unit's threshold and the ordered
@@ -31,8 +33,9 @@ struct CoopArgs {
     const uint16_t* q;
     const uint16_t* K;
     const uint16_t* V;
-    const uint32_t* qcodes;
-    const uint32_t* codes;
+    const float* W_H;
+    uint32_t* qcodes;
+    uint32_t* codes;
     const int32_t* seq_len;
     const int32_t* kbud;
     uint16_t* scores;
@@ -43,6 +46,7 @@ struct CoopArgs {
     uint32_t* unit_counter;
     uint32_t* unit_hist;
     unsigned long long* rec;
+    unsigned long long* qrec;
     uint32_t* attn_counter;
     uint32_t* error_word;
     float* partials;
@@ -52,6 +56,7 @@ struct CoopArgs {
     int64_t sb, sh, sn;
     float scale_log2;
     uint32_t epoch;
+    int append;
 };
 
 template <int WD>
@@ -68,6 +73,77 @@ __device__ __forceinline__ CodeW<WD> coop_load_code(const uint32_t* p) {
     return c;
 }
 
+
+// x + y across a lane pair that differs in lane bit 5 (swap32) or bit 4 (swap16): the lane with the
+// bit clear gets the pair's total of x, the lane with the bit set the pair's total of y (one
+// lane-swap per dword instead of two moves, and the number of live values halves).
+__device__ __forceinline__ double swapadd32(double x, double y) {
+    uint32_t xl = (uint32_t)__double2loint(x), xh = (uint32_t)__double2hiint(x);
+    uint32_t yl = (uint32_t)__double2loint(y), yh = (uint32_t)__double2hiint(y);
+    asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1\n\tv_permlane32_swap_b32 %2, %3\n\ts_nop 1"
+                 : "+v"(xl), "+v"(yl), "+v"(xh), "+v"(yh));
+    return __hiloint2double((int)xh, (int)xl) + __hiloint2double((int)yh, (int)yl);
+}
+__device__ __forceinline__ double swapadd16(double x, double y) {
+    uint32_t xl = (uint32_t)__double2loint(x), xh = (uint32_t)__double2hiint(x);
+    uint32_t yl = (uint32_t)__double2loint(y), yh = (uint32_t)__double2hiint(y);
+    asm volatile("s_nop 1\n\tv_permlane16_swap_b32 %0, %1\n\tv_permlane16_swap_b32 %2, %3\n\ts_nop 1"
+                 : "+v"(xl), "+v"(yl), "+v"(xh), "+v"(yh));
+    return __hiloint2double((int)xh, (int)xl) + __hiloint2double((int)yh, (int)yl);
+}
+// x + (x of the lane 8 positions away in the same row of 16 lanes)
+__device__ __forceinline__ double rotadd8(double x) {
+    const int lo = __builtin_amdgcn_update_dpp(0, __double2loint(x), 0x128, 0xf, 0xf, false);  // row_ror:8
+    const int hi = __builtin_amdgcn_update_dpp(0, __double2hiint(x), 0x128, 0xf, 0xf, false);
+    return x + __hiloint2double(hi, lo);
+}
+
+// HashEncode (Alg. 2: Sign(x . W_H), BitPack) of ONE 128-channel bf16 vector x against a KV head's
+// weights Wh [128][r], by the whole workgroup, accumulating in fp64 (every product of a bf16 and
+// an fp32 value is exact in fp64).  s_word: WD code words in LDS, zero on entry, complete after
+// the caller's next barrier.  A wave owns r/4 hash columns (one code word at r = 128, two at
+// r = 256); its lanes are (column group of 4 = one 128-bit weight load) x (1024/r parts of the
+// channel range), so all loads of a thread are independent and in flight together.  The partial
+// sums are combined across the parts with lane swaps, each step halving the live values: lane
+// (bit5, bit4) ends up with the total of column 4 cg + bit4 + 2 bit5.
+template <int WD>
+__device__ __forceinline__ void coop_encode_vec(const float* __restrict__ Wh,
+                                                const uint16_t* __restrict__ x, uint32_t* s_word) {
+    constexpr int R = WD * 32, CG = R / 16, P = 64 / CG, CP = HATA_D / P;  // CP = 16 or 32 channels
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int cg = lane % CG, p = lane / CG;
+    const float* wp = Wh + (int64_t)(p * CP) * R + wave * (R / 4) + 4 * cg;
+    uint32_t xw[CP / 2];  // this part's channels, bf16 pairs
+#pragma unroll
+    for (int i = 0; i < CP / 8; ++i) {
+        const uint4 v = reinterpret_cast<const uint4*>(x + p * CP)[i];
+        xw[4 * i] = v.x; xw[4 * i + 1] = v.y; xw[4 * i + 2] = v.z; xw[4 * i + 3] = v.w;
+    }
+    double a0 = 0.0, a1 = 0.0, a2 = 0.0, a3 = 0.0;
+#pragma unroll
+    for (int c0 = 0; c0 < CP; c0 += 16) {
+        float4 w[16];
+#pragma unroll
+        for (int j = 0; j < 16; ++j) w[j] = *reinterpret_cast<const float4*>(wp + (int64_t)(c0 + j) * R);
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            const uint32_t pair = xw[(c0 + j) >> 1];
+            const double xd = (double)(((c0 + j) & 1) ? bf16_hi(pair) : bf16_lo(pair));
+            a0 = fma((double)w[j].x, xd, a0);
+            a1 = fma((double)w[j].y, xd, a1);
+            a2 = fma((double)w[j].z, xd, a2);
+            a3 = fma((double)w[j].w, xd, a3);
+        }
+    }
+    const int b5 = lane >> 5, b4 = (lane >> 4) & 1;
+    const int col = wave * (R / 4) + 4 * cg + b4 + 2 * b5;  // hash column this lane ends up with
+    const double e = swapadd32(a0, a2);  // column 0 + 2 b5
+    const double o = swapadd32(a1, a3);  // column 1 + 2 b5
+    double t = swapadd16(e, o);
+    if (P == 8) t = rotadd8(t);
+    if (t >= 0.0) atomicOr(&s_word[col >> 5], 1u << (col & 31));
+}
+
 // WD in {4, 8} (r = 128, 256); G in {1, 2, 4, 5, 8} (all heads of the group in one attention tile)
 template <int WD, int G>
 __global__ __launch_bounds__(256, 3) void decode_step_coop_kernel(const CoopArgs a) {
@@ -78,6 +154,7 @@ __global__ __launch_bounds__(256, 3) void decode_step_coop_kernel(const CoopArgs
     __shared__ uint32_t scan4[4];
     __shared__ int s_flag;
     __shared__ uint32_t s_rec[2];
+    __shared__ uint32_t s_codes[(G + 1) * WD];  // codes of the G query heads and of the appended key
     const int tid = threadIdx.x;
     const int c = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
     const int64_t u = (int64_t)b * a.Hkv + h;
@@ -86,48 +163,85 @@ __global__ __launch_bounds__(256, 3) void decode_step_coop_kernel(const CoopArgs
     const int hq0 = h * G;
     uint16_t* outp = a.out + ((int64_t)b * a.Hq + hq0) * HATA_D;
     float* outp32 = a.out_f32 ? a.out_f32 + ((int64_t)b * a.Hq + hq0) * HATA_D : nullptr;
-    if (base >= L) {
-        if (L == 0 && c == 0) {  // empty sequence: nothing selected, zero output
-            for (int i = tid; i < G * HATA_D; i += 256) {
-                outp[i] = 0;
-                if (outp32) outp32[i] = 0.f;
-            }
-            for (int p = tid; p < a.k_max; p += 256) a.idx[u * a.k_max + p] = -1;
-        }
-        return;
-    }
+    if (base >= L && c != 0) return;  // chunk 0 always runs the encoding (it publishes the query codes)
 #define TC(i) HATA_TRACE_AT(i, u == 0 && c == 0)
 #define TU(i) HATA_TRACE_AT(i, u == 0)
     TC(40);
     const int end = min(base + a.chunk, L);
+    // ---- 0. HashEncode(Q) and HashEncode(K_new).  The G query vectors of the unit are dealt out
+    // to its nc workgroups (vector v to chunk v mod nc), each published as epoch-stamped words
+    // that every workgroup of the unit then picks up; the workgroup whose chunk holds the
+    // appended row L - 1 also encodes that key, updates the code cache and scores the row from
+    // the code it just computed.
     const int nc = (L + a.chunk - 1) / a.chunk;
-    const int keff = min(clampi(a.kbud[b], 0, a.k_max), L);
-    // ---- 1. score the chunk
-    for (int i = tid; i < a.NB; i += 256) hist[i] = 0;
-    uint32_t qc[G][WD];
+    const bool own = a.append && L > 0 && base <= L - 1 && L - 1 < base + a.chunk;
     {
-        const uint32_t* qp = a.qcodes + ((int64_t)b * a.Hq + hq0) * WD;
-#pragma unroll
-        for (int g = 0; g < G; ++g)
-#pragma unroll
-            for (int w = 0; w < WD; ++w) qc[g][w] = __builtin_amdgcn_readfirstlane(qp[g * WD + w]);
+        const uint16_t* qv = a.q + ((int64_t)b * a.Hq + hq0) * HATA_D;
+        const float* Wh = a.W_H + (int64_t)h * HATA_D * (WD * 32);
+        unsigned long long* qrec = a.qrec + ((int64_t)b * a.Hq + hq0) * WD;
+        if (tid < (G + 1) * WD) s_codes[tid] = 0;
+        for (int i = tid; i < a.NB; i += 256) hist[i] = 0;
+        __syncthreads();
+        for (int v = c; v < G; v += max(nc, 1)) {
+            coop_encode_vec<WD>(Wh, qv + v * HATA_D, &s_codes[v * WD]);
+            __syncthreads();
+            if (tid < WD)
+                __hip_atomic_store(qrec + v * WD + tid,
+                                   ((unsigned long long)a.epoch << 32) | s_codes[v * WD + tid],
+                                   __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        if (own)
+            coop_encode_vec<WD>(Wh, a.K + b * a.sb + h * a.sh + (int64_t)(L - 1) * a.sn, &s_codes[G * WD]);
+        if (tid < 64) {  // one wave collects the G * WD (<= 64) query code words of the unit
+            const int i = min(tid, G * WD - 1);
+            int budget = HATA_COOP_SPIN_LIMIT;
+            unsigned long long r;
+            for (;;) {
+                r = __hip_atomic_load(qrec + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                const bool miss = (uint32_t)(r >> 32) != a.epoch;
+                if (__builtin_amdgcn_ballot_w64(miss) == 0ull) break;
+                if (--budget <= 0) { if (tid == 0) a.error_word[0] = 1u; break; }  // gave up: results invalid
+                __builtin_amdgcn_s_sleep(1);
+            }
+            if (tid < G * WD) s_codes[tid] = (uint32_t)r;
+        }
+        __syncthreads();
     }
-    __syncthreads();
+    if (c == 0)
+        for (int i = tid; i < G * WD; i += 256) a.qcodes[((int64_t)b * a.Hq + hq0) * WD + i] = s_codes[i];
+    if (own && tid < WD) a.codes[(u * a.L_cap + (L - 1)) * WD + tid] = s_codes[G * WD + tid];
+    if (base >= L) {  // empty sequence: nothing selected, zero output
+        for (int i = tid; i < G * HATA_D; i += 256) {
+            outp[i] = 0;
+            if (outp32) outp32[i] = 0.f;
+        }
+        for (int p = tid; p < a.k_max; p += 256) a.idx[u * a.k_max + p] = -1;
+        return;
+    }
+    TC(50);
+    const int keff = min(clampi(a.kbud[b], 0, a.k_max), L);
+    // ---- 1. score the chunk (the appended row from the code just computed, the rest from the cache)
+    uint32_t qc[G][WD];
+#pragma unroll
+    for (int g = 0; g < G; ++g)
+#pragma unroll
+        for (int w = 0; w < WD; ++w) qc[g][w] = __builtin_amdgcn_readfirstlane(s_codes[g * WD + w]);
     {
         const uint32_t* cp = a.codes + u * a.L_cap * WD;
         uint16_t* sp = a.scores + u * a.L_cap;
+        const int end_main = own ? L - 1 : end;
         constexpr int UNR = (WD <= 4) ? 8 : 4;
-        for (int n0 = base + tid; n0 < end; n0 += 256 * UNR) {
+        for (int n0 = base + tid; n0 < end_main; n0 += 256 * UNR) {
             CodeW<WD> kc[UNR];
 #pragma unroll
             for (int j = 0; j < UNR; ++j) {
                 const int n = n0 + j * 256;
-                if (n < end) kc[j] = coop_load_code<WD>(cp + (int64_t)n * WD);
+                if (n < end_main) kc[j] = coop_load_code<WD>(cp + (int64_t)n * WD);
             }
 #pragma unroll
             for (int j = 0; j < UNR; ++j) {
                 const int n = n0 + j * 256;
-                if (n < end) {
+                if (n < end_main) {
                     uint32_t s = 0;
 #pragma unroll
                     for (int g = 0; g < G; ++g)
@@ -138,6 +252,16 @@ __global__ __launch_bounds__(256, 3) void decode_step_coop_kernel(const CoopArgs
                     atomicAdd(&hist[s], 1u);
                 }
             }
+        }
+        if (own && tid == 0) {
+            uint32_t s = 0;
+#pragma unroll
+            for (int g = 0; g < G; ++g)
+#pragma unroll
+                for (int w = 0; w < WD; ++w) s += __popc(qc[g][w] ^ s_codes[G * WD + w]);
+            sp[L - 1] = (uint16_t)s;
+            s_sc[L - 1 - base] = (uint16_t)s;
+            atomicAdd(&hist[s], 1u);
         }
     }
     __syncthreads();
@@ -313,17 +437,18 @@ int coop_capacity(const hata_ctx* c) {
 }
 
 hipError_t launch_coop_step(hata_ctx* c, const void* q, const void* K, const void* V,
-                            const uint32_t* codes, const int32_t* seq_len, const int32_t* k, int B,
-                            float sm_scale, void* out, float* out_f32, hipStream_t s) {
+                            const float* W_H, uint32_t* codes, int append, const int32_t* seq_len,
+                            const int32_t* k, int B, float sm_scale, void* out, float* out_f32, hipStream_t s) {
     const hata_config& f = c->cfg;
     const void* fn = coop_kernel_for(c->Wd, c->G);
     if (!fn || c->chunk > HATA_COOP_MAX_CHUNK) return hipErrorNotSupported;
     CoopArgs a;
     a.q = (const uint16_t*)q; a.K = (const uint16_t*)K; a.V = (const uint16_t*)V;
+    a.W_H = W_H; a.append = append;
     a.qcodes = c->qcodes; a.codes = codes; a.seq_len = seq_len; a.kbud = k;
     a.scores = c->scores; a.idx = c->idx; a.chunk_hist = c->chunk_hist;
     a.chunk_info = c->chunk_info; a.unit_info = c->unit_info; a.unit_counter = c->unit_counter;
-    a.unit_hist = c->unit_hist; a.rec = c->coop_rec; a.attn_counter = c->attn_counter;
+    a.unit_hist = c->unit_hist; a.rec = c->coop_rec; a.qrec = c->coop_qrec; a.attn_counter = c->attn_counter;
     a.error_word = c->error_word; a.partials = c->partials;
     a.out = (uint16_t*)out; a.out_f32 = out_f32;
     a.Hq = f.Hq; a.Hkv = f.Hkv; a.L_cap = f.L_cap; a.k_max = f.k_max; a.chunk = c->chunk;

@@ -29,6 +29,7 @@ struct hata_ctx {
     uint32_t* unit_hist;     // [B_max*Hkv, NB] total histogram of a unit (self-clearing)
     uint32_t* attn_counter;  // [B_max*Hq] finished attention slices (self-resetting)
     unsigned long long* coop_rec;  // [B_max*Hkv, n_chunks, 2] epoch-stamped chunk records (cooperative step)
+    unsigned long long* coop_qrec; // [B_max*Hq, Wd] epoch-stamped query code words (cooperative step)
     uint32_t* error_word;    // [1] set by a cooperative launch that gave up waiting
     uint32_t epoch;          // launch counter of the cooperative step
     int coop_capacity;       // workgroups of the cooperative kernel that can be resident at once (0 = unusable)
@@ -56,11 +57,11 @@ hipError_t launch_attention(const hata_ctx* c, int mode, const void* q, const vo
                             const int32_t* seq_len, int B, float sm_scale, void* out,
                             float* out_f32, hipStream_t s);
 
-// score + select + attend in one cooperative launch; returns hipErrorNotSupported if this shape
-// has no cooperative kernel
+// encode + score + select + attend in one cooperative launch; returns hipErrorNotSupported if
+// this shape has no cooperative kernel
 hipError_t launch_coop_step(hata_ctx* c, const void* q, const void* K, const void* V,
-                            const uint32_t* codes, const int32_t* seq_len, const int32_t* k, int B,
-                            float sm_scale, void* out, float* out_f32, hipStream_t s);
+                            const float* W_H, uint32_t* codes, int append, const int32_t* seq_len,
+                            const int32_t* k, int B, float sm_scale, void* out, float* out_f32, hipStream_t s);
 int coop_capacity(const hata_ctx* c);
 
 }  // namespace hata
