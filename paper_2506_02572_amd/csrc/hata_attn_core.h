@@ -194,7 +194,7 @@ __device__ __forceinline__ void attn_merge(
         const int g = i / HATA_D, ch = i % HATA_D;
         const float* pp = part0 + g * head_stride + 2 + ch;
 #pragma unroll
-        for (int j = 0; j < 16; ++j) av[r][j] = ld_dev(pp + (int64_t)min(j, ns - 1) * HATA_PSTRIDE);
+        for (int j = 0; j < 16; ++j) av[r][j] = (j < ns) ? ld_dev(pp + (int64_t)j * HATA_PSTRIDE) : 0.f;
     }
     for (int g = wave; g < HT; g += 4) {
         const float* pp = part0 + g * head_stride;
@@ -231,7 +231,7 @@ __device__ __forceinline__ void attn_merge(
             for (int s0 = 16; s0 < ns; s0 += 16) {
                 float bv[16];
 #pragma unroll
-                for (int j = 0; j < 16; ++j) bv[j] = ld_dev(pp + (int64_t)min(s0 + j, ns - 1) * HATA_PSTRIDE);
+                for (int j = 0; j < 16; ++j) bv[j] = (s0 + j < ns) ? ld_dev(pp + (int64_t)(s0 + j) * HATA_PSTRIDE) : 0.f;
 #pragma unroll
                 for (int j = 0; j < 16; ++j)
                     if (s0 + j < ns) A = fmaf(sm_w[g * nsp + s0 + j], bv[j], A);

@@ -295,7 +295,7 @@ __global__ __launch_bounds__(256, 3) void decode_step_coop_kernel(const CoopArgs
     TC(44);
     if (s_flag) {
         TU(51);
-        unit_threshold<true>(a.chunk_hist + u * a.n_chunks * a.NBP, a.unit_hist + u * a.NB, nc, keff,
+        unit_threshold<true, (G * WD * 32) / 256 + 1>(a.chunk_hist + u * a.n_chunks * a.NBP, a.unit_hist + u * a.NB, nc, keff,
                              a.NB, a.NBP, ci_u, a.unit_info + u * 2, hist, TS, rec_u, a.epoch);
         TU(52);
     }

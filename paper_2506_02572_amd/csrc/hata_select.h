@@ -17,6 +17,8 @@ namespace hata {
 // LDS a workgroup needs to run unit_threshold()
 struct ThresholdLds {
     uint32_t scan4[4];
+    uint32_t wtot[4];
+    float wlow[4];
     int T, need, bmin;
     uint32_t c_lt[HATA_MAX_CHUNKS];
     uint32_t c_eq[HATA_MAX_CHUNKS];
@@ -29,7 +31,7 @@ struct ThresholdLds {
 // from the nc chunk histograms of the unit (`hp`, pitch NBP, uint16 counts) and -- FUSED -- the
 // unit's total histogram `unit_hist` (NB words) that the scoring workgroups of this launch
 // accumulated with atomics; it is read with device-coherent loads and cleared for the next
-// launch.  Not FUSED: the total is summed from the chunk rows.  `tot` is NB words of LDS.
+// launch.  Not FUSED: the total is summed from the chunk rows.  `tot` is unused.
 // Must be called by all 256 threads.
 //
 // Only the few 8-bin columns between the lowest occupied score and T matter for the per-chunk
@@ -54,63 +56,74 @@ __device__ __forceinline__ uint32_t bin_of(const Bins8& v, int e) {
     return (e & 1) ? (w >> 16) : (w & 0xffffu);
 }
 
-template <bool FUSED>
+template <bool FUSED, int MAXSEG = 17>
 __device__ __forceinline__ void unit_threshold(
     const uint16_t* __restrict__ hp, uint32_t* __restrict__ unit_hist_u, int nc, int keff, int NB,
     int NBP, int32_t* __restrict__ chunk_info_u, int32_t* __restrict__ unit_info_u, uint32_t* tot,
     ThresholdLds& S, unsigned long long* __restrict__ rec_u = nullptr, uint32_t epoch = 0) {
-    const int tid = threadIdx.x;
-    if (tid == 0) { S.T = (keff > 0) ? NB : 0; S.need = 0; S.bmin = NB; }
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    if (tid == 0) { S.T = (keff > 0) ? NB : 0; S.need = 0; }
     for (int c = tid; c < nc; c += 256) { S.c_lt[c] = 0; S.c_eq[c] = 0; }
-    // total histogram of the unit
+    // Total histogram of the unit, held in registers: thread t owns the seg consecutive score
+    // values from t * seg (seg <= MAXSEG; NB <= 4097 needs 17); all loads are in flight together.
+    const int seg = (NB + 255) / 256;
+    const int s0 = tid * seg;
+    uint32_t x[MAXSEG];
     if constexpr (FUSED) {
-        for (int i0 = tid; i0 < NB; i0 += 256 * 4) {
-            uint32_t x[4];
 #pragma unroll
-            for (int j = 0; j < 4; ++j)  // clamped index: unconditional loads, all in flight
-                x[j] = __hip_atomic_load(unit_hist_u + min(i0 + j * 256, NB - 1), __ATOMIC_RELAXED,
+        for (int j = 0; j < MAXSEG; ++j)  // clamped index: unconditional loads
+            if (j < seg)
+                x[j] = __hip_atomic_load(unit_hist_u + min(s0 + j, NB - 1), __ATOMIC_RELAXED,
                                          __HIP_MEMORY_SCOPE_AGENT);
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const int i = i0 + j * 256;
-                if (i < NB) {
-                    tot[i] = x[j];
-                    if (x[j]) unit_hist_u[i] = 0;  // left clean for the next launch
-                }
+        for (int j = 0; j < MAXSEG; ++j) {
+            if (j < seg && s0 + j < NB) {
+                if (x[j]) unit_hist_u[s0 + j] = 0;  // left clean for the next launch
+            } else {
+                x[j] = 0;
             }
         }
     } else {
-        for (int i = tid; i < NB; i += 256) {
-            uint32_t t = 0;
-            for (int c = 0; c < nc; ++c) t += hp[(int64_t)c * NBP + i];
-            tot[i] = t;
+#pragma unroll
+        for (int j = 0; j < MAXSEG; ++j) x[j] = 0;
+        for (int c = 0; c < nc; ++c) {
+#pragma unroll
+            for (int j = 0; j < MAXSEG; ++j)
+                if (j < seg && s0 + j < NB) x[j] += hp[(int64_t)c * NBP + s0 + j];
         }
     }
+    uint32_t local = 0;
+    int first_nz = NB;
+#pragma unroll
+    for (int j = MAXSEG - 1; j >= 0; --j) {
+        local += x[j];
+        if (x[j]) first_nz = s0 + j;
+    }
+    // T = smallest score value whose inclusive prefix count reaches keff; bmin = lowest occupied
+    // score (values <= 4097 are exact in the float lane reductions)
+    const uint32_t incl_w = wave_incl_scan(local);
+    const float low_w = wave_max64(-(float)first_nz);
+    if (lane == 63) { S.wtot[wave] = incl_w; S.wlow[wave] = low_w; }
     __syncthreads();
     HATA_TRACE_AT(10, FUSED && blockIdx.y == 0 && blockIdx.z == 0);
-    // T = smallest score value whose inclusive prefix count reaches keff; bmin = lowest occupied
-    // score.  One wave does it (lane l owns bins [l*seg, (l+1)*seg)): a wave scan needs no barrier.
-    if (tid < 64) {
-        const int seg = (NB + 63) / 64;
-        const int s0 = tid * seg, s1 = min(NB, s0 + seg);
-        uint32_t local = 0;
-        int first_nz = NB;
-        for (int i = s1 - 1; i >= s0; --i) {
-            const uint32_t v = tot[i];
-            local += v;
-            if (v) first_nz = i;
-        }
-        if (first_nz < NB) atomicMin(&S.bmin, first_nz);
-        const uint32_t incl = wave_incl_scan(local);
-        const uint32_t before = incl - local;
-        if (keff > 0 && before < (uint32_t)keff && incl >= (uint32_t)keff) {
+    {
+        const uint32_t w0 = S.wtot[0], w1 = S.wtot[1], w2 = S.wtot[2];
+        const uint32_t before = (wave > 0 ? w0 : 0u) + (wave > 1 ? w1 : 0u) + (wave > 2 ? w2 : 0u) + incl_w - local;
+        if (keff > 0 && before < (uint32_t)keff && before + local >= (uint32_t)keff) {
             uint32_t run = before;
-            for (int i = s0; i < s1; ++i) {
-                const uint32_t v = tot[i];
-                if (run + v >= (uint32_t)keff) { S.T = i; S.need = keff - (int)run; break; }
-                run += v;
+            bool found = false;
+#pragma unroll
+            for (int j = 0; j < MAXSEG; ++j) {
+                if (!found && run + x[j] >= (uint32_t)keff) {
+                    S.T = s0 + j;
+                    S.need = keff - (int)run;
+                    found = true;
+                }
+                run += x[j];
             }
         }
+        if (tid == 0)
+            S.bmin = (int)(-fmaxf(fmaxf(S.wlow[0], S.wlow[1]), fmaxf(S.wlow[2], S.wlow[3])));
     }
     __syncthreads();
     const int T = S.T, need = S.need;
