@@ -25,14 +25,15 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBPS = 8000.0
 
-# HBM bytes per launch of the scoring kernel, from the rocprofv3 --pmc runs summarised in
-# profiles/score_kernel_hbm_traffic.md: FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0 (factors from a plain
-# 256 MiB copy in the same runs).  None = not measured for that workload.
-SCORE_KERNEL_TRAFFIC_BYTES = {
-    "cfg2_llama3_8b_32k": 5080269,
-    "cfg3_batched_ragged": 45563085,
-    "cfg4_long_128k_r256": 36281549,
-    "cfg5_gqa8_append": 39114752,
+# HBM bytes per launch, from the rocprofv3 --pmc runs summarised in profiles/hbm_traffic_pmc.md:
+# FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0 (factors from a plain 256 MiB copy in the same runs).
+# "step": the single-launch decode step (decode_step_coop_kernel); "score": the scoring kernel
+# alone (hata_hamming_score).  None = not measured for that workload.
+HBM_TRAFFIC_BYTES = {
+    "cfg2_llama3_8b_32k": {"step": None, "score": None},
+    "cfg3_batched_ragged": {"step": None, "score": None},
+    "cfg4_long_128k_r256": {"step": None, "score": None},
+    "cfg5_gqa8_append": {"step": None, "score": None},
 }
 
 
@@ -47,8 +48,8 @@ def parse():
     ap.add_argument("--no-dense", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=10.0)
     ap.add_argument("--pmc-probe", action="store_true",
-                    help="run only a known-size copy kernel and the scoring kernel (for rocprofv3 --pmc "
-                         "FETCH_SIZE / WRITE_SIZE runs that calibrate and measure HBM traffic)")
+                    help="run only a known-size copy kernel, the decode step and the scoring kernel (for "
+                         "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs that calibrate and measure HBM traffic)")
     return ap.parse_args()
 
 
@@ -133,7 +134,7 @@ def main():
 
     if args.pmc_probe:
         # a plain copy of known size (reads and writes COPY_BYTES each) calibrates the counters;
-        # then the scoring launch, the same call the roofline leg times
+        # then the decode step and the scoring launch, the same calls the timed legs issue
         COPY_BYTES = 256 << 20
         src = torch.empty(COPY_BYTES // 4, dtype=torch.int32, device=dev).fill_(1)
         dst = torch.empty_like(src)
@@ -146,10 +147,17 @@ def main():
         for i in range(40):
             ctx.hata_hamming_score(qcodes_buf, codes_all[i % n_layers], seq_steps[0], w.B, scores_buf, stream)
         torch.cuda.synchronize()
+        for i in range(40):
+            ctx.hata_decode_step(q_steps[0], K_all[i % n_layers], V_all[i % n_layers], W_H,
+                                 codes_all[i % n_layers], seq_steps[0], kbud, w.B, True, scale, out, out32,
+                                 stream)
+        ctx.hata_check(stream)
         code_bytes = int(inp.seq_len.sum() + (w.B if w.append_steps else 0)) * w.Hkv * (w.r // 8)
         print(json.dumps({"pmc_probe": True, "workload": w.name, "copy_bytes_each_way": COPY_BYTES,
                           "score_code_bytes": code_bytes,
-                          "score_write_bytes": code_bytes // (w.r // 8) * 2}))
+                          "score_write_bytes": code_bytes // (w.r // 8) * 2,
+                          "step_algorithmic_bytes": w.algorithmic_bytes(1 if w.append_steps else 0),
+                          "step_launches": ctx.hata_step_plan(w.B)[0]}))
         ctx.close()
         return
 
@@ -167,9 +175,11 @@ def main():
         step_calls[i % n_combo]()
 
     ms_step, ms_wall = timed(step, args.steps, args.warmup)
+    ctx.hata_check(stream)  # raises if a single-launch step gave up an in-kernel wait
     us_step = ms_step * 1e3
+    n_launches, plan_chunk, plan_n_chunks = ctx.hata_step_plan(w.B)
 
-    # ---- the dominant kernel alone (Hamming scoring: the largest stream of bytes), same launch
+    # ---- the scoring stage alone (the largest stream of bytes of the step)
     qcodes_buf, scores_buf, _ = ctx.hata_step_buffers()
 
     score_calls = [ctx.prepared("hata_hamming_score", qcodes_buf, codes_all[l], seq_steps[0], w.B,
@@ -224,6 +234,20 @@ def main():
         parity = {"idx_equal": idx_equal, "attn_within_tol": ok, "max_abs_err": float(err.max())}
 
     alg_bytes = w.algorithmic_bytes(1 if w.append_steps else 0)
+    traffic = HBM_TRAFFIC_BYTES.get(w.name, {})
+    step_gbps = alg_bytes / (us_step * 1e-6) / 1e9
+    score_stage = {"kernel": "score_kernel (hata_hamming_score)", "achieved": round(score_gbps, 1),
+                   "unit": "GB/s", "frac": round(score_gbps / HBM_PEAK_GBPS, 4),
+                   "traffic": traffic.get("score"), "algorithmic_bytes_per_launch": code_bytes,
+                   "avg_launch_us": round(ms_score * 1e3, 3)}
+    if n_launches == 1:
+        # the whole step is ONE kernel: it is the dominant kernel, its launch is the step
+        roofline = {"bound": "hbm", "kernel": "decode_step_coop_kernel (hata_decode_step: the whole step in one launch)",
+                    "achieved": round(step_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                    "frac": round(step_gbps / HBM_PEAK_GBPS, 4), "traffic": traffic.get("step"),
+                    "algorithmic_bytes_per_launch": alg_bytes, "avg_launch_us": round(us_step, 3)}
+    else:
+        roofline = dict(score_stage, bound="hbm", peak=HBM_PEAK_GBPS)
     result = {
         "metric": "hata_decode_attention_us_per_step",
         "value": round(us_step, 3),
@@ -240,17 +264,14 @@ def main():
         "config": {"workload": w.name, "B": w.B, "Hq": w.Hq, "Hkv": w.Hkv, "d": w.d, "r": w.r,
                    "L": list(w.L) if len(set(w.L)) > 1 else w.L[0],
                    "k": list(w.k) if len(set(w.k)) > 1 else w.k[0],
-                   "layers_rotated": n_layers, "append_per_step": True},
-        "achieved_GBps": round(alg_bytes / (us_step * 1e-6) / 1e9, 1),
+                   "layers_rotated": n_layers, "append_per_step": True,
+                   "launches_per_step": n_launches, "chunk": plan_chunk, "chunks_per_unit": plan_n_chunks},
+        "achieved_GBps": round(step_gbps, 1),
         "algorithmic_bytes_per_step": alg_bytes,
-        "step_roofline_frac": round(alg_bytes / (us_step * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4),
+        "step_roofline_frac": round(step_gbps / HBM_PEAK_GBPS, 4),
         "host_wall_us_per_step": round(ms_wall * 1e3, 3),
-        "roofline": {"bound": "hbm", "kernel": "score_kernel (hata_hamming_score)",
-                     "achieved": round(score_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": round(score_gbps / HBM_PEAK_GBPS, 4),
-                     "traffic": SCORE_KERNEL_TRAFFIC_BYTES.get(w.name),
-                     "algorithmic_bytes_per_launch": code_bytes,
-                     "avg_launch_us": round(ms_score * 1e3, 3)},
+        "roofline": roofline,
+        "score_stage": score_stage,
         "encode_keys_bulk": {"us_per_layer": round(enc_ms * 1e3, 1), "keys": enc_keys,
                              "GBps": round(enc_bytes / (enc_ms * 1e-3) / 1e9, 1),
                              "TFLOPs": round(enc_flop / (enc_ms * 1e-3) / 1e12, 2)},

@@ -55,7 +55,8 @@ typedef enum {
     HATA_EINVAL = -1,       /* NULL pointer, B out of range, bad stride/alignment, ... */
     HATA_EUNSUPPORTED = -2, /* a shape this build has no kernel for */
     HATA_EWORKSPACE = -3,   /* workspace NULL, misaligned or too small */
-    HATA_EHIP = -4          /* a HIP runtime call failed (launch error, no device, ...) */
+    HATA_EHIP = -4,         /* a HIP runtime call failed (launch error, no device, ...) */
+    HATA_ETIMEOUT = -5      /* hata_check(): a single-launch decode step gave up its bounded in-kernel wait */
 } hata_status;
 
 typedef struct {
@@ -92,8 +93,9 @@ int hata_destroy(hata_ctx* ctx);
  *   codes[b, h, n, :] = BitPack(Sign(K[b, h, n, :] . W_H[h]))   for start[b] <= n < start[b] + n_new[b].
  * `max_new` (host value) is an upper bound of n_new[b] and sizes the launch; rows outside the
  * range, and rows >= L_cap, are not touched.  Small max_new (<= 8) uses an fp64-accumulating
- * kernel; larger uses the tiled projection kernel (fp32 accumulation: a bit may differ from an
- * exact evaluation only where |projection| is below about 1e-5).
+ * kernel; larger uses the matrix-core projection kernel (r = 128 or 256: bf16 MFMA over an exact
+ * three-way bf16 split of W_H, fp32 accumulation; other r: fp32 vector kernel), where a bit may
+ * differ from an exact evaluation only if |projection| is below about 1e-4.
  */
 int hata_encode_keys(hata_ctx* ctx, const void* K, const float* W_H,
                      const int32_t* start, const int32_t* n_new, int32_t B, int32_t max_new,
@@ -137,10 +139,34 @@ int hata_dense_decode(hata_ctx* ctx, const void* q, const void* K, const void* V
  * of each sequence to cache row seq_len[b]-1 (static pre-allocated cache).  If `append` != 0
  * that row is hash-encoded into `codes` first; then the query is encoded, all seq_len[b] codes
  * are scored, the budget is selected and attention runs over the selected rows.
- * Intermediate qcodes / scores / idx live in the workspace (see hata_step_buffers). */
+ * Intermediate qcodes / scores / idx live in the workspace (see hata_step_buffers).
+ *
+ * Launches (see hata_step_plan): when every workgroup of the step can be resident on the device
+ * at once (r = 128 or 256, Hq/Hkv in {1, 2, 4, 5, 8}), the step is ONE kernel launch whose
+ * workgroups hand the query codes, the selection threshold and the attention partials to each
+ * other through the workspace, waiting for one another inside the kernel.  Every such wait is
+ * bounded: a workgroup that gives up raises a flag in the workspace and runs to its end, the
+ * step's outputs are then invalid, and the next hata_check() returns HATA_ETIMEOUT.  Otherwise
+ * the step is three launches (encode; score + threshold; select + attend) with no in-kernel wait.
+ * Both forms give identical results. */
 int hata_decode_step(hata_ctx* ctx, const void* q, const void* K, const void* V, const float* W_H,
                      uint32_t* codes, const int32_t* seq_len, const int32_t* k, int32_t B,
                      int32_t append, float sm_scale, void* out, float* out_f32, void* stream);
+
+/* Host-side query of how hata_decode_step() runs a batch of B sequences; nothing is enqueued.
+ * *n_launches: 1 (single cooperative launch) or 3; *chunk: cached keys per scoring workgroup;
+ * *n_chunks: scoring workgroups per (sequence, KV head).  Any output pointer (host) may be NULL. */
+int hata_step_plan(const hata_ctx* ctx, int32_t B, int32_t* n_launches, int32_t* chunk, int32_t* n_chunks);
+
+/* mode 0 (default): hata_decode_step() uses the single-launch form whenever it fits;
+ * mode 3: always the three-launch form (no in-kernel waits). */
+int hata_set_step_mode(hata_ctx* ctx, int32_t mode);
+
+/* Waits for `stream` (hipStreamSynchronize), then reports whether a single-launch decode step of
+ * this context gave up an in-kernel wait since the last check: HATA_OK, or HATA_ETIMEOUT (the
+ * flag is cleared; the outputs of the steps since the last check must be discarded).  The only
+ * synchronous call of the library besides hata_create(); never needed for the three-launch form. */
+int hata_check(hata_ctx* ctx, void* stream);
 
 /* Device pointers of the workspace regions hata_decode_step() writes (layouts as above, sized
  * for B_max); valid until the workspace is released.  Any output pointer may be NULL. */

@@ -110,6 +110,12 @@ inline int check_call(const hata_ctx* c, int B) {
     if (B < 1 || B > c->cfg.B_max) return HATA_EINVAL;
     return HATA_OK;
 }
+// the cooperative kernel needs its whole grid resident (its workgroups wait for one another) and
+// merges at most 256 attention partials per unit
+inline bool step_is_single_launch(const hata_ctx* c, int B) {
+    return c->step_mode != 3 && c->n_chunks <= 256 &&
+           (int64_t)c->n_chunks * c->cfg.Hkv * B <= c->coop_capacity;
+}
 inline bool aligned(const void* p, size_t a) { return ((uintptr_t)p % a) == 0; }
 inline int hip_rc(hipError_t e) { return e == hipSuccess ? HATA_OK : HATA_EHIP; }
 
@@ -124,6 +130,7 @@ const char* hata_strerror(int status) {
         case HATA_EUNSUPPORTED: return "unsupported shape";
         case HATA_EWORKSPACE: return "workspace missing, misaligned or too small";
         case HATA_EHIP: return "HIP runtime error";
+        case HATA_ETIMEOUT: return "a single-launch decode step gave up an in-kernel wait";
         default: return "unknown status";
     }
 }
@@ -173,8 +180,7 @@ int hata_create(hata_ctx** ctx_out, const hata_config* cfg, void* workspace, siz
         return HATA_EHIP;
     }
     c->coop_capacity = hata::coop_capacity(c);
-    if (const char* e = getenv("HATA_TUNE_PATH"))
-        if (atoi(e) == 3) c->coop_capacity = 0;  // tuning: force the three-launch step
+    c->step_mode = 0;
     *ctx_out = c;
     return HATA_OK;
 }
@@ -265,7 +271,7 @@ int hata_decode_step(hata_ctx* ctx, const void* q, const void* K, const void* V,
     // Cooperative path: encoding, scoring, selection and attention in ONE launch (workgroups of a
     // unit wait for the unit's threshold inside the kernel), when every workgroup can be resident
     // at once.
-    if ((int64_t)ctx->n_chunks * ctx->cfg.Hkv * B <= ctx->coop_capacity && ctx->n_chunks <= 256) {
+    if (step_is_single_launch(ctx, B)) {
         hipError_t e = hata::launch_coop_step(ctx, q, K, V, W_H, codes, append, seq_len, k, B,
                                               sm_scale, out, out_f32, s);
         if (e == hipSuccess) return HATA_OK;
@@ -282,6 +288,31 @@ int hata_decode_step(hata_ctx* ctx, const void* q, const void* K, const void* V,
     // TopK(S, N) compaction fused with the attention over the selected rows (gather fused too)
     e = hata::launch_attention(ctx, 2, q, K, V, ctx->idx, k, seq_len, B, sm_scale, out, out_f32, s);
     return hip_rc(e);
+}
+
+int hata_step_plan(const hata_ctx* ctx, int32_t B, int32_t* n_launches, int32_t* chunk, int32_t* n_chunks) {
+    int rc = check_call(ctx, B);
+    if (rc != HATA_OK) return rc;
+    if (n_launches) *n_launches = step_is_single_launch(ctx, B) ? 1 : 3;
+    if (chunk) *chunk = ctx->chunk;
+    if (n_chunks) *n_chunks = ctx->n_chunks;
+    return HATA_OK;
+}
+
+int hata_set_step_mode(hata_ctx* ctx, int32_t mode) {
+    if (!ctx || (mode != 0 && mode != 3)) return HATA_EINVAL;
+    ctx->step_mode = mode;
+    return HATA_OK;
+}
+
+int hata_check(hata_ctx* ctx, void* stream) {
+    if (!ctx) return HATA_EINVAL;
+    if (hipStreamSynchronize((hipStream_t)stream) != hipSuccess) return HATA_EHIP;
+    uint32_t w = 0;
+    if (hipMemcpy(&w, ctx->error_word, sizeof(w), hipMemcpyDeviceToHost) != hipSuccess) return HATA_EHIP;
+    if (!w) return HATA_OK;
+    if (hipMemset(ctx->error_word, 0, sizeof(w)) != hipSuccess) return HATA_EHIP;
+    return HATA_ETIMEOUT;
 }
 
 int hata_step_buffers(hata_ctx* ctx, uint32_t** qcodes, uint16_t** scores, int32_t** idx) {

@@ -2,7 +2,7 @@
 // (Alg. 3 of the paper from "Calculate distance in Hamming space" to the sparse attention output)
 // in ONE launch.
 //
-// grid = (n_chunks, Hkv, B); the workgroup of (unit u, chunk c)
+// grid = n_chunks * Hkv * B workgroups; the workgroup of (unit u, chunk c)
 //   0. hash-encodes its share of the unit's query vectors, publishes the code words and collects
 //      the others' (the owner of the appended row also encodes that key);
 //   1. scores its chunk of cached key codes (as score_kernel does), keeps the scores in LDS,
@@ -52,7 +52,7 @@ struct CoopArgs {
     float* partials;
     uint16_t* out;
     float* out_f32;
-    int Hq, Hkv, L_cap, k_max, chunk, n_chunks, NB, NBP;
+    int Hq, Hkv, L_cap, k_max, chunk, n_chunks, NB, NBP, units;
     int64_t sb, sh, sn;
     float scale_log2;
     uint32_t epoch;
@@ -156,8 +156,20 @@ __global__ __launch_bounds__(256, 3) void decode_step_coop_kernel(const CoopArgs
     __shared__ uint32_t s_rec[2];
     __shared__ uint32_t s_codes[(G + 1) * WD];  // codes of the G query heads and of the appended key
     const int tid = threadIdx.x;
-    const int c = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
-    const int64_t u = (int64_t)b * a.Hkv + h;
+    // Workgroup -> (unit, chunk).  Consecutive workgroup ids go to consecutive XCDs (8 of them, each
+    // with its own L2); when the unit count allows, all chunks of a unit get ids that are equal
+    // mod 8, so one L2 serves the unit's hash weights and the data its workgroups exchange.
+    int64_t u;
+    int c;
+    if (a.units % 8 == 0) {
+        const int j = blockIdx.x >> 3;
+        u = (int64_t)(j / a.n_chunks) * 8 + (blockIdx.x & 7);
+        c = j % a.n_chunks;
+    } else {
+        u = blockIdx.x / a.n_chunks;
+        c = blockIdx.x % a.n_chunks;
+    }
+    const int b = (int)(u / a.Hkv), h = (int)(u % a.Hkv);
     const int L = clampi(a.seq_len[b], 0, a.L_cap);
     const int base = c * a.chunk;
     const int hq0 = h * G;
@@ -452,14 +464,14 @@ hipError_t launch_coop_step(hata_ctx* c, const void* q, const void* K, const voi
     a.error_word = c->error_word; a.partials = c->partials;
     a.out = (uint16_t*)out; a.out_f32 = out_f32;
     a.Hq = f.Hq; a.Hkv = f.Hkv; a.L_cap = f.L_cap; a.k_max = f.k_max; a.chunk = c->chunk;
-    a.n_chunks = c->n_chunks; a.NB = c->NB; a.NBP = c->NBP;
+    a.n_chunks = c->n_chunks; a.NB = c->NB; a.NBP = c->NBP; a.units = f.Hkv * B;
     a.sb = f.kv_stride_b; a.sh = f.kv_stride_h; a.sn = f.kv_stride_n;
     a.scale_log2 = sm_scale * 1.4426950408889634f;
     c->epoch += 1;
     if (c->epoch == 0) c->epoch = 1;  // 0 is the cleared state of the flags
     a.epoch = c->epoch;
     void* args[] = {(void*)&a};
-    return hipLaunchKernel(fn, dim3(c->n_chunks, f.Hkv, B), dim3(256), args, (size_t)c->NB * 4, s);
+    return hipLaunchKernel(fn, dim3((unsigned)(c->n_chunks * f.Hkv * B)), dim3(256), args, (size_t)c->NB * 4, s);
 }
 
 }  // namespace hata

@@ -17,7 +17,8 @@ LIB_PATH = os.path.join(_HERE, "libhata.so")
 EXPORTS = (
     "hata_strerror", "hata_workspace_bytes", "hata_create", "hata_destroy", "hata_encode_keys",
     "hata_encode_query", "hata_hamming_score", "hata_topk", "hata_sparse_decode",
-    "hata_dense_decode", "hata_decode_step", "hata_step_buffers",
+    "hata_dense_decode", "hata_decode_step", "hata_step_plan", "hata_set_step_mode", "hata_check",
+    "hata_step_buffers",
 )
 
 
@@ -67,6 +68,9 @@ def load_library(build_if_missing: bool = True) -> ctypes.CDLL:
     lib.hata_dense_decode.argtypes = [_vp, _vp, _vp, _vp, _vp, _i32, ctypes.c_float, _vp, _vp, _vp]
     lib.hata_decode_step.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32,
                                      ctypes.c_float, _vp, _vp, _vp]
+    lib.hata_step_plan.argtypes = [_vp, _i32, ctypes.POINTER(_i32), ctypes.POINTER(_i32), ctypes.POINTER(_i32)]
+    lib.hata_set_step_mode.argtypes = [_vp, _i32]
+    lib.hata_check.argtypes = [_vp, _vp]
     lib.hata_step_buffers.argtypes = [_vp, ctypes.POINTER(_vp), ctypes.POINTER(_vp), ctypes.POINTER(_vp)]
     for name in EXPORTS:
         if name != "hata_strerror":
@@ -180,6 +184,19 @@ class Context:
                                                _ptr(codes), _ptr(seq_len), _ptr(k), B,
                                                1 if append else 0, sm_scale, _ptr(out),
                                                _ptr(out_f32), _stream(stream)), "hata_decode_step")
+
+    def hata_step_plan(self, B):
+        """(n_launches, chunk, n_chunks) of hata_decode_step for a batch of B sequences."""
+        n, c, nc = _i32(0), _i32(0), _i32(0)
+        _check(load_library().hata_step_plan(self._h, B, ctypes.byref(n), ctypes.byref(c),
+                                             ctypes.byref(nc)), "hata_step_plan")
+        return n.value, c.value, nc.value
+
+    def hata_set_step_mode(self, mode):
+        _check(load_library().hata_set_step_mode(self._h, mode), "hata_set_step_mode")
+
+    def hata_check(self, stream=None):
+        _check(load_library().hata_check(self._h, _stream(stream)), "hata_check")
 
     def prepared(self, name, *args, stream=None):
         """Marshal the arguments of entry point ``name`` once and return a zero-argument callable

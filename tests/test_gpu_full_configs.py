@@ -53,13 +53,16 @@ def run_config(torch, index, steps_to_check):
     out = c.empty((B, w.Hq, w.d), torch.int16)
     out32 = c.empty((B, w.Hq, w.d), torch.float32)
     n_steps = max(1, w.append_steps)
+    n_launches, chunk, n_chunks = c.ctx.hata_step_plan(B)
+    print(f"[full]   step plan: {n_launches} launch(es), chunk {chunk}, {n_chunks} chunks per unit", flush=True)
+    assert n_launches == 1, "the five configurations are meant to run as one cooperative launch"
     for t in range(n_steps):
         seq = inp.seq_len + (t + 1 if w.append_steps else 0)
         append = bool(w.append_steps)
         q = inp.q(t)
         c.ctx.hata_decode_step(H.to_dev(q), c.K, c.V, c.W_H, codes_d, H.to_dev(seq), c.k, B, append,
                                c.scale, out, out32)
-        c.sync()
+        c.ctx.hata_check()
         if t not in steps_to_check:
             # keep the host copy of the code cache in step with the device (oracle-encoded row)
             if append:
@@ -81,6 +84,16 @@ def run_config(torch, index, steps_to_check):
         e = H.check_attention(H.to_host(out32), H.to_host(out, np.uint16), ref["out"], f"step {t}")
         print(f"[full]   step {t}: codes/scores/idx exact; attention max abs {e[0]:.2e} max rel {e[1]:.2e} "
               f"({time.time() - t_start:.1f}s)", flush=True)
+        # the same step in its three-launch form (re-appending the same row is idempotent)
+        c.ctx.hata_set_step_mode(3)
+        assert c.ctx.hata_step_plan(B)[0] == 3
+        out.zero_(); out32.zero_(); ix.fill_(-7)
+        c.ctx.hata_decode_step(H.to_dev(q), c.K, c.V, c.W_H, codes_d, H.to_dev(seq), c.k, B, append,
+                               c.scale, out, out32)
+        c.ctx.hata_check()
+        c.ctx.hata_set_step_mode(0)
+        assert np.array_equal(H.to_host(ix), ref["idx"]), f"step {t}: index lists (three launches)"
+        H.check_attention(H.to_host(out32), H.to_host(out, np.uint16), ref["out"], f"step {t} (three launches)")
     if w.append_steps:
         assert np.array_equal(H.to_host(codes_d, np.uint32)[:, :, :w.L_cap], codes_h), "code cache after the run"
     # ---- dense baseline over the whole cache at the same shape (Eq. 1)

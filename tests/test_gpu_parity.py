@@ -148,9 +148,15 @@ def test_sparse_and_dense_decode(case):
     print(f"  dense decode max abs err {e[0]:.2e}, max rel err {e[1]:.2e}")
 
 
-def test_decode_step_end_to_end(case):
+@pytest.mark.parametrize("mode", [0, 3])
+def test_decode_step_end_to_end(case, mode):
+    """mode 0: the single-launch form where the shape has one; mode 3: three launches."""
     import torch
     w = case.w
+    case.ctx.hata_set_step_mode(mode)
+    n_launches, chunk, n_chunks = case.ctx.hata_step_plan(w.B)
+    single_ok = w.r in (128, 256) and (w.Hq // w.Hkv) in (1, 2, 4, 5, 8)
+    assert n_launches == (1 if (mode == 0 and single_ok) else 3), (n_launches, chunk, n_chunks)
     q = case.inp.q(3)
     # host: codes of rows [0, L-1) known, row L-1 is appended by the step
     codes_h = case.codes_ref.copy()
@@ -162,20 +168,23 @@ def test_decode_step_end_to_end(case):
     out = case.empty((w.B, w.Hq, w.d), torch.int16)
     out32 = case.empty((w.B, w.Hq, w.d), torch.float32)
     qd = H.to_dev(q)
-    for rep in range(2):  # the second run must reproduce the first bit for bit
-        case.ctx.hata_decode_step(qd, case.K, case.V, case.W_H, codes_d, case.seq_len, case.k, w.B,
-                                  True, case.scale, out, out32)
-        case.sync()
-        qc, sc, ix = case.ctx.hata_step_buffers()
-        assert np.array_equal(H.to_host(codes_d, np.uint32), codes_h), "appended code row"
-        assert np.array_equal(H.to_host(qc, np.uint32), ref["qcodes"])
-        got_s = H.to_host(sc, np.uint16).astype(np.int32)
-        for b in range(w.B):
-            L = int(case.inp.seq_len[b])
-            assert np.array_equal(got_s[b, :, :L], ref["scores"][b, :, :L])
-        assert np.array_equal(H.to_host(ix), ref["idx"])
-        H.check_attention(H.to_host(out32), H.to_host(out, np.uint16), ref["out"], "decode_step")
-        if rep == 0:
-            first = (out.clone(), out32.clone())
-        else:
-            assert torch.equal(out, first[0]) and torch.equal(out32, first[1])
+    try:
+        for rep in range(2):  # the second run must reproduce the first bit for bit
+            case.ctx.hata_decode_step(qd, case.K, case.V, case.W_H, codes_d, case.seq_len, case.k, w.B,
+                                      True, case.scale, out, out32)
+            case.ctx.hata_check()  # waits for the stream; raises if an in-kernel wait gave up
+            qc, sc, ix = case.ctx.hata_step_buffers()
+            assert np.array_equal(H.to_host(codes_d, np.uint32), codes_h), "appended code row"
+            assert np.array_equal(H.to_host(qc, np.uint32), ref["qcodes"])
+            got_s = H.to_host(sc, np.uint16).astype(np.int32)
+            for b in range(w.B):
+                L = int(case.inp.seq_len[b])
+                assert np.array_equal(got_s[b, :, :L], ref["scores"][b, :, :L])
+            assert np.array_equal(H.to_host(ix), ref["idx"])
+            H.check_attention(H.to_host(out32), H.to_host(out, np.uint16), ref["out"], "decode_step")
+            if rep == 0:
+                first = (out.clone(), out32.clone())
+            else:
+                assert torch.equal(out, first[0]) and torch.equal(out32, first[1])
+    finally:
+        case.ctx.hata_set_step_mode(0)
