@@ -175,9 +175,10 @@ __device__ __forceinline__ void attn_emit(
 
 // Merge ns slices (written by other workgroups of this launch with attn_emit) into the output of
 // the HT heads: part0 = partial of head 0, slice 0; slices are HATA_PSTRIDE apart, heads
-// head_stride apart.  Every load is issued before the first wait: each thread pulls the first 16
-// slices of its NO output channels into registers (later slices batch by batch) while one wave per
-// head turns the (max, sum) pairs into normalised weights in LDS (S.acc is reused; ns <= 256).
+// head_stride apart.  Every load is issued before the first wait: the (max, sum) pairs of the heads
+// a wave prepares, then the first 16 slices of each thread's NO output channels (later slices batch
+// by batch); one wave per head turns the pairs into normalised weights in LDS (S.acc is reused;
+// ns <= 256).
 // Must be called by all 256 threads, after a barrier that follows the last use of S.
 template <int HT>
 __device__ __forceinline__ void attn_merge(
@@ -185,8 +186,26 @@ __device__ __forceinline__ void attn_merge(
     uint16_t* __restrict__ out, float* __restrict__ out_f32) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     constexpr int NO = (HT * HATA_D + 255) / 256;  // outputs (head, channel) per thread
+    constexpr int HPW = (HT + 3) / 4;              // heads whose weights one wave prepares
     float* sm_w = &S.acc[0][0][0];                 // [HT][nsp]
     const int nsp = (ns + 3) & ~3;
+    // the (max, sum) pairs first -- they head the longest dependent chain -- lane l takes slices
+    // l, l + 64, ... (ns <= 256)
+    float mv[HPW][4], lv[HPW][4];
+#pragma unroll
+    for (int hh = 0; hh < HPW; ++hh) {
+        const float* pp = part0 + min(wave + 4 * hh, HT - 1) * head_stride;
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            mv[hh][t] = HATA_NEG_INF;
+            lv[hh][t] = 0.f;
+            if (t * 64 < ns) {
+                const int s2 = min(lane + 64 * t, ns - 1);
+                mv[hh][t] = ld_dev(pp + (int64_t)s2 * HATA_PSTRIDE);
+                lv[hh][t] = ld_dev(pp + (int64_t)s2 * HATA_PSTRIDE + 1);
+            }
+        }
+    }
     float av[NO][16];
 #pragma unroll
     for (int r = 0; r < NO; ++r) {
@@ -196,20 +215,29 @@ __device__ __forceinline__ void attn_merge(
 #pragma unroll
         for (int j = 0; j < 16; ++j) av[r][j] = (j < ns) ? ld_dev(pp + (int64_t)j * HATA_PSTRIDE) : 0.f;
     }
-    for (int g = wave; g < HT; g += 4) {
-        const float* pp = part0 + g * head_stride;
-        float m_loc = HATA_NEG_INF;
-        for (int s2 = lane; s2 < ns; s2 += 64) m_loc = fmaxf(m_loc, ld_dev(pp + (int64_t)s2 * HATA_PSTRIDE));
-        const float M = wave_max64(m_loc);
-        float l_loc = 0.f;
-        for (int s2 = lane; s2 < ns; s2 += 64) {
-            const float w = (M == HATA_NEG_INF) ? 0.f : fast_exp2(ld_dev(pp + (int64_t)s2 * HATA_PSTRIDE) - M);
-            sm_w[g * nsp + s2] = w;
-            l_loc = fmaf(w, ld_dev(pp + (int64_t)s2 * HATA_PSTRIDE + 1), l_loc);
+#pragma unroll
+    for (int hh = 0; hh < HPW; ++hh) {
+        const int g = wave + 4 * hh;
+        if (g < HT) {
+            float m_loc = HATA_NEG_INF;
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                if (lane + 64 * t >= ns) { mv[hh][t] = HATA_NEG_INF; lv[hh][t] = 0.f; }
+                m_loc = fmaxf(m_loc, mv[hh][t]);
+            }
+            const float M = wave_max64(m_loc);
+            float wt[4], l_loc = 0.f;
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                wt[t] = (mv[hh][t] == HATA_NEG_INF) ? 0.f : fast_exp2(mv[hh][t] - M);
+                l_loc = fmaf(wt[t], lv[hh][t], l_loc);
+            }
+            const float Lsum = wave_sum64(l_loc);
+            const float inv = Lsum > 0.f ? 1.f / Lsum : 0.f;
+#pragma unroll
+            for (int t = 0; t < 4; ++t)
+                if (lane + 64 * t < nsp) sm_w[g * nsp + lane + 64 * t] = wt[t] * inv;  // 0 past ns
         }
-        const float Lsum = wave_sum64(l_loc);
-        const float inv = Lsum > 0.f ? 1.f / Lsum : 0.f;
-        for (int s2 = lane; s2 < nsp; s2 += 64) sm_w[g * nsp + s2] = (s2 < ns) ? sm_w[g * nsp + s2] * inv : 0.f;
     }
     __syncthreads();
 #pragma unroll

@@ -305,6 +305,8 @@ __global__ __launch_bounds__(256, 3) void decode_step_coop_kernel(const CoopArgs
     int32_t* ci_u = a.chunk_info + u * (a.n_chunks + 1) * 2;
     unsigned long long* rec_u = a.rec + u * a.n_chunks * 2;
     TC(44);
+    uint32_t qr[G][4];  // query fragments for the attention: in flight across the wait below
+    attn_load_q<G>(a.q + ((int64_t)b * a.Hq + hq0) * HATA_D, qr);
     if (s_flag) {
         TU(51);
         unit_threshold<true, (G * WD * 32) / 256 + 1>(a.chunk_hist + u * a.n_chunks * a.NBP, a.unit_hist + u * a.NB, nc, keff,
@@ -359,10 +361,16 @@ __global__ __launch_bounds__(256, 3) void decode_step_coop_kernel(const CoopArgs
             lt += (live && (int)sv[i] < T) ? 1u : 0u;
             eq += (live && (int)sv[i] == T) ? 1u : 0u;
         }
-        uint32_t total;
-        const uint32_t before = block_excl_scan_256(lt | (eq << 16), scan4, &total);
+        // block-wide exclusive scan of (lt, eq) with ONE barrier, which also marks the point where
+        // every thread has read its scores, so that s_sc can become the row list
+        const uint32_t mine = lt | (eq << 16);
+        const uint32_t incl = wave_incl_scan(mine);
+        if ((tid & 63) == 63) scan4[tid >> 6] = incl;
+        __syncthreads();
+        const int wv = tid >> 6;
+        const uint32_t before = (wv > 0 ? scan4[0] : 0u) + (wv > 1 ? scan4[1] : 0u) + (wv > 2 ? scan4[2] : 0u) + incl - mine;
         uint32_t lt_b = before & 0xffffu, eq_b = before >> 16;
-        // which of this thread's keys are selected, decided before the buffer is reused
+        // which of this thread's keys are selected
         uint32_t sel_mask = 0;  // bit i: key i of this thread is selected
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
@@ -371,7 +379,6 @@ __global__ __launch_bounds__(256, 3) void decode_step_coop_kernel(const CoopArgs
             else if (live && (int)sv[i] == T) { if (eq_b < (uint32_t)take) sel_mask |= 1u << i; ++eq_b; }
         }
         eq_b = before >> 16;
-        __syncthreads();  // every thread has read its scores: s_sc now becomes the row list
         uint32_t r = lt_b + min(eq_b, (uint32_t)take);  // local rank of the thread's first selected key
         for (int i = 0; i < kpt; ++i) {
             if (sel_mask & (1u << i)) {
@@ -388,8 +395,6 @@ __global__ __launch_bounds__(256, 3) void decode_step_coop_kernel(const CoopArgs
     // ---- 4. attention over the rows this chunk contributes
     const uint16_t* Kb = a.K + b * a.sb + h * a.sh;
     const uint16_t* Vb = a.V + b * a.sb + h * a.sh;
-    uint32_t qr[G][4];  // in flight together with the first K/V rows
-    attn_load_q<G>(a.q + ((int64_t)b * a.Hq + hq0) * HATA_D, qr);
     // 8 heads share the registers with the rest of this kernel: 32-row tiles keep it spill-free
     attn_rows<G, (G >= 8 ? 2 : 4)>(qr, Kb, Vb, a.sn, a.L_cap, 0, cnt, a.scale_log2,
                  [&](int row) { return base + (int)s_sc[row]; }, S);
