@@ -118,7 +118,7 @@ def main():
         wall = (time.perf_counter() - t0) * 1e3
         return e0.elapsed_time(e1) / n, wall / n  # ms per call (device events, host wall)
 
-    # ---- prefill-side key-code writer (Alg. 1 lines 2-5), every layer once; timed separately
+    # ---- prefill-side key-code writer (Alg. 1: the key-code fill of the prefill), every layer once; timed separately
     max_prefill = int(inp.seq_len.max()) + w.append_steps
 
     enc_calls = [ctx.prepared("hata_encode_keys", K_all[l], W_H, zero, prefill_len, w.B, max_prefill,

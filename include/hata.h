@@ -89,7 +89,7 @@ int hata_create(hata_ctx** ctx_out, const hata_config* cfg, void* workspace, siz
 int hata_destroy(hata_ctx* ctx);
 
 /*
- * Key-code writer (Alg. 1 lines 2-5 in bulk; Alg. 3 "Update code cache" for one appended key):
+ * Key-code writer (the key-code fill of Alg. 1 in bulk; Alg. 3 "Update code cache" for one appended key):
  *   codes[b, h, n, :] = BitPack(Sign(K[b, h, n, :] . W_H[h]))   for start[b] <= n < start[b] + n_new[b].
  * `max_new` (host value) is an upper bound of n_new[b] and sizes the launch; rows outside the
  * range, and rows >= L_cap, are not touched.  Small max_new (<= 8) uses an fp64-accumulating

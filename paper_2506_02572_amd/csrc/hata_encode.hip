@@ -3,7 +3,7 @@
 //   encode_vectors_kernel  one workgroup per vector (query heads, appended keys);
 //                          fp64 accumulation, so the sign agrees with an exact
 //                          evaluation unless |projection| is below ~1e-13.
-//   encode_bulk_kernel     64 keys per workgroup, fp32 accumulation (prefill, Alg. 1 l.2-5).
+//   encode_bulk_kernel     64 keys per workgroup, fp32 accumulation (prefill, the key-code fill of Alg. 1).
 #include "hata_device.h"
 #include "hata_internal.h"
 
@@ -206,7 +206,7 @@ __global__ __launch_bounds__(256) void encode_bulk_kernel(
 }
 
 // ---------------------------------------------------------------------------------------
-// Prefill key-code writer on the matrix cores (Alg. 1 l.2-5: K_H = HashEncode(K)).
+// Prefill key-code writer on the matrix cores (Alg. 1: K_H = HashEncode(K) during the prefill).
 //
 // The projection [keys, 128] x [128, r] is a dense contraction, so it runs on MFMA
 // (v_mfma_f32_32x32x16_bf16).  K is bf16 already; the fp32 weights are split exactly into

@@ -32,7 +32,7 @@ def run_config(torch, index, steps_to_check):
     c = H.Case(w, oracle_codes=False)
     inp = c.inp
     B = w.B
-    # ---- bulk key encode of the prefill rows (Alg. 1 l.2-5): GPU vs oracle, band counted
+    # ---- bulk key encode of the prefill rows (the key-code fill of Alg. 1): GPU vs oracle, band counted
     prefill = inp.seq_len.copy()
     codes_ref, near = O.encode_keys_batch(inp.K, inp.W_H, np.zeros(B, np.int32), prefill, bulk=True)
     print(f"[full]   oracle bulk encode done at {time.time() - t_start:.1f}s", flush=True)
