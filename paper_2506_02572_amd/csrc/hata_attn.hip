@@ -52,7 +52,9 @@ struct AttnArgs {
 // grid = (splits, Hkv * (G / HT), B); 256 threads.
 template <int HT, int MODE>
 __global__ __launch_bounds__(256) void attn_kernel(const AttnArgs a) {
+    constexpr bool MFMA = HT >= 4;  // matrix-core form of the attention core
     __shared__ __attribute__((aligned(16))) AttnLds<HT> S;
+    __shared__ __attribute__((aligned(16))) uint16_t s_vt[MFMA ? HATA_VT_ELEMS : 8];
     __shared__ int s_rows[MODE == ROWS_SELECT ? HATA_MAX_ROWS_PER_WG : 1];
     __shared__ uint32_t scan4[4];
     __shared__ int s_clo, s_chi, s_last;
@@ -93,8 +95,10 @@ __global__ __launch_bounds__(256) void attn_kernel(const AttnArgs a) {
     const uint16_t* Vb = a.V + b * a.sb + h * a.sh;
     const int32_t* ip = (MODE == ROWS_IDX) ? a.idx_in + u * a.k_max : nullptr;
     // query fragments first: nothing below depends on them until the rows are known
-    uint32_t qr[HT][4];
-    attn_load_q<HT>(a.q + ((int64_t)b * a.Hq + hq0) * HATA_D, qr);
+    uint32_t qr[MFMA ? 1 : HT][4];
+    uint4 qb[4];
+    if constexpr (MFMA) attn_load_q_mfma<HT>(a.q + ((int64_t)b * a.Hq + hq0) * HATA_D, qb);
+    else attn_load_q<HT>(a.q + ((int64_t)b * a.Hq + hq0) * HATA_D, qr);
 
     if constexpr (MODE == ROWS_SELECT) {
         // ordered compaction of the chunks that hold positions [row_begin, row_end)
@@ -130,12 +134,16 @@ __global__ __launch_bounds__(256) void attn_kernel(const AttnArgs a) {
         __syncthreads();
     }
     TA(23);
-    attn_rows<HT, 4>(qr, Kb, Vb, a.sn, a.L_cap, row_begin, row_end, a.scale_log2,
-                  [&](int row) {
-                      if (MODE == ROWS_DENSE) return row;
-                      if (MODE == ROWS_IDX) return (int)ip[row];
-                      return s_rows[row - row_begin];
-                  }, S);
+    auto row_of = [&](int row) {
+        if (MODE == ROWS_DENSE) return row;
+        if (MODE == ROWS_IDX) return (int)ip[row];
+        return s_rows[row - row_begin];
+    };
+    if constexpr (MFMA)
+        attn_rows_mfma<HT, (MODE == ROWS_DENSE ? 2 : 1)>(qb, Kb, Vb, a.sn, a.L_cap, row_begin, row_end,
+                                                         a.scale_log2, row_of, S, s_vt);
+    else
+        attn_rows<HT, 4>(qr, Kb, Vb, a.sn, a.L_cap, row_begin, row_end, a.scale_log2, row_of, S);
     TA(24);
     const int ns = (count + a.rows_per_wg - 1) / a.rows_per_wg;  // workgroups that contribute
     const int64_t head_stride = (int64_t)a.n_splits * HATA_PSTRIDE;

@@ -28,11 +28,13 @@ __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_ex
 // partial layout per (query head, slice): [0] = running max (log2 domain), [1] = sum, [2..2+d) = acc
 #define HATA_PSTRIDE (HATA_D + 2)
 
+// (the accumulator rows are padded by 4 floats so that the 128-bit stores of the matrix-core path,
+// one head per lane, spread over the LDS banks)
 template <int HT>
 struct AttnLds {
     float m[4][HT];
     float l[4][HT];
-    float acc[4][HT][HATA_D];  // reused by the merge for the slice weights
+    float acc[4][HT][HATA_D + 4];  // reused by the merge for the slice weights
 };
 
 // this lane's 8 query elements of each of the HT heads starting at q0 (packed bf16 pairs)
@@ -140,6 +142,147 @@ __device__ __forceinline__ void attn_rows(
 #pragma unroll
             for (int e = 0; e < 8; ++e) S.acc[wave][g][sub * 8 + e] = acc[g][e];
         }
+    }
+    __syncthreads();
+}
+
+// ---- the same step on the matrix cores, for 4 <= HT <= 16 heads ----
+// With 8 heads the VALU form above is instruction-bound (every lane repeats the softmax of its row
+// for all heads, and each q.k needs a 16-lane reduction), so the two contractions go to MFMA with the
+// heads padded to 16:
+//   S[row][head]   = K_tile[16 rows][128] . Q^T[128][16 heads]     4 x v_mfma_f32_16x16x32_bf16
+//   O^T[ch][head] += V_tile^T[16 ch][16 rows] . P[16 rows][16 heads]   per 16-channel tile, P split
+//                    into two bf16 terms (hi + lo) so its rounding stays below 2^-16
+// A wave owns a tile of 16 rows.  Lane = (n = lane % 16, kg = lane / 16): for the loads n is the row
+// and kg selects 8 of every 32 channels (one 128-bit load per 32 channels, straight into the MFMA
+// operand layout); in S and in the accumulators n is the HEAD, so the online-softmax state (max,
+// sum) is one scalar per lane, and the 4 rows a lane holds of S (rows 4 kg .. 4 kg + 3) are exactly
+// the k-slice of P the second contraction wants from it.  Only V needs a transpose (its operand
+// wants 4 rows of one channel per lane): the tile goes through a wave-private LDS buffer, rows
+// padded to 264 B so that the 2-byte transposed reads are bank-conflict free.
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
+typedef __attribute__((ext_vector_type(4))) short s16x4_t;
+typedef __attribute__((ext_vector_type(4))) float f32x4_t;
+
+#define HATA_VT_PITCH 132                    // uint16 per staged V row (264 B)
+#define HATA_VT_WAVE (16 * HATA_VT_PITCH)    // uint16 per wave
+#define HATA_VT_ELEMS (4 * HATA_VT_WAVE)     // uint16 of LDS a workgroup needs for attn_rows_mfma
+
+// Q as the B operand: lane (n, kg) holds q[head n][32 s + 8 kg, + 8) for s < 4; heads >= HT are zero
+template <int HT>
+__device__ __forceinline__ void attn_load_q_mfma(const uint16_t* __restrict__ q0, uint4 (&qb)[4]) {
+    const int lane = threadIdx.x & 63, n = lane & 15, kg = lane >> 4;
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+        qb[s] = make_uint4(0, 0, 0, 0);
+        if (n < HT) qb[s] = *reinterpret_cast<const uint4*>(q0 + (int64_t)n * HATA_D + 32 * s + 8 * kg);
+    }
+}
+
+// Same contract as attn_rows (state of the four waves in S after a workgroup barrier).  IT: 16-row
+// tiles per wave whose loads are in flight together.  vt: HATA_VT_ELEMS uint16 of LDS.
+template <int HT, int IT, typename RowOf>
+__device__ __forceinline__ void attn_rows_mfma(
+    const uint4 (&qb)[4], const uint16_t* __restrict__ Kb, const uint16_t* __restrict__ Vb, int64_t sn,
+    int L_cap, int row_begin, int row_end, float scale_log2, RowOf row_of, AttnLds<HT>& S,
+    uint16_t* vt_all) {
+    static_assert(HT >= 1 && HT <= 16, "heads are padded to one 16-wide MFMA tile");
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int n = lane & 15, kg = lane >> 4;
+    uint16_t* vt = vt_all + wave * HATA_VT_WAVE;
+    float m_run = HATA_NEG_INF, l_run = 0.f;
+    f32x4_t acc[8];
+#pragma unroll
+    for (int c = 0; c < 8; ++c) acc[c] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
+    for (int tile0 = row_begin; tile0 < row_end; tile0 += 64 * IT) {
+        uint4 kr[IT][4], vr[IT][4];
+        bool ok[IT];
+#pragma unroll
+        for (int it = 0; it < IT; ++it) {
+            const int row = tile0 + (it * 4 + wave) * 16 + n;
+            ok[it] = row < row_end;
+            int idx = 0;
+            if (ok[it]) idx = row_of(row);
+            ok[it] = ok[it] && idx >= 0 && idx < L_cap;
+#pragma unroll
+            for (int s = 0; s < 4; ++s) { kr[it][s] = make_uint4(0, 0, 0, 0); vr[it][s] = make_uint4(0, 0, 0, 0); }
+            if (ok[it]) {
+                const int64_t o = (int64_t)idx * sn + 8 * kg;
+#pragma unroll
+                for (int s = 0; s < 4; ++s) {
+                    kr[it][s] = *reinterpret_cast<const uint4*>(Kb + o + 32 * s);
+                    vr[it][s] = *reinterpret_cast<const uint4*>(Vb + o + 32 * s);
+                }
+            }
+        }
+#pragma unroll
+        for (int it = 0; it < IT; ++it) {
+            if (tile0 + (it * 4 + wave) * 16 >= row_end) break;  // wave-uniform: no row in this tile
+            const unsigned long long okmask = __builtin_amdgcn_ballot_w64(ok[it]);  // bits 0..15: the tile's rows
+            f32x4_t sacc = (f32x4_t){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int s = 0; s < 4; ++s)
+                sacc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, kr[it][s]),
+                                                               __builtin_bit_cast(bf16x8_t, qb[s]), sacc, 0, 0, 0);
+            // stage V (row n, channels 32 s + 8 kg) for the transposed reads below
+#pragma unroll
+            for (int s = 0; s < 4; ++s) {
+                uint2* d = reinterpret_cast<uint2*>(vt + n * HATA_VT_PITCH + 32 * s + 8 * kg);
+                d[0] = make_uint2(vr[it][s].x, vr[it][s].y);
+                d[1] = make_uint2(vr[it][s].z, vr[it][s].w);
+            }
+            // online softmax of head n over the rows 4 kg .. 4 kg + 3 this lane holds
+            float sv[4], m_tile = HATA_NEG_INF;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const bool valid = (okmask >> (4 * kg + r)) & 1ull;
+                sv[r] = valid ? sacc[r] * scale_log2 : HATA_NEG_INF;
+                m_tile = fmaxf(m_tile, sv[r]);
+            }
+            m_tile = rows_max4(m_tile);
+            const float m_new = fmaxf(m_run, m_tile);
+            const float alpha = (m_new == HATA_NEG_INF) ? 1.f : fast_exp2(m_run - m_new);
+            float p[4], psum = 0.f;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                p[r] = (sv[r] == HATA_NEG_INF) ? 0.f : fast_exp2(sv[r] - m_new);
+                psum += p[r];
+            }
+            l_run = fmaf(l_run, alpha, psum);
+            m_run = m_new;
+            if (__builtin_amdgcn_ballot_w64(alpha != 1.f) != 0ull) {
+#pragma unroll
+                for (int c = 0; c < 8; ++c) acc[c] *= alpha;
+            }
+            // P as two bf16 terms: hi = p truncated to bf16, lo = (p - hi) truncated to bf16
+            uint32_t hb[4], lb[4];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                hb[r] = __float_as_uint(p[r]) & 0xffff0000u;
+                lb[r] = __float_as_uint(p[r] - __uint_as_float(hb[r]));
+            }
+            const uint2 ph = make_uint2((hb[0] >> 16) | hb[1], (hb[2] >> 16) | hb[3]);
+            const uint2 pl = make_uint2((lb[0] >> 16) | (lb[1] & 0xffff0000u), (lb[2] >> 16) | (lb[3] & 0xffff0000u));
+            const s16x4_t phv = __builtin_bit_cast(s16x4_t, ph), plv = __builtin_bit_cast(s16x4_t, pl);
+            __builtin_amdgcn_wave_barrier();  // (LDS serves a wave's accesses in order: the staged tile is visible)
+#pragma unroll
+            for (int c = 0; c < 8; ++c) {
+                const uint16_t* src = vt + (4 * kg) * HATA_VT_PITCH + 16 * c + n;
+                const uint32_t v0 = src[0], v1 = src[HATA_VT_PITCH], v2 = src[2 * HATA_VT_PITCH], v3 = src[3 * HATA_VT_PITCH];
+                const s16x4_t av = __builtin_bit_cast(s16x4_t, make_uint2(v0 | (v1 << 16), v2 | (v3 << 16)));
+                acc[c] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(av, phv, acc[c], 0, 0, 0);
+                acc[c] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(av, plv, acc[c], 0, 0, 0);
+            }
+            __builtin_amdgcn_wave_barrier();
+        }
+    }
+    // lanes of the 4 row groups hold partial sums of the same head
+    l_run = rows_sum4(l_run);
+    if (n < HT) {
+        if (kg == 0) { S.m[wave][n] = m_run; S.l[wave][n] = l_run; }
+#pragma unroll
+        for (int c = 0; c < 8; ++c)  // acc[c][r] = O[head n][channel 16 c + 4 kg + r]
+            *reinterpret_cast<float4*>(&S.acc[wave][n][16 * c + 4 * kg]) = make_float4(acc[c][0], acc[c][1], acc[c][2], acc[c][3]);
     }
     __syncthreads();
 }

@@ -148,7 +148,13 @@ __device__ __forceinline__ void coop_encode_vec(const float* __restrict__ Wh,
 template <int WD, int G>
 __global__ __launch_bounds__(256, 3) void decode_step_coop_kernel(const CoopArgs a) {
     extern __shared__ uint32_t hist[];  // NB words: chunk histogram, later the unit's total
-    __shared__ ThresholdLds TS;
+    constexpr bool MFMA = G >= 4;  // matrix-core form of the attention core
+    // the threshold search (last arriver only) is over before the attention stages V tiles
+    __shared__ __attribute__((aligned(16))) union {
+        ThresholdLds ts;
+        uint16_t vt[MFMA ? HATA_VT_ELEMS : 8];
+    } U;
+    ThresholdLds& TS = U.ts;
     __shared__ __attribute__((aligned(16))) AttnLds<G> S;
     __shared__ __attribute__((aligned(16))) uint16_t s_sc[HATA_COOP_MAX_CHUNK];  // chunk scores, later the selected rows (offsets in the chunk)
     __shared__ uint32_t scan4[4];
@@ -305,8 +311,11 @@ __global__ __launch_bounds__(256, 3) void decode_step_coop_kernel(const CoopArgs
     int32_t* ci_u = a.chunk_info + u * (a.n_chunks + 1) * 2;
     unsigned long long* rec_u = a.rec + u * a.n_chunks * 2;
     TC(44);
-    uint32_t qr[G][4];  // query fragments for the attention: in flight across the wait below
-    attn_load_q<G>(a.q + ((int64_t)b * a.Hq + hq0) * HATA_D, qr);
+    // query fragments for the attention: in flight across the wait below
+    uint32_t qr[MFMA ? 1 : G][4];
+    uint4 qb[4];
+    if constexpr (MFMA) attn_load_q_mfma<G>(a.q + ((int64_t)b * a.Hq + hq0) * HATA_D, qb);
+    else attn_load_q<G>(a.q + ((int64_t)b * a.Hq + hq0) * HATA_D, qr);
     if (s_flag) {
         TU(51);
         unit_threshold<true, (G * WD * 32) / 256 + 1>(a.chunk_hist + u * a.n_chunks * a.NBP, a.unit_hist + u * a.NB, nc, keff,
@@ -395,9 +404,9 @@ __global__ __launch_bounds__(256, 3) void decode_step_coop_kernel(const CoopArgs
     // ---- 4. attention over the rows this chunk contributes
     const uint16_t* Kb = a.K + b * a.sb + h * a.sh;
     const uint16_t* Vb = a.V + b * a.sb + h * a.sh;
-    // 8 heads share the registers with the rest of this kernel: 32-row tiles keep it spill-free
-    attn_rows<G, (G >= 8 ? 2 : 4)>(qr, Kb, Vb, a.sn, a.L_cap, 0, cnt, a.scale_log2,
-                 [&](int row) { return base + (int)s_sc[row]; }, S);
+    auto row_of = [&](int row) { return base + (int)s_sc[row]; };
+    if constexpr (MFMA) attn_rows_mfma<G, 1>(qb, Kb, Vb, a.sn, a.L_cap, 0, cnt, a.scale_log2, row_of, S, U.vt);
+    else attn_rows<G, 4>(qr, Kb, Vb, a.sn, a.L_cap, 0, cnt, a.scale_log2, row_of, S);
     TC(47);
     const int64_t head_stride = (int64_t)a.n_chunks * HATA_PSTRIDE;
     float* part0 = a.partials + ((int64_t)b * a.Hq + hq0) * head_stride;
