@@ -25,8 +25,14 @@ def torch_mod():
 
 
 def run_config(torch, index, steps_to_check):
+    run_workload(torch, synth.config(index), steps_to_check, single_launch=True)
+
+
+def run_workload(torch, w, steps_to_check, single_launch, dense=True):
+    """Bulk key encode, decode steps in both launch forms and the dense baseline of workload `w`,
+    each against the oracle.  single_launch: whether the step is expected to be one launch."""
     t_start = time.time()
-    w = synth.config(index)
+    index = w.name
     print(f"[full] config {index}: {w.name} B={w.B} Hq={w.Hq} Hkv={w.Hkv} L_cap={w.L_cap} r={w.r} "
           f"k_max={w.k_max}", flush=True)
     c = H.Case(w, oracle_codes=False)
@@ -55,7 +61,7 @@ def run_config(torch, index, steps_to_check):
     n_steps = max(1, w.append_steps)
     n_launches, chunk, n_chunks = c.ctx.hata_step_plan(B)
     print(f"[full]   step plan: {n_launches} launch(es), chunk {chunk}, {n_chunks} chunks per unit", flush=True)
-    assert n_launches == 1, "the five configurations are meant to run as one cooperative launch"
+    assert n_launches == (1 if single_launch else 3), "unexpected launch form of the decode step"
     for t in range(n_steps):
         seq = inp.seq_len + (t + 1 if w.append_steps else 0)
         append = bool(w.append_steps)
@@ -96,6 +102,9 @@ def run_config(torch, index, steps_to_check):
         H.check_attention(H.to_host(out32), H.to_host(out, np.uint16), ref["out"], f"step {t} (three launches)")
     if w.append_steps:
         assert np.array_equal(H.to_host(codes_d, np.uint32)[:, :, :w.L_cap], codes_h), "code cache after the run"
+    if not dense:
+        c.ctx.close()
+        return
     # ---- dense baseline over the whole cache at the same shape (Eq. 1)
     seq = inp.seq_len
     q = inp.q(0)
