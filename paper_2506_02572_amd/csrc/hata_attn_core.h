@@ -319,12 +319,12 @@ __device__ __forceinline__ void attn_emit(
 // Merge ns slices (written by other workgroups of this launch with attn_emit) into the output of
 // the HT heads: part0 = partial of head 0, slice 0; slices are HATA_PSTRIDE apart, heads
 // head_stride apart.  Every load is issued before the first wait: the (max, sum) pairs of the heads
-// a wave prepares, then the first 16 slices of each thread's NO output channels (later slices batch
+// a wave prepares, then the first 16-32 slices of each thread's NO output channels (later slices batch
 // by batch); one wave per head turns the pairs into normalised weights in LDS (S.acc is reused;
 // ns <= 256).
 // Must be called by all 256 threads, after a barrier that follows the last use of S.
-template <int HT>
-__device__ __forceinline__ void attn_merge(
+template <int HT, int NJ>
+__device__ __forceinline__ void attn_merge_nj(
     AttnLds<HT>& S, const float* __restrict__ part0, int64_t head_stride, int ns,
     uint16_t* __restrict__ out, float* __restrict__ out_f32) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -349,14 +349,15 @@ __device__ __forceinline__ void attn_merge(
             }
         }
     }
-    float av[NO][16];
+    // first NJ slices of every output of this thread, all loads in flight
+    float av[NO][NJ];
 #pragma unroll
     for (int r = 0; r < NO; ++r) {
         const int i = min(tid + 256 * r, HT * HATA_D - 1);
         const int g = i / HATA_D, ch = i % HATA_D;
         const float* pp = part0 + g * head_stride + 2 + ch;
 #pragma unroll
-        for (int j = 0; j < 16; ++j) av[r][j] = (j < ns) ? ld_dev(pp + (int64_t)j * HATA_PSTRIDE) : 0.f;
+        for (int j = 0; j < NJ; ++j) av[r][j] = (j < ns) ? ld_dev(pp + (int64_t)j * HATA_PSTRIDE) : 0.f;
     }
 #pragma unroll
     for (int hh = 0; hh < HPW; ++hh) {
@@ -391,7 +392,7 @@ __device__ __forceinline__ void attn_merge(
             const float4* w4 = reinterpret_cast<const float4*>(sm_w + g * nsp);
             float A = 0.f;
 #pragma unroll
-            for (int j4 = 0; j4 < 4; ++j4) {
+            for (int j4 = 0; j4 < NJ / 4; ++j4) {
                 if (j4 * 4 < nsp) {  // weights of slices >= ns are zero
                     const float4 w = w4[j4];
                     A = fmaf(w.x, av[r][4 * j4], A); A = fmaf(w.y, av[r][4 * j4 + 1], A);
@@ -399,7 +400,7 @@ __device__ __forceinline__ void attn_merge(
                 }
             }
             const float* pp = part0 + g * head_stride + 2 + ch;
-            for (int s0 = 16; s0 < ns; s0 += 16) {
+            for (int s0 = NJ; s0 < ns; s0 += 16) {
                 float bv[16];
 #pragma unroll
                 for (int j = 0; j < 16; ++j) bv[j] = (s0 + j < ns) ? ld_dev(pp + (int64_t)(s0 + j) * HATA_PSTRIDE) : 0.f;
@@ -411,6 +412,18 @@ __device__ __forceinline__ void attn_merge(
             if (out_f32) out_f32[i] = A;
         }
     }
+}
+
+// NJ (slices whose loads are in flight together) by the number of slices: a second batch costs a
+// memory round trip, registers bound the first (80 per thread at most)
+template <int HT>
+__device__ __forceinline__ void attn_merge(
+    AttnLds<HT>& S, const float* __restrict__ part0, int64_t head_stride, int ns,
+    uint16_t* __restrict__ out, float* __restrict__ out_f32) {
+    constexpr int NO = (HT * HATA_D + 255) / 256;
+    constexpr int NJ_BIG = NO <= 2 ? 32 : (NO <= 4 ? 20 : 16);
+    if (NJ_BIG > 16 && ns > 16) attn_merge_nj<HT, NJ_BIG>(S, part0, head_stride, ns, out, out_f32);
+    else attn_merge_nj<HT, 16>(S, part0, head_stride, ns, out, out_f32);
 }
 
 }  // namespace hata

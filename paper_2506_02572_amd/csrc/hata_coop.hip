@@ -107,39 +107,58 @@ __device__ __forceinline__ double rotadd8(double x) {
 // sums are combined across the parts with lane swaps, each step halving the live values: lane
 // (bit5, bit4) ends up with the total of column 4 cg + bit4 + 2 bit5.
 template <int WD>
-__device__ __forceinline__ void coop_encode_vec(const float* __restrict__ Wh,
-                                                const uint16_t* __restrict__ x, uint32_t* s_word) {
+struct EncodeLoads {  // what coop_encode_vec needs before its first FMA
+    static constexpr int CP = HATA_D / (64 / (WD * 2));
+    float4 w[16];         // first 16 weight rows of this lane's channel part
+    uint32_t xw[CP / 2];  // the part's channels of x, bf16 pairs
+};
+template <int WD>
+__device__ __forceinline__ void coop_encode_load(const float* __restrict__ Wh,
+                                                 const uint16_t* __restrict__ x, EncodeLoads<WD>& e) {
+    constexpr int R = WD * 32, CG = R / 16, P = 64 / CG, CP = HATA_D / P;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int cg = lane % CG, p = lane / CG;
+    const float* wp = Wh + (int64_t)(p * CP) * R + wave * (R / 4) + 4 * cg;
+#pragma unroll
+    for (int i = 0; i < CP / 8; ++i) {
+        const uint4 v = reinterpret_cast<const uint4*>(x + p * CP)[i];
+        e.xw[4 * i] = v.x; e.xw[4 * i + 1] = v.y; e.xw[4 * i + 2] = v.z; e.xw[4 * i + 3] = v.w;
+    }
+#pragma unroll
+    for (int j = 0; j < 16; ++j) e.w[j] = *reinterpret_cast<const float4*>(wp + (int64_t)j * R);
+}
+template <int WD>
+__device__ __forceinline__ void coop_encode_vec(const float* __restrict__ Wh, const EncodeLoads<WD>& e,
+                                                uint32_t* s_word) {
     constexpr int R = WD * 32, CG = R / 16, P = 64 / CG, CP = HATA_D / P;  // CP = 16 or 32 channels
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int cg = lane % CG, p = lane / CG;
     const float* wp = Wh + (int64_t)(p * CP) * R + wave * (R / 4) + 4 * cg;
-    uint32_t xw[CP / 2];  // this part's channels, bf16 pairs
-#pragma unroll
-    for (int i = 0; i < CP / 8; ++i) {
-        const uint4 v = reinterpret_cast<const uint4*>(x + p * CP)[i];
-        xw[4 * i] = v.x; xw[4 * i + 1] = v.y; xw[4 * i + 2] = v.z; xw[4 * i + 3] = v.w;
-    }
     double a0 = 0.0, a1 = 0.0, a2 = 0.0, a3 = 0.0;
+    auto fma_row = [&](const float4& w, int ch) {
+        const uint32_t pair = e.xw[ch >> 1];
+        const double xd = (double)((ch & 1) ? bf16_hi(pair) : bf16_lo(pair));
+        a0 = fma((double)w.x, xd, a0);
+        a1 = fma((double)w.y, xd, a1);
+        a2 = fma((double)w.z, xd, a2);
+        a3 = fma((double)w.w, xd, a3);
+    };
 #pragma unroll
-    for (int c0 = 0; c0 < CP; c0 += 16) {
-        float4 w[16];
+    for (int j = 0; j < 16; ++j) fma_row(e.w[j], j);
+    // r = 256: the part's other 16 weight rows, 8 at a time (registers)
 #pragma unroll
-        for (int j = 0; j < 16; ++j) w[j] = *reinterpret_cast<const float4*>(wp + (int64_t)(c0 + j) * R);
+    for (int c0 = 16; c0 < CP; c0 += 8) {
+        float4 w[8];
 #pragma unroll
-        for (int j = 0; j < 16; ++j) {
-            const uint32_t pair = xw[(c0 + j) >> 1];
-            const double xd = (double)(((c0 + j) & 1) ? bf16_hi(pair) : bf16_lo(pair));
-            a0 = fma((double)w[j].x, xd, a0);
-            a1 = fma((double)w[j].y, xd, a1);
-            a2 = fma((double)w[j].z, xd, a2);
-            a3 = fma((double)w[j].w, xd, a3);
-        }
+        for (int j = 0; j < 8; ++j) w[j] = *reinterpret_cast<const float4*>(wp + (int64_t)(c0 + j) * R);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) fma_row(w[j], c0 + j);
     }
     const int b5 = lane >> 5, b4 = (lane >> 4) & 1;
     const int col = wave * (R / 4) + 4 * cg + b4 + 2 * b5;  // hash column this lane ends up with
-    const double e = swapadd32(a0, a2);  // column 0 + 2 b5
-    const double o = swapadd32(a1, a3);  // column 1 + 2 b5
-    double t = swapadd16(e, o);
+    const double ev = swapadd32(a0, a2);  // column 0 + 2 b5
+    const double od = swapadd32(a1, a3);  // column 1 + 2 b5
+    double t = swapadd16(ev, od);
     if (P == 8) t = rotadd8(t);
     if (t >= 0.0) atomicOr(&s_word[col >> 5], 1u << (col & 31));
 }
@@ -176,6 +195,13 @@ __global__ __launch_bounds__(256, 3) void decode_step_coop_kernel(const CoopArgs
         c = blockIdx.x % a.n_chunks;
     }
     const int b = (int)(u / a.Hkv), h = (int)(u % a.Hkv);
+    // the query vector this workgroup will encode first (vector c, if c < G) does not depend on the
+    // sequence length: its loads go out before anything else
+    const uint16_t* qv = a.q + ((int64_t)b * a.Hq + h * G) * HATA_D;
+    const float* Wh = a.W_H + (int64_t)h * HATA_D * (WD * 32);
+    EncodeLoads<WD> el;
+    constexpr bool EARLY = WD == 4;  // (at r = 256 the second half of the weights needs the registers)
+    if (EARLY && c < G) coop_encode_load<WD>(Wh, qv + c * HATA_D, el);
     const int L = clampi(a.seq_len[b], 0, a.L_cap);
     const int base = c * a.chunk;
     const int hq0 = h * G;
@@ -194,22 +220,23 @@ __global__ __launch_bounds__(256, 3) void decode_step_coop_kernel(const CoopArgs
     const int nc = (L + a.chunk - 1) / a.chunk;
     const bool own = a.append && L > 0 && base <= L - 1 && L - 1 < base + a.chunk;
     {
-        const uint16_t* qv = a.q + ((int64_t)b * a.Hq + hq0) * HATA_D;
-        const float* Wh = a.W_H + (int64_t)h * HATA_D * (WD * 32);
         unsigned long long* qrec = a.qrec + ((int64_t)b * a.Hq + hq0) * WD;
         if (tid < (G + 1) * WD) s_codes[tid] = 0;
         for (int i = tid; i < a.NB; i += 256) hist[i] = 0;
         __syncthreads();
         for (int v = c; v < G; v += max(nc, 1)) {
-            coop_encode_vec<WD>(Wh, qv + v * HATA_D, &s_codes[v * WD]);
+            if (!EARLY || v != c) coop_encode_load<WD>(Wh, qv + v * HATA_D, el);
+            coop_encode_vec<WD>(Wh, el, &s_codes[v * WD]);
             __syncthreads();
             if (tid < WD)
                 __hip_atomic_store(qrec + v * WD + tid,
                                    ((unsigned long long)a.epoch << 32) | s_codes[v * WD + tid],
                                    __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
-        if (own)
-            coop_encode_vec<WD>(Wh, a.K + b * a.sb + h * a.sh + (int64_t)(L - 1) * a.sn, &s_codes[G * WD]);
+        if (own) {
+            coop_encode_load<WD>(Wh, a.K + b * a.sb + h * a.sh + (int64_t)(L - 1) * a.sn, el);
+            coop_encode_vec<WD>(Wh, el, &s_codes[G * WD]);
+        }
         if (tid < 64) {  // one wave collects the G * WD (<= 64) query code words of the unit
             const int i = min(tid, G * WD - 1);
             int budget = HATA_COOP_SPIN_LIMIT;
