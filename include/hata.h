@@ -162,6 +162,12 @@ int hata_step_plan(const hata_ctx* ctx, int32_t B, int32_t* n_launches, int32_t*
  * mode 3: always the three-launch form (no in-kernel waits). */
 int hata_set_step_mode(hata_ctx* ctx, int32_t mode);
 
+/* Bound of every in-kernel wait of the single-launch form, in polls (0 restores the default, 2^18:
+ * far longer than any step).  A tiny bound makes the waits give up at once -- the kernel still runs
+ * to its end, writes nothing out of bounds, and hata_check() then returns HATA_ETIMEOUT -- which is
+ * how the error path is exercised in the tests. */
+int hata_set_wait_limit(hata_ctx* ctx, int32_t polls);
+
 /* Waits for `stream` (hipStreamSynchronize), then reports whether a single-launch decode step of
  * this context gave up an in-kernel wait since the last check: HATA_OK, or HATA_ETIMEOUT (the
  * flag is cleared; the outputs of the steps since the last check must be discarded).  The only

@@ -181,6 +181,7 @@ int hata_create(hata_ctx** ctx_out, const hata_config* cfg, void* workspace, siz
     }
     c->coop_capacity = hata::coop_capacity(c);
     c->step_mode = 0;
+    c->spin_limit = 0;
     *ctx_out = c;
     return HATA_OK;
 }
@@ -302,6 +303,12 @@ int hata_step_plan(const hata_ctx* ctx, int32_t B, int32_t* n_launches, int32_t*
 int hata_set_step_mode(hata_ctx* ctx, int32_t mode) {
     if (!ctx || (mode != 0 && mode != 3)) return HATA_EINVAL;
     ctx->step_mode = mode;
+    return HATA_OK;
+}
+
+int hata_set_wait_limit(hata_ctx* ctx, int32_t polls) {
+    if (!ctx || polls < 0) return HATA_EINVAL;
+    ctx->spin_limit = polls;
     return HATA_OK;
 }
 

@@ -27,7 +27,7 @@
 namespace hata {
 
 #define HATA_COOP_MAX_CHUNK 4096
-#define HATA_COOP_SPIN_LIMIT (1 << 18)
+#define HATA_COOP_SPIN_LIMIT (1 << 18)  // default bound of every in-kernel wait (polls, ~0.1 us apart at least)
 
 struct CoopArgs {
     const uint16_t* q;
@@ -57,6 +57,7 @@ struct CoopArgs {
     float scale_log2;
     uint32_t epoch;
     int append;
+    int spin_limit;
 };
 
 template <int WD>
@@ -239,7 +240,7 @@ __global__ __launch_bounds__(256, 3) void decode_step_coop_kernel(const CoopArgs
         }
         if (tid < 64) {  // one wave collects the G * WD (<= 64) query code words of the unit
             const int i = min(tid, G * WD - 1);
-            int budget = HATA_COOP_SPIN_LIMIT;
+            int budget = a.spin_limit;
             unsigned long long r;
             for (;;) {
                 r = __hip_atomic_load(qrec + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -352,7 +353,7 @@ __global__ __launch_bounds__(256, 3) void decode_step_coop_kernel(const CoopArgs
     // every workgroup (the last arriver too) picks up its chunk's record: two words that carry
     // this launch's epoch once the threshold of the unit has been published
     if (tid == 0) {
-        int budget = HATA_COOP_SPIN_LIMIT;
+        int budget = a.spin_limit;
         unsigned long long r0, r1;
         for (;;) {
             r0 = __hip_atomic_load(rec_u + 2 * c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -498,6 +499,7 @@ hipError_t launch_coop_step(hata_ctx* c, const void* q, const void* K, const voi
     CoopArgs a;
     a.q = (const uint16_t*)q; a.K = (const uint16_t*)K; a.V = (const uint16_t*)V;
     a.W_H = W_H; a.append = append;
+    a.spin_limit = c->spin_limit > 0 ? c->spin_limit : HATA_COOP_SPIN_LIMIT;
     a.qcodes = c->qcodes; a.codes = codes; a.seq_len = seq_len; a.kbud = k;
     a.scores = c->scores; a.idx = c->idx; a.chunk_hist = c->chunk_hist;
     a.chunk_info = c->chunk_info; a.unit_info = c->unit_info; a.unit_counter = c->unit_counter;

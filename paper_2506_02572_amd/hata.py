@@ -17,7 +17,8 @@ LIB_PATH = os.path.join(_HERE, "libhata.so")
 EXPORTS = (
     "hata_strerror", "hata_workspace_bytes", "hata_create", "hata_destroy", "hata_encode_keys",
     "hata_encode_query", "hata_hamming_score", "hata_topk", "hata_sparse_decode",
-    "hata_dense_decode", "hata_decode_step", "hata_step_plan", "hata_set_step_mode", "hata_check",
+    "hata_dense_decode", "hata_decode_step", "hata_step_plan", "hata_set_step_mode", "hata_set_wait_limit",
+    "hata_check",
     "hata_step_buffers",
 )
 
@@ -70,6 +71,7 @@ def load_library(build_if_missing: bool = True) -> ctypes.CDLL:
                                      ctypes.c_float, _vp, _vp, _vp]
     lib.hata_step_plan.argtypes = [_vp, _i32, ctypes.POINTER(_i32), ctypes.POINTER(_i32), ctypes.POINTER(_i32)]
     lib.hata_set_step_mode.argtypes = [_vp, _i32]
+    lib.hata_set_wait_limit.argtypes = [_vp, _i32]
     lib.hata_check.argtypes = [_vp, _vp]
     lib.hata_step_buffers.argtypes = [_vp, ctypes.POINTER(_vp), ctypes.POINTER(_vp), ctypes.POINTER(_vp)]
     for name in EXPORTS:
@@ -194,6 +196,9 @@ class Context:
 
     def hata_set_step_mode(self, mode):
         _check(load_library().hata_set_step_mode(self._h, mode), "hata_set_step_mode")
+
+    def hata_set_wait_limit(self, polls):
+        _check(load_library().hata_set_wait_limit(self._h, polls), "hata_set_wait_limit")
 
     def hata_check(self, stream=None):
         _check(load_library().hata_check(self._h, _stream(stream)), "hata_check")

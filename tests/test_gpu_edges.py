@@ -112,6 +112,39 @@ def test_step_with_empty_sequence_and_partial_batch(torch_mod):
     ctx.close()
 
 
+def test_single_launch_wait_gives_up_cleanly_and_is_reported(torch_mod):
+    """Error path of the single-launch step, forced from the host: with a wait bound of one poll
+    the workgroups give up at once; the kernel still runs to its end, hata_check() reports
+    HATA_ETIMEOUT once, and the next step (default bound) is correct again."""
+    torch = torch_mod
+    from paper_2506_02572_amd import hata
+    w = synth.Workload("giveup", 2, 8, 2, 128, 128, (5000, 3001), (100, 333), 4, 8.0, L_cap=5120)
+    c = H.Case(w, seed=4321)
+    assert c.ctx.hata_step_plan(w.B)[0] == 1 and c.ctx.hata_step_plan(w.B)[2] >= 2
+    q = c.inp.q(1)
+    codes_h = c.codes_ref.copy()
+    codes_d = H.to_dev(codes_h)
+    out = c.empty((w.B, w.Hq, w.d), torch.int16)
+    out32 = c.empty((w.B, w.Hq, w.d), torch.float32)
+    c.ctx.hata_set_wait_limit(1)
+    c.ctx.hata_decode_step(H.to_dev(q), c.K, c.V, c.W_H, codes_d, c.seq_len, c.k, w.B, False,
+                           c.scale, out, out32)
+    with pytest.raises(hata.HataError, match="gave up"):
+        c.ctx.hata_check()
+    c.ctx.hata_check()  # the flag was cleared by the failed check
+    c.ctx.hata_set_wait_limit(0)
+    ref = O.decode_step(q, c.inp.K, c.inp.V, c.inp.W_H, codes_h, c.inp.seq_len, c.inp.k, w.k_max,
+                        c.scale, append=False)
+    for _ in range(2):
+        c.ctx.hata_decode_step(H.to_dev(q), c.K, c.V, c.W_H, codes_d, c.seq_len, c.k, w.B, False,
+                               c.scale, out, out32)
+        c.ctx.hata_check()
+        _, _, ix = c.ctx.hata_step_buffers()
+        assert np.array_equal(H.to_host(ix), ref["idx"])
+        H.check_attention(H.to_host(out32), H.to_host(out, np.uint16), ref["out"], "after give-up")
+    c.ctx.close()
+
+
 def test_sparse_decode_skips_negative_entries_and_strided_cache(torch_mod):
     torch = torch_mod
     from paper_2506_02572_amd import hata

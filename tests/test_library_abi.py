@@ -29,7 +29,8 @@ def test_every_declared_symbol_is_exported_and_bound():
 def test_strerror_and_workspace_validation():
     lib = hata.load_library()
     assert hata.strerror(0) == "ok"
-    for code in (-1, -2, -3, -4, -99):
+    assert "gave up" in hata.strerror(-5)
+    for code in (-1, -2, -3, -4, -5, -99):
         assert hata.strerror(code)
     n = ctypes.c_size_t(0)
     good = hata.hata_config(1, 32, 8, 128, 128, 32768, 512, 8 * 32768 * 128, 32768 * 128, 128)
@@ -54,6 +55,10 @@ def test_strerror_and_workspace_validation():
     # calls on a NULL context are rejected, nothing is launched
     assert lib.hata_encode_query(None, None, None, 1, None, None) == -1
     assert lib.hata_decode_step(None, None, None, None, None, None, None, None, 1, 0, 1.0, None, None, None) == -1
+    assert lib.hata_step_plan(None, 1, None, None, None) == -1
+    assert lib.hata_set_step_mode(None, 0) == -1
+    assert lib.hata_set_wait_limit(None, 0) == -1
+    assert lib.hata_check(None, None) == -1
     assert lib.hata_destroy(None) == 0
 
 
