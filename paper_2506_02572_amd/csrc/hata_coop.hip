@@ -180,6 +180,7 @@ __global__ __launch_bounds__(256, 3) void decode_step_coop_kernel(const CoopArgs
     __shared__ uint32_t scan4[4];
     __shared__ int s_flag;
     __shared__ uint32_t s_rec[2];
+    __shared__ int s_low;  // lowest score of this chunk
     __shared__ uint32_t s_codes[(G + 1) * WD];  // codes of the G query heads and of the appended key
     const int tid = threadIdx.x;
     // Workgroup -> (unit, chunk).  Consecutive workgroup ids go to consecutive XCDs (8 of them, each
@@ -223,6 +224,7 @@ __global__ __launch_bounds__(256, 3) void decode_step_coop_kernel(const CoopArgs
     {
         unsigned long long* qrec = a.qrec + ((int64_t)b * a.Hq + hq0) * WD;
         if (tid < (G + 1) * WD) s_codes[tid] = 0;
+        if (tid == 0) s_low = a.NB;
         for (int i = tid; i < a.NB; i += 256) hist[i] = 0;
         __syncthreads();
         for (int v = c; v < G; v += max(nc, 1)) {
@@ -277,6 +279,7 @@ __global__ __launch_bounds__(256, 3) void decode_step_coop_kernel(const CoopArgs
         uint16_t* sp = a.scores + u * a.L_cap;
         const int end_main = own ? L - 1 : end;
         constexpr int UNR = (WD <= 4) ? 8 : 4;
+        uint32_t low = 0xffffu;  // lowest score this thread sees
         for (int n0 = base + tid; n0 < end_main; n0 += 256 * UNR) {
             CodeW<WD> kc[UNR];
 #pragma unroll
@@ -296,9 +299,12 @@ __global__ __launch_bounds__(256, 3) void decode_step_coop_kernel(const CoopArgs
                     sp[n] = (uint16_t)s;
                     s_sc[n - base] = (uint16_t)s;
                     atomicAdd(&hist[s], 1u);
+                    low = min(low, s);
                 }
             }
         }
+        low = (uint32_t)(-wave_max64(-(float)low));  // (scores <= 4096 are exact in fp32)
+        if ((tid & 63) == 0 && low < (uint32_t)a.NB) atomicMin(&s_low, (int)low);
         if (own && tid == 0) {
             uint32_t s = 0;
 #pragma unroll
@@ -308,6 +314,7 @@ __global__ __launch_bounds__(256, 3) void decode_step_coop_kernel(const CoopArgs
             sp[L - 1] = (uint16_t)s;
             s_sc[L - 1 - base] = (uint16_t)s;
             atomicAdd(&hist[s], 1u);
+            atomicMin(&s_low, (int)s);
         }
     }
     __syncthreads();
@@ -347,7 +354,8 @@ __global__ __launch_bounds__(256, 3) void decode_step_coop_kernel(const CoopArgs
     if (s_flag) {
         TU(51);
         unit_threshold<true, (G * WD * 32) / 256 + 1>(a.chunk_hist + u * a.n_chunks * a.NBP, a.unit_hist + u * a.NB, nc, keff,
-                             a.NB, a.NBP, ci_u, a.unit_info + u * 2, hist, TS, rec_u, a.epoch);
+                             a.NB, a.NBP, ci_u, a.unit_info + u * 2, hist, TS, rec_u, a.epoch,
+                             s_low < a.NB ? s_low : -1);
         TU(52);
     }
     // every workgroup (the last arriver too) picks up its chunk's record: two words that carry

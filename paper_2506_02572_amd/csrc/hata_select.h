@@ -60,7 +60,8 @@ template <bool FUSED, int MAXSEG = 17>
 __device__ __forceinline__ void unit_threshold(
     const uint16_t* __restrict__ hp, uint32_t* __restrict__ unit_hist_u, int nc, int keff, int NB,
     int NBP, int32_t* __restrict__ chunk_info_u, int32_t* __restrict__ unit_info_u, uint32_t* tot,
-    ThresholdLds& S, unsigned long long* __restrict__ rec_u = nullptr, uint32_t epoch = 0) {
+    ThresholdLds& S, unsigned long long* __restrict__ rec_u = nullptr, uint32_t epoch = 0,
+    int spec_bmin = -1) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     if (tid == 0) { S.T = (keff > 0) ? NB : 0; S.need = 0; }
     for (int c = tid; c < nc; c += 256) { S.c_lt[c] = 0; S.c_eq[c] = 0; }
@@ -69,12 +70,31 @@ __device__ __forceinline__ void unit_threshold(
     const int seg = (NB + 255) / 256;
     const int s0 = tid * seg;
     uint32_t x[MAXSEG];
+    // Speculation (spec_bmin = lowest score of the caller's own chunk, or -1): the per-chunk counts
+    // below need columns [bmin / 8, T / 8] of every chunk row, which are only known after T -- a
+    // second dependent round trip.  T sits in the low tail, a few columns above the lowest score
+    // of any chunk, so SPEC_COLS columns starting a little below the caller's own lowest score are
+    // fetched together with the unit histogram and used if they turn out to cover the range
+    // (3 columns below: the unit's lowest score is a little lower than one chunk's).
+    constexpr int SPEC_COLS = 8, SPEC_IT = 4;
+    const bool spec = FUSED && spec_bmin >= 0 && nc * SPEC_COLS <= 256 * SPEC_IT && NBP / 8 >= SPEC_COLS;
+    const int colA = spec ? min(max(spec_bmin / 8 - 3, 0), NBP / 8 - SPEC_COLS) : 0;
+    Bins8 sx[SPEC_IT];
     if constexpr (FUSED) {
 #pragma unroll
         for (int j = 0; j < MAXSEG; ++j)  // clamped index: unconditional loads
             if (j < seg)
                 x[j] = __hip_atomic_load(unit_hist_u + min(s0 + j, NB - 1), __ATOMIC_RELAXED,
                                          __HIP_MEMORY_SCOPE_AGENT);
+        if (spec) {
+#pragma unroll
+            for (int j = 0; j < SPEC_IT; ++j) {
+                if (j * 256 < nc * SPEC_COLS) {
+                    const int i = min(tid + j * 256, nc * SPEC_COLS - 1);
+                    sx[j] = load_bins8<true>(hp + (int64_t)(i / SPEC_COLS) * NBP + (colA + i % SPEC_COLS) * 8);
+                }
+            }
+        }
 #pragma unroll
         for (int j = 0; j < MAXSEG; ++j) {
             if (j < seg && s0 + j < NB) {
@@ -129,7 +149,28 @@ __device__ __forceinline__ void unit_threshold(
     const int T = S.T, need = S.need;
     HATA_TRACE_AT(11, FUSED && blockIdx.y == 0 && blockIdx.z == 0);
     // per chunk: keys below T and keys equal to T, from columns [bmin / 8, T / 8] of its row
-    if (T < NB) {
+    auto count_item = [&](const Bins8& v, int c, int col) {
+        uint32_t lt = 0;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const uint32_t cnt = bin_of(v, e);
+            lt += (col * 8 + e < T) ? cnt : 0u;
+            if (col * 8 + e == T) S.c_eq[c] = cnt;  // one item per chunk holds bin T
+        }
+        if (lt) atomicAdd(&S.c_lt[c], lt);
+    };
+    if (T < NB && spec && min(S.bmin, T) / 8 >= colA && T / 8 < colA + SPEC_COLS) {
+        // the speculative columns cover [bmin / 8, T / 8]: no second round trip
+        const int col0 = min(S.bmin, T) / 8, col1 = T / 8;
+#pragma unroll
+        for (int j = 0; j < SPEC_IT; ++j) {
+            const int i = tid + j * 256;
+            if (i < nc * SPEC_COLS) {
+                const int c = i / SPEC_COLS, col = colA + i % SPEC_COLS;
+                if (col >= col0 && col <= col1) count_item(sx[j], c, col);
+            }
+        }
+    } else if (T < NB) {
         const int col0 = min(S.bmin, T) / 8;
         const int ncols = T / 8 - col0 + 1;
         const int items = nc * ncols;
@@ -146,14 +187,7 @@ __device__ __forceinline__ void unit_threshold(
                 const int i = i0 + j * 256;
                 if (i < items) {
                     const int c = i / ncols, col = col0 + (i - c * ncols);
-                    uint32_t lt = 0;
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) {
-                        const uint32_t cnt = bin_of(x[j], e);
-                        lt += (col * 8 + e < T) ? cnt : 0u;
-                        if (col * 8 + e == T) S.c_eq[c] = cnt;  // one item per chunk holds bin T
-                    }
-                    if (lt) atomicAdd(&S.c_lt[c], lt);
+                    count_item(x[j], c, col);
                 }
             }
         }
