@@ -269,11 +269,30 @@ __global__ __launch_bounds__(256, 3) void decode_step_coop_kernel(const CoopArgs
     TC(50);
     const int keff = min(clampi(a.kbud[b], 0, a.k_max), L);
     // ---- 1. score the chunk (the appended row from the code just computed, the rest from the cache)
-    uint32_t qc[G][WD];
+    // wave-uniform query codes: as they are, or as bit-count planes for the larger groups
+    constexpr bool PLANES = HammingSum<WD, G>::PLANES;
+    HammingSum<WD, G> dist;
+    uint32_t qc[PLANES ? 1 : G][WD];
+    if constexpr (PLANES) {
+        dist.init(s_codes);
+    } else {
 #pragma unroll
-    for (int g = 0; g < G; ++g)
+        for (int g = 0; g < G; ++g)
 #pragma unroll
-        for (int w = 0; w < WD; ++w) qc[g][w] = __builtin_amdgcn_readfirstlane(s_codes[g * WD + w]);
+            for (int w = 0; w < WD; ++w) qc[g][w] = __builtin_amdgcn_readfirstlane(s_codes[g * WD + w]);
+    }
+    auto distance = [&](const uint32_t (&k)[WD]) {
+        if constexpr (PLANES) {
+            return dist(k);
+        } else {
+            uint32_t s = 0;
+#pragma unroll
+            for (int g = 0; g < G; ++g)
+#pragma unroll
+                for (int w = 0; w < WD; ++w) s += __popc(qc[g][w] ^ k[w]);
+            return s;
+        }
+    };
     {
         const uint32_t* cp = a.codes + u * a.L_cap * WD;
         uint16_t* sp = a.scores + u * a.L_cap;
@@ -291,11 +310,7 @@ __global__ __launch_bounds__(256, 3) void decode_step_coop_kernel(const CoopArgs
             for (int j = 0; j < UNR; ++j) {
                 const int n = n0 + j * 256;
                 if (n < end_main) {
-                    uint32_t s = 0;
-#pragma unroll
-                    for (int g = 0; g < G; ++g)
-#pragma unroll
-                        for (int w = 0; w < WD; ++w) s += __popc(qc[g][w] ^ kc[j].w[w]);
+                    const uint32_t s = distance(kc[j].w);
                     sp[n] = (uint16_t)s;
                     s_sc[n - base] = (uint16_t)s;
                     atomicAdd(&hist[s], 1u);
@@ -306,11 +321,10 @@ __global__ __launch_bounds__(256, 3) void decode_step_coop_kernel(const CoopArgs
         low = (uint32_t)(-wave_max64(-(float)low));  // (scores <= 4096 are exact in fp32)
         if ((tid & 63) == 0 && low < (uint32_t)a.NB) atomicMin(&s_low, (int)low);
         if (own && tid == 0) {
-            uint32_t s = 0;
+            uint32_t kw[WD];
 #pragma unroll
-            for (int g = 0; g < G; ++g)
-#pragma unroll
-                for (int w = 0; w < WD; ++w) s += __popc(qc[g][w] ^ s_codes[G * WD + w]);
+            for (int w = 0; w < WD; ++w) kw[w] = s_codes[G * WD + w];
+            const uint32_t s = distance(kw);
             sp[L - 1] = (uint16_t)s;
             s_sc[L - 1 - base] = (uint16_t)s;
             atomicAdd(&hist[s], 1u);

@@ -120,4 +120,65 @@ __device__ __forceinline__ uint32_t block_excl_scan_256(uint32_t v, uint32_t* ld
     return base + inc - v;
 }
 
+// ---- summed Hamming distance of one key code to the G query codes of a group ----
+// (Alg. 3 of the paper, "distance in Hamming space", with the aggregation over the query heads
+// that share a KV cache: S = sum_g bitcount(xor(q_g, k)).)
+// Direct form (written out in the kernels): G * WD (xor, popcount-accumulate) pairs per key.  For
+// G >= 5 this helper rearranges the sum
+// per BIT: a key bit that is 0 disagrees with the heads whose bit is 1, a key bit that is 1 with
+// the d heads whose bit is 0, so with d[bit] = number of heads with a 0 there,
+//   S = C0 + sum_{bits set in k} (2 d[bit] - G),   C0 = sum_g bitcount(q_g),
+// and with d held bit-sliced in NP = ceil(log2(G + 1)) planes D_p (wave-uniform, like the codes),
+//   S = C0 + 2 sum_p 2^p bitcount(k & D_p) - G bitcount(k):
+// WD * (2 NP + 1) operations instead of 2 G WD (36 instead of 64 at G = 8, r = 128).
+template <int WD, int G>
+struct HammingSum {
+    static constexpr bool PLANES = G >= 5;  // below that the direct form is as short
+    static constexpr int NP = G >= 8 ? 4 : 3;  // G <= 15
+    uint32_t d[NP][WD];
+    uint32_t c0;
+
+    // qp: the G * WD code words of the group (the same for every lane)
+    __device__ __forceinline__ void init(const uint32_t* qp) {
+        static_assert(G >= 1 && G <= 15, "plane count");
+        c0 = 0;
+#pragma unroll
+        for (int w = 0; w < WD; ++w) {
+            uint32_t pl[NP];
+#pragma unroll
+            for (int p = 0; p < NP; ++p) pl[p] = 0;
+#pragma unroll
+            for (int g = 0; g < G; ++g) {
+                const uint32_t qw = __builtin_amdgcn_readfirstlane(qp[g * WD + w]);
+                c0 += __popc(qw);
+                uint32_t carry = ~qw;  // add one to the counters of the bits where this head has a 0
+#pragma unroll
+                for (int p = 0; p < NP; ++p) {
+                    const uint32_t t = pl[p] & carry;
+                    pl[p] ^= carry;
+                    carry = t;
+                }
+            }
+#pragma unroll
+            for (int p = 0; p < NP; ++p) d[p][w] = pl[p];
+        }
+    }
+
+    __device__ __forceinline__ uint32_t operator()(const uint32_t (&k)[WD]) const {
+        uint32_t pk = 0, a[NP];
+#pragma unroll
+        for (int p = 0; p < NP; ++p) a[p] = 0;
+#pragma unroll
+        for (int w = 0; w < WD; ++w) {
+            pk += __popc(k[w]);
+#pragma unroll
+            for (int p = 0; p < NP; ++p) a[p] += __popc(k[w] & d[p][w]);
+        }
+        uint32_t t = a[NP - 1];
+#pragma unroll
+        for (int p = NP - 2; p >= 0; --p) t = 2 * t + a[p];
+        return c0 + 2 * t - G * pk;
+    }
+};
+
 }  // namespace hata

@@ -117,13 +117,19 @@ __global__ __launch_bounds__(256) void score_kernel(
         for (int i = tid; i < NB; i += 256) hist[i] = 0;
         __syncthreads();
     }
-    // wave-uniform query codes
-    uint32_t qc[G][WD];
+    // wave-uniform query codes (as bit-count planes for the larger groups)
+    constexpr bool PLANES = HammingSum<WD, G>::PLANES;
+    HammingSum<WD, G> dist;
+    uint32_t qc[PLANES ? 1 : G][WD];
     const uint32_t* qp = qcodes + ((int64_t)b * Hq + (int64_t)h * G) * WD;
+    if constexpr (PLANES) {
+        dist.init(qp);
+    } else {
 #pragma unroll
-    for (int g = 0; g < G; ++g)
+        for (int g = 0; g < G; ++g)
 #pragma unroll
-        for (int w = 0; w < WD; ++w) qc[g][w] = __builtin_amdgcn_readfirstlane(qp[g * WD + w]);
+            for (int w = 0; w < WD; ++w) qc[g][w] = __builtin_amdgcn_readfirstlane(qp[g * WD + w]);
+    }
 
     const uint32_t* cp = codes + u * L_cap * WD;
     uint16_t* sp = scores + u * L_cap;
@@ -140,10 +146,14 @@ __global__ __launch_bounds__(256) void score_kernel(
             const int n = n0 + j * 256;
             if (n < end) {
                 uint32_t s = 0;
+                if constexpr (PLANES) {
+                    s = dist(kc[j].w);
+                } else {
 #pragma unroll
-                for (int g = 0; g < G; ++g)
+                    for (int g = 0; g < G; ++g)
 #pragma unroll
-                    for (int w = 0; w < WD; ++w) s += __popc(qc[g][w] ^ kc[j].w[w]);
+                        for (int w = 0; w < WD; ++w) s += __popc(qc[g][w] ^ kc[j].w[w]);
+                }
                 sp[n] = (uint16_t)s;
                 if (do_hist) atomicAdd(&hist[s], 1u);
             }
