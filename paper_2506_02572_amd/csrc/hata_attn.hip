@@ -140,7 +140,7 @@ __global__ __launch_bounds__(256) void attn_kernel(const AttnArgs a) {
         return s_rows[row - row_begin];
     };
     if constexpr (MFMA)
-        attn_rows_mfma<HT, (MODE == ROWS_DENSE ? 2 : 1)>(qb, Kb, Vb, a.sn, a.L_cap, row_begin, row_end,
+        attn_rows_mfma<HT, (MODE == ROWS_DENSE ? 2 : 1), false>(qb, Kb, Vb, a.sn, a.L_cap, row_begin, row_end,
                                                          a.scale_log2, row_of, S, s_vt);
     else
         attn_rows<HT, 4>(qr, Kb, Vb, a.sn, a.L_cap, row_begin, row_end, a.scale_log2, row_of, S);

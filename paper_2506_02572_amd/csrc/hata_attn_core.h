@@ -180,8 +180,10 @@ __device__ __forceinline__ void attn_load_q_mfma(const uint16_t* __restrict__ q0
 }
 
 // Same contract as attn_rows (state of the four waves in S after a workgroup barrier).  IT: 16-row
-// tiles per wave whose loads are in flight together.  vt: HATA_VT_ELEMS uint16 of LDS.
-template <int HT, int IT, typename RowOf>
+// tiles per wave whose loads are in flight together; PF: software pipeline -- the loads of the
+// next IT tiles are issued before the current ones are consumed (measured on the dense baseline:
+// no faster than IT = 2 without it, so no caller turns it on).  vt: HATA_VT_ELEMS uint16 of LDS.
+template <int HT, int IT, bool PF, typename RowOf>
 __device__ __forceinline__ void attn_rows_mfma(
     const uint4 (&qb)[4], const uint16_t* __restrict__ Kb, const uint16_t* __restrict__ Vb, int64_t sn,
     int L_cap, int row_begin, int row_end, float scale_log2, RowOf row_of, AttnLds<HT>& S,
@@ -194,42 +196,45 @@ __device__ __forceinline__ void attn_rows_mfma(
     f32x4_t acc[8];
 #pragma unroll
     for (int c = 0; c < 8; ++c) acc[c] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
-    for (int tile0 = row_begin; tile0 < row_end; tile0 += 64 * IT) {
-        uint4 kr[IT][4], vr[IT][4];
-        bool ok[IT];
+
+    struct Stage { uint4 kr[IT][4], vr[IT][4]; bool ok[IT]; };
+    // loads of the IT tiles of this wave in the 64 * IT rows from tile0 (lane: row n, channels 8 kg + 32 s)
+    auto load_stage = [&](int tile0, Stage& st) {
 #pragma unroll
         for (int it = 0; it < IT; ++it) {
             const int row = tile0 + (it * 4 + wave) * 16 + n;
-            ok[it] = row < row_end;
+            st.ok[it] = row < row_end;
             int idx = 0;
-            if (ok[it]) idx = row_of(row);
-            ok[it] = ok[it] && idx >= 0 && idx < L_cap;
+            if (st.ok[it]) idx = row_of(row);
+            st.ok[it] = st.ok[it] && idx >= 0 && idx < L_cap;
 #pragma unroll
-            for (int s = 0; s < 4; ++s) { kr[it][s] = make_uint4(0, 0, 0, 0); vr[it][s] = make_uint4(0, 0, 0, 0); }
-            if (ok[it]) {
+            for (int s = 0; s < 4; ++s) { st.kr[it][s] = make_uint4(0, 0, 0, 0); st.vr[it][s] = make_uint4(0, 0, 0, 0); }
+            if (st.ok[it]) {
                 const int64_t o = (int64_t)idx * sn + 8 * kg;
 #pragma unroll
                 for (int s = 0; s < 4; ++s) {
-                    kr[it][s] = *reinterpret_cast<const uint4*>(Kb + o + 32 * s);
-                    vr[it][s] = *reinterpret_cast<const uint4*>(Vb + o + 32 * s);
+                    st.kr[it][s] = *reinterpret_cast<const uint4*>(Kb + o + 32 * s);
+                    st.vr[it][s] = *reinterpret_cast<const uint4*>(Vb + o + 32 * s);
                 }
             }
         }
+    };
+    auto compute_stage = [&](int tile0, const Stage& st) {
 #pragma unroll
         for (int it = 0; it < IT; ++it) {
             if (tile0 + (it * 4 + wave) * 16 >= row_end) break;  // wave-uniform: no row in this tile
-            const unsigned long long okmask = __builtin_amdgcn_ballot_w64(ok[it]);  // bits 0..15: the tile's rows
+            const unsigned long long okmask = __builtin_amdgcn_ballot_w64(st.ok[it]);  // bits 0..15: the tile's rows
             f32x4_t sacc = (f32x4_t){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int s = 0; s < 4; ++s)
-                sacc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, kr[it][s]),
+                sacc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, st.kr[it][s]),
                                                                __builtin_bit_cast(bf16x8_t, qb[s]), sacc, 0, 0, 0);
             // stage V (row n, channels 32 s + 8 kg) for the transposed reads below
 #pragma unroll
             for (int s = 0; s < 4; ++s) {
                 uint2* d = reinterpret_cast<uint2*>(vt + n * HATA_VT_PITCH + 32 * s + 8 * kg);
-                d[0] = make_uint2(vr[it][s].x, vr[it][s].y);
-                d[1] = make_uint2(vr[it][s].z, vr[it][s].w);
+                d[0] = make_uint2(st.vr[it][s].x, st.vr[it][s].y);
+                d[1] = make_uint2(st.vr[it][s].z, st.vr[it][s].w);
             }
             // online softmax of head n over the rows 4 kg .. 4 kg + 3 this lane holds
             float sv[4], m_tile = HATA_NEG_INF;
@@ -274,6 +279,22 @@ __device__ __forceinline__ void attn_rows_mfma(
                 acc[c] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(av, plv, acc[c], 0, 0, 0);
             }
             __builtin_amdgcn_wave_barrier();
+        }
+    };
+    if constexpr (PF) {
+        Stage cur, nxt;
+        load_stage(row_begin, cur);
+        for (int tile0 = row_begin; tile0 < row_end; tile0 += 64 * IT) {
+            const bool more = tile0 + 64 * IT < row_end;  // workgroup-uniform
+            if (more) load_stage(tile0 + 64 * IT, nxt);
+            compute_stage(tile0, cur);
+            if (more) cur = nxt;
+        }
+    } else {
+        for (int tile0 = row_begin; tile0 < row_end; tile0 += 64 * IT) {
+            Stage st;
+            load_stage(tile0, st);
+            compute_stage(tile0, st);
         }
     }
     // lanes of the 4 row groups hold partial sums of the same head

@@ -455,7 +455,7 @@ __global__ __launch_bounds__(256, 3) void decode_step_coop_kernel(const CoopArgs
     const uint16_t* Kb = a.K + b * a.sb + h * a.sh;
     const uint16_t* Vb = a.V + b * a.sb + h * a.sh;
     auto row_of = [&](int row) { return base + (int)s_sc[row]; };
-    if constexpr (MFMA) attn_rows_mfma<G, 1>(qb, Kb, Vb, a.sn, a.L_cap, 0, cnt, a.scale_log2, row_of, S, U.vt);
+    if constexpr (MFMA) attn_rows_mfma<G, 1, false>(qb, Kb, Vb, a.sn, a.L_cap, 0, cnt, a.scale_log2, row_of, S, U.vt);
     else attn_rows<G, 4>(qr, Kb, Vb, a.sn, a.L_cap, 0, cnt, a.scale_log2, row_of, S);
     TC(47);
     const int64_t head_stride = (int64_t)a.n_chunks * HATA_PSTRIDE;
