@@ -42,7 +42,9 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=400)
     ap.add_argument("--warmup", type=int, default=40)
-    ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
+    ap.add_argument("--workload", default="cfg2",
+                    help="cfg1 .. cfg5 (the benchmark configurations; default cfg2) or a shape-sweep name "
+                         "(paper_2506_02572_amd.synth.SWEEP)")
     ap.add_argument("--layers", type=int, default=0, help="distinct cache copies to rotate over (0 = auto)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
@@ -68,7 +70,7 @@ def main():
         sys.exit(1)
     torch.cuda.set_device(0)
     dev = torch.device("cuda:0")
-    w = synth.config(int(args.workload[3:]))
+    w = synth.workload(args.workload)
     inp = synth.generate(w)
     scale = 1.0 / math.sqrt(w.d)
     n_step_variants = max(1, w.append_steps)

@@ -93,8 +93,8 @@ int hata_destroy(hata_ctx* ctx);
  *   codes[b, h, n, :] = BitPack(Sign(K[b, h, n, :] . W_H[h]))   for start[b] <= n < start[b] + n_new[b].
  * `max_new` (host value) is an upper bound of n_new[b] and sizes the launch; rows outside the
  * range, and rows >= L_cap, are not touched.  Small max_new (<= 8) uses an fp64-accumulating
- * kernel; larger uses the matrix-core projection kernel (r = 128 or 256: bf16 MFMA over an exact
- * three-way bf16 split of W_H, fp32 accumulation; other r: fp32 vector kernel), where a bit may
+ * kernel; larger uses the matrix-core projection kernel (r in {32, 64, 128, 256}: bf16 MFMA over an
+ * exact three-way bf16 split of W_H, fp32 accumulation; other r: fp32 vector kernel), where a bit may
  * differ from an exact evaluation only if |projection| is below about 1e-4.
  */
 int hata_encode_keys(hata_ctx* ctx, const void* K, const float* W_H,
@@ -142,7 +142,7 @@ int hata_dense_decode(hata_ctx* ctx, const void* q, const void* K, const void* V
  * Intermediate qcodes / scores / idx live in the workspace (see hata_step_buffers).
  *
  * Launches (see hata_step_plan): when every workgroup of the step can be resident on the device
- * at once (r = 128 or 256, Hq/Hkv in {1, 2, 4, 5, 8}), the step is ONE kernel launch whose
+ * at once (r in {32, 64, 128, 256}, Hq/Hkv in {1, 2, 4, 5, 8}), the step is ONE kernel launch whose
  * workgroups hand the query codes, the selection threshold and the attention partials to each
  * other through the workspace, waiting for one another inside the kernel.  Every such wait is
  * bounded: a workgroup that gives up raises a flag in the workspace and runs to its end, the

@@ -66,10 +66,17 @@ struct CodeW { uint32_t w[WD]; };
 template <int WD>
 __device__ __forceinline__ CodeW<WD> coop_load_code(const uint32_t* p) {
     CodeW<WD> c;
+    if constexpr (WD == 1) {
+        c.w[0] = p[0];
+    } else if constexpr (WD == 2) {
+        const uint2 v = *reinterpret_cast<const uint2*>(p);
+        c.w[0] = v.x; c.w[1] = v.y;
+    } else {
 #pragma unroll
-    for (int i = 0; i < WD / 4; ++i) {
-        const uint4 v = reinterpret_cast<const uint4*>(p)[i];
-        c.w[4 * i] = v.x; c.w[4 * i + 1] = v.y; c.w[4 * i + 2] = v.z; c.w[4 * i + 3] = v.w;
+        for (int i = 0; i < WD / 4; ++i) {
+            const uint4 v = reinterpret_cast<const uint4*>(p)[i];
+            c.w[4 * i] = v.x; c.w[4 * i + 1] = v.y; c.w[4 * i + 2] = v.z; c.w[4 * i + 3] = v.w;
+        }
     }
     return c;
 }
@@ -92,10 +99,12 @@ __device__ __forceinline__ double swapadd16(double x, double y) {
                  : "+v"(xl), "+v"(yl), "+v"(xh), "+v"(yh));
     return __hiloint2double((int)xh, (int)xl) + __hiloint2double((int)yh, (int)yl);
 }
-// x + (x of the lane 8 positions away in the same row of 16 lanes)
-__device__ __forceinline__ double rotadd8(double x) {
-    const int lo = __builtin_amdgcn_update_dpp(0, __double2loint(x), 0x128, 0xf, 0xf, false);  // row_ror:8
-    const int hi = __builtin_amdgcn_update_dpp(0, __double2hiint(x), 0x128, 0xf, 0xf, false);
+// x + (x of the lane N positions further round the same row of 16 lanes); N = 8, then 4, then 2
+// sums over the lanes that agree in the low bits
+template <int N>
+__device__ __forceinline__ double rotadd(double x) {
+    const int lo = __builtin_amdgcn_update_dpp(0, __double2loint(x), 0x120 + N, 0xf, 0xf, false);  // row_ror:N
+    const int hi = __builtin_amdgcn_update_dpp(0, __double2hiint(x), 0x120 + N, 0xf, 0xf, false);
     return x + __hiloint2double(hi, lo);
 }
 
@@ -103,14 +112,15 @@ __device__ __forceinline__ double rotadd8(double x) {
 // weights Wh [128][r], by the whole workgroup, accumulating in fp64 (every product of a bf16 and
 // an fp32 value is exact in fp64).  s_word: WD code words in LDS, zero on entry, complete after
 // the caller's next barrier.  A wave owns r/4 hash columns (one code word at r = 128, two at
-// r = 256); its lanes are (column group of 4 = one 128-bit weight load) x (1024/r parts of the
+// r = 256, half / a quarter of one below); its lanes are (column group of 4 = one 128-bit weight load) x (1024/r parts of the
 // channel range), so all loads of a thread are independent and in flight together.  The partial
 // sums are combined across the parts with lane swaps, each step halving the live values: lane
 // (bit5, bit4) ends up with the total of column 4 cg + bit4 + 2 bit5.
 template <int WD>
 struct EncodeLoads {  // what coop_encode_vec needs before its first FMA
-    static constexpr int CP = HATA_D / (64 / (WD * 2));
-    float4 w[16];         // first 16 weight rows of this lane's channel part
+    static constexpr int CP = HATA_D / (64 / (WD * 2));  // channels per part: 4, 8, 16, 32 for r = 32 .. 256
+    static constexpr int NW = CP < 16 ? CP : 16;
+    float4 w[NW];         // first (up to) 16 weight rows of this lane's channel part
     uint32_t xw[CP / 2];  // the part's channels of x, bf16 pairs
 };
 template <int WD>
@@ -120,18 +130,23 @@ __device__ __forceinline__ void coop_encode_load(const float* __restrict__ Wh,
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int cg = lane % CG, p = lane / CG;
     const float* wp = Wh + (int64_t)(p * CP) * R + wave * (R / 4) + 4 * cg;
+    if constexpr (CP == 4) {
+        const uint2 v = *reinterpret_cast<const uint2*>(x + p * CP);
+        e.xw[0] = v.x; e.xw[1] = v.y;
+    } else {
 #pragma unroll
-    for (int i = 0; i < CP / 8; ++i) {
-        const uint4 v = reinterpret_cast<const uint4*>(x + p * CP)[i];
-        e.xw[4 * i] = v.x; e.xw[4 * i + 1] = v.y; e.xw[4 * i + 2] = v.z; e.xw[4 * i + 3] = v.w;
+        for (int i = 0; i < CP / 8; ++i) {
+            const uint4 v = reinterpret_cast<const uint4*>(x + p * CP)[i];
+            e.xw[4 * i] = v.x; e.xw[4 * i + 1] = v.y; e.xw[4 * i + 2] = v.z; e.xw[4 * i + 3] = v.w;
+        }
     }
 #pragma unroll
-    for (int j = 0; j < 16; ++j) e.w[j] = *reinterpret_cast<const float4*>(wp + (int64_t)j * R);
+    for (int j = 0; j < EncodeLoads<WD>::NW; ++j) e.w[j] = *reinterpret_cast<const float4*>(wp + (int64_t)j * R);
 }
 template <int WD>
 __device__ __forceinline__ void coop_encode_vec(const float* __restrict__ Wh, const EncodeLoads<WD>& e,
                                                 uint32_t* s_word) {
-    constexpr int R = WD * 32, CG = R / 16, P = 64 / CG, CP = HATA_D / P;  // CP = 16 or 32 channels
+    constexpr int R = WD * 32, CG = R / 16, P = 64 / CG, CP = HATA_D / P;  // CP = 4 .. 32 channels
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int cg = lane % CG, p = lane / CG;
     const float* wp = Wh + (int64_t)(p * CP) * R + wave * (R / 4) + 4 * cg;
@@ -145,7 +160,7 @@ __device__ __forceinline__ void coop_encode_vec(const float* __restrict__ Wh, co
         a3 = fma((double)w.w, xd, a3);
     };
 #pragma unroll
-    for (int j = 0; j < 16; ++j) fma_row(e.w[j], j);
+    for (int j = 0; j < EncodeLoads<WD>::NW; ++j) fma_row(e.w[j], j);
     // r = 256: the part's other 16 weight rows, 8 at a time (registers)
 #pragma unroll
     for (int c0 = 16; c0 < CP; c0 += 8) {
@@ -160,11 +175,15 @@ __device__ __forceinline__ void coop_encode_vec(const float* __restrict__ Wh, co
     const double ev = swapadd32(a0, a2);  // column 0 + 2 b5
     const double od = swapadd32(a1, a3);  // column 1 + 2 b5
     double t = swapadd16(ev, od);
-    if (P == 8) t = rotadd8(t);
+    // the remaining part bits (lane bits 3, 2, 1 for r = 128, 64, 32) by rotations inside the row
+    if (P >= 8) t = rotadd<8>(t);
+    if (P >= 16) t = rotadd<4>(t);
+    if (P >= 32) t = rotadd<2>(t);
     if (t >= 0.0) atomicOr(&s_word[col >> 5], 1u << (col & 31));
 }
 
-// WD in {4, 8} (r = 128, 256); G in {1, 2, 4, 5, 8} (all heads of the group in one attention tile)
+// WD in {1, 2, 4, 8} (r = 32, 64, 128, 256); G in {1, 2, 4, 5, 8} (all heads of the group in one
+// attention tile)
 template <int WD, int G>
 __global__ __launch_bounds__(256, 3) void decode_step_coop_kernel(const CoopArgs a) {
     extern __shared__ uint32_t hist[];  // NB words: chunk histogram, later the unit's total
@@ -202,7 +221,7 @@ __global__ __launch_bounds__(256, 3) void decode_step_coop_kernel(const CoopArgs
     const uint16_t* qv = a.q + ((int64_t)b * a.Hq + h * G) * HATA_D;
     const float* Wh = a.W_H + (int64_t)h * HATA_D * (WD * 32);
     EncodeLoads<WD> el;
-    constexpr bool EARLY = WD == 4;  // (at r = 256 the second half of the weights needs the registers)
+    constexpr bool EARLY = WD <= 4;  // (at r = 256 the second half of the weights needs the registers)
     if (EARLY && c < G) coop_encode_load<WD>(Wh, qv + c * HATA_D, el);
     const int L = clampi(a.seq_len[b], 0, a.L_cap);
     const int base = c * a.chunk;
@@ -297,7 +316,7 @@ __global__ __launch_bounds__(256, 3) void decode_step_coop_kernel(const CoopArgs
         const uint32_t* cp = a.codes + u * a.L_cap * WD;
         uint16_t* sp = a.scores + u * a.L_cap;
         const int end_main = own ? L - 1 : end;
-        constexpr int UNR = (WD <= 4) ? 8 : 4;
+        constexpr int UNR = (WD <= 2) ? 16 : (WD <= 4) ? 8 : 4;  // 64-128 B of codes in flight per lane
         uint32_t low = 0xffffu;  // lowest score this thread sees
         for (int n0 = base + tid; n0 < end_main; n0 += 256 * UNR) {
             CodeW<WD> kc[UNR];
@@ -487,6 +506,16 @@ static const void* coop_fn() { return (const void*)&decode_step_coop_kernel<WD, 
 
 static const void* coop_kernel_for(int Wd, int G) {
     switch (Wd * 100 + G) {
+        case 101: return coop_fn<1, 1>();
+        case 102: return coop_fn<1, 2>();
+        case 104: return coop_fn<1, 4>();
+        case 105: return coop_fn<1, 5>();
+        case 108: return coop_fn<1, 8>();
+        case 201: return coop_fn<2, 1>();
+        case 202: return coop_fn<2, 2>();
+        case 204: return coop_fn<2, 4>();
+        case 205: return coop_fn<2, 5>();
+        case 208: return coop_fn<2, 8>();
         case 401: return coop_fn<4, 1>();
         case 402: return coop_fn<4, 2>();
         case 404: return coop_fn<4, 4>();

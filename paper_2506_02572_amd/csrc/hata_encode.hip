@@ -220,10 +220,9 @@ __global__ __launch_bounds__(256) void encode_bulk_kernel(
 // 128-bit loads (next stage prefetched into registers) and read back in the operand layout
 // (lane = key, 16 B of consecutive channels).  In the 32x32 result a lane holds 16 hash columns of
 // ONE key, so the sign bits are packed inside the lane and joined with the other half-wave.
-// grid = (key blocks, Hkv, B); R / 32 waves per workgroup.
+// grid = (key blocks, Hkv, B); R / 32 waves per workgroup (r = 32, 64, 128 or 256).
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
 typedef __attribute__((ext_vector_type(16))) float f32x16_t;
-#define HATA_MFMA_STAGE 128   // keys per LDS stage
 #define HATA_MFMA_PITCH 136   // LDS row pitch in bf16 elements (272 B: rows shift by 4 banks)
 
 __device__ __forceinline__ uint32_t bf16_rne_bits(float f) { return f32_to_bf16(f); }
@@ -236,9 +235,11 @@ __global__ __launch_bounds__(R * 2) void encode_mfma_kernel(
     int64_t sb, int64_t sh, int64_t sn) {
     constexpr int THREADS = R * 2;
     constexpr int WD = R / 32;
+    constexpr int STAGE = R >= 64 ? 128 : 64;              // keys per LDS stage
+    constexpr int NT = STAGE / 32;                         // 32-key MFMA tiles per stage
     constexpr int ROWS_PER_IT = THREADS / 16;              // rows staged per load instruction
-    constexpr int NIT = HATA_MFMA_STAGE / ROWS_PER_IT;     // load instructions per stage and thread
-    __shared__ __attribute__((aligned(16))) uint16_t tile[HATA_MFMA_STAGE * HATA_MFMA_PITCH];
+    constexpr int NIT = STAGE / ROWS_PER_IT;               // load instructions per stage and thread
+    __shared__ __attribute__((aligned(16))) uint16_t tile[STAGE * HATA_MFMA_PITCH];
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int m = lane & 31, half = lane >> 5;
     const int h = blockIdx.y, b = blockIdx.z;
@@ -292,35 +293,35 @@ __global__ __launch_bounds__(R * 2) void encode_mfma_kernel(
         }
     };
     load_stage(kb0);
-    for (int k0 = kb0; k0 < kb1; k0 += HATA_MFMA_STAGE) {
+    for (int k0 = kb0; k0 < kb1; k0 += STAGE) {
         __syncthreads();  // the previous stage has been consumed
 #pragma unroll
         for (int it = 0; it < NIT; ++it)
             *reinterpret_cast<uint4*>(&tile[(it * ROWS_PER_IT + lrow) * HATA_MFMA_PITCH + lsub * 8]) = pre[it];
         __syncthreads();
-        if (k0 + HATA_MFMA_STAGE < kb1) load_stage(k0 + HATA_MFMA_STAGE);  // overlaps the MFMAs below
+        if (k0 + STAGE < kb1) load_stage(k0 + STAGE);  // overlaps the MFMAs below
 
-        f32x16_t acc[4];
+        f32x16_t acc[NT];
 #pragma unroll
-        for (int t = 0; t < 4; ++t)
+        for (int t = 0; t < NT; ++t)
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[t][i] = 0.f;
 #pragma unroll
         for (int kk = 0; kk < 8; ++kk) {
-            bf16x8_t bfrag[4];
+            bf16x8_t bfrag[NT];
 #pragma unroll
-            for (int t = 0; t < 4; ++t)
+            for (int t = 0; t < NT; ++t)
                 bfrag[t] = *reinterpret_cast<const bf16x8_t*>(
                     &tile[(t * 32 + m) * HATA_MFMA_PITCH + kk * 16 + 8 * half]);
 #pragma unroll
             for (int p = 0; p < 3; ++p)
 #pragma unroll
-                for (int t = 0; t < 4; ++t)
+                for (int t = 0; t < NT; ++t)
                     acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(afrag[p][kk], bfrag[t], acc[t], 0, 0, 0);
         }
         // sign bits: this lane holds hash columns 8*(i/4) + 4*half + i%4 of key t*32 + m
 #pragma unroll
-        for (int t = 0; t < 4; ++t) {
+        for (int t = 0; t < NT; ++t) {
             uint32_t word = 0;
 #pragma unroll
             for (int i = 0; i < 16; ++i)
@@ -367,12 +368,20 @@ hipError_t launch_encode_bulk(const hata_ctx* c, const void* K, const float* W_H
                               uint32_t* codes, hipStream_t s) {
     const hata_config& f = c->cfg;
     if (max_new <= 0 || B <= 0) return hipSuccess;
-    if (f.r == 128 || f.r == 256) {
+    if (f.r == 32 || f.r == 64 || f.r == 128 || f.r == 256) {
         // key blocks of 512..4096 keys: at least ~512 workgroups when the prefill is long enough
         int kpw = 4096;
         while (kpw > 512 && (int64_t)((max_new + kpw - 1) / kpw) * f.Hkv * B < 512) kpw >>= 1;
         const dim3 grid((max_new + kpw - 1) / kpw, f.Hkv, B);
-        if (f.r == 128)
+        if (f.r == 32)
+            hipLaunchKernelGGL((encode_mfma_kernel<32>), grid, dim3(64), 0, s, (const uint16_t*)K,
+                               W_H, start, n_new, codes, f.Hkv, f.L_cap, kpw, f.kv_stride_b,
+                               f.kv_stride_h, f.kv_stride_n);
+        else if (f.r == 64)
+            hipLaunchKernelGGL((encode_mfma_kernel<64>), grid, dim3(128), 0, s, (const uint16_t*)K,
+                               W_H, start, n_new, codes, f.Hkv, f.L_cap, kpw, f.kv_stride_b,
+                               f.kv_stride_h, f.kv_stride_n);
+        else if (f.r == 128)
             hipLaunchKernelGGL((encode_mfma_kernel<128>), grid, dim3(256), 0, s, (const uint16_t*)K,
                                W_H, start, n_new, codes, f.Hkv, f.L_cap, kpw, f.kv_stride_b,
                                f.kv_stride_h, f.kv_stride_n);

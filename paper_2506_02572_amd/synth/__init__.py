@@ -182,6 +182,30 @@ def config(index: int, seed: int = DEFAULT_SEED) -> Workload:
     raise ValueError("config index must be 1..5")
 
 
+# Shape sweep with the same kernels: the axes of the paper's efficiency figure and ablations
+# (model table: Llama-2 without grouping, Qwen-2.5 with 40 query / 8 KV heads; hash-bit ablation;
+# token budgets 0.4 % .. 3.13 %; contexts up to 256K).
+SWEEP = {
+    "mha32_32k": Workload("mha32_32k", 1, 32, 32, 128, 128, (32768,), (512,), 4, 8.0),
+    "g5_40q8kv_32k": Workload("g5_40q8kv_32k", 2, 40, 8, 128, 128, (32768, 20000), (512, 320), 4, 8.0),
+    "r64_32k": Workload("r64_32k", 1, 32, 8, 128, 64, (32768,), (512,), 4, 8.0),
+    "r32_32k": Workload("r32_32k", 1, 32, 8, 128, 32, (32768,), (512,), 4, 8.0),
+    "r256_g8_ragged": Workload("r256_g8_ragged", 2, 64, 8, 128, 256, (24000, 9000), (384, 128), 8, 16.0),
+    "budget0p4_32k": Workload("budget0p4_32k", 1, 32, 8, 128, 128, (32768,), (128,), 4, 8.0),
+    "budget3p13_32k": Workload("budget3p13_32k", 1, 32, 8, 128, 128, (32768,), (1024,), 4, 8.0),
+    "ctx256k": Workload("ctx256k", 1, 32, 8, 128, 128, (262144,), (4096,), 4, 8.0, append_steps=2),
+}
+
+
+def workload(name: str) -> Workload:
+    """cfg1 .. cfg5 (the benchmark configurations) or a name in SWEEP."""
+    if name in SWEEP:
+        return SWEEP[name]
+    if name.startswith("cfg") and name[3:].isdigit():
+        return config(int(name[3:]))
+    raise ValueError(f"unknown workload {name!r}")
+
+
 def outlier_scales(w: Workload, seed: int) -> np.ndarray:
     """Per-(KV head, channel) scale: ``n_outlier`` distinct channels per head get
     ``outlier_scale``; drawn with a partial Fisher-Yates shuffle of the channel ids."""
