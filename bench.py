@@ -48,6 +48,7 @@ def parse():
     ap.add_argument("--layers", type=int, default=0, help="distinct cache copies to rotate over (0 = auto)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
+    ap.add_argument("--no-train", action="store_true", help="skip the learning-to-hash training-step leg")
     ap.add_argument("--cpu-seconds", type=float, default=10.0)
     ap.add_argument("--pmc-probe", action="store_true",
                     help="run only a known-size copy kernel, the decode step and the scoring kernel (for "
@@ -205,6 +206,31 @@ def main():
         ms_dense, _ = timed(dense, max(20, args.steps // 8), 5)
         dense_us = ms_dense * 1e3
 
+    # ---- learning-to-hash training step (Sec. 3.1 / App. B): one SGD step on one head's W_H from a
+    # 32K-triplet chunk (the chunk size of App. B.2), timed separately
+    train_leg = None
+    if not args.no_train:
+        from paper_2506_02572_amd import train as htrain
+        n_tr = 32768
+        tctx = htrain.TrainContext(w.d, w.r, n_tr)
+        Qt = dev_bits(synth.train_vectors(n_tr, tensor_id=synth.TID_Q))
+        Kt = dev_bits(synth.train_vectors(n_tr, tensor_id=synth.TID_K))
+        st = torch.full((n_tr,), -1.0, dtype=torch.float32, device=dev)
+        st[::10] = 5.0
+        Wt = W_H[0].to(torch.float32).contiguous().clone()
+        vt = torch.zeros_like(Wt)
+        hp = htrain.default_hparams(n_tr)
+
+        def tstep(i):
+            tctx.hata_train_step(Qt, Kt, st, n_tr, Wt, vt, hp, None, None, stream)
+        ms_tr, _ = timed(tstep, 50, 5)
+        flop = 4 * 2.0 * n_tr * w.d * w.r  # two projections + two weight-gradient contractions
+        train_leg = {"triplets": n_tr, "r": w.r, "us_per_step": round(ms_tr * 1e3, 1),
+                     "TFLOPs": round(flop / (ms_tr * 1e-3) / 1e12, 1),
+                     "mfma_issue_TFLOPs": round((3 * 3 + 2 * 3) / 4 * flop / (ms_tr * 1e-3) / 1e12, 1),
+                     "launches": 5}
+        tctx.close()
+
     # ---- parity of one step + the oracle timed on this machine's host cores (rank 0, N = 1)
     cpu = None
     parity = None
@@ -279,6 +305,7 @@ def main():
                              "TFLOPs": round(enc_flop / (enc_ms * 1e-3) / 1e12, 2)},
         "dense_decode_us": None if dense_us is None else round(dense_us, 2),
         "speedup_vs_dense": None if dense_us is None else round(dense_us / us_step, 2),
+        "train_step": train_leg,
         "cpu_baseline": cpu,
         "parity": parity,
     }

@@ -8,8 +8,10 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libhata.so")
-SOURCES = ["hata_api.hip", "hata_encode.hip", "hata_score.hip", "hata_topk.hip", "hata_attn.hip", "hata_coop.hip"]
-HEADERS = ["hata_device.h", "hata_internal.h", "hata_select.h", "hata_trace.h", "hata_attn_core.h", os.path.join("..", "..", "include", "hata.h")]
+SOURCES = ["hata_api.hip", "hata_encode.hip", "hata_score.hip", "hata_topk.hip", "hata_attn.hip", "hata_coop.hip",
+           "hata_train.hip"]
+HEADERS = ["hata_device.h", "hata_internal.h", "hata_select.h", "hata_trace.h", "hata_attn_core.h", os.path.join("..", "..", "include", "hata.h"),
+           os.path.join("..", "..", "include", "hata_train.h")]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

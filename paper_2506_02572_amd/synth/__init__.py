@@ -206,6 +206,24 @@ def workload(name: str) -> Workload:
     raise ValueError(f"unknown workload {name!r}")
 
 
+def round_to_bf16_bits(x: np.ndarray) -> np.ndarray:
+    """fp32 -> bf16 bit patterns, round to nearest even (finite inputs)."""
+    u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32)
+    return ((u + 0x7FFF + ((u >> 16) & 1)) >> 16).astype(np.uint16)
+
+
+def train_vectors(n: int, d: int = 128, latent: int = 8, seed: int = DEFAULT_SEED, tensor_id: int = TID_MISC):
+    """Structured stand-in for the q / k vectors of one attention head (the paper samples them from
+    real prefills): a few latent directions carry most of the variance, the rest is noise.
+    Returns bf16 bit patterns [n, d]; the mixing matrix depends on `seed` only, so queries and keys
+    drawn with different tensor ids share it."""
+    mix = fill_f32(seed, TID_MISC + 64, (latent, d), 1.0)
+    z = fill_f32(seed, tensor_id + 32, (n, latent), 1.0)
+    noise = fill_f32(seed, tensor_id + 48, (n, d), 1.0)
+    x = (2.0 / np.sqrt(latent)) * (z @ mix) + 0.5 * noise
+    return round_to_bf16_bits(x.astype(np.float32))
+
+
 def outlier_scales(w: Workload, seed: int) -> np.ndarray:
     """Per-(KV head, channel) scale: ``n_outlier`` distinct channels per head get
     ``outlier_scale``; drawn with a partial Fisher-Yates shuffle of the channel ids."""

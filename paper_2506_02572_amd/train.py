@@ -1,0 +1,100 @@
+"""Thin ctypes binding of the learning-to-hash trainer in ``libhata.so`` (C ABI declared in
+``include/hata_train.h``), plus the host-side construction of training triplets.
+
+Argument marshalling only for the training step: the loss, its gradient and the optimiser run in
+the HIP kernels.  torch allocates device memory and supplies the stream.  No CPU fallback.
+"""
+from __future__ import annotations
+
+import ctypes
+
+import numpy as np
+
+from . import hata as _hata
+
+EXPORTS = ("hata_train_workspace_bytes", "hata_train_create", "hata_train_destroy", "hata_train_step")
+
+
+class hata_train_config(ctypes.Structure):
+    _fields_ = [("d", ctypes.c_int32), ("r", ctypes.c_int32), ("n_max", ctypes.c_int32)]
+
+
+class hata_train_hparams(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_float) for n in ("sigma", "eps", "eta", "lam", "scale_sim", "scale_bal",
+                                               "lr", "momentum", "weight_decay")]
+
+
+def default_hparams(n: int, mean_forms: bool = True) -> hata_train_hparams:
+    """Hyper-parameter table of App. B.2; mean_forms scales the two data terms by 1/n and 1/n^2."""
+    return hata_train_hparams(0.1, 0.01, 2.0, 1.0, 1.0 / n if mean_forms else 1.0,
+                              1.0 / (n * n) if mean_forms else 1.0, 0.1, 0.9, 1e-6)
+
+
+_bound = False
+
+
+def _lib():
+    global _bound
+    lib = _hata.load_library()
+    if not _bound:
+        vp, i32 = ctypes.c_void_p, ctypes.c_int32
+        lib.hata_train_workspace_bytes.argtypes = [ctypes.POINTER(hata_train_config), ctypes.POINTER(ctypes.c_size_t)]
+        lib.hata_train_create.argtypes = [ctypes.POINTER(vp), ctypes.POINTER(hata_train_config), vp, ctypes.c_size_t]
+        lib.hata_train_destroy.argtypes = [vp]
+        lib.hata_train_step.argtypes = [vp, vp, vp, vp, i32, vp, vp, ctypes.POINTER(hata_train_hparams), vp, vp, vp]
+        for n in EXPORTS:
+            getattr(lib, n).restype = ctypes.c_int
+        _bound = True
+    return lib
+
+
+class TrainContext:
+    """Owns a hata_train_ctx and the torch-allocated workspace it points into."""
+
+    def __init__(self, d: int, r: int, n_max: int, device="cuda:0"):
+        import torch
+        lib = _lib()
+        if not torch.cuda.is_available():
+            raise _hata.HataError("no GPU visible: the trainer has no CPU fallback")
+        self.cfg = hata_train_config(d, r, n_max)
+        nbytes = ctypes.c_size_t(0)
+        _hata._check(lib.hata_train_workspace_bytes(ctypes.byref(self.cfg), ctypes.byref(nbytes)),
+                     "hata_train_workspace_bytes")
+        self.workspace = torch.empty(nbytes.value + 256, dtype=torch.uint8, device=device)
+        ws = (self.workspace.data_ptr() + 255) // 256 * 256
+        self._h = ctypes.c_void_p(None)
+        _hata._check(lib.hata_train_create(ctypes.byref(self._h), ctypes.byref(self.cfg),
+                                           ctypes.c_void_p(ws), nbytes.value), "hata_train_create")
+        self.workspace_bytes = nbytes.value
+
+    def close(self):
+        if getattr(self, "_h", None) is not None and self._h.value:
+            _lib().hata_train_destroy(self._h)
+            self._h = ctypes.c_void_p(None)
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def hata_train_step(self, Q, K, s, n, W, v, hp: hata_train_hparams, grad=None, loss=None, stream=None):
+        _hata._check(_lib().hata_train_step(self._h, _hata._ptr(Q), _hata._ptr(K), _hata._ptr(s), n,
+                                            _hata._ptr(W), _hata._ptr(v), ctypes.byref(hp),
+                                            _hata._ptr(grad), _hata._ptr(loss), _hata._stream(stream)),
+                     "hata_train_step")
+
+
+def make_triplets(q: np.ndarray, K: np.ndarray):
+    """Training triplets of one sampled query against its causal keys (App. B.1 steps 2-5):
+    qk scores, the best tenth labelled 20 .. 1 in equal steps, the others -1.
+    q [d], K [m, d] as float arrays; returns (Q [m, d] = q repeated, K, s [m] float32)."""
+    q = np.asarray(q, dtype=np.float64)
+    K = np.asarray(K, dtype=np.float64)
+    m = K.shape[0]
+    scores = K @ q
+    ranking = np.lexsort((np.arange(m), -scores))  # best score first, earlier key first on ties
+    n_pos = max(1, m // 10)
+    s = np.full(m, -1.0, dtype=np.float32)
+    s[ranking[:n_pos]] = 20.0 if n_pos == 1 else np.linspace(20.0, 1.0, n_pos, dtype=np.float64).astype(np.float32)
+    return np.broadcast_to(q, (m, q.shape[0])).copy(), K, s

@@ -11,8 +11,8 @@ from paper_2506_02572_amd import hata
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
-def declared_symbols():
-    text = open(os.path.join(ROOT, "include", "hata.h")).read()
+def declared_symbols(header="hata.h"):
+    text = open(os.path.join(ROOT, "include", header)).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(hata_[a-z_]+)\s*\(", text)))
 
@@ -24,6 +24,27 @@ def test_every_declared_symbol_is_exported_and_bound():
     for n in names:
         assert hasattr(lib, n), f"{n} declared in hata.h but not exported by libhata.so"
     assert sorted(hata.EXPORTS) == names
+
+
+def test_trainer_symbols_are_exported_and_bound():
+    from paper_2506_02572_amd import train
+    lib = hata.load_library()
+    names = [n for n in declared_symbols("hata_train.h") if n.startswith("hata_train_") and
+             n not in ("hata_train_config", "hata_train_hparams", "hata_train_ctx")]
+    assert sorted(names) == sorted(train.EXPORTS)
+    for n in names:
+        assert hasattr(lib, n), f"{n} declared in hata_train.h but not exported by libhata.so"
+    # host-side validation, no GPU needed
+    train._lib()
+    n = ctypes.c_size_t(0)
+    assert lib.hata_train_workspace_bytes(ctypes.byref(train.hata_train_config(128, 128, 32768)), ctypes.byref(n)) == 0
+    assert n.value > 256 * 128 * 128 * 4
+    assert lib.hata_train_workspace_bytes(ctypes.byref(train.hata_train_config(128, 100, 10)), ctypes.byref(n)) == -2
+    assert lib.hata_train_workspace_bytes(None, ctypes.byref(n)) == -1
+    h = ctypes.c_void_p()
+    assert lib.hata_train_create(ctypes.byref(h), ctypes.byref(train.hata_train_config(128, 128, 10)), None, 0) == -3
+    assert lib.hata_train_step(None, None, None, None, 1, None, None, None, None, None, None) == -1
+    assert lib.hata_train_destroy(None) == 0
 
 
 def test_strerror_and_workspace_validation():
