@@ -228,7 +228,7 @@ def main():
         train_leg = {"triplets": n_tr, "r": w.r, "us_per_step": round(ms_tr * 1e3, 1),
                      "TFLOPs": round(flop / (ms_tr * 1e-3) / 1e12, 1),
                      "mfma_issue_TFLOPs": round((3 * 3 + 2 * 3) / 4 * flop / (ms_tr * 1e-3) / 1e12, 1),
-                     "launches": 5}
+                     "launches": 6}
         tctx.close()
 
     # ---- parity of one step + the oracle timed on this machine's host cores (rank 0, N = 1)

@@ -61,7 +61,7 @@ int hata_train_create(hata_train_ctx** ctx_out, const hata_train_config* cfg, vo
 int hata_train_destroy(hata_train_ctx* ctx);
 
 /* One SGD step on W (and v) from the n triplets (Q[i], K[i], s[i]), 1 <= n <= n_max.
- * hp: host pointer.  grad and loss may be NULL.  Five small launches on `stream`; the projections
+ * hp: host pointer.  grad and loss may be NULL.  Six small launches on `stream`; the projections
  * and the weight-gradient contraction run on the matrix cores (bf16 MFMA over exact three-way bf16
  * splits of the fp32 operands, fp32 accumulation). */
 int hata_train_step(hata_train_ctx* ctx, const void* Q, const void* K, const float* s, int32_t n,

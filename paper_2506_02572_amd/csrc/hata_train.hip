@@ -11,7 +11,8 @@
 //
 // Launches of a step:
 //   1. train_colsum_kernel   h(k) of every key -> per-workgroup column sums (the balance term
-//                            couples every row to sum_n h(k_n), so that sum comes first)
+//                            couples every row to sum_n h(k_n), so that sum comes first);
+//      train_colreduce_kernel adds them up
 //   2. train_grad_kernel     forward of q and k again, dL/dz elementwise in the MFMA result
 //                            registers, then X^T dZ with those registers as the B operand (the
 //                            contraction index -- the row -- may be enumerated in any order, so the
@@ -29,6 +30,7 @@ struct hata_train_ctx {
     hata_train_config cfg;
     int n_wgs_max;
     float* colsum_part;  // [n_wgs_max, r]
+    float* colsum;       // [r]  sum_n h(k_n)
     float* dw_part;      // [n_wgs_max, d, r]
     float* loss_part;    // [column groups (<= 2), n_wgs_max]
     float* P;            // [r, r]
@@ -43,17 +45,20 @@ typedef __attribute__((ext_vector_type(16))) float tr_f32x16_t;
 #define TR_ROWS 128   // triplets per workgroup (one LDS stage)
 #define TR_PITCH 136  // LDS row pitch in bf16 elements (272 B: conflict-free 16-B and transposed reads)
 
-// fp32 -> three bf16 terms whose sum carries all 24 mantissa bits
+// fp32 -> three bf16 terms whose sum carries all 24 mantissa bits (each term is the remainder
+// truncated to its upper 8 significant bits, so both subtractions are exact)
 __device__ __forceinline__ void split3(float x, uint32_t& hi, uint32_t& mid, uint32_t& lo) {
-    hi = f32_to_bf16(x);
-    const float r1 = x - __uint_as_float(hi << 16);
-    mid = f32_to_bf16(r1);
-    const float r2 = r1 - __uint_as_float(mid << 16);
-    lo = f32_to_bf16(r2);
+    const uint32_t hb = __float_as_uint(x) & 0xffff0000u;
+    const float r1 = x - __uint_as_float(hb);
+    const uint32_t mb = __float_as_uint(r1) & 0xffff0000u;
+    const float r2 = r1 - __uint_as_float(mb);
+    hi = hb >> 16;
+    mid = mb >> 16;
+    lo = __float_as_uint(r2) >> 16;
 }
 
 // h = 2 Sigmoid(z) - 1
-__device__ __forceinline__ float relaxed_sign(float z) { return 2.f / (1.f + __expf(-z)) - 1.f; }
+__device__ __forceinline__ float relaxed_sign(float z) { return fmaf(2.f, __builtin_amdgcn_rcpf(1.f + __expf(-z)), -1.f); }
 
 // Weight fragments of hash column `col` as the B operand:
 // frag[plane][kk] holds W[16 kk + 8 half + e][col], e = 0..7
@@ -131,11 +136,24 @@ __global__ __launch_bounds__((R < 128 ? R : 128) * 2) void train_colsum_kernel(
     if (half == 0) colsum_part[(int64_t)blockIdx.x * R + col] = cs;
 }
 
+// sum of the per-workgroup column sums: one workgroup per hash column
+__global__ __launch_bounds__(256) void train_colreduce_kernel(const float* __restrict__ colsum_part, int r,
+                                                              int n_wgs, float* __restrict__ colsum) {
+    __shared__ float red[4];
+    const int j = blockIdx.x, tid = threadIdx.x;
+    float acc = 0.f;
+    for (int g = tid; g < n_wgs; g += 256) acc += colsum_part[(int64_t)g * r + j];
+    acc = wave_sum64(acc);
+    if ((tid & 63) == 0) red[tid >> 6] = acc;
+    __syncthreads();
+    if (tid == 0) colsum[j] = red[0] + red[1] + red[2] + red[3];
+}
+
 template <int R>
 __global__ __launch_bounds__((R < 128 ? R : 128) * 2) void train_grad_kernel(
     const uint16_t* __restrict__ Q, const uint16_t* __restrict__ K, const float* __restrict__ s,
-    const float* __restrict__ W, int n, int n_wgs, float sigma, float c_sim2, float c_bal2,
-    const float* __restrict__ colsum_part, float* __restrict__ dw_part, float* __restrict__ loss_part) {
+    const float* __restrict__ W, int n, float sigma, float c_sim2, float c_bal2,
+    const float* __restrict__ colsum, float* __restrict__ dw_part, float* __restrict__ loss_part) {
     constexpr int THREADS = (R < 128 ? R : 128) * 2;
     __shared__ __attribute__((aligned(16))) uint16_t tile_q[TR_ROWS * TR_PITCH];
     __shared__ __attribute__((aligned(16))) uint16_t tile_k[TR_ROWS * TR_PITCH];
@@ -148,11 +166,7 @@ __global__ __launch_bounds__((R < 128 ? R : 128) * 2) void train_grad_kernel(
     const int col = blockIdx.y * 128 + w * 32 + m;
     tr_bf16x8_t wfrag[3][8];
     load_weight_planes<R>(W, col, half, wfrag);
-    for (int j = tid; j < R; j += THREADS) {
-        float acc = 0.f;
-        for (int g = 0; g < n_wgs; ++g) acc += colsum_part[(int64_t)g * R + j];
-        s_col[j] = acc;
-    }
+    for (int j = tid; j < R; j += THREADS) s_col[j] = colsum[j];
     for (int i = tid; i < TR_ROWS; i += THREADS) s_lab[i] = (row0 + i < n) ? s[row0 + i] : 0.f;
     stage_rows<THREADS>(Q, row0, n, tile_q);
     stage_rows<THREADS>(K, row0, n, tile_k);
@@ -252,6 +266,7 @@ __global__ __launch_bounds__(256) void train_gram_kernel(const float* __restrict
     float sq = 0.f;
     if (i < r) {
         float acc = 0.f;
+#pragma unroll 16
         for (int c = 0; c < HATA_D; ++c) acc = fmaf(W[(int64_t)c * r + i], W[(int64_t)c * r + j], acc);
         acc -= (i == j) ? 1.f : 0.f;
         P[(int64_t)i * r + j] = acc;
@@ -267,7 +282,7 @@ __global__ __launch_bounds__(256) void train_gram_kernel(const float* __restrict
 __global__ __launch_bounds__(256) void train_assemble_kernel(
     const float* __restrict__ W, int r, int n_wgs, float sigma, float lam, float c_sim, float c_bal,
     const float* __restrict__ dw_part, const float* __restrict__ P, const float* __restrict__ fro_part,
-    const float* __restrict__ colsum_part, const float* __restrict__ loss_part,
+    const float* __restrict__ colsum, const float* __restrict__ loss_part,
     float* __restrict__ G, float* __restrict__ grad, float* __restrict__ loss) {
     __shared__ float s_fro;
     __shared__ float red[4];
@@ -285,11 +300,19 @@ __global__ __launch_bounds__(256) void train_assemble_kernel(
     const int e = blockIdx.x * 256 + tid;
     if (e < HATA_D * r) {
         const int c = e / r, j = e % r;
-        float g = 0.f;
-        for (int wg = 0; wg < n_wgs; ++wg) g += dw_part[(int64_t)wg * HATA_D * r + e];
+        // (eight independent chains: the loads of a chain step are in flight together)
+        float gp[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        int wg = 0;
+        for (; wg + 8 <= n_wgs; wg += 8) {
+#pragma unroll
+            for (int u = 0; u < 8; ++u) gp[u] += dw_part[(int64_t)(wg + u) * HATA_D * r + e];
+        }
+        for (; wg < n_wgs; ++wg) gp[0] += dw_part[(int64_t)wg * HATA_D * r + e];
+        float g = ((gp[0] + gp[1]) + (gp[2] + gp[3])) + ((gp[4] + gp[5]) + (gp[6] + gp[7]));
         g *= sigma;
         if (fro > 0.f) {
             float wp = 0.f;
+#pragma unroll 16
             for (int i = 0; i < r; ++i) wp = fmaf(W[(int64_t)c * r + i], P[(int64_t)i * r + j], wp);
             g += lam * 2.f * wp / fro;
         }
@@ -300,11 +323,7 @@ __global__ __launch_bounds__(256) void train_assemble_kernel(
         // similarity: sum of the workgroup partials; balance: squared norm of the column sums
         float ls = 0.f, lb = 0.f;
         for (int wg = tid; wg < n_wgs * ((r + 127) / 128); wg += 256) ls += loss_part[wg];
-        for (int j = tid; j < r; j += 256) {
-            float cs = 0.f;
-            for (int wg = 0; wg < n_wgs; ++wg) cs += colsum_part[(int64_t)wg * r + j];
-            lb = fmaf(cs, cs, lb);
-        }
+        for (int j = tid; j < r; j += 256) lb = fmaf(colsum[j], colsum[j], lb);
         ls = wave_sum64(ls);
         lb = wave_sum64(lb);
         __syncthreads();
@@ -339,7 +358,7 @@ __global__ __launch_bounds__(256) void train_update_kernel(float* __restrict__ W
 namespace {
 constexpr size_t kAlignT = 256;
 inline size_t align_up_t(size_t x) { return (x + kAlignT - 1) / kAlignT * kAlignT; }
-struct TrainPlan { int n_wgs_max; size_t off_colsum, off_dw, off_loss, off_P, off_fro, off_G, total; };
+struct TrainPlan { int n_wgs_max; size_t off_colsum, off_cs, off_dw, off_loss, off_P, off_fro, off_G, total; };
 int make_train_plan(const hata_train_config* f, TrainPlan* p) {
     if (!f) return HATA_EINVAL;
     if (f->n_max < 1) return HATA_EINVAL;
@@ -349,6 +368,7 @@ int make_train_plan(const hata_train_config* f, TrainPlan* p) {
     if (p->n_wgs_max > 65535) return HATA_EUNSUPPORTED;
     size_t o = 0;
     p->off_colsum = o; o = align_up_t(o + (size_t)p->n_wgs_max * f->r * 4);
+    p->off_cs = o;     o = align_up_t(o + (size_t)f->r * 4);
     p->off_dw = o;     o = align_up_t(o + (size_t)p->n_wgs_max * f->d * f->r * 4);
     p->off_loss = o;   o = align_up_t(o + (size_t)p->n_wgs_max * 2 * 4);
     p->off_P = o;      o = align_up_t(o + (size_t)f->r * f->r * 4);
@@ -384,6 +404,7 @@ int hata_train_create(hata_train_ctx** ctx_out, const hata_train_config* cfg, vo
     c->n_wgs_max = p.n_wgs_max;
     char* w = (char*)workspace;
     c->colsum_part = (float*)(w + p.off_colsum);
+    c->colsum = (float*)(w + p.off_cs);
     c->dw_part = (float*)(w + p.off_dw);
     c->loss_part = (float*)(w + p.off_loss);
     c->P = (float*)(w + p.off_P);
@@ -414,9 +435,11 @@ int hata_train_step(hata_train_ctx* ctx, const void* Q, const void* K, const flo
 #define HATA_TRAIN_LAUNCH(RR)                                                                          \
     hipLaunchKernelGGL((hata::train_colsum_kernel<RR>), dim3(n_wgs, (RR + 127) / 128),                 \
                        dim3((RR < 128 ? RR : 128) * 2), 0, st, k, W, n, hp->sigma, ctx->colsum_part);  \
+    hipLaunchKernelGGL(hata::train_colreduce_kernel, dim3(RR), dim3(256), 0, st, ctx->colsum_part, RR, \
+                       n_wgs, ctx->colsum);                                                            \
     hipLaunchKernelGGL((hata::train_grad_kernel<RR>), dim3(n_wgs, (RR + 127) / 128),                   \
-                       dim3((RR < 128 ? RR : 128) * 2), 0, st, q, k, s, W, n, n_wgs, hp->sigma,        \
-                       2.f * c_sim, 2.f * c_bal, ctx->colsum_part, ctx->dw_part, ctx->loss_part)
+                       dim3((RR < 128 ? RR : 128) * 2), 0, st, q, k, s, W, n, hp->sigma,               \
+                       2.f * c_sim, 2.f * c_bal, ctx->colsum, ctx->dw_part, ctx->loss_part)
     switch (r) {
         case 32: HATA_TRAIN_LAUNCH(32); break;
         case 64: HATA_TRAIN_LAUNCH(64); break;
@@ -428,7 +451,7 @@ int hata_train_step(hata_train_ctx* ctx, const void* Q, const void* K, const flo
     const int count = ctx->cfg.d * r;
     hipLaunchKernelGGL(hata::train_assemble_kernel, dim3((count + 255) / 256), dim3(256), 0, st, W, r,
                        n_wgs, hp->sigma, hp->lam, c_sim, c_bal, ctx->dw_part, ctx->P, ctx->fro_part,
-                       ctx->colsum_part, ctx->loss_part, ctx->G, grad, loss);
+                       ctx->colsum, ctx->loss_part, ctx->G, grad, loss);
     hipLaunchKernelGGL(hata::train_update_kernel, dim3((count + 255) / 256), dim3(256), 0, st, W, v,
                        ctx->G, count, hp->lr, hp->momentum, hp->weight_decay);
     return hipGetLastError() == hipSuccess ? HATA_OK : HATA_EHIP;
