@@ -174,6 +174,14 @@ int hata_set_wait_limit(hata_ctx* ctx, int32_t polls);
  * synchronous call of the library besides hata_create(); never needed for the three-launch form. */
 int hata_check(hata_ctx* ctx, void* stream);
 
+/* KV cache in host memory (the paper's offloading variant, Sec. 5.3: hash codes stay on the GPU,
+ * K and V live in pinned host memory and only the selected rows cross the bus).  Every K / V
+ * argument above may be the device-side address of PINNED, MAPPED host memory (hipHostMalloc):
+ * the attention kernels then gather the selected rows over the bus themselves, nothing is staged.
+ * This helper returns that address for a host pointer (*dev_out; host pointers in and out) or
+ * HATA_EINVAL if the memory is not pinned and mapped -- pass nothing else to a kernel. */
+int hata_host_device_pointer(void* host, void** dev_out);
+
 /* Device pointers of the workspace regions hata_decode_step() writes (layouts as above, sized
  * for B_max); valid until the workspace is released.  Any output pointer may be NULL. */
 int hata_step_buffers(hata_ctx* ctx, uint32_t** qcodes, uint16_t** scores, int32_t** idx);

@@ -322,6 +322,18 @@ int hata_check(hata_ctx* ctx, void* stream) {
     return HATA_ETIMEOUT;
 }
 
+int hata_host_device_pointer(void* host, void** dev_out) {
+    if (!host || !dev_out) return HATA_EINVAL;
+    *dev_out = nullptr;
+    void* d = nullptr;
+    if (hipHostGetDevicePointer(&d, host, 0) != hipSuccess || !d) {
+        (void)hipGetLastError();  // not pinned / not mapped: leave no sticky error behind
+        return HATA_EINVAL;
+    }
+    *dev_out = d;
+    return HATA_OK;
+}
+
 int hata_step_buffers(hata_ctx* ctx, uint32_t** qcodes, uint16_t** scores, int32_t** idx) {
     if (!ctx) return HATA_EINVAL;
     if (qcodes) *qcodes = ctx->qcodes;

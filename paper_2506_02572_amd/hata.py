@@ -19,7 +19,7 @@ EXPORTS = (
     "hata_encode_query", "hata_hamming_score", "hata_topk", "hata_sparse_decode",
     "hata_dense_decode", "hata_decode_step", "hata_step_plan", "hata_set_step_mode", "hata_set_wait_limit",
     "hata_check",
-    "hata_step_buffers",
+    "hata_host_device_pointer", "hata_step_buffers",
 )
 
 
@@ -73,6 +73,7 @@ def load_library(build_if_missing: bool = True) -> ctypes.CDLL:
     lib.hata_set_step_mode.argtypes = [_vp, _i32]
     lib.hata_set_wait_limit.argtypes = [_vp, _i32]
     lib.hata_check.argtypes = [_vp, _vp]
+    lib.hata_host_device_pointer.argtypes = [_vp, ctypes.POINTER(_vp)]
     lib.hata_step_buffers.argtypes = [_vp, ctypes.POINTER(_vp), ctypes.POINTER(_vp), ctypes.POINTER(_vp)]
     for name in EXPORTS:
         if name != "hata_strerror":
@@ -91,11 +92,17 @@ def _check(status: int, what: str) -> None:
 
 
 def _ptr(t):
-    """Device pointer of a torch tensor (or None)."""
+    """Device pointer of a torch tensor (or None).  A pinned host tensor (KV cache kept in host
+    memory) is passed by the device-side address of its mapping."""
     if t is None:
         return None
     if not t.is_cuda:
-        raise HataError("expected a device tensor")
+        if t.device.type == "cpu" and t.is_pinned():
+            dev = ctypes.c_void_p()
+            _check(load_library().hata_host_device_pointer(ctypes.c_void_p(t.data_ptr()), ctypes.byref(dev)),
+                   "hata_host_device_pointer")
+            return dev
+        raise HataError("expected a device tensor (or a pinned host tensor)")
     return ctypes.c_void_p(t.data_ptr())
 
 

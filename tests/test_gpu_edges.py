@@ -145,6 +145,40 @@ def test_single_launch_wait_gives_up_cleanly_and_is_reported(torch_mod):
     c.ctx.close()
 
 
+def test_kv_cache_in_pinned_host_memory(torch_mod):
+    """The offloading variant (Sec. 5.3 of the paper): codes on the GPU, K and V in pinned host
+    memory; the step gathers the selected rows over the bus.  Same results as with a device cache."""
+    torch = torch_mod
+    w = synth.Workload("kvhost", 2, 8, 2, 128, 128, (6000, 4500), (128, 96), 4, 8.0, append_steps=1)
+    c = H.Case(w, seed=777)
+    Kh = torch.from_numpy(c.inp.K.view(np.int16)).pin_memory()
+    Vh = torch.from_numpy(c.inp.V.view(np.int16)).pin_memory()
+    seq = c.inp.seq_len + 1
+    codes_h = c.codes_ref.copy()
+    codes_d = H.to_dev(codes_h)
+    q = c.inp.q(0)
+    ref = O.decode_step(q, c.inp.K, c.inp.V, c.inp.W_H, codes_h, seq, c.inp.k, w.k_max, c.scale, append=True)
+    out = c.empty((w.B, w.Hq, w.d), torch.int16)
+    out32 = c.empty((w.B, w.Hq, w.d), torch.float32)
+    for mode in (0, 3):
+        c.ctx.hata_set_step_mode(mode)
+        out32.zero_()
+        c.ctx.hata_decode_step(H.to_dev(q), Kh, Vh, c.W_H, codes_d, H.to_dev(seq), c.k, w.B, True,
+                               c.scale, out, out32)
+        c.ctx.hata_check()
+        _, _, ix = c.ctx.hata_step_buffers()
+        assert np.array_equal(H.to_host(ix), ref["idx"])
+        assert np.array_equal(H.to_host(codes_d, np.uint32), codes_h), "appended key code (key read from host memory)"
+        H.check_attention(H.to_host(out32), H.to_host(out, np.uint16), ref["out"], f"host KV, mode {mode}")
+    c.ctx.hata_set_step_mode(0)
+    # unpinned host memory is refused on the host side, before any launch
+    from paper_2506_02572_amd import hata
+    with pytest.raises(hata.HataError):
+        c.ctx.hata_decode_step(H.to_dev(q), torch.from_numpy(c.inp.K.view(np.int16)), Vh, c.W_H, codes_d,
+                               H.to_dev(seq), c.k, w.B, True, c.scale, out, out32)
+    c.ctx.close()
+
+
 def test_sparse_decode_skips_negative_entries_and_strided_cache(torch_mod):
     torch = torch_mod
     from paper_2506_02572_amd import hata
