@@ -148,7 +148,10 @@ int hata_dense_decode(hata_ctx* ctx, const void* q, const void* K, const void* V
  * bounded: a workgroup that gives up raises a flag in the workspace and runs to its end, the
  * step's outputs are then invalid, and the next hata_check() returns HATA_ETIMEOUT.  Otherwise
  * the step is three launches (encode; score + threshold; select + attend) with no in-kernel wait.
- * Both forms give identical results. */
+ * Both forms select the same rows and agree on the output to rounding.  Either form may be
+ * recorded into a HIP graph and replayed (no memset nodes, no host-side state a replay depends
+ * on: the single-launch kernel retires the words its workgroups publish before it ends);
+ * hata_check() is a synchronising call and stays outside the capture. */
 int hata_decode_step(hata_ctx* ctx, const void* q, const void* K, const void* V, const float* W_H,
                      uint32_t* codes, const int32_t* seq_len, const int32_t* k, int32_t B,
                      int32_t append, float sm_scale, void* out, float* out_f32, void* stream);

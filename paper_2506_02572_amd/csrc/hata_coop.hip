@@ -15,7 +15,7 @@
 // So the scores never make a round trip through memory for the selection, and the only serial
 // pieces are the two last-arriver tails.
 //
-// The wait in step 2 needs every workgroup of a unit to be running; the host launches this kernel
+// The waits need every workgroup of a unit to be running; the host launches this kernel
 // only when the whole grid can be resident at once.  The wait is bounded anyway: a workgroup that
 // gives up sets the context's error word and runs to its end, so every wave always terminates.
 #include "hata_attn_core.h"
@@ -283,6 +283,8 @@ __global__ __launch_bounds__(256, 3) void decode_step_coop_kernel(const CoopArgs
             if (outp32) outp32[i] = 0.f;
         }
         for (int p = tid; p < a.k_max; p += 256) a.idx[u * a.k_max + p] = -1;
+        // (this workgroup is the unit's only one: it retires the query code words it published)
+        for (int i = tid; i < G * WD; i += 256) a.qrec[((int64_t)b * a.Hq + hq0) * WD + i] = 0ull;
         return;
     }
     TC(50);
@@ -480,7 +482,16 @@ __global__ __launch_bounds__(256, 3) void decode_step_coop_kernel(const CoopArgs
     const int64_t head_stride = (int64_t)a.n_chunks * HATA_PSTRIDE;
     float* part0 = a.partials + ((int64_t)b * a.Hq + hq0) * head_stride;
     attn_emit<G>(S, nc == 1, outp, outp32, part0 + (int64_t)c * HATA_PSTRIDE, head_stride);
-    if (nc == 1) return;
+    // The workgroup that finishes the unit retires the unit's published words (query code words,
+    // chunk records): every workgroup of the unit has consumed them by now.  A later launch that
+    // carries the SAME epoch -- a replay of a captured HIP graph freezes the kernel arguments --
+    // therefore never mistakes this launch's words for its own.
+    auto retire_records = [&]() {
+        unsigned long long* qrec = a.qrec + ((int64_t)b * a.Hq + hq0) * WD;
+        for (int i = tid; i < 2 * nc; i += 256) rec_u[i] = 0ull;
+        for (int i = tid; i < G * WD; i += 256) qrec[i] = 0ull;
+    };
+    if (nc == 1) { retire_records(); return; }
     TC(48);
     wait_stores();
     __syncthreads();
@@ -496,6 +507,7 @@ __global__ __launch_bounds__(256, 3) void decode_step_coop_kernel(const CoopArgs
     if (!s_flag) return;
     TU(53);
     attn_merge<G>(S, part0, head_stride, nc, outp, outp32);
+    retire_records();
     TU(54);
 #undef TC
 #undef TU

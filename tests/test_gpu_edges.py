@@ -251,3 +251,63 @@ def test_error_codes_on_device_box(torch_mod):
     with pytest.raises(hata.HataError):   # k_max above L_cap
         hata.Context(1, 8, 2, 128, 128, 64, 128)
     ctx.close()
+
+
+def test_decode_steps_replayed_from_a_captured_graph(torch_mod):
+    """Three decode steps (three contexts, i.e. three 'layers') captured in one HIP graph and
+    replayed with new inputs between replays: every replay must equal the eager result of the same
+    inputs.  (A captured launch freezes its arguments, the launch counter of the single-launch form
+    included: the kernel retires what it published, so a replay cannot pick up stale words.)"""
+    torch = torch_mod
+    from paper_2506_02572_amd import hata
+    w = synth.Workload("graph", 2, 8, 2, 128, 128, (5000, 3001), (100, 333), 4, 8.0, L_cap=5120)
+    cases = [H.Case(w, seed=900 + i) for i in range(3)]
+    assert cases[0].ctx.hata_step_plan(w.B)[0] == 1
+    codes = [H.to_dev(c.codes_ref) for c in cases]
+    qbuf = [torch.zeros((w.B, w.Hq, w.d), dtype=torch.int16, device="cuda") for _ in cases]
+    outs = [torch.zeros((w.B, w.Hq, w.d), dtype=torch.int16, device="cuda") for _ in cases]
+    outs32 = [torch.zeros((w.B, w.Hq, w.d), dtype=torch.float32, device="cuda") for _ in cases]
+
+    def enqueue():
+        for c, cd, qd, o, o32 in zip(cases, codes, qbuf, outs, outs32):
+            c.ctx.hata_decode_step(qd, c.K, c.V, c.W_H, cd, c.seq_len, c.k, w.B, False, c.scale, o, o32)
+
+    def set_queries(step):
+        for c, qd in zip(cases, qbuf):
+            qd.copy_(H.to_dev(c.inp.q(step)))
+
+    # eager references for four different query sets
+    eager = []
+    for step in range(4):
+        set_queries(step)
+        enqueue()
+        torch.cuda.synchronize()
+        eager.append(([o.clone() for o in outs32], [c.ctx.hata_step_buffers()[2].clone() for c in cases]))
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        set_queries(0)
+        enqueue()  # warm-up on the capture stream
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        enqueue()
+    for step in (1, 3, 0, 2, 2):
+        set_queries(step)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        for i, c in enumerate(cases):
+            c.ctx.hata_check()
+            assert torch.equal(outs32[i], eager[step][0][i]), f"replay with query set {step}, layer {i}: output"
+            assert torch.equal(c.ctx.hata_step_buffers()[2], eager[step][1][i]), f"replay {step}, layer {i}: index list"
+        outs32[0].add_(1.0)  # eager work between the replays
+        torch.cuda.synchronize()
+    # and against the oracle once
+    c = cases[1]
+    ref = O.decode_step(c.inp.q(2), c.inp.K, c.inp.V, c.inp.W_H, c.codes_ref.copy(), c.inp.seq_len, c.inp.k,
+                        w.k_max, c.scale, append=False)
+    assert np.array_equal(H.to_host(c.ctx.hata_step_buffers()[2]), ref["idx"])
+    for c in cases:
+        c.ctx.close()
