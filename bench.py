@@ -152,6 +152,18 @@ def main():
     enc_bytes = enc_keys * (w.d * 2 + w.r // 8)
     enc_flop = 2.0 * enc_keys * w.d * w.r
 
+    # ---- the same with the cache fill fused in (Alg. 1: KCache <- K, VCache <- V, K_H = HashEncode(K))
+    fill_leg = None
+    if not args.kv_host and not args.pmc_probe and w.r in (32, 64, 128, 256) and max_prefill == w.L_cap:
+        K_dst, V_dst = torch.empty_like(K_all[0]), torch.empty_like(V_all[0])
+        codes_dst = torch.empty_like(codes_all[0])
+        fill_calls = [ctx.prepared("hata_prefill_write", K_all[l], V_all[l], zero, prefill_len, w.B, w.L_cap,
+                                   K_dst, V_dst, codes_dst, W_H, stream=stream) for l in range(n_layers)]
+        ms_fill, _ = timed(lambda i: fill_calls[i % n_layers](), n_layers, 1)
+        fill_bytes = enc_keys * (4 * w.d * 2 + w.r // 8)  # K and V read and written once, codes written
+        fill_leg = {"us_per_layer": round(ms_fill * 1e3, 1), "GBps": round(fill_bytes / (ms_fill * 1e-3) / 1e9, 1)}
+        del K_dst, V_dst, codes_dst, fill_calls
+
     if args.pmc_probe:
         # a plain copy of known size (reads and writes COPY_BYTES each) calibrates the counters;
         # then the decode step and the scoring launch, the same calls the timed legs issue
@@ -321,6 +333,7 @@ def main():
         "encode_keys_bulk": {"us_per_layer": round(enc_ms * 1e3, 1), "keys": enc_keys,
                              "GBps": round(enc_bytes / (enc_ms * 1e-3) / 1e9, 1),
                              "TFLOPs": round(enc_flop / (enc_ms * 1e-3) / 1e12, 2)},
+        "prefill_write": fill_leg,
         "dense_decode_us": None if dense_us is None else round(dense_us, 2),
         "speedup_vs_dense": None if dense_us is None else round(dense_us / us_step, 2),
         "train_step": train_leg,

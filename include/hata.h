@@ -101,6 +101,15 @@ int hata_encode_keys(hata_ctx* ctx, const void* K, const float* W_H,
                      const int32_t* start, const int32_t* n_new, int32_t B, int32_t max_new,
                      uint32_t* codes, void* stream);
 
+/* Prefill cache fill in one pass (Alg. 1: KCache <- K, VCache <- V, K_H = HashEncode(K)): the rows
+ *   K_new[b, h, i, :], V_new[b, h, i, :], i < n_new[b]   (bf16, layout [B, Hkv, max_new, d], contiguous)
+ * are written to cache rows start[b] + i of K and V (strides of the context) while their key codes
+ * go to `codes` -- the keys are read once.  Same numerics as hata_encode_keys' matrix-core kernel;
+ * r must be 32, 64, 128 or 256 (HATA_EUNSUPPORTED otherwise).  Rows >= L_cap are not touched. */
+int hata_prefill_write(hata_ctx* ctx, const void* K_new, const void* V_new, const int32_t* start,
+                       const int32_t* n_new, int32_t B, int32_t max_new, void* K, void* V,
+                       uint32_t* codes, const float* W_H, void* stream);
+
 /* Query-code writer (Alg. 3 "HashEncode(Q)"): qcodes[b, hq, :] = BitPack(Sign(q[b, hq, :] . W_H[hq / G])).
  * fp64 accumulation. */
 int hata_encode_query(hata_ctx* ctx, const void* q, const float* W_H, int32_t B,

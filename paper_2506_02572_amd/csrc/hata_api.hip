@@ -207,6 +207,23 @@ int hata_encode_keys(hata_ctx* ctx, const void* K, const float* W_H, const int32
     return hip_rc(hata::launch_encode_bulk(ctx, K, W_H, start, n_new, B, max_new, codes, s));
 }
 
+int hata_prefill_write(hata_ctx* ctx, const void* K_new, const void* V_new, const int32_t* start,
+                       const int32_t* n_new, int32_t B, int32_t max_new, void* K, void* V,
+                       uint32_t* codes, const float* W_H, void* stream) {
+    int rc = check_call(ctx, B);
+    if (rc != HATA_OK) return rc;
+    if (!K_new || !V_new || !start || !n_new || !K || !V || !codes || !W_H) return HATA_EINVAL;
+    if (max_new < 0 || max_new > ctx->cfg.L_cap) return HATA_EINVAL;
+    if (!aligned(K_new, 16) || !aligned(V_new, 16) || !aligned(K, 16) || !aligned(V, 16) ||
+        !aligned(codes, 16) || !aligned(W_H, 16))
+        return HATA_EINVAL;
+    const int r = ctx->cfg.r;
+    if (r != 32 && r != 64 && r != 128 && r != 256) return HATA_EUNSUPPORTED;
+    if (max_new == 0) return HATA_OK;
+    return hip_rc(hata::launch_encode_bulk(ctx, K, W_H, start, n_new, B, max_new, codes,
+                                           (hipStream_t)stream, K_new, V_new, K, V));
+}
+
 int hata_encode_query(hata_ctx* ctx, const void* q, const float* W_H, int32_t B, uint32_t* qcodes,
                       void* stream) {
     int rc = check_call(ctx, B);

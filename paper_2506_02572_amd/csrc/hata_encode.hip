@@ -232,7 +232,11 @@ __global__ __launch_bounds__(R * 2) void encode_mfma_kernel(
     const uint16_t* __restrict__ K, const float* __restrict__ W_H,
     const int32_t* __restrict__ start, const int32_t* __restrict__ n_new,
     uint32_t* __restrict__ codes, int Hkv, int L_cap, int keys_per_wg,
-    int64_t sb, int64_t sh, int64_t sn) {
+    int64_t sb, int64_t sh, int64_t sn,
+    // fused cache fill (all null otherwise): the keys are read from K_new [B, Hkv, max_new, d] and
+    // written to the cache K as they pass through; V_new is copied to V alongside
+    const uint16_t* __restrict__ K_new, const uint16_t* __restrict__ V_new,
+    uint16_t* __restrict__ K_out, uint16_t* __restrict__ V_out, int max_new) {
     constexpr int THREADS = R * 2;
     constexpr int WD = R / 32;
     constexpr int STAGE = R >= 64 ? 128 : 64;              // keys per LDS stage
@@ -244,13 +248,19 @@ __global__ __launch_bounds__(R * 2) void encode_mfma_kernel(
     const int m = lane & 31, half = lane >> 5;
     const int h = blockIdx.y, b = blockIdx.z;
     const int first = start[b];
-    const int cnt = min(n_new[b], L_cap - first);
+    int cnt = min(n_new[b], L_cap - first);
+    if (K_new != nullptr) cnt = min(cnt, max_new);  // the source holds max_new rows per unit
     const int kb0 = blockIdx.x * keys_per_wg;
     if (first < 0 || kb0 >= cnt) return;
     const int kb1 = min(kb0 + keys_per_wg, cnt);
     const int64_t u = (int64_t)b * Hkv + h;
     const uint16_t* Kb = K + b * sb + h * sh + (int64_t)first * sn;
     uint32_t* cb = codes + (u * L_cap + first) * WD;
+    const bool fill = K_new != nullptr;
+    const uint16_t* Ksrc = fill ? K_new + u * (int64_t)max_new * HATA_D : nullptr;
+    const uint16_t* Vsrc = fill ? V_new + u * (int64_t)max_new * HATA_D : nullptr;
+    uint16_t* Kdst = fill ? K_out + b * sb + h * sh + (int64_t)first * sn : nullptr;
+    uint16_t* Vdst = fill ? V_out + b * sb + h * sh + (int64_t)first * sn : nullptr;
 
     // weight fragments: a[plane][kk] holds W_H[h][kk*16 + 8*half + e][32 w + m], e = 0..7
     bf16x8_t afrag[3][8];
@@ -289,7 +299,16 @@ __global__ __launch_bounds__(R * 2) void encode_mfma_kernel(
         for (int it = 0; it < NIT; ++it) {
             const int key = k0 + it * ROWS_PER_IT + lrow;
             pre[it] = make_uint4(0, 0, 0, 0);
-            if (key < kb1) pre[it] = *reinterpret_cast<const uint4*>(Kb + (int64_t)key * sn + lsub * 8);
+            if (key < kb1) {
+                if (fill) {
+                    pre[it] = *reinterpret_cast<const uint4*>(Ksrc + (int64_t)key * HATA_D + lsub * 8);
+                    const uint4 vv = *reinterpret_cast<const uint4*>(Vsrc + (int64_t)key * HATA_D + lsub * 8);
+                    *reinterpret_cast<uint4*>(Kdst + (int64_t)key * sn + lsub * 8) = pre[it];
+                    *reinterpret_cast<uint4*>(Vdst + (int64_t)key * sn + lsub * 8) = vv;
+                } else {
+                    pre[it] = *reinterpret_cast<const uint4*>(Kb + (int64_t)key * sn + lsub * 8);
+                }
+            }
         }
     };
     load_stage(kb0);
@@ -365,9 +384,14 @@ hipError_t launch_encode_vectors(const hata_ctx* c, const void* q, uint32_t* qco
 
 hipError_t launch_encode_bulk(const hata_ctx* c, const void* K, const float* W_H,
                               const int32_t* start, const int32_t* n_new, int B, int max_new,
-                              uint32_t* codes, hipStream_t s) {
+                              uint32_t* codes, hipStream_t s, const void* K_new, const void* V_new,
+                              void* K_out, void* V_out) {
     const hata_config& f = c->cfg;
     if (max_new <= 0 || B <= 0) return hipSuccess;
+    const uint16_t* kn = (const uint16_t*)K_new;
+    const uint16_t* vn = (const uint16_t*)V_new;
+    uint16_t* ko = (uint16_t*)K_out;
+    uint16_t* vo = (uint16_t*)V_out;
     if (f.r == 32 || f.r == 64 || f.r == 128 || f.r == 256) {
         // key blocks of 512..4096 keys: at least ~512 workgroups when the prefill is long enough
         int kpw = 4096;
@@ -376,21 +400,22 @@ hipError_t launch_encode_bulk(const hata_ctx* c, const void* K, const float* W_H
         if (f.r == 32)
             hipLaunchKernelGGL((encode_mfma_kernel<32>), grid, dim3(64), 0, s, (const uint16_t*)K,
                                W_H, start, n_new, codes, f.Hkv, f.L_cap, kpw, f.kv_stride_b,
-                               f.kv_stride_h, f.kv_stride_n);
+                               f.kv_stride_h, f.kv_stride_n, kn, vn, ko, vo, max_new);
         else if (f.r == 64)
             hipLaunchKernelGGL((encode_mfma_kernel<64>), grid, dim3(128), 0, s, (const uint16_t*)K,
                                W_H, start, n_new, codes, f.Hkv, f.L_cap, kpw, f.kv_stride_b,
-                               f.kv_stride_h, f.kv_stride_n);
+                               f.kv_stride_h, f.kv_stride_n, kn, vn, ko, vo, max_new);
         else if (f.r == 128)
             hipLaunchKernelGGL((encode_mfma_kernel<128>), grid, dim3(256), 0, s, (const uint16_t*)K,
                                W_H, start, n_new, codes, f.Hkv, f.L_cap, kpw, f.kv_stride_b,
-                               f.kv_stride_h, f.kv_stride_n);
+                               f.kv_stride_h, f.kv_stride_n, kn, vn, ko, vo, max_new);
         else
             hipLaunchKernelGGL((encode_mfma_kernel<256>), grid, dim3(512), 0, s, (const uint16_t*)K,
                                W_H, start, n_new, codes, f.Hkv, f.L_cap, kpw, f.kv_stride_b,
-                               f.kv_stride_h, f.kv_stride_n);
+                               f.kv_stride_h, f.kv_stride_n, kn, vn, ko, vo, max_new);
         return hipGetLastError();
     }
+    if (kn) return hipErrorNotSupported;  // the fused cache fill exists for the MFMA widths only
     const int tiles = (max_new + 63) / 64;
     hipLaunchKernelGGL(encode_bulk_kernel, dim3(tiles, f.Hkv, B), dim3(256), 0, s,
                        (const uint16_t*)K, W_H, start, n_new, codes, f.Hkv, f.r, c->Wd, f.L_cap,

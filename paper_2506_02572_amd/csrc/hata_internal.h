@@ -45,9 +45,12 @@ hipError_t launch_encode_vectors(const hata_ctx* c, const void* q, uint32_t* qco
                                  const void* K, const int32_t* start, const int32_t* n_new,
                                  int max_new, int from_seq_len, uint32_t* codes,
                                  const float* W_H, int B, hipStream_t s);
+// K_new .. V_out non-null: fused cache fill (rows read from K_new / V_new [B, Hkv, max_new, d],
+// written to the caches K_out / V_out while the key codes are computed)
 hipError_t launch_encode_bulk(const hata_ctx* c, const void* K, const float* W_H,
                               const int32_t* start, const int32_t* n_new, int B, int max_new,
-                              uint32_t* codes, hipStream_t s);
+                              uint32_t* codes, hipStream_t s, const void* K_new = nullptr,
+                              const void* V_new = nullptr, void* K_out = nullptr, void* V_out = nullptr);
 hipError_t launch_score(const hata_ctx* c, const uint32_t* qcodes, const uint32_t* codes,
                         const int32_t* seq_len, int B, uint16_t* scores, const int32_t* kbud,
                         hipStream_t s);

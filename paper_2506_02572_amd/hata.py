@@ -16,7 +16,7 @@ LIB_PATH = os.path.join(_HERE, "libhata.so")
 
 EXPORTS = (
     "hata_strerror", "hata_workspace_bytes", "hata_create", "hata_destroy", "hata_encode_keys",
-    "hata_encode_query", "hata_hamming_score", "hata_topk", "hata_sparse_decode",
+    "hata_prefill_write", "hata_encode_query", "hata_hamming_score", "hata_topk", "hata_sparse_decode",
     "hata_dense_decode", "hata_decode_step", "hata_step_plan", "hata_set_step_mode", "hata_set_wait_limit",
     "hata_check",
     "hata_host_device_pointer", "hata_step_buffers",
@@ -62,6 +62,7 @@ def load_library(build_if_missing: bool = True) -> ctypes.CDLL:
     lib.hata_create.argtypes = [ctypes.POINTER(_vp), ctypes.POINTER(hata_config), _vp, ctypes.c_size_t]
     lib.hata_destroy.argtypes = [_vp]
     lib.hata_encode_keys.argtypes = [_vp, _vp, _vp, _vp, _vp, _i32, _i32, _vp, _vp]
+    lib.hata_prefill_write.argtypes = [_vp, _vp, _vp, _vp, _vp, _i32, _i32, _vp, _vp, _vp, _vp, _vp]
     lib.hata_encode_query.argtypes = [_vp, _vp, _vp, _i32, _vp, _vp]
     lib.hata_hamming_score.argtypes = [_vp, _vp, _vp, _vp, _i32, _vp, _vp]
     lib.hata_topk.argtypes = [_vp, _vp, _vp, _vp, _i32, _vp, _vp]
@@ -164,6 +165,11 @@ class Context:
         _check(load_library().hata_encode_keys(self._h, _ptr(K), _ptr(W_H), _ptr(start), _ptr(n_new),
                                                B, max_new, _ptr(codes), _stream(stream)),
                "hata_encode_keys")
+
+    def hata_prefill_write(self, K_new, V_new, start, n_new, B, max_new, K, V, codes, W_H, stream=None):
+        _check(load_library().hata_prefill_write(self._h, _ptr(K_new), _ptr(V_new), _ptr(start), _ptr(n_new),
+                                                 B, max_new, _ptr(K), _ptr(V), _ptr(codes), _ptr(W_H),
+                                                 _stream(stream)), "hata_prefill_write")
 
     def hata_encode_query(self, q, W_H, B, qcodes, stream=None):
         _check(load_library().hata_encode_query(self._h, _ptr(q), _ptr(W_H), B, _ptr(qcodes),

@@ -311,3 +311,43 @@ def test_decode_steps_replayed_from_a_captured_graph(torch_mod):
     assert np.array_equal(H.to_host(c.ctx.hata_step_buffers()[2]), ref["idx"])
     for c in cases:
         c.ctx.close()
+
+
+@pytest.mark.parametrize("r", [128, 64])
+def test_prefill_write_fills_caches_and_codes_in_one_pass(torch_mod, r):
+    """Alg. 1 of the paper in one call: new K / V rows land in the caches at start[b] + i and their
+    key codes in the code cache; rows outside the range keep what they held."""
+    torch = torch_mod
+    w = synth.Workload("prefill", 2, 8, 2, 128, r, (3000, 1700), (64, 64), 4, 8.0, L_cap=3072)
+    c = H.Case(w, seed=31, oracle_codes=False)
+    B, Hkv, d = w.B, w.Hkv, w.d
+    start = np.array([100, 0], np.int32)
+    n_new = np.array([2500, 1700], np.int32)
+    max_new = 2560
+    # new rows = the generator's rows [0, n_new) of each unit, to be stored from row start[b] on
+    K_new = np.zeros((B, Hkv, max_new, d), np.uint16)
+    V_new = np.zeros((B, Hkv, max_new, d), np.uint16)
+    for b in range(B):
+        K_new[b, :, :n_new[b]] = c.inp.K[b, :, :n_new[b]]
+        V_new[b, :, :n_new[b]] = c.inp.V[b, :, :n_new[b]]
+    K_cache = torch.full((B, Hkv, w.L_cap, d), 0x1111, dtype=torch.int16, device="cuda")
+    V_cache = torch.full((B, Hkv, w.L_cap, d), 0x2222, dtype=torch.int16, device="cuda")
+    codes = torch.full((B, Hkv, w.L_cap, w.W), 0x33333333, dtype=torch.int32, device="cuda")
+    c.ctx.hata_prefill_write(H.to_dev(K_new), H.to_dev(V_new), H.to_dev(start), H.to_dev(n_new), B, max_new,
+                             K_cache, V_cache, codes, c.W_H)
+    c.sync()
+    Kc, Vc, cc = H.to_host(K_cache, np.uint16), H.to_host(V_cache, np.uint16), H.to_host(codes, np.uint32)
+    # the oracle encodes the rows where they now sit in the cache
+    K_host = np.full((B, Hkv, w.L_cap, d), 0x1111, np.uint16)
+    for b in range(B):
+        K_host[b, :, start[b]:start[b] + n_new[b]] = K_new[b, :, :n_new[b]]
+    ref, near = O.encode_keys_batch(K_host, c.inp.W_H, start, n_new, bulk=True)
+    for b in range(B):
+        lo, hi = int(start[b]), int(start[b] + n_new[b])
+        assert np.array_equal(Kc[b, :, lo:hi], K_new[b, :, :n_new[b]]) and np.array_equal(Vc[b, :, lo:hi], V_new[b, :, :n_new[b]])
+        assert np.all(Kc[b, :, :lo] == 0x1111) and np.all(Kc[b, :, hi:] == 0x1111)
+        assert np.all(Vc[b, :, :lo] == 0x2222) and np.all(Vc[b, :, hi:] == 0x2222)
+        assert np.all(cc[b, :, :lo] == 0x33333333) and np.all(cc[b, :, hi:] == 0x33333333)
+        diff = (cc[b, :, lo:hi] ^ ref[b, :, lo:hi]) & ~near[b, :, lo:hi]
+        assert not np.any(diff), "key codes differ outside the |projection| < 1e-4 band"
+    c.ctx.close()
