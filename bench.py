@@ -8,7 +8,7 @@ synthetic, resident in HBM before the timed region.  Consecutive steps rotate ov
 distinct copies ("layers") of the K/V/code caches so that the traffic is HBM traffic and
 not Infinity-Cache hits, as a model with tens of layers does for every token.
 
-Prints ONE JSON line (see the design doc for every field).
+Prints ONE JSON line.
 """
 from __future__ import annotations
 

@@ -151,7 +151,7 @@ int hata_dense_decode(hata_ctx* ctx, const void* q, const void* K, const void* V
  * Intermediate qcodes / scores / idx live in the workspace (see hata_step_buffers).
  *
  * Launches (see hata_step_plan): when every workgroup of the step can be resident on the device
- * at once (r in {32, 64, 128, 256}, Hq/Hkv in {1, 2, 4, 5, 8}), the step is ONE kernel launch whose
+ * at once (r in {32, 64, 128, 256}, Hq/Hkv in {1, 2, 4, 5, 8}, or 16 with r <= 128), the step is ONE kernel launch whose
  * workgroups hand the query codes, the selection threshold and the attention partials to each
  * other through the workspace, waiting for one another inside the kernel.  Every such wait is
  * bounded: a workgroup that gives up raises a flag in the workspace and runs to its end, the

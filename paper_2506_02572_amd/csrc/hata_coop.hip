@@ -182,10 +182,11 @@ __device__ __forceinline__ void coop_encode_vec(const float* __restrict__ Wh, co
     if (t >= 0.0) atomicOr(&s_word[col >> 5], 1u << (col & 31));
 }
 
-// WD in {1, 2, 4, 8} (r = 32, 64, 128, 256); G in {1, 2, 4, 5, 8} (all heads of the group in one
-// attention tile)
+// WD in {1, 2, 4, 8} (r = 32, 64, 128, 256); G in {1, 2, 4, 5, 8, 16} (all heads of the group in one
+// attention tile; 16 only up to r = 128: one wave collects the G * WD <= 64 query code words)
 template <int WD, int G>
-__global__ __launch_bounds__(256, 3) void decode_step_coop_kernel(const CoopArgs a) {
+__global__ __launch_bounds__(256, (G >= 16 ? 2 : 3)) void decode_step_coop_kernel(const CoopArgs a) {
+    static_assert(G * WD <= 64, "query code words of a unit are collected by one wave");
     extern __shared__ uint32_t hist[];  // NB words: chunk histogram, later the unit's total
     constexpr bool MFMA = G >= 4;  // matrix-core form of the attention core
     // the threshold search (last arriver only) is over before the attention stages V tiles
@@ -523,6 +524,9 @@ static const void* coop_kernel_for(int Wd, int G) {
         case 104: return coop_fn<1, 4>();
         case 105: return coop_fn<1, 5>();
         case 108: return coop_fn<1, 8>();
+        case 116: return coop_fn<1, 16>();
+        case 216: return coop_fn<2, 16>();
+        case 416: return coop_fn<4, 16>();
         case 201: return coop_fn<2, 1>();
         case 202: return coop_fn<2, 2>();
         case 204: return coop_fn<2, 4>();

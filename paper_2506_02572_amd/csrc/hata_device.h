@@ -134,13 +134,13 @@ __device__ __forceinline__ uint32_t block_excl_scan_256(uint32_t v, uint32_t* ld
 template <int WD, int G>
 struct HammingSum {
     static constexpr bool PLANES = G >= 5;  // below that the direct form is as short
-    static constexpr int NP = G >= 8 ? 4 : 3;  // G <= 15
+    static constexpr int NP = G >= 16 ? 5 : G >= 8 ? 4 : 3;  // G <= 31
     uint32_t d[NP][WD];
     uint32_t c0;
 
     // qp: the G * WD code words of the group (the same for every lane)
     __device__ __forceinline__ void init(const uint32_t* qp) {
-        static_assert(G >= 1 && G <= 15, "plane count");
+        static_assert(G >= 1 && G <= 31, "plane count");
         c0 = 0;
 #pragma unroll
         for (int w = 0; w < WD; ++w) {

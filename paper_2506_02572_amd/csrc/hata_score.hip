@@ -251,8 +251,9 @@ hipError_t launch_score(const hata_ctx* c, const uint32_t* qcodes, const uint32_
 #define HATA_CASE(WD, GG) case WD * 100 + GG: launch_t<WD, GG>(c, qcodes, codes, seq_len, B, scores, kbud, s); break;
         HATA_CASE(4, 1) HATA_CASE(4, 2) HATA_CASE(4, 4) HATA_CASE(4, 5) HATA_CASE(4, 8)
         HATA_CASE(8, 1) HATA_CASE(8, 2) HATA_CASE(8, 4) HATA_CASE(8, 5) HATA_CASE(8, 8)
-        HATA_CASE(2, 1) HATA_CASE(2, 4) HATA_CASE(2, 8)
-        HATA_CASE(1, 1) HATA_CASE(1, 4) HATA_CASE(1, 8)
+        HATA_CASE(2, 1) HATA_CASE(2, 2) HATA_CASE(2, 4) HATA_CASE(2, 5) HATA_CASE(2, 8)
+        HATA_CASE(1, 1) HATA_CASE(1, 2) HATA_CASE(1, 4) HATA_CASE(1, 5) HATA_CASE(1, 8)
+        HATA_CASE(1, 16) HATA_CASE(2, 16) HATA_CASE(4, 16) HATA_CASE(8, 16)
 #undef HATA_CASE
         default:
             hipLaunchKernelGGL(score_kernel_generic, dim3(c->n_chunks, f.Hkv, B), dim3(256),

@@ -188,6 +188,7 @@ def config(index: int, seed: int = DEFAULT_SEED) -> Workload:
 SWEEP = {
     "mha32_32k": Workload("mha32_32k", 1, 32, 32, 128, 128, (32768,), (512,), 4, 8.0),
     "g5_40q8kv_32k": Workload("g5_40q8kv_32k", 2, 40, 8, 128, 128, (32768, 20000), (512, 320), 4, 8.0),
+    "g16_128q8kv_32k": Workload("g16_128q8kv_32k", 1, 128, 8, 128, 128, (32768,), (512,), 4, 8.0),
     "r64_32k": Workload("r64_32k", 1, 32, 8, 128, 64, (32768,), (512,), 4, 8.0),
     "r32_32k": Workload("r32_32k", 1, 32, 8, 128, 32, (32768,), (512,), 4, 8.0),
     "r256_g8_ragged": Workload("r256_g8_ragged", 2, 64, 8, 128, 256, (24000, 9000), (384, 128), 8, 16.0),

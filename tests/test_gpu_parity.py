@@ -155,7 +155,8 @@ def test_decode_step_end_to_end(case, mode):
     w = case.w
     case.ctx.hata_set_step_mode(mode)
     n_launches, chunk, n_chunks = case.ctx.hata_step_plan(w.B)
-    single_ok = w.r in (32, 64, 128, 256) and (w.Hq // w.Hkv) in (1, 2, 4, 5, 8)
+    g = w.Hq // w.Hkv
+    single_ok = w.r in (32, 64, 128, 256) and (g in (1, 2, 4, 5, 8) or (g == 16 and w.r <= 128))
     assert n_launches == (1 if (mode == 0 and single_ok) else 3), (n_launches, chunk, n_chunks)
     q = case.inp.q(3)
     # host: codes of rows [0, L-1) known, row L-1 is appended by the step

@@ -27,6 +27,10 @@ def test_group_of_5_ragged_batch(torch_mod):
     run_workload(torch_mod, synth.SWEEP["g5_40q8kv_32k"], {0}, True)
 
 
+def test_group_of_16(torch_mod):
+    run_workload(torch_mod, synth.SWEEP["g16_128q8kv_32k"], {0}, True)
+
+
 def test_hash_bits_64_and_32(torch_mod):
     run_workload(torch_mod, synth.SWEEP["r64_32k"], {0}, True)
     run_workload(torch_mod, synth.SWEEP["r32_32k"], {0}, True)
