@@ -148,7 +148,8 @@ int hata_dense_decode(hata_ctx* ctx, const void* q, const void* K, const void* V
  * of each sequence to cache row seq_len[b]-1 (static pre-allocated cache).  If `append` != 0
  * that row is hash-encoded into `codes` first; then the query is encoded, all seq_len[b] codes
  * are scored, the budget is selected and attention runs over the selected rows.
- * Intermediate qcodes / scores / idx live in the workspace (see hata_step_buffers).
+ * Intermediate qcodes / idx (and scores, see hata_keep_step_scores) live in the workspace
+ * (see hata_step_buffers).
  *
  * Launches (see hata_step_plan): when every workgroup of the step can be resident on the device
  * at once (r in {32, 64, 128, 256}, Hq/Hkv in {1, 2, 4, 5, 8}, or 16 with r <= 128), the step is ONE kernel launch whose
@@ -173,6 +174,12 @@ int hata_step_plan(const hata_ctx* ctx, int32_t B, int32_t* n_launches, int32_t*
 /* mode 0 (default): hata_decode_step() uses the single-launch form whenever it fits;
  * mode 3: always the three-launch form (no in-kernel waits). */
 int hata_set_step_mode(hata_ctx* ctx, int32_t mode);
+
+/* The Hamming scores of a step are an intermediate: the single-launch form keeps them on chip and
+ * writes the score region of the workspace only if asked to (keep != 0; default off, which saves
+ * 2 bytes of HBM writes per cached key).  The three-launch form always writes it (its second
+ * launch reads it back). */
+int hata_keep_step_scores(hata_ctx* ctx, int32_t keep);
 
 /* Bound of every in-kernel wait of the single-launch form, in polls (0 restores the default, 2^18:
  * far longer than any step).  A tiny bound makes the waits give up at once -- the kernel still runs

@@ -183,6 +183,7 @@ int hata_create(hata_ctx** ctx_out, const hata_config* cfg, void* workspace, siz
     c->coop_capacity = hata::coop_capacity(c);
     c->step_mode = 0;
     c->spin_limit = 0;
+    c->keep_scores = 0;
     *ctx_out = c;
     return HATA_OK;
 }
@@ -321,6 +322,12 @@ int hata_step_plan(const hata_ctx* ctx, int32_t B, int32_t* n_launches, int32_t*
 int hata_set_step_mode(hata_ctx* ctx, int32_t mode) {
     if (!ctx || (mode != 0 && mode != 3)) return HATA_EINVAL;
     ctx->step_mode = mode;
+    return HATA_OK;
+}
+
+int hata_keep_step_scores(hata_ctx* ctx, int32_t keep) {
+    if (!ctx) return HATA_EINVAL;
+    ctx->keep_scores = keep ? 1 : 0;
     return HATA_OK;
 }
 

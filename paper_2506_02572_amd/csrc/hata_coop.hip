@@ -58,6 +58,7 @@ struct CoopArgs {
     uint32_t epoch;
     int append;
     int spin_limit;
+    int keep_scores;  // also write the score array (a by-product the kernel itself never reads back)
 };
 
 template <int WD>
@@ -333,7 +334,7 @@ __global__ __launch_bounds__(256, (G >= 16 ? 2 : 3)) void decode_step_coop_kerne
                 const int n = n0 + j * 256;
                 if (n < end_main) {
                     const uint32_t s = distance(kc[j].w);
-                    sp[n] = (uint16_t)s;
+                    if (a.keep_scores) sp[n] = (uint16_t)s;
                     s_sc[n - base] = (uint16_t)s;
                     atomicAdd(&hist[s], 1u);
                     low = min(low, s);
@@ -347,7 +348,7 @@ __global__ __launch_bounds__(256, (G >= 16 ? 2 : 3)) void decode_step_coop_kerne
 #pragma unroll
             for (int w = 0; w < WD; ++w) kw[w] = s_codes[G * WD + w];
             const uint32_t s = distance(kw);
-            sp[L - 1] = (uint16_t)s;
+            if (a.keep_scores) sp[L - 1] = (uint16_t)s;
             s_sc[L - 1 - base] = (uint16_t)s;
             atomicAdd(&hist[s], 1u);
             atomicMin(&s_low, (int)s);
@@ -507,8 +508,8 @@ __global__ __launch_bounds__(256, (G >= 16 ? 2 : 3)) void decode_step_coop_kerne
     TC(49);
     if (!s_flag) return;
     TU(53);
+    retire_records();  // (before the merge: the stores complete while the partials are being fetched)
     attn_merge<G>(S, part0, head_stride, nc, outp, outp32);
-    retire_records();
     TU(54);
 #undef TC
 #undef TU
@@ -567,6 +568,7 @@ hipError_t launch_coop_step(hata_ctx* c, const void* q, const void* K, const voi
     a.q = (const uint16_t*)q; a.K = (const uint16_t*)K; a.V = (const uint16_t*)V;
     a.W_H = W_H; a.append = append;
     a.spin_limit = c->spin_limit > 0 ? c->spin_limit : HATA_COOP_SPIN_LIMIT;
+    a.keep_scores = c->keep_scores;
     a.qcodes = c->qcodes; a.codes = codes; a.seq_len = seq_len; a.kbud = k;
     a.scores = c->scores; a.idx = c->idx; a.chunk_hist = c->chunk_hist;
     a.chunk_info = c->chunk_info; a.unit_info = c->unit_info; a.unit_counter = c->unit_counter;

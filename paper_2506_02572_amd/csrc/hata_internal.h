@@ -33,6 +33,7 @@ struct hata_ctx {
     uint32_t* error_word;    // [1] set by a cooperative launch that gave up waiting
     uint32_t epoch;          // launch counter of the cooperative step
     int spin_limit;          // polls an in-kernel wait makes before it gives up (0 = the default)
+    int keep_scores;         // single-launch step also writes the score array
     int step_mode;           // 0 = single launch when it fits, 3 = always three launches
     int coop_capacity;       // workgroups of the cooperative kernel that can be resident at once (0 = unusable)
     float* partials;       // [B_max*Hq, max(sparse_splits, dense_splits), d + 2]

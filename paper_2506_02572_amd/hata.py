@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libhata.so")
 EXPORTS = (
     "hata_strerror", "hata_workspace_bytes", "hata_create", "hata_destroy", "hata_encode_keys",
     "hata_prefill_write", "hata_encode_query", "hata_hamming_score", "hata_topk", "hata_sparse_decode",
-    "hata_dense_decode", "hata_decode_step", "hata_step_plan", "hata_set_step_mode", "hata_set_wait_limit",
+    "hata_dense_decode", "hata_decode_step", "hata_step_plan", "hata_set_step_mode", "hata_keep_step_scores", "hata_set_wait_limit",
     "hata_check",
     "hata_host_device_pointer", "hata_step_buffers",
 )
@@ -72,6 +72,7 @@ def load_library(build_if_missing: bool = True) -> ctypes.CDLL:
                                      ctypes.c_float, _vp, _vp, _vp]
     lib.hata_step_plan.argtypes = [_vp, _i32, ctypes.POINTER(_i32), ctypes.POINTER(_i32), ctypes.POINTER(_i32)]
     lib.hata_set_step_mode.argtypes = [_vp, _i32]
+    lib.hata_keep_step_scores.argtypes = [_vp, _i32]
     lib.hata_set_wait_limit.argtypes = [_vp, _i32]
     lib.hata_check.argtypes = [_vp, _vp]
     lib.hata_host_device_pointer.argtypes = [_vp, ctypes.POINTER(_vp)]
@@ -209,6 +210,9 @@ class Context:
 
     def hata_set_step_mode(self, mode):
         _check(load_library().hata_set_step_mode(self._h, mode), "hata_set_step_mode")
+
+    def hata_keep_step_scores(self, keep):
+        _check(load_library().hata_keep_step_scores(self._h, 1 if keep else 0), "hata_keep_step_scores")
 
     def hata_set_wait_limit(self, polls):
         _check(load_library().hata_set_wait_limit(self._h, polls), "hata_set_wait_limit")

@@ -59,6 +59,7 @@ def run_workload(torch, w, steps_to_check, single_launch, dense=True):
     out = c.empty((B, w.Hq, w.d), torch.int16)
     out32 = c.empty((B, w.Hq, w.d), torch.float32)
     n_steps = max(1, w.append_steps)
+    c.ctx.hata_keep_step_scores(True)  # the score array is inspected below
     n_launches, chunk, n_chunks = c.ctx.hata_step_plan(B)
     print(f"[full]   step plan: {n_launches} launch(es), chunk {chunk}, {n_chunks} chunks per unit", flush=True)
     assert n_launches == (1 if single_launch else 3), "unexpected launch form of the decode step"

@@ -154,6 +154,7 @@ def test_decode_step_end_to_end(case, mode):
     import torch
     w = case.w
     case.ctx.hata_set_step_mode(mode)
+    case.ctx.hata_keep_step_scores(True)  # the score array is inspected below
     n_launches, chunk, n_chunks = case.ctx.hata_step_plan(w.B)
     g = w.Hq // w.Hkv
     single_ok = w.r in (32, 64, 128, 256) and (g in (1, 2, 4, 5, 8) or (g == 16 and w.r <= 128))

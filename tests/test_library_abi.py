@@ -79,6 +79,7 @@ def test_strerror_and_workspace_validation():
     assert lib.hata_step_plan(None, 1, None, None, None) == -1
     assert lib.hata_set_step_mode(None, 0) == -1
     assert lib.hata_set_wait_limit(None, 0) == -1
+    assert lib.hata_keep_step_scores(None, 0) == -1
     assert lib.hata_check(None, None) == -1
     assert lib.hata_host_device_pointer(None, None) == -1
     assert lib.hata_destroy(None) == 0
