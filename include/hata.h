@@ -158,6 +158,10 @@ int hata_dense_decode(hata_ctx* ctx, const void* q, const void* K, const void* V
  * bounded: a workgroup that gives up raises a flag in the workspace and runs to its end, the
  * step's outputs are then invalid, and the next hata_check() returns HATA_ETIMEOUT.  Otherwise
  * the step is three launches (encode; score + threshold; select + attend) with no in-kernel wait.
+ * The residency test assumes the device runs nothing else at that moment and that the context is
+ * used on the device that was current in hata_create(): a process that overlaps other kernels
+ * with the step (other streams, other processes) should call hata_set_step_mode(ctx, 3), or watch
+ * hata_check().
  * Both forms select the same rows and agree on the output to rounding.  Either form may be
  * recorded into a HIP graph and replayed (no memset nodes, no host-side state a replay depends
  * on: the single-launch kernel retires the words its workgroups publish before it ends);
