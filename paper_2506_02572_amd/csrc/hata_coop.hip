@@ -58,6 +58,7 @@ struct CoopArgs {
     uint32_t epoch;
     int append;
     int spin_limit;
+    int prefetch;     // fetch the first batch of key codes before the query codes are known
     int keep_scores;  // also write the score array (a by-product the kernel itself never reads back)
 };
 
@@ -242,6 +243,10 @@ __global__ __launch_bounds__(256, (G >= 16 ? 2 : 3)) void decode_step_coop_kerne
     // the code it just computed.
     const int nc = (L + a.chunk - 1) / a.chunk;
     const bool own = a.append && L > 0 && base <= L - 1 && L - 1 < base + a.chunk;
+    const uint32_t* cp = a.codes + u * a.L_cap * WD;
+    const int end_main = own ? L - 1 : end;  // the owner scores row L - 1 from the code it computes
+    constexpr int UNR = (WD <= 2) ? 16 : (WD <= 4) ? 8 : 4;  // 64-128 B of codes in flight per lane
+    CodeW<WD> kc[UNR];
     {
         unsigned long long* qrec = a.qrec + ((int64_t)b * a.Hq + hq0) * WD;
         if (tid < (G + 1) * WD) s_codes[tid] = 0;
@@ -260,6 +265,17 @@ __global__ __launch_bounds__(256, (G >= 16 ? 2 : 3)) void decode_step_coop_kerne
         if (own) {
             coop_encode_load<WD>(Wh, a.K + b * a.sb + h * a.sh + (int64_t)(L - 1) * a.sn, el);
             coop_encode_vec<WD>(Wh, el, &s_codes[G * WD]);
+        }
+        // Small grids (workgroups on at most half the CUs: the step is a chain of latencies, not a stream):
+        // the first batch of the chunk's key codes is fetched while the query codes are collected.
+        // With more workgroups per CU these loads would only queue in front of the encoders' own.
+        if (a.prefetch) {
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int j = 0; j < UNR; ++j) {
+                const int n = base + tid + j * 256;
+                if (n < end_main) kc[j] = coop_load_code<WD>(cp + (int64_t)n * WD);
+            }
         }
         if (tid < 64) {  // one wave collects the G * WD (<= 64) query code words of the unit
             const int i = min(tid, G * WD - 1);
@@ -317,17 +333,15 @@ __global__ __launch_bounds__(256, (G >= 16 ? 2 : 3)) void decode_step_coop_kerne
         }
     };
     {
-        const uint32_t* cp = a.codes + u * a.L_cap * WD;
         uint16_t* sp = a.scores + u * a.L_cap;
-        const int end_main = own ? L - 1 : end;
-        constexpr int UNR = (WD <= 2) ? 16 : (WD <= 4) ? 8 : 4;  // 64-128 B of codes in flight per lane
         uint32_t low = 0xffffu;  // lowest score this thread sees
         for (int n0 = base + tid; n0 < end_main; n0 += 256 * UNR) {
-            CodeW<WD> kc[UNR];
+            if (!a.prefetch || n0 != base + tid) {  // (the first batch may be in the registers already)
 #pragma unroll
-            for (int j = 0; j < UNR; ++j) {
-                const int n = n0 + j * 256;
-                if (n < end_main) kc[j] = coop_load_code<WD>(cp + (int64_t)n * WD);
+                for (int j = 0; j < UNR; ++j) {
+                    const int n = n0 + j * 256;
+                    if (n < end_main) kc[j] = coop_load_code<WD>(cp + (int64_t)n * WD);
+                }
             }
 #pragma unroll
             for (int j = 0; j < UNR; ++j) {
@@ -569,6 +583,13 @@ hipError_t launch_coop_step(hata_ctx* c, const void* q, const void* K, const voi
     a.W_H = W_H; a.append = append;
     a.spin_limit = c->spin_limit > 0 ? c->spin_limit : HATA_COOP_SPIN_LIMIT;
     a.keep_scores = c->keep_scores;
+    {
+        int dev = 0, cus = 0;
+        a.prefetch = 0;
+        if (hipGetDevice(&dev) == hipSuccess &&
+            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess)
+            a.prefetch = (int64_t)c->n_chunks * f.Hkv * B * 2 <= cus ? 1 : 0;  // (measured: pays up to half a grid)
+    }
     a.qcodes = c->qcodes; a.codes = codes; a.seq_len = seq_len; a.kbud = k;
     a.scores = c->scores; a.idx = c->idx; a.chunk_hist = c->chunk_hist;
     a.chunk_info = c->chunk_info; a.unit_info = c->unit_info; a.unit_counter = c->unit_counter;
