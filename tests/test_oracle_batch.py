@@ -119,3 +119,54 @@ def test_generator_is_counter_based_and_gaussian():
     assert abs(w.std() * math.sqrt(128) - 1.0) < 0.02
     sc = synth.outlier_scales(synth.config(4), 7)
     assert np.all((sc == 16.0).sum(axis=1) == 8) and np.all((sc == 1.0).sum(axis=1) == 120)
+
+
+def test_decode_step_against_a_pure_python_brute_force_on_a_tiny_case():
+    """The whole step of Alg. 3 written again with nothing but Python numbers -- fractions for the
+    projections (so the sign of every hash bit is exact), bin().count for the distances, sorted()
+    on (distance, row) for the selection, math.exp for the softmax -- on a case small enough for
+    that: every integer result must be identical, the output equal to 1e-12."""
+    from fractions import Fraction
+    w = synth.Workload("tiny", 2, 4, 2, 128, 32, (9, 5), (3, 7), 2, 8.0, L_cap=12, k_max=7)
+    inp = synth.generate(w, seed=3)
+    q = inp.q(0)
+    scale = 1.0 / math.sqrt(w.d)
+    codes, _ = O.encode_keys_batch(inp.K, inp.W_H, np.zeros(w.B, np.int32), inp.seq_len - 1)
+    res = O.decode_step(q, inp.K, inp.V, inp.W_H, codes, inp.seq_len, inp.k, w.k_max, scale, append=True)
+
+    def f32(bits):  # bf16 bit pattern -> exact Fraction
+        return Fraction(float(np.array([int(bits) << 16], np.uint32).view(np.float32)[0]))
+
+    def code_of(vec_bits, h):  # Alg. 2: bit j set iff the projection on column j is >= 0
+        x = [f32(v) for v in vec_bits]
+        word = 0
+        for j in range(w.r):
+            proj = sum(x[c] * Fraction(float(inp.W_H[h, c, j])) for c in range(w.d))
+            if proj >= 0:
+                word |= 1 << j
+        return word
+
+    G = w.Hq // w.Hkv
+    for b in range(w.B):
+        L, kk = int(inp.seq_len[b]), int(inp.k[b])
+        for h in range(w.Hkv):
+            kcodes = [code_of(inp.K[b, h, n], h) for n in range(L)]
+            got_codes = [int(codes[b, h, n, 0]) for n in range(L)]
+            assert kcodes == got_codes, (b, h)
+            qcodes = [code_of(q[b, h * G + g], h) for g in range(G)]
+            assert qcodes == [int(res["qcodes"][b, h * G + g, 0]) for g in range(G)]
+            dist = [sum(bin(qc ^ kc).count("1") for qc in qcodes) for kc in kcodes]
+            assert dist == [int(v) for v in res["scores"][b, h, :L]]
+            keep = sorted(n for _, n in sorted((dv, n) for n, dv in enumerate(dist))[:min(kk, L)])
+            got_idx = [int(v) for v in res["idx"][b, h] if v >= 0]
+            assert keep == got_idx, (b, h, keep, got_idx)
+            assert all(int(v) == -1 for v in res["idx"][b, h, len(keep):])
+            for g in range(G):
+                qv = [float(f32(v)) for v in q[b, h * G + g]]
+                logits = [scale * sum(qv[c] * float(f32(inp.K[b, h, n, c])) for c in range(w.d)) for n in keep]
+                m = max(logits)
+                wts = [math.exp(v - m) for v in logits]
+                z = sum(wts)
+                for c in range(0, w.d, 17):
+                    want = sum(wt * float(f32(inp.V[b, h, n, c])) for wt, n in zip(wts, keep)) / z
+                    assert abs(res["out"][b, h * G + g, c] - want) <= 1e-12 * max(1.0, abs(want))
