@@ -52,6 +52,9 @@ def parse():
                     help="offloading variant (Sec. 5.3 of the paper): K and V in pinned host memory, hash "
                          "codes on the GPU; the selected rows are gathered over the bus")
     ap.add_argument("--no-train", action="store_true", help="skip the learning-to-hash training-step leg")
+    ap.add_argument("--paged", type=int, default=0, metavar="PAGE_ROWS",
+                    help="also time the step on the paged (block-table) layout: the caches are re-laid as "
+                         "pools of PAGE_ROWS-row pages in a random page order (needs L_cap %% PAGE_ROWS == 0)")
     ap.add_argument("--cpu-seconds", type=float, default=10.0)
     ap.add_argument("--pmc-probe", action="store_true",
                     help="run only a known-size copy kernel, the decode step and the scoring kernel (for "
@@ -290,6 +293,43 @@ def main():
         ok = bool(np.all(err <= 2e-3 + 1e-3 * np.abs(ref["out"])))
         parity = {"idx_equal": idx_equal, "attn_within_tol": ok, "max_abs_err": float(err.max())}
 
+    # ---- the step on the paged layout (last: the caches are re-laid in place, page order random)
+    paged_leg = None
+    if args.paged and not args.kv_host and w.L_cap % args.paged == 0 and n_launches == 1:
+        P = args.paged
+        ctx.hata_decode_step(q_steps[0], K_all[0], V_all[0], W_H, codes_all[0], seq_steps[0], kbud, w.B, True,
+                             scale, out, out32, stream)
+        torch.cuda.synchronize()
+        ref_out = out32.clone()  # the same step on the contiguous layout, for a bit-for-bit comparison
+        nb = w.L_cap // P
+        n_pages = w.B * nb
+        perm = torch.randperm(n_pages, generator=torch.Generator().manual_seed(1))  # page of block (b, blk)
+        table = perm.view(w.B, nb).to(torch.int32).to(dev)
+        inv = torch.argsort(perm).to(dev)                                           # block held by page p
+
+        def to_pool(t, last):  # [B, Hkv, L_cap, last] -> [n_pages, Hkv, P, last] in the same memory
+            blocks = t.view(w.B, w.Hkv, nb, P, last).permute(0, 2, 1, 3, 4).reshape(n_pages, w.Hkv, P, last)
+            t.view(n_pages, w.Hkv, P, last).copy_(blocks.index_select(0, inv))
+
+        for l in range(n_layers):
+            to_pool(K_all[l], w.d)
+            to_pool(V_all[l], w.d)
+            to_pool(codes_all[l], w.W)
+        paged_calls = []
+        for i in range(n_combo):
+            l, t = i % n_layers, i % n_step_variants
+            paged_calls.append(ctx.prepared("hata_decode_step_paged", q_steps[t % len(q_steps)], K_all[l], V_all[l],
+                                            W_H, codes_all[l], table, nb, P, n_pages, seq_steps[t], kbud, w.B,
+                                            True, scale, out, out32, stream=stream))
+        ctx.hata_decode_step_paged(q_steps[0], K_all[0], V_all[0], W_H, codes_all[0], table, nb, P, n_pages,
+                                   seq_steps[0], kbud, w.B, True, scale, out, out32, stream)
+        torch.cuda.synchronize()
+        same = bool(torch.equal(ref_out, out32))
+        ms_paged, _ = timed(lambda i: paged_calls[i % n_combo](), args.steps, args.warmup)
+        ctx.hata_check(stream)
+        paged_leg = {"page_rows": P, "n_pages": n_pages, "us_per_step": round(ms_paged * 1e3, 3),
+                     "same_bits_as_contiguous": same}
+
     alg_bytes = w.algorithmic_bytes(1 if w.append_steps else 0)
     traffic = HBM_TRAFFIC_BYTES.get(w.name, {})
     step_gbps = alg_bytes / (us_step * 1e-6) / 1e9
@@ -334,6 +374,7 @@ def main():
                              "GBps": round(enc_bytes / (enc_ms * 1e-3) / 1e9, 1),
                              "TFLOPs": round(enc_flop / (enc_ms * 1e-3) / 1e12, 2)},
         "prefill_write": fill_leg,
+        "paged_step": paged_leg,
         "dense_decode_us": None if dense_us is None else round(dense_us, 2),
         "speedup_vs_dense": None if dense_us is None else round(dense_us / us_step, 2),
         "train_step": train_leg,

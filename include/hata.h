@@ -170,6 +170,38 @@ int hata_decode_step(hata_ctx* ctx, const void* q, const void* K, const void* V,
                      uint32_t* codes, const int32_t* seq_len, const int32_t* k, int32_t B,
                      int32_t append, float sm_scale, void* out, float* out_f32, void* stream);
 
+/*
+ * Paged (block-table) cache layout: the serving-side layout in which sequences grow page by page
+ * out of shared pools instead of owning L_cap rows each.
+ *   K_pool, V_pool  [n_pages, Hkv, page_rows, d]  bf16, contiguous (the context's K/V strides are not used)
+ *   codes_pool      [n_pages, Hkv, page_rows, r/32] uint32
+ *   block_table     [B, max_blocks] int32 (device): row n of sequence b is row n % page_rows of
+ *                   page block_table[b, n / page_rows]
+ * page_rows is a power of two >= 16 (256 or more keeps a page's codes a multi-KB contiguous read);
+ * max_blocks * page_rows <= 2^30; n_pages * Hkv * page_rows < 2^31.  Sequence lengths are clamped to
+ * min(L_cap, max_blocks * page_rows); L_cap still sizes the workspace and the launch.  Page numbers
+ * read from the table are clamped to [0, n_pages) (a wrong entry gives wrong results, never an
+ * access outside the pools); entries past a sequence's last block are not read.  Two sequences
+ * may share pages for reading; the page that holds an appended row must belong to one sequence.
+ *
+ * hata_decode_step_paged: hata_decode_step on that layout, same outputs (Idx holds LOGICAL row
+ * numbers).  It exists in the single-launch form only: HATA_EUNSUPPORTED when the shape or the
+ * batch does not fit it (see hata_decode_step; hata_set_step_mode does not apply).
+ */
+int hata_decode_step_paged(hata_ctx* ctx, const void* q, const void* K_pool, const void* V_pool,
+                           const float* W_H, uint32_t* codes_pool, const int32_t* block_table,
+                           int32_t max_blocks, int32_t page_rows, int32_t n_pages,
+                           const int32_t* seq_len, const int32_t* k, int32_t B, int32_t append,
+                           float sm_scale, void* out, float* out_f32, void* stream);
+
+/* hata_prefill_write into the paged layout above (Alg. 1 in one pass): row start[b] + i of
+ * sequence b goes to the page its block-table entry names; the blocks that cover rows
+ * start[b] .. start[b] + n_new[b] - 1 must be assigned in the table before the call. */
+int hata_prefill_write_paged(hata_ctx* ctx, const void* K_new, const void* V_new, const int32_t* start,
+                             const int32_t* n_new, int32_t B, int32_t max_new, void* K_pool, void* V_pool,
+                             uint32_t* codes_pool, const int32_t* block_table, int32_t max_blocks,
+                             int32_t page_rows, int32_t n_pages, const float* W_H, void* stream);
+
 /* Host-side query of how hata_decode_step() runs a batch of B sequences; nothing is enqueued.
  * *n_launches: 1 (single cooperative launch) or 3; *chunk: cached keys per scoring workgroup;
  * *n_chunks: scoring workgroups per (sequence, KV head).  Any output pointer (host) may be NULL. */

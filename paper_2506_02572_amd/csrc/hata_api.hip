@@ -118,6 +118,20 @@ inline bool step_is_single_launch(const hata_ctx* c, int B) {
            (int64_t)c->n_chunks * c->cfg.Hkv * B <= c->coop_capacity;
 }
 inline bool aligned(const void* p, size_t a) { return ((uintptr_t)p % a) == 0; }
+
+// Validates a block-table description and fills the view the launchers take.
+inline int make_page_view(const hata_ctx* c, const int32_t* block_table, int32_t max_blocks,
+                          int32_t page_rows, int32_t n_pages, hata::PageView* pv) {
+    if (!block_table || max_blocks < 1 || n_pages < 1) return HATA_EINVAL;
+    if (page_rows < 16 || page_rows > (1 << 20) || (page_rows & (page_rows - 1)) != 0) return HATA_EINVAL;
+    if ((int64_t)max_blocks * page_rows > (1ll << 30)) return HATA_EINVAL;
+    // rows of the pools are indexed with 32-bit integers on the device
+    if ((int64_t)n_pages * c->cfg.Hkv * page_rows > 0x7fffffffll) return HATA_EINVAL;
+    int shift = 0;
+    while ((1 << shift) < page_rows) ++shift;
+    pv->table = block_table; pv->max_blocks = max_blocks; pv->shift = shift; pv->n_pages = n_pages;
+    return HATA_OK;
+}
 inline int hip_rc(hipError_t e) { return e == hipSuccess ? HATA_OK : HATA_EHIP; }
 
 }  // namespace
@@ -174,13 +188,15 @@ int hata_create(hata_ctx** ctx_out, const hata_config* cfg, void* workspace, siz
     c->error_word = (uint32_t*)(w + p.off_err);
     c->epoch = 0;
     c->coop_capacity = 0;
+    c->coop_capacity_paged = 0;
     c->partials = (float*)(w + p.off_partials);
     // control words and the self-resetting arrival counters start from zero
     if (hipMemset(c->chunk_info, 0, p.off_partials - p.off_cinfo) != hipSuccess) {
         delete c;
         return HATA_EHIP;
     }
-    c->coop_capacity = hata::coop_capacity(c);
+    c->coop_capacity = hata::coop_capacity(c, false);
+    c->coop_capacity_paged = hata::coop_capacity(c, true);
     c->step_mode = 0;
     c->spin_limit = 0;
     c->keep_scores = 0;
@@ -224,6 +240,27 @@ int hata_prefill_write(hata_ctx* ctx, const void* K_new, const void* V_new, cons
     if (max_new == 0) return HATA_OK;
     return hip_rc(hata::launch_encode_bulk(ctx, K, W_H, start, n_new, B, max_new, codes,
                                            (hipStream_t)stream, K_new, V_new, K, V));
+}
+
+int hata_prefill_write_paged(hata_ctx* ctx, const void* K_new, const void* V_new, const int32_t* start,
+                             const int32_t* n_new, int32_t B, int32_t max_new, void* K_pool, void* V_pool,
+                             uint32_t* codes_pool, const int32_t* block_table, int32_t max_blocks,
+                             int32_t page_rows, int32_t n_pages, const float* W_H, void* stream) {
+    int rc = check_call(ctx, B);
+    if (rc != HATA_OK) return rc;
+    if (!K_new || !V_new || !start || !n_new || !K_pool || !V_pool || !codes_pool || !W_H) return HATA_EINVAL;
+    if (max_new < 0 || max_new > ctx->cfg.L_cap) return HATA_EINVAL;
+    if (!aligned(K_new, 16) || !aligned(V_new, 16) || !aligned(K_pool, 16) || !aligned(V_pool, 16) ||
+        !aligned(codes_pool, 16) || !aligned(W_H, 16) || !aligned(block_table, 4))
+        return HATA_EINVAL;
+    hata::PageView pv;
+    rc = make_page_view(ctx, block_table, max_blocks, page_rows, n_pages, &pv);
+    if (rc != HATA_OK) return rc;
+    const int r = ctx->cfg.r;
+    if (r != 32 && r != 64 && r != 128 && r != 256) return HATA_EUNSUPPORTED;
+    if (max_new == 0) return HATA_OK;
+    return hip_rc(hata::launch_encode_bulk(ctx, K_pool, W_H, start, n_new, B, max_new, codes_pool,
+                                           (hipStream_t)stream, K_new, V_new, K_pool, V_pool, &pv));
 }
 
 int hata_encode_query(hata_ctx* ctx, const void* q, const float* W_H, int32_t B, uint32_t* qcodes,
@@ -307,6 +344,29 @@ int hata_decode_step(hata_ctx* ctx, const void* q, const void* K, const void* V,
     if (e != hipSuccess) return HATA_EHIP;
     // TopK(S, N) compaction fused with the attention over the selected rows (gather fused too)
     e = hata::launch_attention(ctx, 2, q, K, V, ctx->idx, k, seq_len, B, sm_scale, out, out_f32, s);
+    return hip_rc(e);
+}
+
+int hata_decode_step_paged(hata_ctx* ctx, const void* q, const void* K_pool, const void* V_pool,
+                           const float* W_H, uint32_t* codes_pool, const int32_t* block_table,
+                           int32_t max_blocks, int32_t page_rows, int32_t n_pages,
+                           const int32_t* seq_len, const int32_t* k, int32_t B, int32_t append,
+                           float sm_scale, void* out, float* out_f32, void* stream) {
+    int rc = check_call(ctx, B);
+    if (rc != HATA_OK) return rc;
+    if (!q || !K_pool || !V_pool || !W_H || !codes_pool || !seq_len || !k || !out) return HATA_EINVAL;
+    if (!aligned(q, 16) || !aligned(K_pool, 16) || !aligned(V_pool, 16) || !aligned(codes_pool, 16) ||
+        !aligned(W_H, 16) || !aligned(out, 2) || !aligned(block_table, 4))
+        return HATA_EINVAL;
+    hata::PageView pv;
+    rc = make_page_view(ctx, block_table, max_blocks, page_rows, n_pages, &pv);
+    if (rc != HATA_OK) return rc;
+    // the block table is read by the single-launch kernel only
+    if (ctx->n_chunks > 256 || (int64_t)ctx->n_chunks * ctx->cfg.Hkv * B > ctx->coop_capacity_paged)
+        return HATA_EUNSUPPORTED;
+    hipError_t e = hata::launch_coop_step(ctx, q, K_pool, V_pool, W_H, codes_pool, append, seq_len, k, B,
+                                          sm_scale, out, out_f32, (hipStream_t)stream, &pv);
+    if (e == hipErrorNotSupported) return HATA_EUNSUPPORTED;
     return hip_rc(e);
 }
 

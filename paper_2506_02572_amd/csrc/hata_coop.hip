@@ -60,6 +60,7 @@ struct CoopArgs {
     int spin_limit;
     int prefetch;     // fetch the first batch of key codes before the query codes are known
     int keep_scores;  // also write the score array (a by-product the kernel itself never reads back)
+    hata::PageView pv;  // block table (used by the PAGED instantiations only)
 };
 
 template <int WD>
@@ -186,7 +187,7 @@ __device__ __forceinline__ void coop_encode_vec(const float* __restrict__ Wh, co
 
 // WD in {1, 2, 4, 8} (r = 32, 64, 128, 256); G in {1, 2, 4, 5, 8, 16} (all heads of the group in one
 // attention tile; 16 only up to r = 128: one wave collects the G * WD <= 64 query code words)
-template <int WD, int G>
+template <int WD, int G, bool PAGED>
 __global__ __launch_bounds__(256, (G >= 16 ? 2 : 3)) void decode_step_coop_kernel(const CoopArgs a) {
     static_assert(G * WD <= 64, "query code words of a unit are collected by one wave");
     extern __shared__ uint32_t hist[];  // NB words: chunk histogram, later the unit's total
@@ -204,6 +205,8 @@ __global__ __launch_bounds__(256, (G >= 16 ? 2 : 3)) void decode_step_coop_kerne
     __shared__ uint32_t s_rec[2];
     __shared__ int s_low;  // lowest score of this chunk
     __shared__ uint32_t s_codes[(G + 1) * WD];  // codes of the G query heads and of the appended key
+    // PAGED: where the pages of this chunk's rows start (pages of 16 rows or more: at most MAX_CHUNK / 16 + 1)
+    __shared__ int s_page[PAGED ? HATA_COOP_MAX_CHUNK / 16 + 2 : 1];
     const int tid = threadIdx.x;
     // Workgroup -> (unit, chunk).  Consecutive workgroup ids go to consecutive XCDs (8 of them, each
     // with its own L2); when the unit count allows, all chunks of a unit get ids that are equal
@@ -226,8 +229,29 @@ __global__ __launch_bounds__(256, (G >= 16 ? 2 : 3)) void decode_step_coop_kerne
     EncodeLoads<WD> el;
     constexpr bool EARLY = WD <= 4;  // (at r = 256 the second half of the weights needs the registers)
     if (EARLY && c < G) coop_encode_load<WD>(Wh, qv + c * HATA_D, el);
-    const int L = clampi(a.seq_len[b], 0, a.L_cap);
     const int base = c * a.chunk;
+    const int blk0 = PAGED ? base >> a.pv.shift : 0;  // first block of the sequence this chunk touches
+    // PAGED: the chunk's block-table entries are fetched alongside the sequence length (one entry
+    // per thread covers every case: at most MAX_CHUNK / 16 = 256 blocks when pages are small and
+    // therefore aligned with the chunk, a handful when they are large)
+    int nblk = 0, my_page = 0;
+    if constexpr (PAGED) {
+        nblk = min(((base + a.chunk - 1) >> a.pv.shift) + 1, a.pv.max_blocks) - blk0;
+        if (threadIdx.x < nblk) my_page = a.pv.table[(int64_t)b * a.pv.max_blocks + blk0 + threadIdx.x];
+    }
+    const int L = clampi(a.seq_len[b], 0, PAGED ? min(a.L_cap, a.pv.max_blocks << a.pv.shift) : a.L_cap);
+    // Row n of the unit (a row of this chunk when PAGED) -> its row in the code array, in rows of
+    // one (sequence or page, head): the contiguous cache is [B, Hkv, L_cap], the pools are
+    // [n_pages, Hkv, page_rows] with K and V rows of exactly d elements.
+    // (s_page holds, per block, the pool row at which this head's part of the page starts: a
+    // 32-bit number, the host has checked that the pools have fewer than 2^31 rows)
+    auto row_in_page = [&](int page_row0, int n) -> int64_t {
+        return (int64_t)(page_row0 + (n & ((1 << a.pv.shift) - 1)));
+    };
+    auto cache_row = [&](int n) -> int64_t {
+        if constexpr (PAGED) return row_in_page(s_page[(n >> a.pv.shift) - blk0], n);
+        else return u * a.L_cap + n;
+    };
     const int hq0 = h * G;
     uint16_t* outp = a.out + ((int64_t)b * a.Hq + hq0) * HATA_D;
     float* outp32 = a.out_f32 ? a.out_f32 + ((int64_t)b * a.Hq + hq0) * HATA_D : nullptr;
@@ -243,15 +267,41 @@ __global__ __launch_bounds__(256, (G >= 16 ? 2 : 3)) void decode_step_coop_kerne
     // the code it just computed.
     const int nc = (L + a.chunk - 1) / a.chunk;
     const bool own = a.append && L > 0 && base <= L - 1 && L - 1 < base + a.chunk;
-    const uint32_t* cp = a.codes + u * a.L_cap * WD;
     const int end_main = own ? L - 1 : end;  // the owner scores row L - 1 from the code it computes
     constexpr int UNR = (WD <= 2) ? 16 : (WD <= 4) ? 8 : 4;  // 64-128 B of codes in flight per lane
     CodeW<WD> kc[UNR];
+    // codes of rows n0, n0 + 256, ... (those below `stop`) into kc; PAGED: all page lookups first,
+    // so that the loads go out together instead of one per LDS round trip
+    auto load_codes = [&](int n0, int stop) {
+        if constexpr (PAGED) {
+            int pg[UNR];
+#pragma unroll
+            for (int j = 0; j < UNR; ++j)
+                pg[j] = s_page[(max(min(n0 + j * 256, stop - 1), base) >> a.pv.shift) - blk0];
+#pragma unroll
+            for (int j = 0; j < UNR; ++j) {
+                const int n = n0 + j * 256;
+                if (n < stop) kc[j] = coop_load_code<WD>(a.codes + row_in_page(pg[j], n) * WD);
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < UNR; ++j) {
+                const int n = n0 + j * 256;
+                if (n < stop) kc[j] = coop_load_code<WD>(a.codes + cache_row(n) * WD);
+            }
+        }
+    };
     {
         unsigned long long* qrec = a.qrec + ((int64_t)b * a.Hq + hq0) * WD;
         if (tid < (G + 1) * WD) s_codes[tid] = 0;
         if (tid == 0) s_low = a.NB;
         for (int i = tid; i < a.NB; i += 256) hist[i] = 0;
+        if constexpr (PAGED) {
+            if (tid < nblk) s_page[tid] = (clampi(my_page, 0, a.pv.n_pages - 1) * a.Hkv + h) << a.pv.shift;
+            for (int i = tid + 256; i < nblk; i += 256)
+                s_page[i] = (clampi(a.pv.table[(int64_t)b * a.pv.max_blocks + blk0 + i], 0, a.pv.n_pages - 1) * a.Hkv + h)
+                            << a.pv.shift;
+        }
         __syncthreads();
         for (int v = c; v < G; v += max(nc, 1)) {
             if (!EARLY || v != c) coop_encode_load<WD>(Wh, qv + v * HATA_D, el);
@@ -263,7 +313,8 @@ __global__ __launch_bounds__(256, (G >= 16 ? 2 : 3)) void decode_step_coop_kerne
                                    __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
         if (own) {
-            coop_encode_load<WD>(Wh, a.K + b * a.sb + h * a.sh + (int64_t)(L - 1) * a.sn, el);
+            coop_encode_load<WD>(Wh, PAGED ? a.K + cache_row(L - 1) * HATA_D
+                                           : a.K + b * a.sb + h * a.sh + (int64_t)(L - 1) * a.sn, el);
             coop_encode_vec<WD>(Wh, el, &s_codes[G * WD]);
         }
         // Small grids (workgroups on at most half the CUs: the step is a chain of latencies, not a stream):
@@ -271,11 +322,7 @@ __global__ __launch_bounds__(256, (G >= 16 ? 2 : 3)) void decode_step_coop_kerne
         // With more workgroups per CU these loads would only queue in front of the encoders' own.
         if (a.prefetch) {
             __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int j = 0; j < UNR; ++j) {
-                const int n = base + tid + j * 256;
-                if (n < end_main) kc[j] = coop_load_code<WD>(cp + (int64_t)n * WD);
-            }
+            load_codes(base + tid, end_main);
         }
         if (tid < 64) {  // one wave collects the G * WD (<= 64) query code words of the unit
             const int i = min(tid, G * WD - 1);
@@ -294,7 +341,7 @@ __global__ __launch_bounds__(256, (G >= 16 ? 2 : 3)) void decode_step_coop_kerne
     }
     if (c == 0)
         for (int i = tid; i < G * WD; i += 256) a.qcodes[((int64_t)b * a.Hq + hq0) * WD + i] = s_codes[i];
-    if (own && tid < WD) a.codes[(u * a.L_cap + (L - 1)) * WD + tid] = s_codes[G * WD + tid];
+    if (own && tid < WD) a.codes[cache_row(L - 1) * WD + tid] = s_codes[G * WD + tid];
     if (base >= L) {  // empty sequence: nothing selected, zero output
         for (int i = tid; i < G * HATA_D; i += 256) {
             outp[i] = 0;
@@ -336,13 +383,7 @@ __global__ __launch_bounds__(256, (G >= 16 ? 2 : 3)) void decode_step_coop_kerne
         uint16_t* sp = a.scores + u * a.L_cap;
         uint32_t low = 0xffffu;  // lowest score this thread sees
         for (int n0 = base + tid; n0 < end_main; n0 += 256 * UNR) {
-            if (!a.prefetch || n0 != base + tid) {  // (the first batch may be in the registers already)
-#pragma unroll
-                for (int j = 0; j < UNR; ++j) {
-                    const int n = n0 + j * 256;
-                    if (n < end_main) kc[j] = coop_load_code<WD>(cp + (int64_t)n * WD);
-                }
-            }
+            if (!a.prefetch || n0 != base + tid) load_codes(n0, end_main);  // (the first batch may be in the registers already)
 #pragma unroll
             for (int j = 0; j < UNR; ++j) {
                 const int n = n0 + j * 256;
@@ -489,11 +530,18 @@ __global__ __launch_bounds__(256, (G >= 16 ? 2 : 3)) void decode_step_coop_kerne
     __syncthreads();
     TC(46);
     // ---- 4. attention over the rows this chunk contributes
-    const uint16_t* Kb = a.K + b * a.sb + h * a.sh;
-    const uint16_t* Vb = a.V + b * a.sb + h * a.sh;
-    auto row_of = [&](int row) { return base + (int)s_sc[row]; };
-    if constexpr (MFMA) attn_rows_mfma<G, 1, false>(qb, Kb, Vb, a.sn, a.L_cap, 0, cnt, a.scale_log2, row_of, S, U.vt);
-    else attn_rows<G, 4>(qr, Kb, Vb, a.sn, a.L_cap, 0, cnt, a.scale_log2, row_of, S);
+    if constexpr (PAGED) {  // rows of the pools (the host has checked that their count fits an int)
+        auto row_of = [&](int row) { return (int)cache_row(base + (int)s_sc[row]); };
+        const int rows = (a.pv.n_pages * a.Hkv) << a.pv.shift;
+        if constexpr (MFMA) attn_rows_mfma<G, 1, false>(qb, a.K, a.V, HATA_D, rows, 0, cnt, a.scale_log2, row_of, S, U.vt);
+        else attn_rows<G, 4>(qr, a.K, a.V, HATA_D, rows, 0, cnt, a.scale_log2, row_of, S);
+    } else {
+        const uint16_t* Kb = a.K + b * a.sb + h * a.sh;
+        const uint16_t* Vb = a.V + b * a.sb + h * a.sh;
+        auto row_of = [&](int row) { return base + (int)s_sc[row]; };
+        if constexpr (MFMA) attn_rows_mfma<G, 1, false>(qb, Kb, Vb, a.sn, a.L_cap, 0, cnt, a.scale_log2, row_of, S, U.vt);
+        else attn_rows<G, 4>(qr, Kb, Vb, a.sn, a.L_cap, 0, cnt, a.scale_log2, row_of, S);
+    }
     TC(47);
     const int64_t head_stride = (int64_t)a.n_chunks * HATA_PSTRIDE;
     float* part0 = a.partials + ((int64_t)b * a.Hq + hq0) * head_stride;
@@ -530,40 +578,42 @@ __global__ __launch_bounds__(256, (G >= 16 ? 2 : 3)) void decode_step_coop_kerne
 }
 
 template <int WD, int G>
-static const void* coop_fn() { return (const void*)&decode_step_coop_kernel<WD, G>; }
+static const void* coop_fn(bool paged) {
+    return paged ? (const void*)&decode_step_coop_kernel<WD, G, true> : (const void*)&decode_step_coop_kernel<WD, G, false>;
+}
 
-static const void* coop_kernel_for(int Wd, int G) {
+static const void* coop_kernel_for(int Wd, int G, bool paged) {
     switch (Wd * 100 + G) {
-        case 101: return coop_fn<1, 1>();
-        case 102: return coop_fn<1, 2>();
-        case 104: return coop_fn<1, 4>();
-        case 105: return coop_fn<1, 5>();
-        case 108: return coop_fn<1, 8>();
-        case 116: return coop_fn<1, 16>();
-        case 216: return coop_fn<2, 16>();
-        case 416: return coop_fn<4, 16>();
-        case 201: return coop_fn<2, 1>();
-        case 202: return coop_fn<2, 2>();
-        case 204: return coop_fn<2, 4>();
-        case 205: return coop_fn<2, 5>();
-        case 208: return coop_fn<2, 8>();
-        case 401: return coop_fn<4, 1>();
-        case 402: return coop_fn<4, 2>();
-        case 404: return coop_fn<4, 4>();
-        case 405: return coop_fn<4, 5>();
-        case 408: return coop_fn<4, 8>();
-        case 801: return coop_fn<8, 1>();
-        case 802: return coop_fn<8, 2>();
-        case 804: return coop_fn<8, 4>();
-        case 805: return coop_fn<8, 5>();
-        case 808: return coop_fn<8, 8>();
+        case 101: return coop_fn<1, 1>(paged);
+        case 102: return coop_fn<1, 2>(paged);
+        case 104: return coop_fn<1, 4>(paged);
+        case 105: return coop_fn<1, 5>(paged);
+        case 108: return coop_fn<1, 8>(paged);
+        case 116: return coop_fn<1, 16>(paged);
+        case 216: return coop_fn<2, 16>(paged);
+        case 416: return coop_fn<4, 16>(paged);
+        case 201: return coop_fn<2, 1>(paged);
+        case 202: return coop_fn<2, 2>(paged);
+        case 204: return coop_fn<2, 4>(paged);
+        case 205: return coop_fn<2, 5>(paged);
+        case 208: return coop_fn<2, 8>(paged);
+        case 401: return coop_fn<4, 1>(paged);
+        case 402: return coop_fn<4, 2>(paged);
+        case 404: return coop_fn<4, 4>(paged);
+        case 405: return coop_fn<4, 5>(paged);
+        case 408: return coop_fn<4, 8>(paged);
+        case 801: return coop_fn<8, 1>(paged);
+        case 802: return coop_fn<8, 2>(paged);
+        case 804: return coop_fn<8, 4>(paged);
+        case 805: return coop_fn<8, 5>(paged);
+        case 808: return coop_fn<8, 8>(paged);
         default: return nullptr;
     }
 }
 
 // how many workgroups of this context's cooperative kernel fit on the device at once
-int coop_capacity(const hata_ctx* c) {
-    const void* fn = coop_kernel_for(c->Wd, c->G);
+int coop_capacity(const hata_ctx* c, bool paged) {
+    const void* fn = coop_kernel_for(c->Wd, c->G, paged);
     if (!fn || c->chunk > HATA_COOP_MAX_CHUNK) return 0;
     int per_cu = 0, dev = 0, cus = 0;
     if (hipGetDevice(&dev) != hipSuccess) return 0;
@@ -574,15 +624,17 @@ int coop_capacity(const hata_ctx* c) {
 
 hipError_t launch_coop_step(hata_ctx* c, const void* q, const void* K, const void* V,
                             const float* W_H, uint32_t* codes, int append, const int32_t* seq_len,
-                            const int32_t* k, int B, float sm_scale, void* out, float* out_f32, hipStream_t s) {
+                            const int32_t* k, int B, float sm_scale, void* out, float* out_f32, hipStream_t s,
+                            const PageView* pages) {
     const hata_config& f = c->cfg;
-    const void* fn = coop_kernel_for(c->Wd, c->G);
+    const void* fn = coop_kernel_for(c->Wd, c->G, pages != nullptr);
     if (!fn || c->chunk > HATA_COOP_MAX_CHUNK) return hipErrorNotSupported;
     CoopArgs a;
     a.q = (const uint16_t*)q; a.K = (const uint16_t*)K; a.V = (const uint16_t*)V;
     a.W_H = W_H; a.append = append;
     a.spin_limit = c->spin_limit > 0 ? c->spin_limit : HATA_COOP_SPIN_LIMIT;
     a.keep_scores = c->keep_scores;
+    a.pv = pages ? *pages : PageView{nullptr, 0, 0, 0};
     {
         int dev = 0, cus = 0;
         a.prefetch = 0;

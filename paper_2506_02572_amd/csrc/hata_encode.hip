@@ -236,7 +236,10 @@ __global__ __launch_bounds__(R * 2) void encode_mfma_kernel(
     // fused cache fill (all null otherwise): the keys are read from K_new [B, Hkv, max_new, d] and
     // written to the cache K as they pass through; V_new is copied to V alongside
     const uint16_t* __restrict__ K_new, const uint16_t* __restrict__ V_new,
-    uint16_t* __restrict__ K_out, uint16_t* __restrict__ V_out, int max_new) {
+    uint16_t* __restrict__ K_out, uint16_t* __restrict__ V_out, int max_new,
+    // block table of the destination (fused fill only; null table: contiguous caches).  Paged
+    // pools are [n_pages, Hkv, page_rows, d] / [n_pages, Hkv, page_rows, WD].
+    const PageView pv) {
     constexpr int THREADS = R * 2;
     constexpr int WD = R / 32;
     constexpr int STAGE = R >= 64 ? 128 : 64;              // keys per LDS stage
@@ -248,7 +251,8 @@ __global__ __launch_bounds__(R * 2) void encode_mfma_kernel(
     const int m = lane & 31, half = lane >> 5;
     const int h = blockIdx.y, b = blockIdx.z;
     const int first = start[b];
-    int cnt = min(n_new[b], L_cap - first);
+    const bool paged = pv.table != nullptr;
+    int cnt = min(n_new[b], (paged ? min(L_cap, pv.max_blocks << pv.shift) : L_cap) - first);
     if (K_new != nullptr) cnt = min(cnt, max_new);  // the source holds max_new rows per unit
     const int kb0 = blockIdx.x * keys_per_wg;
     if (first < 0 || kb0 >= cnt) return;
@@ -261,6 +265,12 @@ __global__ __launch_bounds__(R * 2) void encode_mfma_kernel(
     const uint16_t* Vsrc = fill ? V_new + u * (int64_t)max_new * HATA_D : nullptr;
     uint16_t* Kdst = fill ? K_out + b * sb + h * sh + (int64_t)first * sn : nullptr;
     uint16_t* Vdst = fill ? V_out + b * sb + h * sh + (int64_t)first * sn : nullptr;
+    // paged destination: row (first + key) of sequence b -> row of the pools, in rows of one head
+    auto pool_row = [&](int key) -> int64_t {
+        const int n = first + key;
+        const int p = clampi(pv.table[(int64_t)b * pv.max_blocks + (n >> pv.shift)], 0, pv.n_pages - 1);
+        return (((int64_t)p * Hkv + h) << pv.shift) + (n & ((1 << pv.shift) - 1));
+    };
 
     // weight fragments: a[plane][kk] holds W_H[h][kk*16 + 8*half + e][32 w + m], e = 0..7
     bf16x8_t afrag[3][8];
@@ -303,8 +313,14 @@ __global__ __launch_bounds__(R * 2) void encode_mfma_kernel(
                 if (fill) {
                     pre[it] = *reinterpret_cast<const uint4*>(Ksrc + (int64_t)key * HATA_D + lsub * 8);
                     const uint4 vv = *reinterpret_cast<const uint4*>(Vsrc + (int64_t)key * HATA_D + lsub * 8);
-                    *reinterpret_cast<uint4*>(Kdst + (int64_t)key * sn + lsub * 8) = pre[it];
-                    *reinterpret_cast<uint4*>(Vdst + (int64_t)key * sn + lsub * 8) = vv;
+                    if (paged) {
+                        const int64_t o = pool_row(key) * HATA_D + lsub * 8;
+                        *reinterpret_cast<uint4*>(K_out + o) = pre[it];
+                        *reinterpret_cast<uint4*>(V_out + o) = vv;
+                    } else {
+                        *reinterpret_cast<uint4*>(Kdst + (int64_t)key * sn + lsub * 8) = pre[it];
+                        *reinterpret_cast<uint4*>(Vdst + (int64_t)key * sn + lsub * 8) = vv;
+                    }
                 } else {
                     pre[it] = *reinterpret_cast<const uint4*>(Kb + (int64_t)key * sn + lsub * 8);
                 }
@@ -347,7 +363,10 @@ __global__ __launch_bounds__(R * 2) void encode_mfma_kernel(
                 word |= (acc[t][i] >= 0.f ? 1u : 0u) << (8 * (i / 4) + 4 * half + (i % 4));
             word |= (uint32_t)__shfl_xor((int)word, 32, 64);
             const int key = k0 + t * 32 + m;
-            if (half == 0 && key < kb1) cb[(int64_t)key * WD + w] = word;
+            if (half == 0 && key < kb1) {
+                if (paged) codes[pool_row(key) * WD + w] = word;
+                else cb[(int64_t)key * WD + w] = word;
+            }
         }
     }
 }
@@ -385,8 +404,10 @@ hipError_t launch_encode_vectors(const hata_ctx* c, const void* q, uint32_t* qco
 hipError_t launch_encode_bulk(const hata_ctx* c, const void* K, const float* W_H,
                               const int32_t* start, const int32_t* n_new, int B, int max_new,
                               uint32_t* codes, hipStream_t s, const void* K_new, const void* V_new,
-                              void* K_out, void* V_out) {
+                              void* K_out, void* V_out, const PageView* pages) {
     const hata_config& f = c->cfg;
+    const PageView pv = pages ? *pages : PageView{nullptr, 0, 0, 0};
+    if (pages && !K_new) return hipErrorNotSupported;  // the block table addresses the fused fill only
     if (max_new <= 0 || B <= 0) return hipSuccess;
     const uint16_t* kn = (const uint16_t*)K_new;
     const uint16_t* vn = (const uint16_t*)V_new;
@@ -400,19 +421,19 @@ hipError_t launch_encode_bulk(const hata_ctx* c, const void* K, const float* W_H
         if (f.r == 32)
             hipLaunchKernelGGL((encode_mfma_kernel<32>), grid, dim3(64), 0, s, (const uint16_t*)K,
                                W_H, start, n_new, codes, f.Hkv, f.L_cap, kpw, f.kv_stride_b,
-                               f.kv_stride_h, f.kv_stride_n, kn, vn, ko, vo, max_new);
+                               f.kv_stride_h, f.kv_stride_n, kn, vn, ko, vo, max_new, pv);
         else if (f.r == 64)
             hipLaunchKernelGGL((encode_mfma_kernel<64>), grid, dim3(128), 0, s, (const uint16_t*)K,
                                W_H, start, n_new, codes, f.Hkv, f.L_cap, kpw, f.kv_stride_b,
-                               f.kv_stride_h, f.kv_stride_n, kn, vn, ko, vo, max_new);
+                               f.kv_stride_h, f.kv_stride_n, kn, vn, ko, vo, max_new, pv);
         else if (f.r == 128)
             hipLaunchKernelGGL((encode_mfma_kernel<128>), grid, dim3(256), 0, s, (const uint16_t*)K,
                                W_H, start, n_new, codes, f.Hkv, f.L_cap, kpw, f.kv_stride_b,
-                               f.kv_stride_h, f.kv_stride_n, kn, vn, ko, vo, max_new);
+                               f.kv_stride_h, f.kv_stride_n, kn, vn, ko, vo, max_new, pv);
         else
             hipLaunchKernelGGL((encode_mfma_kernel<256>), grid, dim3(512), 0, s, (const uint16_t*)K,
                                W_H, start, n_new, codes, f.Hkv, f.L_cap, kpw, f.kv_stride_b,
-                               f.kv_stride_h, f.kv_stride_n, kn, vn, ko, vo, max_new);
+                               f.kv_stride_h, f.kv_stride_n, kn, vn, ko, vo, max_new, pv);
         return hipGetLastError();
     }
     if (kn) return hipErrorNotSupported;  // the fused cache fill exists for the MFMA widths only

@@ -36,10 +36,20 @@ struct hata_ctx {
     int keep_scores;         // single-launch step also writes the score array
     int step_mode;           // 0 = single launch when it fits, 3 = always three launches
     int coop_capacity;       // workgroups of the cooperative kernel that can be resident at once (0 = unusable)
+    int coop_capacity_paged; // the same for the block-table variant of that kernel
     float* partials;       // [B_max*Hq, max(sparse_splits, dense_splits), d + 2]
 };
 
 namespace hata {
+
+// Block table of a paged cache (table == nullptr: the contiguous layout).  Page p of the pools
+// holds 1 << shift rows of every KV head -- K, V [n_pages, Hkv, page_rows, d], codes [n_pages,
+// Hkv, page_rows, Wd] -- and row n of sequence b lives in page table[b * max_blocks + (n >> shift)]
+// at row n & (page_rows - 1).  Device code clamps the page numbers it reads to [0, n_pages).
+struct PageView {
+    const int32_t* table;
+    int max_blocks, shift, n_pages;
+};
 
 // every launcher returns hipGetLastError() of its launches
 hipError_t launch_encode_vectors(const hata_ctx* c, const void* q, uint32_t* qcodes,
@@ -51,7 +61,8 @@ hipError_t launch_encode_vectors(const hata_ctx* c, const void* q, uint32_t* qco
 hipError_t launch_encode_bulk(const hata_ctx* c, const void* K, const float* W_H,
                               const int32_t* start, const int32_t* n_new, int B, int max_new,
                               uint32_t* codes, hipStream_t s, const void* K_new = nullptr,
-                              const void* V_new = nullptr, void* K_out = nullptr, void* V_out = nullptr);
+                              const void* V_new = nullptr, void* K_out = nullptr, void* V_out = nullptr,
+                              const PageView* pages = nullptr);
 hipError_t launch_score(const hata_ctx* c, const uint32_t* qcodes, const uint32_t* codes,
                         const int32_t* seq_len, int B, uint16_t* scores, const int32_t* kbud,
                         hipStream_t s);
@@ -67,7 +78,8 @@ hipError_t launch_attention(const hata_ctx* c, int mode, const void* q, const vo
 // this shape has no cooperative kernel
 hipError_t launch_coop_step(hata_ctx* c, const void* q, const void* K, const void* V,
                             const float* W_H, uint32_t* codes, int append, const int32_t* seq_len,
-                            const int32_t* k, int B, float sm_scale, void* out, float* out_f32, hipStream_t s);
-int coop_capacity(const hata_ctx* c);
+                            const int32_t* k, int B, float sm_scale, void* out, float* out_f32, hipStream_t s,
+                            const PageView* pages = nullptr);
+int coop_capacity(const hata_ctx* c, bool paged);
 
 }  // namespace hata

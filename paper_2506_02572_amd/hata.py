@@ -16,8 +16,8 @@ LIB_PATH = os.path.join(_HERE, "libhata.so")
 
 EXPORTS = (
     "hata_strerror", "hata_workspace_bytes", "hata_create", "hata_destroy", "hata_encode_keys",
-    "hata_prefill_write", "hata_encode_query", "hata_hamming_score", "hata_topk", "hata_sparse_decode",
-    "hata_dense_decode", "hata_decode_step", "hata_step_plan", "hata_set_step_mode", "hata_keep_step_scores", "hata_set_wait_limit",
+    "hata_prefill_write", "hata_prefill_write_paged", "hata_encode_query", "hata_hamming_score", "hata_topk", "hata_sparse_decode",
+    "hata_dense_decode", "hata_decode_step", "hata_decode_step_paged", "hata_step_plan", "hata_set_step_mode", "hata_keep_step_scores", "hata_set_wait_limit",
     "hata_check",
     "hata_host_device_pointer", "hata_step_buffers",
 )
@@ -63,6 +63,8 @@ def load_library(build_if_missing: bool = True) -> ctypes.CDLL:
     lib.hata_destroy.argtypes = [_vp]
     lib.hata_encode_keys.argtypes = [_vp, _vp, _vp, _vp, _vp, _i32, _i32, _vp, _vp]
     lib.hata_prefill_write.argtypes = [_vp, _vp, _vp, _vp, _vp, _i32, _i32, _vp, _vp, _vp, _vp, _vp]
+    lib.hata_prefill_write_paged.argtypes = [_vp, _vp, _vp, _vp, _vp, _i32, _i32, _vp, _vp, _vp, _vp, _i32,
+                                             _i32, _i32, _vp, _vp]
     lib.hata_encode_query.argtypes = [_vp, _vp, _vp, _i32, _vp, _vp]
     lib.hata_hamming_score.argtypes = [_vp, _vp, _vp, _vp, _i32, _vp, _vp]
     lib.hata_topk.argtypes = [_vp, _vp, _vp, _vp, _i32, _vp, _vp]
@@ -70,6 +72,8 @@ def load_library(build_if_missing: bool = True) -> ctypes.CDLL:
     lib.hata_dense_decode.argtypes = [_vp, _vp, _vp, _vp, _vp, _i32, ctypes.c_float, _vp, _vp, _vp]
     lib.hata_decode_step.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32,
                                      ctypes.c_float, _vp, _vp, _vp]
+    lib.hata_decode_step_paged.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _vp, _vp,
+                                           _i32, _i32, ctypes.c_float, _vp, _vp, _vp]
     lib.hata_step_plan.argtypes = [_vp, _i32, ctypes.POINTER(_i32), ctypes.POINTER(_i32), ctypes.POINTER(_i32)]
     lib.hata_set_step_mode.argtypes = [_vp, _i32]
     lib.hata_keep_step_scores.argtypes = [_vp, _i32]
@@ -172,6 +176,13 @@ class Context:
                                                  B, max_new, _ptr(K), _ptr(V), _ptr(codes), _ptr(W_H),
                                                  _stream(stream)), "hata_prefill_write")
 
+    def hata_prefill_write_paged(self, K_new, V_new, start, n_new, B, max_new, K_pool, V_pool, codes_pool,
+                                 block_table, max_blocks, page_rows, n_pages, W_H, stream=None):
+        _check(load_library().hata_prefill_write_paged(
+            self._h, _ptr(K_new), _ptr(V_new), _ptr(start), _ptr(n_new), B, max_new, _ptr(K_pool),
+            _ptr(V_pool), _ptr(codes_pool), _ptr(block_table), max_blocks, page_rows, n_pages, _ptr(W_H),
+            _stream(stream)), "hata_prefill_write_paged")
+
     def hata_encode_query(self, q, W_H, B, qcodes, stream=None):
         _check(load_library().hata_encode_query(self._h, _ptr(q), _ptr(W_H), B, _ptr(qcodes),
                                                 _stream(stream)), "hata_encode_query")
@@ -200,6 +211,14 @@ class Context:
                                                _ptr(codes), _ptr(seq_len), _ptr(k), B,
                                                1 if append else 0, sm_scale, _ptr(out),
                                                _ptr(out_f32), _stream(stream)), "hata_decode_step")
+
+    def hata_decode_step_paged(self, q, K_pool, V_pool, W_H, codes_pool, block_table, max_blocks,
+                               page_rows, n_pages, seq_len, k, B, append, sm_scale, out, out_f32=None,
+                               stream=None):
+        _check(load_library().hata_decode_step_paged(
+            self._h, _ptr(q), _ptr(K_pool), _ptr(V_pool), _ptr(W_H), _ptr(codes_pool), _ptr(block_table),
+            max_blocks, page_rows, n_pages, _ptr(seq_len), _ptr(k), B, 1 if append else 0, sm_scale,
+            _ptr(out), _ptr(out_f32), _stream(stream)), "hata_decode_step_paged")
 
     def hata_step_plan(self, B):
         """(n_launches, chunk, n_chunks) of hata_decode_step for a batch of B sequences."""
