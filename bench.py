@@ -52,6 +52,10 @@ def parse():
                     help="offloading variant (Sec. 5.3 of the paper): K and V in pinned host memory, hash "
                          "codes on the GPU; the selected rows are gathered over the bus")
     ap.add_argument("--no-train", action="store_true", help="skip the learning-to-hash training-step leg")
+    ap.add_argument("--graph-layers", type=int, default=32, metavar="N",
+                    help="also time N consecutive layer steps captured in ONE HIP graph (a token's pass "
+                         "through N attention layers): all hash-aware, and with the first two layers dense "
+                         "(the paper keeps them dense, Sec. 5.1); 0 skips the leg")
     ap.add_argument("--paged", type=int, default=0, metavar="PAGE_ROWS",
                     help="also time the step on the paged (block-table) layout: the caches are re-laid as "
                          "pools of PAGE_ROWS-row pages in a random page order (needs L_cap %% PAGE_ROWS == 0)")
@@ -214,6 +218,41 @@ def main():
     us_step = ms_step * 1e3
     n_launches, plan_chunk, plan_n_chunks = ctx.hata_step_plan(w.B)
 
+    # ---- N layer steps in one HIP graph (launch gaps out of the way), with and without the dense first layers
+    graph_leg = None
+    if args.graph_layers > 0 and not args.kv_host:
+        NL = args.graph_layers
+
+        def enqueue(dense_first):
+            for i in range(NL):
+                l = i % n_layers
+                if i < dense_first:
+                    ctx.hata_dense_decode(q_steps[0], K_all[l], V_all[l], seq_steps[0], w.B, scale, out, out32)
+                else:
+                    ctx.hata_decode_step(q_steps[0], K_all[l], V_all[l], W_H, codes_all[l], seq_steps[0], kbud,
+                                         w.B, True, scale, out, out32)
+
+        side = torch.cuda.Stream()
+        side.wait_stream(stream)
+        with torch.cuda.stream(side):
+            enqueue(2)  # warm-up on a side stream before the capture
+        stream.wait_stream(side)
+        torch.cuda.synchronize()
+        graphs = {}
+        for name, dense_first in (("hata_all_layers", 0), ("first_two_dense", 2)):
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g):
+                enqueue(dense_first)
+            graphs[name] = g
+        reps = max(10, args.steps // NL)
+        graph_leg = {"layers": NL, "replays": reps}
+        for name, g in graphs.items():
+            ms_g, _ = timed(lambda i: g.replay(), reps, 2)
+            graph_leg[name + "_us_per_replay"] = round(ms_g * 1e3, 1)
+            graph_leg[name + "_us_per_layer"] = round(ms_g * 1e3 / NL, 3)
+        ctx.hata_check(stream)
+        del graphs
+
     # ---- the scoring stage alone (the largest stream of bytes of the step)
     qcodes_buf, scores_buf, _ = ctx.hata_step_buffers()
 
@@ -375,6 +414,7 @@ def main():
                              "TFLOPs": round(enc_flop / (enc_ms * 1e-3) / 1e12, 2)},
         "prefill_write": fill_leg,
         "paged_step": paged_leg,
+        "graph_of_layers": graph_leg,
         "dense_decode_us": None if dense_us is None else round(dense_us, 2),
         "speedup_vs_dense": None if dense_us is None else round(dense_us / us_step, 2),
         "train_step": train_leg,
