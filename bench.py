@@ -8,7 +8,10 @@ synthetic, resident in HBM before the timed region.  Consecutive steps rotate ov
 distinct copies ("layers") of the K/V/code caches so that the traffic is HBM traffic and
 not Infinity-Cache hits, as a model with tens of layers does for every token.
 
-Prints ONE JSON line.
+Prints ONE JSON line.  Beside the step itself it carries separately timed legs of the same
+library: the scoring stage alone, the prefill key encode and the fused prefill cache fill, dense
+attention (the comparison baseline), 32 layer steps replayed from one HIP graph, the step on the
+paged cache layout (--paged), the learning-to-hash training step, and the CPU oracle.
 """
 from __future__ import annotations
 
