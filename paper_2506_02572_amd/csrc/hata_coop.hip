@@ -491,13 +491,23 @@ __global__ __launch_bounds__(256, (G >= 16 ? 2 : 3)) void decode_step_coop_kerne
                 sv[4 * i4 + 0] = sv[4 * i4 + 1] = sv[4 * i4 + 2] = sv[4 * i4 + 3] = 0xffffffffu;
             }
         }
-        uint32_t lt = 0, eq = 0;
+        // bit i of m_lt / m_eq: key i of this thread is live and scores below / exactly the threshold
+        const int nlive = clampi(end - base - n_first, 0, kpt);
+        const uint32_t live = (1u << nlive) - 1u;  // (nlive <= 16)
+        uint32_t m_lt = 0, m_eq = 0;
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            const bool live = i < kpt && base + n_first + i < end;
-            lt += (live && (int)sv[i] < T) ? 1u : 0u;
-            eq += (live && (int)sv[i] == T) ? 1u : 0u;
+        for (int i4 = 0; i4 < 4; ++i4) {
+            if (i4 * 4 < kpt) {
+#pragma unroll
+                for (int i = 4 * i4; i < 4 * i4 + 4; ++i) {
+                    m_lt |= ((int)sv[i] < T ? 1u : 0u) << i;
+                    m_eq |= ((int)sv[i] == T ? 1u : 0u) << i;
+                }
+            }
         }
+        m_lt &= live;
+        m_eq &= live;
+        const uint32_t lt = __popc(m_lt), eq = __popc(m_eq);
         // block-wide exclusive scan of (lt, eq) with ONE barrier, which also marks the point where
         // every thread has read its scores, so that s_sc can become the row list
         const uint32_t mine = lt | (eq << 16);
@@ -506,25 +516,22 @@ __global__ __launch_bounds__(256, (G >= 16 ? 2 : 3)) void decode_step_coop_kerne
         __syncthreads();
         const int wv = tid >> 6;
         const uint32_t before = (wv > 0 ? scan4[0] : 0u) + (wv > 1 ? scan4[1] : 0u) + (wv > 2 ? scan4[2] : 0u) + incl - mine;
-        uint32_t lt_b = before & 0xffffu, eq_b = before >> 16;
-        // which of this thread's keys are selected
-        uint32_t sel_mask = 0;  // bit i: key i of this thread is selected
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            const bool live = i < kpt && base + n_first + i < end;
-            if (live && (int)sv[i] < T) sel_mask |= 1u << i;
-            else if (live && (int)sv[i] == T) { if (eq_b < (uint32_t)take) sel_mask |= 1u << i; ++eq_b; }
-        }
-        eq_b = before >> 16;
-        uint32_t r = lt_b + min(eq_b, (uint32_t)take);  // local rank of the thread's first selected key
-        for (int i = 0; i < kpt; ++i) {
-            if (sel_mask & (1u << i)) {
-                if (r < (uint32_t)cnt) {
-                    s_sc[r] = (uint16_t)(n_first + i);
-                    io[off + r] = base + n_first + i;
-                }
-                ++r;
+        const uint32_t lt_b = before & 0xffffu, eq_b = before >> 16;
+        // ties go to the lowest rows: this thread keeps the first `avail` of its keys at the threshold
+        const uint32_t ties_before = min(eq_b, (uint32_t)take);  // ties taken by the threads before this one
+        const uint32_t avail = min(eq, (uint32_t)take - ties_before);
+        uint32_t keep = m_eq;
+        while ((uint32_t)__popc(keep) > avail) keep &= ~(0x80000000u >> __clz(keep));  // drop the highest row
+        uint32_t sel = m_lt | keep;
+        uint32_t r = lt_b + ties_before;  // local rank of the thread's first selected key
+        while (sel) {  // (a thread holds k / L of its keys on average: mostly zero or one turn)
+            const int i = __ffs(sel) - 1;
+            sel &= sel - 1;
+            if (r < (uint32_t)cnt) {
+                s_sc[r] = (uint16_t)(n_first + i);
+                io[off + r] = base + n_first + i;
             }
+            ++r;
         }
     }
     __syncthreads();
