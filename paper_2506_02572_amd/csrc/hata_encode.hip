@@ -227,7 +227,7 @@ typedef __attribute__((ext_vector_type(16))) float f32x16_t;
 
 __device__ __forceinline__ uint32_t bf16_rne_bits(float f) { return f32_to_bf16(f); }
 
-template <int R>
+template <int R, bool PAGED>
 __global__ __launch_bounds__(R * 2) void encode_mfma_kernel(
     const uint16_t* __restrict__ K, const float* __restrict__ W_H,
     const int32_t* __restrict__ start, const int32_t* __restrict__ n_new,
@@ -237,8 +237,8 @@ __global__ __launch_bounds__(R * 2) void encode_mfma_kernel(
     // written to the cache K as they pass through; V_new is copied to V alongside
     const uint16_t* __restrict__ K_new, const uint16_t* __restrict__ V_new,
     uint16_t* __restrict__ K_out, uint16_t* __restrict__ V_out, int max_new,
-    // block table of the destination (fused fill only; null table: contiguous caches).  Paged
-    // pools are [n_pages, Hkv, page_rows, d] / [n_pages, Hkv, page_rows, WD].
+    // block table of the destination (PAGED instantiation, fused fill only).  Paged pools are
+    // [n_pages, Hkv, page_rows, d] / [n_pages, Hkv, page_rows, WD].
     const PageView pv) {
     constexpr int THREADS = R * 2;
     constexpr int WD = R / 32;
@@ -251,7 +251,7 @@ __global__ __launch_bounds__(R * 2) void encode_mfma_kernel(
     const int m = lane & 31, half = lane >> 5;
     const int h = blockIdx.y, b = blockIdx.z;
     const int first = start[b];
-    const bool paged = pv.table != nullptr;
+    constexpr bool paged = PAGED;
     int cnt = min(n_new[b], (paged ? min(L_cap, pv.max_blocks << pv.shift) : L_cap) - first);
     if (K_new != nullptr) cnt = min(cnt, max_new);  // the source holds max_new rows per unit
     const int kb0 = blockIdx.x * keys_per_wg;
@@ -313,7 +313,7 @@ __global__ __launch_bounds__(R * 2) void encode_mfma_kernel(
                 if (fill) {
                     pre[it] = *reinterpret_cast<const uint4*>(Ksrc + (int64_t)key * HATA_D + lsub * 8);
                     const uint4 vv = *reinterpret_cast<const uint4*>(Vsrc + (int64_t)key * HATA_D + lsub * 8);
-                    if (paged) {
+                    if constexpr (paged) {
                         const int64_t o = pool_row(key) * HATA_D + lsub * 8;
                         *reinterpret_cast<uint4*>(K_out + o) = pre[it];
                         *reinterpret_cast<uint4*>(V_out + o) = vv;
@@ -364,7 +364,7 @@ __global__ __launch_bounds__(R * 2) void encode_mfma_kernel(
             word |= (uint32_t)__shfl_xor((int)word, 32, 64);
             const int key = k0 + t * 32 + m;
             if (half == 0 && key < kb1) {
-                if (paged) codes[pool_row(key) * WD + w] = word;
+                if constexpr (paged) codes[pool_row(key) * WD + w] = word;
                 else cb[(int64_t)key * WD + w] = word;
             }
         }
@@ -418,22 +418,22 @@ hipError_t launch_encode_bulk(const hata_ctx* c, const void* K, const float* W_H
         int kpw = 4096;
         while (kpw > 512 && (int64_t)((max_new + kpw - 1) / kpw) * f.Hkv * B < 512) kpw >>= 1;
         const dim3 grid((max_new + kpw - 1) / kpw, f.Hkv, B);
-        if (f.r == 32)
-            hipLaunchKernelGGL((encode_mfma_kernel<32>), grid, dim3(64), 0, s, (const uint16_t*)K,
-                               W_H, start, n_new, codes, f.Hkv, f.L_cap, kpw, f.kv_stride_b,
-                               f.kv_stride_h, f.kv_stride_n, kn, vn, ko, vo, max_new, pv);
-        else if (f.r == 64)
-            hipLaunchKernelGGL((encode_mfma_kernel<64>), grid, dim3(128), 0, s, (const uint16_t*)K,
-                               W_H, start, n_new, codes, f.Hkv, f.L_cap, kpw, f.kv_stride_b,
-                               f.kv_stride_h, f.kv_stride_n, kn, vn, ko, vo, max_new, pv);
-        else if (f.r == 128)
-            hipLaunchKernelGGL((encode_mfma_kernel<128>), grid, dim3(256), 0, s, (const uint16_t*)K,
-                               W_H, start, n_new, codes, f.Hkv, f.L_cap, kpw, f.kv_stride_b,
-                               f.kv_stride_h, f.kv_stride_n, kn, vn, ko, vo, max_new, pv);
-        else
-            hipLaunchKernelGGL((encode_mfma_kernel<256>), grid, dim3(512), 0, s, (const uint16_t*)K,
-                               W_H, start, n_new, codes, f.Hkv, f.L_cap, kpw, f.kv_stride_b,
-                               f.kv_stride_h, f.kv_stride_n, kn, vn, ko, vo, max_new, pv);
+#define HATA_LAUNCH_MFMA(R_, P_)                                                                        \
+    hipLaunchKernelGGL((encode_mfma_kernel<R_, P_>), grid, dim3(R_ * 2), 0, s, (const uint16_t*)K, W_H, \
+                       start, n_new, codes, f.Hkv, f.L_cap, kpw, f.kv_stride_b, f.kv_stride_h,          \
+                       f.kv_stride_n, kn, vn, ko, vo, max_new, pv)
+        if (pages) {
+            if (f.r == 32) HATA_LAUNCH_MFMA(32, true);
+            else if (f.r == 64) HATA_LAUNCH_MFMA(64, true);
+            else if (f.r == 128) HATA_LAUNCH_MFMA(128, true);
+            else HATA_LAUNCH_MFMA(256, true);
+        } else {
+            if (f.r == 32) HATA_LAUNCH_MFMA(32, false);
+            else if (f.r == 64) HATA_LAUNCH_MFMA(64, false);
+            else if (f.r == 128) HATA_LAUNCH_MFMA(128, false);
+            else HATA_LAUNCH_MFMA(256, false);
+        }
+#undef HATA_LAUNCH_MFMA
         return hipGetLastError();
     }
     if (kn) return hipErrorNotSupported;  // the fused cache fill exists for the MFMA widths only
