@@ -213,3 +213,64 @@ def test_paged_arguments_are_validated(torch_mod):
         ctx96.hata_decode_step_paged(*args(256, 4, 4))
     ctx.close()
     ctx96.close()
+
+
+def test_two_sequences_share_the_pages_of_a_common_prefix(torch_mod):
+    """Prefix sharing: the block tables of two sequences name the SAME pages for their first rows
+    (read-only), each has private pages after that, and each appends into a private page.  Both
+    must equal the oracle run on the logical caches."""
+    torch = torch_mod
+    page_rows, shared_blocks = 256, 9
+    w = synth.Workload("prefix", 2, 8, 2, 128, 128, (4000, 3100), (160, 96), 4, 8.0, L_cap=4096)
+    c = H.Case(w, seed=53, oracle_codes=False)
+    B, Hkv, d = w.B, w.Hkv, w.d
+    seq = c.inp.seq_len
+    # logical caches: sequence 1 starts with the first shared_blocks * page_rows rows of sequence 0
+    Kl, Vl = c.inp.K.copy(), c.inp.V.copy()
+    n_shared = shared_blocks * page_rows
+    Kl[1, :, :n_shared] = Kl[0, :, :n_shared]
+    Vl[1, :, :n_shared] = Vl[0, :, :n_shared]
+    codes_h, _ = O.encode_keys_batch(Kl, c.inp.W_H, np.zeros(B, np.int32), seq)
+    for b in range(B):
+        codes_h[b, :, int(seq[b]) - 1:] = 0xDEADBEEF  # row L-1 is appended by the step
+    codes_before = codes_h.copy()
+    q = c.inp.q(4)
+    ref = O.decode_step(q, Kl, Vl, c.inp.W_H, codes_h, seq, c.inp.k, w.k_max, c.scale, append=True)
+    # pages: shared prefix pages, then private ones
+    blocks = [(int(L) + page_rows - 1) // page_rows for L in seq]
+    n_pages = blocks[0] + (blocks[1] - shared_blocks) + 3
+    rng = np.random.default_rng(5)
+    perm = rng.permutation(n_pages)
+    max_blocks = max(blocks)
+    table = np.full((B, max_blocks), -7, np.int32)
+    table[0, :blocks[0]] = perm[:blocks[0]]
+    table[1, :shared_blocks] = table[0, :shared_blocks]
+    table[1, shared_blocks:blocks[1]] = perm[blocks[0]:blocks[0] + blocks[1] - shared_blocks]
+    assert blocks[0] - 1 >= shared_blocks and blocks[1] - 1 >= shared_blocks  # the appended rows sit in private pages
+    K_pool = np.full((n_pages, Hkv, page_rows, d), JUNK16, np.uint16)
+    V_pool = np.full((n_pages, Hkv, page_rows, d), JUNK16, np.uint16)
+    C_pool = np.full((n_pages, Hkv, page_rows, w.W), JUNK32, np.uint32)
+    Kx, Vx, Cx = Kl.copy(), Vl.copy(), codes_before.copy()
+    for b in range(B):
+        Kx[b, :, int(seq[b]):] = JUNK16
+        Vx[b, :, int(seq[b]):] = JUNK16
+        Cx[b, :, int(seq[b]):] = JUNK32
+    for b in (1, 0):  # (sequence 0 last: it owns the shared pages in full)
+        for pool, logical in ((K_pool, Kx), (V_pool, Vx), (C_pool, Cx)):
+            scatter(pool, logical[b:b + 1], table[b:b + 1], blocks[b:b + 1], page_rows, seq[b:b + 1])
+    Kd, Vd, Cd, Td = H.to_dev(K_pool), H.to_dev(V_pool), H.to_dev(C_pool), H.to_dev(table)
+    out = c.empty((B, w.Hq, d), torch.int16)
+    out32 = c.empty((B, w.Hq, d), torch.float32)
+    c.ctx.hata_decode_step_paged(H.to_dev(q), Kd, Vd, c.W_H, Cd, Td, max_blocks, page_rows, n_pages, c.seq_len,
+                                 c.k, B, True, c.scale, out, out32)
+    c.ctx.hata_check()
+    _, _, ix = c.ctx.hata_step_buffers()
+    assert np.array_equal(H.to_host(ix), ref["idx"])
+    H.check_attention(H.to_host(out32), H.to_host(out, np.uint16), ref["out"], "prefix-shared pages")
+    got = gather(H.to_host(Cd, np.uint32), table[0:1], blocks[0:1], page_rows, (1, Hkv, w.L_cap, w.W), JUNK32)
+    L0 = int(seq[0])
+    assert np.array_equal(got[0, :, :L0], codes_h[0, :, :L0])
+    got1 = gather(H.to_host(Cd, np.uint32), table[1:2], blocks[1:2], page_rows, (1, Hkv, w.L_cap, w.W), JUNK32)
+    L1 = int(seq[1])
+    assert np.array_equal(got1[0, :, :L1], codes_h[1, :, :L1])
+    c.ctx.close()
