@@ -95,10 +95,11 @@ int make_plan(const hata_config* f, Plan* p) {
     p->off_hist = o;     o = align_up(o + (size_t)units * p->n_chunks * p->NBP * 2);
     p->off_cinfo = o;    o = align_up(o + (size_t)units * (p->n_chunks + 1) * 2 * 4);
     p->off_uinfo = o;    o = align_up(o + (size_t)units * 2 * 4);
-    p->off_ucnt = o;     o = align_up(o + (size_t)units * 4);
-    p->off_acnt = o;     o = align_up(o + (size_t)f->B_max * f->Hq * 4);
-    p->off_uflag = o;    o = align_up(o + (size_t)units * p->n_chunks * 2 * 8);
-    p->off_qrec = o;     o = align_up(o + (size_t)f->B_max * f->Hq * p->Wd * 8);
+    // (the single-launch step keeps each unit's two arrival counters on a cache line of their own)
+    p->off_ucnt = o;     o = align_up(o + (size_t)units * HATA_COUNTER_STRIDE * 4);
+    p->off_acnt = o;     o = align_up(o + (size_t)f->B_max * f->Hq * HATA_COUNTER_STRIDE * 4);
+    p->off_uflag = o;    o = align_up(o + (size_t)units * p->n_chunks * HATA_REC_STRIDE * 8);
+    p->off_qrec = o;     o = align_up(o + (size_t)f->B_max * f->Hq * p->Wd * p->n_chunks * 8);
     p->off_err = o;      o = align_up(o + 4);
     p->off_uhist = o;    o = align_up(o + (size_t)units * p->NB * 4);
     p->off_partials = o; o = align_up(o + (size_t)f->B_max * f->Hq * max_splits * (128 + 2) * 4);

@@ -292,7 +292,10 @@ __global__ __launch_bounds__(256, (G >= 16 ? 2 : 3)) void decode_step_coop_kerne
         }
     };
     {
-        unsigned long long* qrec = a.qrec + ((int64_t)b * a.Hq + hq0) * WD;
+        // every chunk of the unit has its own copy of the G * WD published words (the encoders write
+        // all copies, a workgroup polls -- and afterwards clears -- only its own)
+        unsigned long long* qrec_u = a.qrec + u * a.n_chunks * (G * WD);
+        unsigned long long* qrec = qrec_u + c * (G * WD);
         if (tid < (G + 1) * WD) s_codes[tid] = 0;
         if (tid == 0) s_low = a.NB;
         for (int i = tid; i < a.NB; i += 256) hist[i] = 0;
@@ -307,9 +310,9 @@ __global__ __launch_bounds__(256, (G >= 16 ? 2 : 3)) void decode_step_coop_kerne
             if (!EARLY || v != c) coop_encode_load<WD>(Wh, qv + v * HATA_D, el);
             coop_encode_vec<WD>(Wh, el, &s_codes[v * WD]);
             __syncthreads();
-            if (tid < WD)
-                __hip_atomic_store(qrec + v * WD + tid,
-                                   ((unsigned long long)a.epoch << 32) | s_codes[v * WD + tid],
+            for (int i = tid; i < WD * max(nc, 1); i += 256)
+                __hip_atomic_store(qrec_u + (i / WD) * (G * WD) + v * WD + i % WD,
+                                   ((unsigned long long)a.epoch << 32) | s_codes[v * WD + i % WD],
                                    __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
         if (own) {
@@ -335,7 +338,12 @@ __global__ __launch_bounds__(256, (G >= 16 ? 2 : 3)) void decode_step_coop_kerne
                 if (--budget <= 0) { if (tid == 0) a.error_word[0] = 1u; break; }  // gave up: results invalid
                 __builtin_amdgcn_s_sleep(1);
             }
-            if (tid < G * WD) s_codes[tid] = (uint32_t)r;
+            if (tid < G * WD) {
+                s_codes[tid] = (uint32_t)r;
+                // retired at once: a later launch that carries the SAME epoch (a replay of a captured
+                // HIP graph freezes the kernel arguments) must not mistake these words for its own
+                qrec[tid] = 0ull;
+            }
         }
         __syncthreads();
     }
@@ -348,8 +356,6 @@ __global__ __launch_bounds__(256, (G >= 16 ? 2 : 3)) void decode_step_coop_kerne
             if (outp32) outp32[i] = 0.f;
         }
         for (int p = tid; p < a.k_max; p += 256) a.idx[u * a.k_max + p] = -1;
-        // (this workgroup is the unit's only one: it retires the query code words it published)
-        for (int i = tid; i < G * WD; i += 256) a.qrec[((int64_t)b * a.Hq + hq0) * WD + i] = 0ull;
         return;
     }
     TC(50);
@@ -429,14 +435,14 @@ __global__ __launch_bounds__(256, (G >= 16 ? 2 : 3)) void decode_step_coop_kerne
     __syncthreads();
     TC(43);
     if (tid == 0) {
-        const uint32_t done = atomicAdd(&a.unit_counter[u], 1u);
+        const uint32_t done = atomicAdd(&a.unit_counter[u * HATA_COUNTER_STRIDE], 1u);
         const int last = (done == (uint32_t)(nc - 1));
-        if (last) a.unit_counter[u] = 0;
+        if (last) a.unit_counter[u * HATA_COUNTER_STRIDE] = 0;
         s_flag = last;
     }
     __syncthreads();
     int32_t* ci_u = a.chunk_info + u * (a.n_chunks + 1) * 2;
-    unsigned long long* rec_u = a.rec + u * a.n_chunks * 2;
+    unsigned long long* rec_u = a.rec + u * a.n_chunks * HATA_REC_STRIDE;
     TC(44);
     // query fragments for the attention: in flight across the wait below
     uint32_t qr[MFMA ? 1 : G][4];
@@ -456,14 +462,17 @@ __global__ __launch_bounds__(256, (G >= 16 ? 2 : 3)) void decode_step_coop_kerne
         int budget = a.spin_limit;
         unsigned long long r0, r1;
         for (;;) {
-            r0 = __hip_atomic_load(rec_u + 2 * c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            r1 = __hip_atomic_load(rec_u + 2 * c + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            r0 = __hip_atomic_load(rec_u + HATA_REC_STRIDE * c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            r1 = __hip_atomic_load(rec_u + HATA_REC_STRIDE * c + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             if (((uint32_t)(r0 >> 32) == a.epoch && (uint32_t)(r1 >> 32) == a.epoch) || --budget <= 0) break;
             __builtin_amdgcn_s_sleep(1);
         }
         if (budget <= 0) { a.error_word[0] = 1u; r0 = 0; r1 = 0; }  // gave up: this launch's results are invalid
         s_rec[0] = (uint32_t)r0;
         s_rec[1] = (uint32_t)r1;
+        // this workgroup is the record's only reader: retired at once (see the query code words above)
+        rec_u[HATA_REC_STRIDE * c] = 0ull;
+        rec_u[HATA_REC_STRIDE * c + 1] = 0ull;
     }
     __syncthreads();
     TC(45);
@@ -553,21 +562,12 @@ __global__ __launch_bounds__(256, (G >= 16 ? 2 : 3)) void decode_step_coop_kerne
     const int64_t head_stride = (int64_t)a.n_chunks * HATA_PSTRIDE;
     float* part0 = a.partials + ((int64_t)b * a.Hq + hq0) * head_stride;
     attn_emit<G>(S, nc == 1, outp, outp32, part0 + (int64_t)c * HATA_PSTRIDE, head_stride);
-    // The workgroup that finishes the unit retires the unit's published words (query code words,
-    // chunk records): every workgroup of the unit has consumed them by now.  A later launch that
-    // carries the SAME epoch -- a replay of a captured HIP graph freezes the kernel arguments --
-    // therefore never mistakes this launch's words for its own.
-    auto retire_records = [&]() {
-        unsigned long long* qrec = a.qrec + ((int64_t)b * a.Hq + hq0) * WD;
-        for (int i = tid; i < 2 * nc; i += 256) rec_u[i] = 0ull;
-        for (int i = tid; i < G * WD; i += 256) qrec[i] = 0ull;
-    };
-    if (nc == 1) { retire_records(); return; }
+    if (nc == 1) return;
     TC(48);
     wait_stores();
     __syncthreads();
     if (tid == 0) {
-        uint32_t* cntp = a.attn_counter + u;
+        uint32_t* cntp = a.attn_counter + u * HATA_COUNTER_STRIDE;
         const uint32_t done = atomicAdd(cntp, 1u);
         const int last = (done == (uint32_t)(nc - 1));
         if (last) *cntp = 0;
@@ -577,7 +577,6 @@ __global__ __launch_bounds__(256, (G >= 16 ? 2 : 3)) void decode_step_coop_kerne
     TC(49);
     if (!s_flag) return;
     TU(53);
-    retire_records();  // (before the merge: the stores complete while the partials are being fetched)
     attn_merge<G>(S, part0, head_stride, nc, outp, outp32);
     TU(54);
 #undef TC

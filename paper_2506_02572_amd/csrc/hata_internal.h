@@ -5,6 +5,14 @@
 
 #include "../../include/hata.h"
 
+// Words between the arrival counters of consecutive units in the single-launch step (128 bytes:
+// the workgroups of different units then never queue their arrivals on one cache line).  The
+// three-launch kernels index the same arrays densely.
+#define HATA_COUNTER_STRIDE 32
+// 64-bit words between the records of consecutive chunks (two are used): a cache line per chunk, so
+// that the workgroups polling for their records do not all read the same lines
+#define HATA_REC_STRIDE 8
+
 struct hata_ctx {
     hata_config cfg;
     int G;            // query heads per KV head
@@ -25,11 +33,11 @@ struct hata_ctx {
     uint16_t* chunk_hist;  // [B_max*Hkv, n_chunks, NBP]
     int32_t* chunk_info;   // [B_max*Hkv, n_chunks + 1, 2] = {output offset, ties taken}
     int32_t* unit_info;    // [B_max*Hkv, 2] = {threshold, selected count}
-    uint32_t* unit_counter;  // [B_max*Hkv] scored chunks of a unit (self-resetting)
+    uint32_t* unit_counter;  // [B_max*Hkv (* HATA_COUNTER_STRIDE in the cooperative step)] scored chunks of a unit (self-resetting)
     uint32_t* unit_hist;     // [B_max*Hkv, NB] total histogram of a unit (self-clearing)
-    uint32_t* attn_counter;  // [B_max*Hq] finished attention slices (self-resetting)
-    unsigned long long* coop_rec;  // [B_max*Hkv, n_chunks, 2] epoch-stamped chunk records (cooperative step)
-    unsigned long long* coop_qrec; // [B_max*Hq, Wd] epoch-stamped query code words (cooperative step)
+    uint32_t* attn_counter;  // [B_max*Hq (cooperative step: per unit, HATA_COUNTER_STRIDE apart)] finished attention slices (self-resetting)
+    unsigned long long* coop_rec;  // [B_max*Hkv, n_chunks, HATA_REC_STRIDE] epoch-stamped chunk records, two words used (cooperative step)
+    unsigned long long* coop_qrec; // [B_max*Hkv, n_chunks, G*Wd] epoch-stamped query code words, one copy per chunk (cooperative step)
     uint32_t* error_word;    // [1] set by a cooperative launch that gave up waiting
     uint32_t epoch;          // launch counter of the cooperative step
     int spin_limit;          // polls an in-kernel wait makes before it gives up (0 = the default)

@@ -8,6 +8,7 @@
 // and the index list comes out ascending.  No atomic decides an output position.
 #pragma once
 #include "hata_device.h"
+#include "hata_internal.h"
 #include "hata_trace.h"
 
 namespace hata {
@@ -216,16 +217,17 @@ __device__ __forceinline__ void unit_threshold(
         for (int c = c0; c < c1; ++c) {
             const uint32_t can = (uint32_t)need > eqb ? (uint32_t)need - eqb : 0u;
             const uint32_t take = min(can, S.c_eq[c]);
-            st_dev(reinterpret_cast<uint32_t*>(chunk_info_u) + c * 2 + 0, off);
-            st_dev(reinterpret_cast<uint32_t*>(chunk_info_u) + c * 2 + 1, take);
-            if (rec_u) {
+            if (!rec_u) {  // (the single-launch step reads the records below instead)
+                st_dev(reinterpret_cast<uint32_t*>(chunk_info_u) + c * 2 + 0, off);
+                st_dev(reinterpret_cast<uint32_t*>(chunk_info_u) + c * 2 + 1, take);
+            } else {
                 // two self-validating words per chunk (each carries the launch epoch in its upper
                 // half, so a waiting workgroup needs no separate flag): {off, selected count} and
                 // {ties granted, T}
                 const uint32_t cnt_c = S.c_lt[c] + take;
-                __hip_atomic_store(rec_u + 2 * c, ((unsigned long long)epoch << 32) | (off << 13) | cnt_c,
+                __hip_atomic_store(rec_u + HATA_REC_STRIDE * c, ((unsigned long long)epoch << 32) | (off << 13) | cnt_c,
                                    __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                __hip_atomic_store(rec_u + 2 * c + 1, ((unsigned long long)epoch << 32) | (take << 13) | (uint32_t)T,
+                __hip_atomic_store(rec_u + HATA_REC_STRIDE * c + 1, ((unsigned long long)epoch << 32) | (take << 13) | (uint32_t)T,
                                    __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
             off += S.c_lt[c] + take;
@@ -233,8 +235,8 @@ __device__ __forceinline__ void unit_threshold(
         }
     }
     HATA_TRACE_AT(13, FUSED && blockIdx.x < 8);
-    if (tid == 0) {
-        // (write-through: a cooperative launch reads these from other workgroups right away)
+    if (tid == 0 && !rec_u) {
+        // (write-through: the next launch's workgroups read these)
         st_dev(reinterpret_cast<uint32_t*>(chunk_info_u) + nc * 2 + 0, (uint32_t)keff);
         st_dev(reinterpret_cast<uint32_t*>(chunk_info_u) + nc * 2 + 1, 0u);
         st_dev(reinterpret_cast<uint32_t*>(unit_info_u) + 0, (uint32_t)T);
