@@ -435,6 +435,81 @@ __device__ __forceinline__ void attn_merge_nj(
     }
 }
 
+// The same merge for ONE head by a whole workgroup (the heads of a unit can then be merged by
+// different workgroups side by side).  pp = the head's partial of slice 0; thread -> (channel
+// tid % 128, slices of parity tid / 128), so 2 * NJ slices are in flight at once; the two halves
+// meet in LDS.  sm: 384 floats of LDS nobody else uses until the call returns.  Must be called by
+// all 256 threads, after a barrier that follows the last use of sm.
+template <int NJ>
+__device__ __forceinline__ void attn_merge_head(
+    float* __restrict__ sm, const float* __restrict__ pp, int ns, uint16_t* __restrict__ out,
+    float* __restrict__ out_f32) {
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int ch = tid & 127, par = tid >> 7;
+    float* sm_w = sm;           // [256] normalised slice weights (ns <= 256)
+    float* sm_half = sm + 256;  // [128] the odd slices' sums
+    float mv[4], lv[4];
+    if (wave == 0) {
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            mv[t] = HATA_NEG_INF;
+            lv[t] = 0.f;
+            if (t * 64 < ns) {
+                const int s2 = min(lane + 64 * t, ns - 1);
+                mv[t] = ld_dev(pp + (int64_t)s2 * HATA_PSTRIDE);
+                lv[t] = ld_dev(pp + (int64_t)s2 * HATA_PSTRIDE + 1);
+            }
+        }
+    }
+    const float* pc = pp + 2 + ch;
+    float av[NJ];
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) {
+        const int s2 = par + 2 * j;
+        av[j] = (s2 < ns) ? ld_dev(pc + (int64_t)s2 * HATA_PSTRIDE) : 0.f;
+    }
+    if (wave == 0) {
+        float m_loc = HATA_NEG_INF;
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            if (lane + 64 * t >= ns) { mv[t] = HATA_NEG_INF; lv[t] = 0.f; }
+            m_loc = fmaxf(m_loc, mv[t]);
+        }
+        const float M = wave_max64(m_loc);
+        float wt[4], l_loc = 0.f;
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            wt[t] = (mv[t] == HATA_NEG_INF) ? 0.f : fast_exp2(mv[t] - M);
+            l_loc = fmaf(wt[t], lv[t], l_loc);
+        }
+        const float Lsum = wave_sum64(l_loc);
+        const float inv = Lsum > 0.f ? 1.f / Lsum : 0.f;
+#pragma unroll
+        for (int t = 0; t < 4; ++t) sm_w[lane + 64 * t] = wt[t] * inv;  // 0 past ns
+    }
+    __syncthreads();
+    float A = 0.f;
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) A = fmaf(sm_w[min(par + 2 * j, 255)], av[j], A);  // (av is 0 past ns)
+    for (int s0 = 2 * NJ; s0 < ns; s0 += 2 * NJ) {
+        float bv[NJ];
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) {
+            const int s2 = s0 + par + 2 * j;
+            bv[j] = (s2 < ns) ? ld_dev(pc + (int64_t)s2 * HATA_PSTRIDE) : 0.f;
+        }
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) A = fmaf(sm_w[min(s0 + par + 2 * j, 255)], bv[j], A);
+    }
+    if (par) sm_half[ch] = A;
+    __syncthreads();
+    if (!par) {
+        A += sm_half[ch];
+        out[ch] = (uint16_t)f32_to_bf16(A);
+        if (out_f32) out_f32[ch] = A;
+    }
+}
+
 // NJ (slices whose loads are in flight together) by the number of slices: a second batch costs a
 // memory round trip, registers bound the first (80 per thread at most)
 template <int HT>

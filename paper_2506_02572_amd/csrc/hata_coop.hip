@@ -11,9 +11,14 @@
 //      chunk offsets (unit_threshold) and publishes an epoch flag; the others WAIT for that flag;
 //   3. compacts its own chunk (ordered, from the LDS scores) -- writing its part of Idx -- and
 //      attends over exactly the rows it selected, for all query heads of the group;
-//   4. writes its partial (max, sum, weighted V); the last workgroup of the unit to finish merges.
+//   4. writes its partial (max, sum, weighted V) and arrives; the first min(G, nc) workgroups of the
+//      unit wait for all arrivals and merge one query head each (with one head per KV head: the
+//      last workgroup to arrive merges).
 // So the scores never make a round trip through memory for the selection, and the only serial
-// pieces are the two last-arriver tails.
+// pieces are the threshold tail and the merge.
+// What workgroups poll or bump lives on cache lines of its own per unit / per chunk (counters,
+// records, one copy of the query code words per chunk): polls and arrivals that share lines across
+// units queue behind each other at the memory side.
 //
 // The waits need every workgroup of a unit to be running; the host launches this kernel
 // only when the whole grid can be resident at once.  The wait is bounded anyway: a workgroup that
@@ -60,6 +65,7 @@ struct CoopArgs {
     int spin_limit;
     int prefetch;     // fetch the first batch of key codes before the query codes are known
     int keep_scores;  // also write the score array (a by-product the kernel itself never reads back)
+    int par_merge;    // the heads of a unit are merged side by side by several of its workgroups
     hata::PageView pv;  // block table (used by the PAGED instantiations only)
 };
 
@@ -566,6 +572,41 @@ __global__ __launch_bounds__(256, (G >= 16 ? 2 : 3)) void decode_step_coop_kerne
     TC(48);
     wait_stores();
     __syncthreads();
+    if (a.par_merge) {
+        // Many slices x many heads: every workgroup arrives (low half of the unit's counter); the
+        // first nm = min(G, nc) workgroups of the unit wait for all nc arrivals, sign off (high
+        // half: "I no longer look at the counter") and merge one query head each (heads c,
+        // c + nm, ...).  Whoever brings the counter to its final value clears it.
+        uint32_t* cntp = a.attn_counter + u * HATA_COUNTER_STRIDE;
+        const int nm = min(G, nc);
+        const uint32_t all_done = ((uint32_t)nm << 16) | (uint32_t)nc;
+        if (tid == 0) {
+            uint32_t seen = atomicAdd(cntp, 1u) + 1u;
+            if (c >= nm) {
+                if (seen == all_done) *cntp = 0;  // (possible only after a merging workgroup gave up its wait)
+            } else {
+                int budget = a.spin_limit;
+                while ((seen & 0xffffu) != (uint32_t)nc) {
+                    if (--budget <= 0) { a.error_word[0] = 1u; break; }  // gave up: results invalid
+                    __builtin_amdgcn_s_sleep(1);
+                    seen = __hip_atomic_load(cntp, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
+            }
+        }
+        if (c >= nm) return;
+        __syncthreads();
+        // the sign-off goes out now and is looked at after the merge (one lane of the last wave: its
+        // return value queues behind that lane's own partial loads)
+        uint32_t signed_off = 0;
+        if (tid == 255) signed_off = atomicAdd(cntp, 0x10000u) + 0x10000u;
+        float* sm = &S.acc[0][0][0];
+        for (int g = c; g < G; g += nm) {
+            if (g != c) __syncthreads();  // the previous head's use of sm
+            attn_merge_head<16>(sm, part0 + g * head_stride, nc, outp + g * HATA_D, outp32 ? outp32 + g * HATA_D : nullptr);
+        }
+        if (tid == 255 && signed_off == all_done) *cntp = 0;
+        return;
+    }
     if (tid == 0) {
         uint32_t* cntp = a.attn_counter + u * HATA_COUNTER_STRIDE;
         const uint32_t done = atomicAdd(cntp, 1u);
@@ -640,6 +681,7 @@ hipError_t launch_coop_step(hata_ctx* c, const void* q, const void* K, const voi
     a.W_H = W_H; a.append = append;
     a.spin_limit = c->spin_limit > 0 ? c->spin_limit : HATA_COOP_SPIN_LIMIT;
     a.keep_scores = c->keep_scores;
+    a.par_merge = c->par_merge;
     a.pv = pages ? *pages : PageView{nullptr, 0, 0, 0};
     {
         int dev = 0, cus = 0;

@@ -42,6 +42,7 @@ struct hata_ctx {
     uint32_t epoch;          // launch counter of the cooperative step
     int spin_limit;          // polls an in-kernel wait makes before it gives up (0 = the default)
     int keep_scores;         // single-launch step also writes the score array
+    int par_merge;           // single-launch step merges the heads of a unit in several workgroups
     int step_mode;           // 0 = single launch when it fits, 3 = always three launches
     int coop_capacity;       // workgroups of the cooperative kernel that can be resident at once (0 = unusable)
     int coop_capacity_paged; // the same for the block-table variant of that kernel
