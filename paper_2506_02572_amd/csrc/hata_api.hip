@@ -41,8 +41,7 @@ int validate_config(const hata_config* f) {
     return HATA_OK;
 }
 
-// Launch shapes: enough workgroups to cover 256 CUs a few times over, but chunks as large as
-// that allows (fewer partial histograms / attention partials to combine).
+// Launch shapes.
 int make_plan(const hata_config* f, Plan* p) {
     int rc = validate_config(f);
     if (rc != HATA_OK) return rc;
@@ -51,11 +50,13 @@ int make_plan(const hata_config* f, Plan* p) {
     p->NB = p->G * f->r + 1;
     p->NBP = (p->NB + 7) / 8 * 8;
     const int64_t units = (int64_t)f->B_max * f->Hkv;
-    // one scoring workgroup per CU at least, chunks of at most 4096 keys (larger only if the
-    // cache is so long that a unit would otherwise exceed 1024 chunks)
-    const int64_t target_wgs = 128;
+    // chunks of at most 4096 keys (larger only if the cache is so long that a unit would otherwise
+    // exceed 1024 chunks), halved while that keeps the grid within two workgroups per CU: measured
+    // with the single-launch step, more and smaller chunks win until then (cfg 2: 20.5 / 17.3 /
+    // 16.9 us at 4096 / 2048 / 1024 keys), and a grid that size is resident for every kernel variant
+    const int64_t max_wgs = 512;
     int chunk = 4096;
-    while (chunk > 1024 && units * ((f->L_cap + chunk - 1) / chunk) < target_wgs) chunk >>= 1;
+    while (chunk > 1024 && units * ((f->L_cap + chunk / 2 - 1) / (chunk / 2)) <= max_wgs) chunk >>= 1;
     while (chunk < 8192 && (f->L_cap + chunk - 1) / chunk > 1024) chunk <<= 1;
     // tuning overrides (launch-shape sweeps): HATA_TUNE_CHUNK in {1024,2048,4096,8192},
     // HATA_TUNE_ROWS in {16..256, power of two}; invalid values are ignored
