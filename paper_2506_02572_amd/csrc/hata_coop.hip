@@ -326,7 +326,7 @@ __global__ __launch_bounds__(256, (G >= 16 ? 2 : 3)) void decode_step_coop_kerne
                                            : a.K + b * a.sb + h * a.sh + (int64_t)(L - 1) * a.sn, el);
             coop_encode_vec<WD>(Wh, el, &s_codes[G * WD]);
         }
-        // Small grids (workgroups on at most half the CUs: the step is a chain of latencies, not a stream):
+        // Small grids (at most one workgroup per CU: the step is a chain of latencies, not a stream):
         // the first batch of the chunk's key codes is fetched while the query codes are collected.
         // With more workgroups per CU these loads would only queue in front of the encoders' own.
         if (a.prefetch) {
@@ -688,7 +688,7 @@ hipError_t launch_coop_step(hata_ctx* c, const void* q, const void* K, const voi
         a.prefetch = 0;
         if (hipGetDevice(&dev) == hipSuccess &&
             hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess)
-            a.prefetch = (int64_t)c->n_chunks * f.Hkv * B * 2 <= cus ? 1 : 0;  // (measured: pays up to half a grid)
+            a.prefetch = (int64_t)c->n_chunks * f.Hkv * B <= cus ? 1 : 0;  // (measured: pays up to one workgroup per CU)
     }
     a.qcodes = c->qcodes; a.codes = codes; a.seq_len = seq_len; a.kbud = k;
     a.scores = c->scores; a.idx = c->idx; a.chunk_hist = c->chunk_hist;
