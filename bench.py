@@ -33,10 +33,10 @@ HBM_PEAK_GBPS = 8000.0
 # "step": the single-launch decode step (decode_step_coop_kernel); "score": the scoring kernel
 # alone (hata_hamming_score).  None = not measured for that workload.
 HBM_TRAFFIC_BYTES = {
-    "cfg2_llama3_8b_32k": {"step": 8321024, "score": 4938957},
-    "cfg3_batched_ragged": {"step": 72608461, "score": 45563494},
-    "cfg4_long_128k_r256": {"step": 46007808, "score": 36296909},
-    "cfg5_gqa8_append": {"step": 58952806, "score": 39123149},
+    "cfg2_llama3_8b_32k": {"step": 9222963, "score": 5082317},
+    "cfg3_batched_ragged": {"step": 72893542, "score": 45563085},
+    "cfg4_long_128k_r256": {"step": 48662118, "score": 36862976},
+    "cfg5_gqa8_append": {"step": 59414426, "score": 39123354},
 }
 
 
