@@ -76,6 +76,11 @@ def test_strerror_and_workspace_validation():
     # calls on a NULL context are rejected, nothing is launched
     assert lib.hata_encode_query(None, None, None, 1, None, None) == -1
     assert lib.hata_decode_step(None, None, None, None, None, None, None, None, 1, 0, 1.0, None, None, None) == -1
+    assert lib.hata_decode_step_paged(None, None, None, None, None, None, None, 4, 256, 4, None, None, 1, 0, 1.0,
+                                      None, None, None) == -1
+    assert lib.hata_prefill_write_paged(None, None, None, None, None, 1, 16, None, None, None, None, 4, 256, 4,
+                                        None, None) == -1
+    assert lib.hata_prefill_write(None, None, None, None, None, 1, 16, None, None, None, None, None) == -1
     assert lib.hata_step_plan(None, 1, None, None, None) == -1
     assert lib.hata_set_step_mode(None, 0) == -1
     assert lib.hata_set_wait_limit(None, 0) == -1
