@@ -220,6 +220,7 @@ def main():
     ctx.hata_check(stream)  # raises if a single-launch step gave up an in-kernel wait
     us_step = ms_step * 1e3
     n_launches, plan_chunk, plan_n_chunks = ctx.hata_step_plan(w.B)
+    n_sub = ctx.hata_step_sub_batches(w.B)  # launches of the single-launch form (batch slices), 0 = three-launch form
 
     # ---- N layer steps in one HIP graph (launch gaps out of the way), with and without the dense first layers
     graph_leg = None
@@ -380,11 +381,12 @@ def main():
                    "traffic": traffic.get("score"), "algorithmic_bytes_per_launch": code_bytes,
                    "avg_launch_us": round(ms_score * 1e3, 3)}
     if n_launches == 1:
-        # the whole step is ONE kernel: it is the dominant kernel, its launch is the step
+        # the whole step is ONE kernel (launched once per slice of a batch too large to be resident at
+        # once): it is the dominant kernel, its launches are the step
         roofline = {"bound": "hbm", "kernel": "decode_step_coop_kernel (hata_decode_step: the whole step in one launch)",
                     "achieved": round(step_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                     "frac": round(step_gbps / HBM_PEAK_GBPS, 4), "traffic": traffic.get("step"),
-                    "algorithmic_bytes_per_launch": alg_bytes, "avg_launch_us": round(us_step, 3)}
+                    "algorithmic_bytes_per_launch": alg_bytes // n_sub, "avg_launch_us": round(us_step / n_sub, 3)}
     else:
         roofline = dict(score_stage, bound="hbm", peak=HBM_PEAK_GBPS)
     result = {
@@ -405,7 +407,8 @@ def main():
                    "k": list(w.k) if len(set(w.k)) > 1 else w.k[0],
                    "layers_rotated": n_layers, "append_per_step": True,
                    "kv_cache": "pinned host memory (rows gathered over the bus)" if args.kv_host else "HBM",
-                   "launches_per_step": n_launches, "chunk": plan_chunk, "chunks_per_unit": plan_n_chunks},
+                   "launches_per_step": n_sub if n_launches == 1 else n_launches, "chunk": plan_chunk,
+                   "chunks_per_unit": plan_n_chunks},
         "achieved_GBps": round(step_gbps, 1),
         "algorithmic_bytes_per_step": alg_bytes,
         "step_roofline_frac": round(step_gbps / HBM_PEAK_GBPS, 4),

@@ -151,8 +151,10 @@ int hata_dense_decode(hata_ctx* ctx, const void* q, const void* K, const void* V
  * Intermediate qcodes / idx (and scores, see hata_keep_step_scores) live in the workspace
  * (see hata_step_buffers).
  *
- * Launches (see hata_step_plan): when every workgroup of the step can be resident on the device
- * at once (r in {32, 64, 128, 256}, Hq/Hkv in {1, 2, 4, 5, 8}, or 16 with r <= 128), the step is ONE kernel launch whose
+ * Launches (see hata_step_plan): for r in {32, 64, 128, 256} and Hq/Hkv in {1, 2, 4, 5, 8}, or 16
+ * with r <= 128, when the workgroups of at least one sequence can be resident on the device at once,
+ * the step is ONE kernel launch (one per slice of a batch too large to be resident as a whole:
+ * hata_step_sub_batches) whose
  * workgroups hand the query codes, the selection threshold and the attention partials to each
  * other through the workspace, waiting for one another inside the kernel.  Every such wait is
  * bounded: a workgroup that gives up raises a flag in the workspace and runs to its end, the
@@ -185,8 +187,8 @@ int hata_decode_step(hata_ctx* ctx, const void* q, const void* K, const void* V,
  * may share pages for reading; the page that holds an appended row must belong to one sequence.
  *
  * hata_decode_step_paged: hata_decode_step on that layout, same outputs (Idx holds LOGICAL row
- * numbers).  It exists in the single-launch form only: HATA_EUNSUPPORTED when the shape or the
- * batch does not fit it (see hata_decode_step; hata_set_step_mode does not apply).
+ * numbers).  It exists in the single-launch form only: HATA_EUNSUPPORTED when the shape does not
+ * fit it (see hata_decode_step; hata_set_step_mode does not apply).
  */
 int hata_decode_step_paged(hata_ctx* ctx, const void* q, const void* K_pool, const void* V_pool,
                            const float* W_H, uint32_t* codes_pool, const int32_t* block_table,
@@ -203,9 +205,16 @@ int hata_prefill_write_paged(hata_ctx* ctx, const void* K_new, const void* V_new
                              int32_t page_rows, int32_t n_pages, const float* W_H, void* stream);
 
 /* Host-side query of how hata_decode_step() runs a batch of B sequences; nothing is enqueued.
- * *n_launches: 1 (single cooperative launch) or 3; *chunk: cached keys per scoring workgroup;
- * *n_chunks: scoring workgroups per (sequence, KV head).  Any output pointer (host) may be NULL. */
+ * *n_launches: 1 (single-launch form) or 3 (three-launch form); *chunk: cached keys per scoring
+ * workgroup; *n_chunks: scoring workgroups per (sequence, KV head).  Any output pointer (host)
+ * may be NULL. */
 int hata_step_plan(const hata_ctx* ctx, int32_t B, int32_t* n_launches, int32_t* chunk, int32_t* n_chunks);
+
+/* A batch with more (sequence, KV head) units than one launch can keep resident still runs in the
+ * single-launch form, as consecutive launches over equal slices of the batch (each a whole step
+ * for its sequences).  *n_sub (host): the number of such launches for a batch of B, 1 when the
+ * batch fits one launch, 0 when hata_decode_step() uses the three-launch form. */
+int hata_step_sub_batches(const hata_ctx* ctx, int32_t B, int32_t* n_sub);
 
 /* mode 0 (default): hata_decode_step() uses the single-launch form whenever it fits;
  * mode 3: always the three-launch form (no in-kernel waits). */

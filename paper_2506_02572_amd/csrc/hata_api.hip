@@ -115,9 +115,16 @@ inline int check_call(const hata_ctx* c, int B) {
 }
 // the cooperative kernel needs its whole grid resident (its workgroups wait for one another) and
 // merges at most 256 attention partials per unit
-inline bool step_is_single_launch(const hata_ctx* c, int B) {
-    return c->step_mode != 3 && c->n_chunks <= 256 &&
-           (int64_t)c->n_chunks * c->cfg.Hkv * B <= c->coop_capacity;
+// Single-launch form of the step: the number of launches a batch of B sequences is cut into -- every
+// launch must be resident as a whole, so a batch with more (sequence, KV head) units than that
+// allows goes in equal slices, one launch each -- or 0 when the form is not available.
+inline int coop_sub_batches(const hata_ctx* c, int B, bool paged) {
+    if (c->step_mode == 3 || c->n_chunks > 256) return 0;
+    const int cap = paged ? c->coop_capacity_paged : c->coop_capacity;
+    const int64_t per_seq = (int64_t)c->n_chunks * c->cfg.Hkv;
+    if (cap <= 0 || per_seq > cap) return 0;
+    const int per_launch = (int)(cap / per_seq);
+    return (B + per_launch - 1) / per_launch;
 }
 inline bool aligned(const void* p, size_t a) { return ((uintptr_t)p % a) == 0; }
 
@@ -335,11 +342,15 @@ int hata_decode_step(hata_ctx* ctx, const void* q, const void* K, const void* V,
     // Cooperative path: encoding, scoring, selection and attention in ONE launch (workgroups of a
     // unit wait for the unit's threshold inside the kernel), when every workgroup can be resident
     // at once.
-    if (step_is_single_launch(ctx, B)) {
-        hipError_t e = hata::launch_coop_step(ctx, q, K, V, W_H, codes, append, seq_len, k, B,
-                                              sm_scale, out, out_f32, s);
+    if (const int ns = coop_sub_batches(ctx, B, false)) {
+        hipError_t e = hipSuccess;
+        for (int i = 0; i < ns && e == hipSuccess; ++i) {
+            const int b0 = (int)((int64_t)i * B / ns), b1 = (int)((int64_t)(i + 1) * B / ns);
+            e = hata::launch_coop_step(ctx, q, K, V, W_H, codes, append, seq_len, k, b1 - b0, sm_scale, out,
+                                       out_f32, s, nullptr, b0);
+        }
         if (e == hipSuccess) return HATA_OK;
-        if (e != hipErrorNotSupported) return HATA_EHIP;
+        if (e != hipErrorNotSupported) return HATA_EHIP;  // (not supported: no kernel for this shape, nothing was launched)
     }
     // Alg. 3: HashEncode(Q), HashEncode(K_new) and the code-cache update, in one launch
     hipError_t e = hata::launch_encode_vectors(ctx, q, ctx->qcodes, append ? K : nullptr, seq_len,
@@ -369,10 +380,17 @@ int hata_decode_step_paged(hata_ctx* ctx, const void* q, const void* K_pool, con
     rc = make_page_view(ctx, block_table, max_blocks, page_rows, n_pages, &pv);
     if (rc != HATA_OK) return rc;
     // the block table is read by the single-launch kernel only
-    if (ctx->n_chunks > 256 || (int64_t)ctx->n_chunks * ctx->cfg.Hkv * B > ctx->coop_capacity_paged)
-        return HATA_EUNSUPPORTED;
-    hipError_t e = hata::launch_coop_step(ctx, q, K_pool, V_pool, W_H, codes_pool, append, seq_len, k, B,
-                                          sm_scale, out, out_f32, (hipStream_t)stream, &pv);
+    const int mode = ctx->step_mode;
+    ctx->step_mode = 0;  // (hata_set_step_mode does not apply here)
+    const int ns = coop_sub_batches(ctx, B, true);
+    ctx->step_mode = mode;
+    if (ns == 0) return HATA_EUNSUPPORTED;
+    hipError_t e = hipSuccess;
+    for (int i = 0; i < ns && e == hipSuccess; ++i) {
+        const int b0 = (int)((int64_t)i * B / ns), b1 = (int)((int64_t)(i + 1) * B / ns);
+        e = hata::launch_coop_step(ctx, q, K_pool, V_pool, W_H, codes_pool, append, seq_len, k, b1 - b0, sm_scale,
+                                   out, out_f32, (hipStream_t)stream, &pv, b0);
+    }
     if (e == hipErrorNotSupported) return HATA_EUNSUPPORTED;
     return hip_rc(e);
 }
@@ -380,9 +398,17 @@ int hata_decode_step_paged(hata_ctx* ctx, const void* q, const void* K_pool, con
 int hata_step_plan(const hata_ctx* ctx, int32_t B, int32_t* n_launches, int32_t* chunk, int32_t* n_chunks) {
     int rc = check_call(ctx, B);
     if (rc != HATA_OK) return rc;
-    if (n_launches) *n_launches = step_is_single_launch(ctx, B) ? 1 : 3;
+    if (n_launches) *n_launches = coop_sub_batches(ctx, B, false) ? 1 : 3;
     if (chunk) *chunk = ctx->chunk;
     if (n_chunks) *n_chunks = ctx->n_chunks;
+    return HATA_OK;
+}
+
+int hata_step_sub_batches(const hata_ctx* ctx, int32_t B, int32_t* n_sub) {
+    int rc = check_call(ctx, B);
+    if (rc != HATA_OK) return rc;
+    if (!n_sub) return HATA_EINVAL;
+    *n_sub = coop_sub_batches(ctx, B, false);
     return HATA_OK;
 }
 

@@ -672,7 +672,7 @@ int coop_capacity(const hata_ctx* c, bool paged) {
 hipError_t launch_coop_step(hata_ctx* c, const void* q, const void* K, const void* V,
                             const float* W_H, uint32_t* codes, int append, const int32_t* seq_len,
                             const int32_t* k, int B, float sm_scale, void* out, float* out_f32, hipStream_t s,
-                            const PageView* pages) {
+                            const PageView* pages, int b0) {
     const hata_config& f = c->cfg;
     const void* fn = coop_kernel_for(c->Wd, c->G, pages != nullptr);
     if (!fn || c->chunk > HATA_COOP_MAX_CHUNK) return hipErrorNotSupported;
@@ -683,6 +683,20 @@ hipError_t launch_coop_step(hata_ctx* c, const void* q, const void* K, const voi
     a.keep_scores = c->keep_scores;
     a.par_merge = c->par_merge;
     a.pv = pages ? *pages : PageView{nullptr, 0, 0, 0};
+    // sequences [b0, b0 + B) of the caller's batch: every per-sequence and per-unit base moves up
+    const int64_t u0 = (int64_t)b0 * f.Hkv;
+    a.q += (int64_t)b0 * f.Hq * HATA_D;
+    if (pages) {
+        a.pv.table += (int64_t)b0 * pages->max_blocks;
+    } else {
+        a.K += b0 * f.kv_stride_b;
+        a.V += b0 * f.kv_stride_b;
+        codes += u0 * f.L_cap * c->Wd;
+    }
+    seq_len += b0;
+    k += b0;
+    out = (uint16_t*)out + (int64_t)b0 * f.Hq * HATA_D;
+    if (out_f32) out_f32 += (int64_t)b0 * f.Hq * HATA_D;
     {
         int dev = 0, cus = 0;
         a.prefetch = 0;
@@ -690,11 +704,16 @@ hipError_t launch_coop_step(hata_ctx* c, const void* q, const void* K, const voi
             hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess)
             a.prefetch = (int64_t)c->n_chunks * f.Hkv * B <= cus ? 1 : 0;  // (measured: pays up to one workgroup per CU)
     }
-    a.qcodes = c->qcodes; a.codes = codes; a.seq_len = seq_len; a.kbud = k;
-    a.scores = c->scores; a.idx = c->idx; a.chunk_hist = c->chunk_hist;
-    a.chunk_info = c->chunk_info; a.unit_info = c->unit_info; a.unit_counter = c->unit_counter;
-    a.unit_hist = c->unit_hist; a.rec = c->coop_rec; a.qrec = c->coop_qrec; a.attn_counter = c->attn_counter;
-    a.error_word = c->error_word; a.partials = c->partials;
+    a.qcodes = c->qcodes + (int64_t)b0 * f.Hq * c->Wd; a.codes = codes; a.seq_len = seq_len; a.kbud = k;
+    a.scores = c->scores + u0 * f.L_cap; a.idx = c->idx + u0 * f.k_max;
+    a.chunk_hist = c->chunk_hist + u0 * c->n_chunks * c->NBP;
+    a.chunk_info = c->chunk_info + u0 * (c->n_chunks + 1) * 2; a.unit_info = c->unit_info + u0 * 2;
+    a.unit_counter = c->unit_counter + u0 * HATA_COUNTER_STRIDE;
+    a.unit_hist = c->unit_hist + u0 * c->NB; a.rec = c->coop_rec + u0 * c->n_chunks * HATA_REC_STRIDE;
+    a.qrec = c->coop_qrec + u0 * c->n_chunks * c->G * c->Wd;
+    a.attn_counter = c->attn_counter + u0 * HATA_COUNTER_STRIDE;
+    a.error_word = c->error_word;
+    a.partials = c->partials + (int64_t)b0 * f.Hq * c->n_chunks * HATA_PSTRIDE;
     a.out = (uint16_t*)out; a.out_f32 = out_f32;
     a.Hq = f.Hq; a.Hkv = f.Hkv; a.L_cap = f.L_cap; a.k_max = f.k_max; a.chunk = c->chunk;
     a.n_chunks = c->n_chunks; a.NB = c->NB; a.NBP = c->NBP; a.units = f.Hkv * B;

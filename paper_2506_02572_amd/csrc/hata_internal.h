@@ -88,7 +88,7 @@ hipError_t launch_attention(const hata_ctx* c, int mode, const void* q, const vo
 hipError_t launch_coop_step(hata_ctx* c, const void* q, const void* K, const void* V,
                             const float* W_H, uint32_t* codes, int append, const int32_t* seq_len,
                             const int32_t* k, int B, float sm_scale, void* out, float* out_f32, hipStream_t s,
-                            const PageView* pages = nullptr);
+                            const PageView* pages = nullptr, int b0 = 0);
 int coop_capacity(const hata_ctx* c, bool paged);
 
 }  // namespace hata

@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libhata.so")
 EXPORTS = (
     "hata_strerror", "hata_workspace_bytes", "hata_create", "hata_destroy", "hata_encode_keys",
     "hata_prefill_write", "hata_prefill_write_paged", "hata_encode_query", "hata_hamming_score", "hata_topk", "hata_sparse_decode",
-    "hata_dense_decode", "hata_decode_step", "hata_decode_step_paged", "hata_step_plan", "hata_set_step_mode", "hata_keep_step_scores", "hata_set_wait_limit",
+    "hata_dense_decode", "hata_decode_step", "hata_decode_step_paged", "hata_step_plan", "hata_step_sub_batches", "hata_set_step_mode", "hata_keep_step_scores", "hata_set_wait_limit",
     "hata_check",
     "hata_host_device_pointer", "hata_step_buffers",
 )
@@ -75,6 +75,7 @@ def load_library(build_if_missing: bool = True) -> ctypes.CDLL:
     lib.hata_decode_step_paged.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _vp, _vp,
                                            _i32, _i32, ctypes.c_float, _vp, _vp, _vp]
     lib.hata_step_plan.argtypes = [_vp, _i32, ctypes.POINTER(_i32), ctypes.POINTER(_i32), ctypes.POINTER(_i32)]
+    lib.hata_step_sub_batches.argtypes = [_vp, _i32, ctypes.POINTER(_i32)]
     lib.hata_set_step_mode.argtypes = [_vp, _i32]
     lib.hata_keep_step_scores.argtypes = [_vp, _i32]
     lib.hata_set_wait_limit.argtypes = [_vp, _i32]
@@ -226,6 +227,12 @@ class Context:
         _check(load_library().hata_step_plan(self._h, B, ctypes.byref(n), ctypes.byref(c),
                                              ctypes.byref(nc)), "hata_step_plan")
         return n.value, c.value, nc.value
+
+    def hata_step_sub_batches(self, B):
+        """Launches of the single-launch form for a batch of B (0: the three-launch form is used)."""
+        n = _i32(0)
+        _check(load_library().hata_step_sub_batches(self._h, B, ctypes.byref(n)), "hata_step_sub_batches")
+        return n.value
 
     def hata_set_step_mode(self, mode):
         _check(load_library().hata_set_step_mode(self._h, mode), "hata_set_step_mode")

@@ -351,3 +351,62 @@ def test_prefill_write_fills_caches_and_codes_in_one_pass(torch_mod, r):
         diff = (cc[b, :, lo:hi] ^ ref[b, :, lo:hi]) & ~near[b, :, lo:hi]
         assert not np.any(diff), "key codes differ outside the |projection| < 1e-4 band"
     c.ctx.close()
+
+
+def test_batch_larger_than_one_launch_runs_in_sub_batches(torch_mod):
+    """More (sequence, KV head) units than one launch can keep resident: the single-launch form is
+    issued once per slice of the batch; every sequence must come out as from the oracle, on the
+    contiguous and on the paged layout."""
+    import os
+    torch = torch_mod
+    from paper_2506_02572_amd import hata
+    lens = tuple(3000 + 257 * (i % 19) for i in range(20))
+    ks = tuple(64 + 16 * (i % 5) for i in range(20))
+    w = synth.Workload("bigbatch", 20, 32, 8, 128, 128, lens, ks, 4, 8.0, L_cap=8192, k_max=128)
+    os.environ["HATA_TUNE_CHUNK"] = "1024"  # 8 chunks x 8 KV heads per sequence: 20 sequences = 1280 workgroups
+    try:
+        c = H.Case(w, seed=61)
+    finally:
+        del os.environ["HATA_TUNE_CHUNK"]
+    B = w.B
+    n_launches, chunk, n_chunks = c.ctx.hata_step_plan(B)
+    n_sub = c.ctx.hata_step_sub_batches(B)
+    assert (n_launches, chunk, n_chunks) == (1, 1024, 8) and n_sub >= 2, (n_launches, chunk, n_chunks, n_sub)
+    assert c.ctx.hata_step_sub_batches(2) == 1
+    q = c.inp.q(5)
+    seq = c.inp.seq_len
+    codes_h = c.codes_ref.copy()
+    for b in range(B):
+        codes_h[b, :, int(seq[b]) - 1:] = 0xDEADBEEF
+    codes_before = codes_h.copy()
+    ref = O.decode_step(q, c.inp.K, c.inp.V, c.inp.W_H, codes_h, seq, c.inp.k, w.k_max, c.scale, append=True)
+    out = c.empty((B, w.Hq, w.d), torch.int16)
+    out32 = c.empty((B, w.Hq, w.d), torch.float32)
+    codes_d = H.to_dev(codes_before)
+    qd = H.to_dev(q)
+    c.ctx.hata_keep_step_scores(True)
+    c.ctx.hata_decode_step(qd, c.K, c.V, c.W_H, codes_d, c.seq_len, c.k, B, True, c.scale, out, out32)
+    c.ctx.hata_check()
+    qc, sc, ix = c.ctx.hata_step_buffers()
+    assert np.array_equal(H.to_host(codes_d, np.uint32), codes_h), "appended code rows"
+    assert np.array_equal(H.to_host(qc, np.uint32), ref["qcodes"])
+    got_s = H.to_host(sc, np.uint16).astype(np.int32)
+    for b in range(B):
+        assert np.array_equal(got_s[b, :, :int(seq[b])], ref["scores"][b, :, :int(seq[b])])
+    assert np.array_equal(H.to_host(ix), ref["idx"])
+    H.check_attention(H.to_host(out32), H.to_host(out, np.uint16), ref["out"], "sub-batched step")
+    first = out32.clone()
+    # the paged layout with one page per chunk, identity order: same pools as the contiguous caches
+    # seen as [B * 8 pages, Hkv, 1024, .] after moving the block axis in front of the heads
+    P, nb = 1024, w.L_cap // 1024
+    def pool(t, last):
+        return t.view(B, w.Hkv, nb, P, last).permute(0, 2, 1, 3, 4).contiguous().view(B * nb, w.Hkv, P, last)
+    table = torch.arange(B * nb, dtype=torch.int32, device="cuda").view(B, nb).contiguous()
+    Kp, Vp, Cp = pool(c.K, w.d), pool(c.V, w.d), pool(H.to_dev(codes_before), w.W)
+    out32.zero_()
+    c.ctx.hata_decode_step_paged(qd, Kp, Vp, c.W_H, Cp, table, nb, P, B * nb, c.seq_len, c.k, B, True, c.scale,
+                                 out, out32)
+    c.ctx.hata_check()
+    assert np.array_equal(H.to_host(c.ctx.hata_step_buffers()[2]), ref["idx"])
+    assert torch.equal(out32, first)
+    c.ctx.close()
