@@ -216,7 +216,14 @@ int hata_step_plan(const hata_ctx* ctx, int32_t B, int32_t* n_launches, int32_t*
  * batch fits one launch, 0 when hata_decode_step() uses the three-launch form. */
 int hata_step_sub_batches(const hata_ctx* ctx, int32_t B, int32_t* n_sub);
 
-/* mode 0 (default): hata_decode_step() uses the single-launch form whenever it fits;
+/* mode 0 (default): hata_decode_step() uses the single-launch form whenever it fits, a batch too
+ *   large to be resident as consecutive launches over slices of it;
+ * mode 1: as mode 0, but a batch of any size goes in ONE launch.  Its workgroups then become
+ *   resident in the order of their indices as earlier ones retire -- a unit's workgroups have
+ *   neighbouring indices, so the unit with the lowest index still at work is always resident as a
+ *   whole and finishes -- which is how the hardware dispatches a grid, not a guarantee of the
+ *   programming model: should a wait ever give up, hata_check() reports it (HATA_ETIMEOUT) and
+ *   the step must be repeated in mode 0 or 3;
  * mode 3: always the three-launch form (no in-kernel waits). */
 int hata_set_step_mode(hata_ctx* ctx, int32_t mode);
 

@@ -123,6 +123,7 @@ inline int coop_sub_batches(const hata_ctx* c, int B, bool paged) {
     const int cap = paged ? c->coop_capacity_paged : c->coop_capacity;
     const int64_t per_seq = (int64_t)c->n_chunks * c->cfg.Hkv;
     if (cap <= 0 || per_seq > cap) return 0;
+    if (c->step_mode == 1) return 1;  // the whole batch in one grid, whatever its size
     const int per_launch = (int)(cap / per_seq);
     return (B + per_launch - 1) / per_launch;
 }
@@ -413,7 +414,7 @@ int hata_step_sub_batches(const hata_ctx* ctx, int32_t B, int32_t* n_sub) {
 }
 
 int hata_set_step_mode(hata_ctx* ctx, int32_t mode) {
-    if (!ctx || (mode != 0 && mode != 3)) return HATA_EINVAL;
+    if (!ctx || (mode != 0 && mode != 1 && mode != 3)) return HATA_EINVAL;
     ctx->step_mode = mode;
     return HATA_OK;
 }

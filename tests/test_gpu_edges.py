@@ -396,6 +396,15 @@ def test_batch_larger_than_one_launch_runs_in_sub_batches(torch_mod):
     assert np.array_equal(H.to_host(ix), ref["idx"])
     H.check_attention(H.to_host(out32), H.to_host(out, np.uint16), ref["out"], "sub-batched step")
     first = out32.clone()
+    # mode 1: the whole batch in ONE grid that is larger than what is resident at once
+    c.ctx.hata_set_step_mode(1)
+    assert c.ctx.hata_step_sub_batches(B) == 1
+    out32.zero_()
+    c.ctx.hata_decode_step(qd, c.K, c.V, c.W_H, H.to_dev(codes_before), c.seq_len, c.k, B, True, c.scale, out, out32)
+    c.ctx.hata_check()
+    assert np.array_equal(H.to_host(c.ctx.hata_step_buffers()[2]), ref["idx"])
+    assert torch.equal(out32, first)
+    c.ctx.hata_set_step_mode(0)
     # the paged layout with one page per chunk, identity order: same pools as the contiguous caches
     # seen as [B * 8 pages, Hkv, 1024, .] after moving the block axis in front of the heads
     P, nb = 1024, w.L_cap // 1024
