@@ -197,6 +197,7 @@ SWEEP = {
     "ctx256k": Workload("ctx256k", 1, 32, 8, 128, 128, (262144,), (4096,), 4, 8.0, append_steps=2),
     # a serving-size batch: more (sequence, KV head) units than one launch can keep resident
     "b32_32k": Workload("b32_32k", 32, 32, 8, 128, 128, (32768,) * 32, (512,) * 32, 4, 8.0),
+    "b64_32k": Workload("b64_32k", 64, 32, 8, 128, 128, (32768,) * 64, (512,) * 64, 4, 8.0),
 }
 
 
