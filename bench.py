@@ -59,6 +59,9 @@ def parse():
                     help="also time N consecutive layer steps captured in ONE HIP graph (a token's pass "
                          "through N attention layers): all hash-aware, and with the first two layers dense "
                          "(the paper keeps them dense, Sec. 5.1); 0 skips the leg")
+    ap.add_argument("--step-mode", type=int, default=0, choices=(0, 1, 3),
+                    help="hata_set_step_mode: 0 = single-launch form, a batch too large to be resident in "
+                         "slices (default); 1 = the whole batch as one grid; 3 = three-launch form")
     ap.add_argument("--paged", type=int, default=0, metavar="PAGE_ROWS",
                     help="also time the step on the paged (block-table) layout: the caches are re-laid as "
                          "pools of PAGE_ROWS-row pages in a random page order (needs L_cap %% PAGE_ROWS == 0)")
@@ -130,6 +133,7 @@ def main():
     out = torch.empty((w.B, w.Hq, w.d), dtype=torch.int16, device=dev)
     out32 = torch.empty((w.B, w.Hq, w.d), dtype=torch.float32, device=dev)
     ctx = hata.Context(w.B, w.Hq, w.Hkv, w.d, w.r, w.L_cap, w.k_max)
+    ctx.hata_set_step_mode(args.step_mode)
     stream = torch.cuda.current_stream()
 
     def timed(fn, n, warm):
@@ -407,7 +411,8 @@ def main():
                    "k": list(w.k) if len(set(w.k)) > 1 else w.k[0],
                    "layers_rotated": n_layers, "append_per_step": True,
                    "kv_cache": "pinned host memory (rows gathered over the bus)" if args.kv_host else "HBM",
-                   "launches_per_step": n_sub if n_launches == 1 else n_launches, "chunk": plan_chunk,
+                   "launches_per_step": n_sub if n_launches == 1 else n_launches, "step_mode": args.step_mode,
+                   "chunk": plan_chunk,
                    "chunks_per_unit": plan_n_chunks},
         "achieved_GBps": round(step_gbps, 1),
         "algorithmic_bytes_per_step": alg_bytes,
