@@ -297,25 +297,36 @@ __global__ __launch_bounds__(256) void train_assemble_kernel(
         __syncthreads();
     }
     const float fro = s_fro;
-    const int e = blockIdx.x * 256 + tid;
+    // 64 elements per workgroup; wave w sums a quarter of the partials (and a quarter of the W P
+    // row-column product) of each, the four quarters meet in LDS in a fixed order
+    __shared__ float quart[4][64];
+    const int el = tid & 63, sl = tid >> 6;
+    const int e = blockIdx.x * 64 + el;
+    float g = 0.f;
     if (e < HATA_D * r) {
         const int c = e / r, j = e % r;
         // (eight independent chains: the loads of a chain step are in flight together)
         float gp[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-        int wg = 0;
-        for (; wg + 8 <= n_wgs; wg += 8) {
+        int wg = (int)((int64_t)sl * n_wgs / 4);
+        const int wg_end = (int)((int64_t)(sl + 1) * n_wgs / 4);
+        for (; wg + 8 <= wg_end; wg += 8) {
 #pragma unroll
             for (int u = 0; u < 8; ++u) gp[u] += dw_part[(int64_t)(wg + u) * HATA_D * r + e];
         }
-        for (; wg < n_wgs; ++wg) gp[0] += dw_part[(int64_t)wg * HATA_D * r + e];
-        float g = ((gp[0] + gp[1]) + (gp[2] + gp[3])) + ((gp[4] + gp[5]) + (gp[6] + gp[7]));
-        g *= sigma;
+        for (; wg < wg_end; ++wg) gp[0] += dw_part[(int64_t)wg * HATA_D * r + e];
+        g = (((gp[0] + gp[1]) + (gp[2] + gp[3])) + ((gp[4] + gp[5]) + (gp[6] + gp[7]))) * sigma;
         if (fro > 0.f) {
             float wp = 0.f;
-#pragma unroll 16
-            for (int i = 0; i < r; ++i) wp = fmaf(W[(int64_t)c * r + i], P[(int64_t)i * r + j], wp);
+            const int i0 = sl * (r / 4), i1 = i0 + r / 4;  // (r is a multiple of 32)
+#pragma unroll 8
+            for (int i = i0; i < i1; ++i) wp = fmaf(W[(int64_t)c * r + i], P[(int64_t)i * r + j], wp);
             g += lam * 2.f * wp / fro;
         }
+    }
+    quart[sl][el] = g;
+    __syncthreads();
+    if (sl == 0 && e < HATA_D * r) {
+        g = (quart[0][el] + quart[1][el]) + (quart[2][el] + quart[3][el]);
         G[e] = g;
         if (grad) grad[e] = g;
     }
@@ -449,7 +460,7 @@ int hata_train_step(hata_train_ctx* ctx, const void* Q, const void* K, const flo
 #undef HATA_TRAIN_LAUNCH
     hipLaunchKernelGGL(hata::train_gram_kernel, dim3(r), dim3(256), 0, st, W, r, ctx->P, ctx->fro_part);
     const int count = ctx->cfg.d * r;
-    hipLaunchKernelGGL(hata::train_assemble_kernel, dim3((count + 255) / 256), dim3(256), 0, st, W, r,
+    hipLaunchKernelGGL(hata::train_assemble_kernel, dim3((count + 63) / 64), dim3(256), 0, st, W, r,
                        n_wgs, hp->sigma, hp->lam, c_sim, c_bal, ctx->dw_part, ctx->P, ctx->fro_part,
                        ctx->colsum, ctx->loss_part, ctx->G, grad, loss);
     hipLaunchKernelGGL(hata::train_update_kernel, dim3((count + 255) / 256), dim3(256), 0, st, W, v,
