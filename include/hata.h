@@ -85,6 +85,23 @@ int hata_workspace_bytes(const hata_config* cfg, size_t* out);
  * current device.  ctx_out, cfg: host pointers. */
 int hata_create(hata_ctx** ctx_out, const hata_config* cfg, void* workspace, size_t workspace_bytes);
 
+/* Launch-shape choices a caller may fix instead of taking the defaults (sweeps over launch
+ * shapes; tests of the batch slicing on small inputs; a device that is not the caller's alone).
+ * A zero-initialised struct, or a NULL pointer, means "all defaults". */
+typedef struct {
+    int32_t chunk;         /* cached keys per scoring workgroup: 0 = default, else 1024, 2048, 4096 or 8192 */
+    int32_t attn_rows;     /* selected rows per attention workgroup of the three-launch form: 0 = default, else a power of two in 16..256 */
+    int32_t par_merge;     /* single-launch form, merge of a unit's partials: -1 = default, 0 = by the last workgroup to arrive, 1 = a query head per workgroup */
+    int32_t shared_device; /* != 0: other work may run on the device beside the step, so the context starts in step mode 3 (see hata_set_step_mode) */
+} hata_tuning;
+
+/* hata_workspace_bytes / hata_create with the launch shapes of `tuning` (host pointer, may be
+ * NULL): the chunk size changes the workspace size, so both calls must be given the same values.
+ * HATA_EINVAL for a value outside the sets above. */
+int hata_workspace_bytes_tuned(const hata_config* cfg, const hata_tuning* tuning, size_t* out);
+int hata_create_tuned(hata_ctx** ctx_out, const hata_config* cfg, const hata_tuning* tuning,
+                      void* workspace, size_t workspace_bytes);
+
 /* Frees the host-side context (the workspace is the caller's). */
 int hata_destroy(hata_ctx* ctx);
 
@@ -157,13 +174,16 @@ int hata_dense_decode(hata_ctx* ctx, const void* q, const void* K, const void* V
  * hata_step_sub_batches) whose
  * workgroups hand the query codes, the selection threshold and the attention partials to each
  * other through the workspace, waiting for one another inside the kernel.  Every such wait is
- * bounded: a workgroup that gives up raises a flag in the workspace and runs to its end, the
- * step's outputs are then invalid, and the next hata_check() returns HATA_ETIMEOUT.  Otherwise
+ * bounded: a workgroup that gives up raises a flag in the workspace and runs to its end; the
+ * outputs of every (sequence, KV head) unit one of whose workgroups gave up are then overwritten
+ * with NaN (out: bf16 0x7fc0, out_f32: NaN), so the failure shows in the data itself (the idx
+ * rows of such a step are unspecified: -1 where the unit could still be marked, else whatever its
+ * workgroups wrote), and the next hata_check() returns HATA_ETIMEOUT.  Otherwise
  * the step is three launches (encode; score + threshold; select + attend) with no in-kernel wait.
  * The residency test assumes the device runs nothing else at that moment and that the context is
  * used on the device that was current in hata_create(): a process that overlaps other kernels
- * with the step (other streams, other processes) should call hata_set_step_mode(ctx, 3), or watch
- * hata_check().
+ * with the step (other streams, other processes) should create the context with
+ * hata_tuning.shared_device set (or call hata_set_step_mode(ctx, 3)), or watch hata_check().
  * Both forms select the same rows and agree on the output to rounding.  Either form may be
  * recorded into a HIP graph and replayed (no memset nodes, no host-side state a replay depends
  * on: the single-launch kernel retires the words its workgroups publish before it ends);
@@ -219,9 +239,12 @@ int hata_step_sub_batches(const hata_ctx* ctx, int32_t B, int32_t* n_sub);
 /* mode 0 (default): hata_decode_step() uses the single-launch form whenever it fits, a batch too
  *   large to be resident as consecutive launches over slices of it;
  * mode 1: as mode 0, but a batch of any size goes in ONE launch.  Its workgroups then become
- *   resident in the order of their indices as earlier ones retire -- a unit's workgroups have
- *   neighbouring indices, so the unit with the lowest index still at work is always resident as a
- *   whole and finishes -- which is how the hardware dispatches a grid, not a guarantee of the
+ *   resident in the order of their indices as earlier ones retire.  The workgroups of a unit lie
+ *   within a span of 8 * chunks-per-unit consecutive indices when the number of units is a
+ *   multiple of eight (eight units are interleaved, one per L2), chunks-per-unit otherwise; the
+ *   mode is taken only when such a span fits the device at once (else the batch goes in slices as
+ *   in mode 0), so the units with the lowest indices still at work are always resident as a whole
+ *   and finish -- which is how the hardware dispatches a grid, not a guarantee of the
  *   programming model: should a wait ever give up, hata_check() reports it (HATA_ETIMEOUT) and
  *   the step must be repeated in mode 0 or 3;
  * mode 3: always the three-launch form (no in-kernel waits). */
@@ -241,8 +264,9 @@ int hata_set_wait_limit(hata_ctx* ctx, int32_t polls);
 
 /* Waits for `stream` (hipStreamSynchronize), then reports whether a single-launch decode step of
  * this context gave up an in-kernel wait since the last check: HATA_OK, or HATA_ETIMEOUT (the
- * flag is cleared; the outputs of the steps since the last check must be discarded).  The only
- * synchronous call of the library besides hata_create(); never needed for the three-launch form. */
+ * flag and the workspace's control words are cleared; the outputs of the steps since the last
+ * check must be discarded).  The only synchronous call of the library besides hata_create();
+ * never needed for the three-launch form. */
 int hata_check(hata_ctx* ctx, void* stream);
 
 /* KV cache in host memory (the paper's offloading variant, Sec. 5.3: hash codes stay on the GPU,

@@ -1,16 +1,21 @@
 // C-ABI entry points of libhata: argument validation, workspace carving, launch-shape
 // selection and the stage sequence of one decode step (Alg. 3 of the paper).
 #include <new>
-#include <stdlib.h>
 #include <string.h>
 
 #include "hata_internal.h"
 #include "hata_trace.h"
 
 #ifdef HATA_TRACE
-__device__ unsigned long long g_hata_trace[64];
+__device__ unsigned long long g_hata_trace[HATA_TRACE_WGS * 32];
+// host_out: HATA_TRACE_WGS * 32 words (host)
 extern "C" int hata_debug_trace(unsigned long long* host_out) {
-    return (int)hipMemcpyFromSymbol(host_out, HIP_SYMBOL(g_hata_trace), sizeof(unsigned long long) * 64);
+    return (int)hipMemcpyFromSymbol(host_out, HIP_SYMBOL(g_hata_trace), sizeof(unsigned long long) * HATA_TRACE_WGS * 32);
+}
+extern "C" int hata_debug_trace_reset(void) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(g_hata_trace)) != hipSuccess) return -1;
+    return (int)hipMemset(p, 0, sizeof(unsigned long long) * HATA_TRACE_WGS * 32);
 }
 #endif
 
@@ -42,7 +47,7 @@ int validate_config(const hata_config* f) {
 }
 
 // Launch shapes.
-int make_plan(const hata_config* f, Plan* p) {
+int make_plan(const hata_config* f, const hata_tuning* t, Plan* p) {
     int rc = validate_config(f);
     if (rc != HATA_OK) return rc;
     p->G = f->Hq / f->Hkv;
@@ -58,11 +63,10 @@ int make_plan(const hata_config* f, Plan* p) {
     int chunk = 4096;
     while (chunk > 1024 && units * ((f->L_cap + chunk / 2 - 1) / (chunk / 2)) <= max_wgs) chunk >>= 1;
     while (chunk < 8192 && (f->L_cap + chunk - 1) / chunk > 1024) chunk <<= 1;
-    // tuning overrides (launch-shape sweeps): HATA_TUNE_CHUNK in {1024,2048,4096,8192},
-    // HATA_TUNE_ROWS in {16..256, power of two}; invalid values are ignored
-    if (const char* e = getenv("HATA_TUNE_CHUNK")) {
-        const int v = atoi(e);
-        if ((v == 1024 || v == 2048 || v == 4096 || v == 8192) && (f->L_cap + v - 1) / v <= 1024) chunk = v;
+    if (t && t->chunk != 0) {  // the caller's choice (launch-shape sweeps, tests of the batch slicing)
+        const int v = t->chunk;
+        if (!(v == 1024 || v == 2048 || v == 4096 || v == 8192) || (f->L_cap + v - 1) / v > 1024) return HATA_EINVAL;
+        chunk = v;
     }
     p->chunk = chunk;
     p->n_chunks = (f->L_cap + chunk - 1) / chunk;
@@ -73,9 +77,10 @@ int make_plan(const hata_config* f, Plan* p) {
     const int64_t attn_units = units * (G / p->HT);
     int rows = 256;
     while (rows > 16 && attn_units * ((f->k_max + rows - 1) / rows) < 512) rows >>= 1;
-    if (const char* e = getenv("HATA_TUNE_ROWS")) {
-        const int v = atoi(e);
-        if (v >= 16 && v <= 256 && (v & (v - 1)) == 0) rows = v;
+    if (t && t->attn_rows != 0) {
+        const int v = t->attn_rows;
+        if (v < 16 || v > 256 || (v & (v - 1)) != 0) return HATA_EINVAL;
+        rows = v;
     }
     while (rows < 256 && (f->k_max + rows - 1) / rows > 256) rows <<= 1;
     p->sparse_rows = rows;
@@ -123,7 +128,13 @@ inline int coop_sub_batches(const hata_ctx* c, int B, bool paged) {
     const int cap = paged ? c->coop_capacity_paged : c->coop_capacity;
     const int64_t per_seq = (int64_t)c->n_chunks * c->cfg.Hkv;
     if (cap <= 0 || per_seq > cap) return 0;
-    if (c->step_mode == 1) return 1;  // the whole batch in one grid, whatever its size
+    // the whole batch in one grid, whatever its size, if the workgroups of the units that are at
+    // work together -- eight units interleaved when their number is a multiple of eight, else
+    // one -- fit the device at once; otherwise in slices, as in mode 0
+    if (c->step_mode == 1) {
+        const int64_t span = ((int64_t)B * c->cfg.Hkv % 8 == 0 ? 8 : 1) * (int64_t)c->n_chunks;
+        if (span <= cap) return 1;
+    }
     const int per_launch = (int)(cap / per_seq);
     return (B + per_launch - 1) / per_launch;
 }
@@ -160,20 +171,24 @@ const char* hata_strerror(int status) {
     }
 }
 
-int hata_workspace_bytes(const hata_config* cfg, size_t* out) {
+int hata_workspace_bytes_tuned(const hata_config* cfg, const hata_tuning* tuning, size_t* out) {
     if (!out) return HATA_EINVAL;
     Plan p;
-    int rc = make_plan(cfg, &p);
+    int rc = make_plan(cfg, tuning, &p);
     if (rc != HATA_OK) return rc;
     *out = p.total;
     return HATA_OK;
 }
 
-int hata_create(hata_ctx** ctx_out, const hata_config* cfg, void* workspace, size_t workspace_bytes) {
+int hata_workspace_bytes(const hata_config* cfg, size_t* out) { return hata_workspace_bytes_tuned(cfg, nullptr, out); }
+
+int hata_create_tuned(hata_ctx** ctx_out, const hata_config* cfg, const hata_tuning* tuning, void* workspace,
+                      size_t workspace_bytes) {
     if (!ctx_out) return HATA_EINVAL;
     *ctx_out = nullptr;
+    if (tuning && (tuning->par_merge < -1 || tuning->par_merge > 1)) return HATA_EINVAL;
     Plan p;
-    int rc = make_plan(cfg, &p);
+    int rc = make_plan(cfg, tuning, &p);
     if (rc != HATA_OK) return rc;
     if (!workspace || !aligned(workspace, kAlign) || workspace_bytes < p.total) return HATA_EWORKSPACE;
     hata_ctx* c = new (std::nothrow) hata_ctx;
@@ -200,23 +215,35 @@ int hata_create(hata_ctx** ctx_out, const hata_config* cfg, void* workspace, siz
     c->coop_capacity = 0;
     c->coop_capacity_paged = 0;
     c->partials = (float*)(w + p.off_partials);
+    c->control_bytes = p.off_partials - p.off_cinfo;
     // control words and the self-resetting arrival counters start from zero
-    if (hipMemset(c->chunk_info, 0, p.off_partials - p.off_cinfo) != hipSuccess) {
+    if (hipMemset(c->chunk_info, 0, c->control_bytes) != hipSuccess) {
         delete c;
         return HATA_EHIP;
     }
+    // the device's size is looked up once, here: no launch queries the runtime
+    int dev = 0;
+    c->cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&c->cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
+        c->cus = 0;
     c->coop_capacity = hata::coop_capacity(c, false);
     c->coop_capacity_paged = hata::coop_capacity(c, true);
-    c->step_mode = 0;
+    // a device shared with other work cannot promise that a whole grid is resident: three launches
+    c->step_mode = (tuning && tuning->shared_device) ? 3 : 0;
     c->spin_limit = 0;
     c->keep_scores = 0;
     // with more than one query head per KV head the merge is spread over the unit's workgroups,
     // a head each (measured: never slower, 1-5 us faster with many slices or heads; with one head
-    // the last arriver merging alone is 0.6 us faster); HATA_TUNE_PARMERGE = 0 / 1 overrides
+    // the last arriver merging alone is 0.6 us faster)
     c->par_merge = c->G >= 2 ? 1 : 0;
-    if (const char* e = getenv("HATA_TUNE_PARMERGE")) c->par_merge = atoi(e) != 0 ? 1 : 0;
+    if (tuning && tuning->par_merge >= 0) c->par_merge = tuning->par_merge;
     *ctx_out = c;
     return HATA_OK;
+}
+
+int hata_create(hata_ctx** ctx_out, const hata_config* cfg, void* workspace, size_t workspace_bytes) {
+    return hata_create_tuned(ctx_out, cfg, nullptr, workspace, workspace_bytes);
 }
 
 int hata_destroy(hata_ctx* ctx) {
@@ -437,7 +464,9 @@ int hata_check(hata_ctx* ctx, void* stream) {
     uint32_t w = 0;
     if (hipMemcpy(&w, ctx->error_word, sizeof(w), hipMemcpyDeviceToHost) != hipSuccess) return HATA_EHIP;
     if (!w) return HATA_OK;
-    if (hipMemset(ctx->error_word, 0, sizeof(w)) != hipSuccess) return HATA_EHIP;
+    // a step that gave up may have left counters and published words half-way: start clean again
+    // (the stream is idle here)
+    if (hipMemset(ctx->chunk_info, 0, ctx->control_bytes) != hipSuccess) return HATA_EHIP;
     return HATA_ETIMEOUT;
 }
 

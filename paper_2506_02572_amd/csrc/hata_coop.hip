@@ -66,6 +66,7 @@ struct CoopArgs {
     int prefetch;     // fetch the first batch of key codes before the query codes are known
     int keep_scores;  // also write the score array (a by-product the kernel itself never reads back)
     int par_merge;    // the heads of a unit are merged side by side by several of its workgroups
+    int cmajor;       // workgroup order: chunk-major (every unit's chunk 0 first) instead of unit-major
     hata::PageView pv;  // block table (used by the PAGED instantiations only)
 };
 
@@ -210,19 +211,30 @@ __global__ __launch_bounds__(256, (G >= 16 ? 2 : 3)) void decode_step_coop_kerne
     __shared__ int s_flag;
     __shared__ uint32_t s_rec[2];
     __shared__ int s_low;  // lowest score of this chunk
+    __shared__ int s_bad;  // this workgroup gave up a wait: the unit's outputs are invalid
     __shared__ uint32_t s_codes[(G + 1) * WD];  // codes of the G query heads and of the appended key
     // PAGED: where the pages of this chunk's rows start (pages of 16 rows or more: at most MAX_CHUNK / 16 + 1)
     __shared__ int s_page[PAGED ? HATA_COOP_MAX_CHUNK / 16 + 2 : 1];
     const int tid = threadIdx.x;
     // Workgroup -> (unit, chunk).  Consecutive workgroup ids go to consecutive XCDs (8 of them, each
     // with its own L2); when the unit count allows, all chunks of a unit get ids that are equal
-    // mod 8, so one L2 serves the unit's hash weights and the data its workgroups exchange.
+    // mod 8, so one L2 serves the unit's hash weights and the data its workgroups exchange.  Within
+    // an XCD the order is chunk-major when the whole grid is resident: workgroups start in index
+    // order, so every unit's chunk 0 .. G-1 -- the ones that encode the query vectors everybody waits
+    // for -- start first, and the chunks past the end of short sequences, which return at once,
+    // start last (measured against unit-major: 2 us per step with 32 and with 128 units).
     int64_t u;
     int c;
     if (a.units % 8 == 0) {
         const int j = blockIdx.x >> 3;
-        u = (int64_t)(j / a.n_chunks) * 8 + (blockIdx.x & 7);
-        c = j % a.n_chunks;
+        if (a.cmajor) {
+            const int ug = a.units >> 3;  // groups of 8 units
+            u = (int64_t)(j % ug) * 8 + (blockIdx.x & 7);
+            c = j / ug;
+        } else {
+            u = (int64_t)(j / a.n_chunks) * 8 + (blockIdx.x & 7);
+            c = j % a.n_chunks;
+        }
     } else {
         u = blockIdx.x / a.n_chunks;
         c = blockIdx.x % a.n_chunks;
@@ -262,8 +274,8 @@ __global__ __launch_bounds__(256, (G >= 16 ? 2 : 3)) void decode_step_coop_kerne
     uint16_t* outp = a.out + ((int64_t)b * a.Hq + hq0) * HATA_D;
     float* outp32 = a.out_f32 ? a.out_f32 + ((int64_t)b * a.Hq + hq0) * HATA_D : nullptr;
     if (base >= L && c != 0) return;  // chunk 0 always runs the encoding (it publishes the query codes)
-#define TC(i) HATA_TRACE_AT(i, u == 0 && c == 0)
-#define TU(i) HATA_TRACE_AT(i, u == 0)
+#define TC(i) HATA_TRACE_AT(i, true)
+#define TU(i) HATA_TRACE_AT(i, true)
     TC(40);
     const int end = min(base + a.chunk, L);
     // ---- 0. HashEncode(Q) and HashEncode(K_new).  The G query vectors of the unit are dealt out
@@ -303,7 +315,7 @@ __global__ __launch_bounds__(256, (G >= 16 ? 2 : 3)) void decode_step_coop_kerne
         unsigned long long* qrec_u = a.qrec + u * a.n_chunks * (G * WD);
         unsigned long long* qrec = qrec_u + c * (G * WD);
         if (tid < (G + 1) * WD) s_codes[tid] = 0;
-        if (tid == 0) s_low = a.NB;
+        if (tid == 0) { s_low = a.NB; s_bad = 0; }
         for (int i = tid; i < a.NB; i += 256) hist[i] = 0;
         if constexpr (PAGED) {
             if (tid < nblk) s_page[tid] = (clampi(my_page, 0, a.pv.n_pages - 1) * a.Hkv + h) << a.pv.shift;
@@ -341,7 +353,7 @@ __global__ __launch_bounds__(256, (G >= 16 ? 2 : 3)) void decode_step_coop_kerne
                 r = __hip_atomic_load(qrec + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 const bool miss = (uint32_t)(r >> 32) != a.epoch;
                 if (__builtin_amdgcn_ballot_w64(miss) == 0ull) break;
-                if (--budget <= 0) { if (tid == 0) a.error_word[0] = 1u; break; }  // gave up: results invalid
+                if (--budget <= 0) { if (tid == 0) { a.error_word[0] = 1u; s_bad = 1; } break; }  // gave up: results invalid
                 __builtin_amdgcn_s_sleep(1);
             }
             if (tid < G * WD) {
@@ -473,7 +485,7 @@ __global__ __launch_bounds__(256, (G >= 16 ? 2 : 3)) void decode_step_coop_kerne
             if (((uint32_t)(r0 >> 32) == a.epoch && (uint32_t)(r1 >> 32) == a.epoch) || --budget <= 0) break;
             __builtin_amdgcn_s_sleep(1);
         }
-        if (budget <= 0) { a.error_word[0] = 1u; r0 = 0; r1 = 0; }  // gave up: this launch's results are invalid
+        if (budget <= 0) { a.error_word[0] = 1u; s_bad = 1; r0 = 0; r1 = 0; }  // gave up: this launch's results are invalid
         s_rec[0] = (uint32_t)r0;
         s_rec[1] = (uint32_t)r1;
         // this workgroup is the record's only reader: retired at once (see the query code words above)
@@ -568,29 +580,48 @@ __global__ __launch_bounds__(256, (G >= 16 ? 2 : 3)) void decode_step_coop_kerne
     const int64_t head_stride = (int64_t)a.n_chunks * HATA_PSTRIDE;
     float* part0 = a.partials + ((int64_t)b * a.Hq + hq0) * head_stride;
     attn_emit<G>(S, nc == 1, outp, outp32, part0 + (int64_t)c * HATA_PSTRIDE, head_stride);
-    if (nc == 1) return;
+    // A wait that gave up leaves the unit without valid results.  That is made visible in the data
+    // itself: the workgroup that writes a head's output overwrites it with NaN, and whoever writes
+    // head 0 also sets the unit's index list to -1 (a caller that never calls hata_check() still
+    // cannot mistake the step for a good one).  The arrival counter carries the news: bits 0..9
+    // count arrivals, bits 10..19 the arrivals that had given up a wait, bits 20..31 the sign-offs.
+    auto poison = [&](int g) {
+        if (tid < HATA_D) {
+            outp[g * HATA_D + tid] = 0x7fc0;
+            if (outp32) outp32[g * HATA_D + tid] = __builtin_nanf("");
+        }
+        if (g == 0)
+            for (int p = tid; p < a.k_max; p += 256) io[p] = -1;
+    };
+    if (nc == 1) {
+        if (s_bad)
+            for (int g = 0; g < G; ++g) poison(g);
+        return;
+    }
     TC(48);
     wait_stores();
     __syncthreads();
+    uint32_t* cntp = a.attn_counter + u * HATA_COUNTER_STRIDE;
+    const uint32_t arrival = 1u + (s_bad ? (1u << 10) : 0u);
     if (a.par_merge) {
-        // Many slices x many heads: every workgroup arrives (low half of the unit's counter); the
-        // first nm = min(G, nc) workgroups of the unit wait for all nc arrivals, sign off (high
-        // half: "I no longer look at the counter") and merge one query head each (heads c,
-        // c + nm, ...).  Whoever brings the counter to its final value clears it.
-        uint32_t* cntp = a.attn_counter + u * HATA_COUNTER_STRIDE;
+        // Many slices x many heads: every workgroup arrives; the first nm = min(G, nc) workgroups
+        // of the unit wait for all nc arrivals, sign off ("I no longer look at the counter") and
+        // merge one query head each (heads c, c + nm, ...).  Whoever brings the counter to its final
+        // value -- nc arrivals, nm sign-offs -- clears it.
         const int nm = min(G, nc);
-        const uint32_t all_done = ((uint32_t)nm << 16) | (uint32_t)nc;
+        auto final_value = [&](uint32_t v) { return (v & 0x3ffu) == (uint32_t)nc && (v >> 20) == (uint32_t)nm; };
         if (tid == 0) {
-            uint32_t seen = atomicAdd(cntp, 1u) + 1u;
+            uint32_t seen = atomicAdd(cntp, arrival) + arrival;
             if (c >= nm) {
-                if (seen == all_done) *cntp = 0;  // (possible only after a merging workgroup gave up its wait)
+                if (final_value(seen)) *cntp = 0;  // (possible only after a merging workgroup gave up its wait)
             } else {
                 int budget = a.spin_limit;
-                while ((seen & 0xffffu) != (uint32_t)nc) {
-                    if (--budget <= 0) { a.error_word[0] = 1u; break; }  // gave up: results invalid
+                while ((seen & 0x3ffu) != (uint32_t)nc) {
+                    if (--budget <= 0) { a.error_word[0] = 1u; s_bad = 1; break; }  // gave up: results invalid
                     __builtin_amdgcn_s_sleep(1);
                     seen = __hip_atomic_load(cntp, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 }
+                if ((seen >> 10) & 0x3ffu) s_bad = 1;  // some workgroup of the unit gave up a wait
             }
         }
         if (c >= nm) return;
@@ -598,20 +629,22 @@ __global__ __launch_bounds__(256, (G >= 16 ? 2 : 3)) void decode_step_coop_kerne
         // the sign-off goes out now and is looked at after the merge (one lane of the last wave: its
         // return value queues behind that lane's own partial loads)
         uint32_t signed_off = 0;
-        if (tid == 255) signed_off = atomicAdd(cntp, 0x10000u) + 0x10000u;
+        if (tid == 255) signed_off = atomicAdd(cntp, 1u << 20) + (1u << 20);
         float* sm = &S.acc[0][0][0];
         for (int g = c; g < G; g += nm) {
             if (g != c) __syncthreads();  // the previous head's use of sm
             attn_merge_head<16>(sm, part0 + g * head_stride, nc, outp + g * HATA_D, outp32 ? outp32 + g * HATA_D : nullptr);
+            if (s_bad) poison(g);
         }
-        if (tid == 255 && signed_off == all_done) *cntp = 0;
+        if (tid == 255 && final_value(signed_off)) *cntp = 0;
+        TU(54);
         return;
     }
     if (tid == 0) {
-        uint32_t* cntp = a.attn_counter + u * HATA_COUNTER_STRIDE;
-        const uint32_t done = atomicAdd(cntp, 1u);
-        const int last = (done == (uint32_t)(nc - 1));
+        const uint32_t done = atomicAdd(cntp, arrival);
+        const int last = ((done & 0x3ffu) == (uint32_t)(nc - 1));
         if (last) *cntp = 0;
+        if (done >> 10) s_bad = 1;
         s_flag = last;
     }
     __syncthreads();
@@ -619,6 +652,8 @@ __global__ __launch_bounds__(256, (G >= 16 ? 2 : 3)) void decode_step_coop_kerne
     if (!s_flag) return;
     TU(53);
     attn_merge<G>(S, part0, head_stride, nc, outp, outp32);
+    if (s_bad)
+        for (int g = 0; g < G; ++g) poison(g);
     TU(54);
 #undef TC
 #undef TU
@@ -662,11 +697,10 @@ static const void* coop_kernel_for(int Wd, int G, bool paged) {
 int coop_capacity(const hata_ctx* c, bool paged) {
     const void* fn = coop_kernel_for(c->Wd, c->G, paged);
     if (!fn || c->chunk > HATA_COOP_MAX_CHUNK) return 0;
-    int per_cu = 0, dev = 0, cus = 0;
-    if (hipGetDevice(&dev) != hipSuccess) return 0;
-    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
+    int per_cu = 0;
+    if (c->cus <= 0) return 0;
     if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, 256, (size_t)c->NB * 4) != hipSuccess) return 0;
-    return per_cu * cus;
+    return per_cu * c->cus;
 }
 
 hipError_t launch_coop_step(hata_ctx* c, const void* q, const void* K, const void* V,
@@ -682,6 +716,9 @@ hipError_t launch_coop_step(hata_ctx* c, const void* q, const void* K, const voi
     a.spin_limit = c->spin_limit > 0 ? c->spin_limit : HATA_COOP_SPIN_LIMIT;
     a.keep_scores = c->keep_scores;
     a.par_merge = c->par_merge;
+    // chunk-major order needs the whole grid resident (an oversubscribed grid relies on a unit's
+    // workgroups having neighbouring indices)
+    a.cmajor = (c->step_mode != 1) ? 1 : 0;
     a.pv = pages ? *pages : PageView{nullptr, 0, 0, 0};
     // sequences [b0, b0 + B) of the caller's batch: every per-sequence and per-unit base moves up
     const int64_t u0 = (int64_t)b0 * f.Hkv;
@@ -697,13 +734,8 @@ hipError_t launch_coop_step(hata_ctx* c, const void* q, const void* K, const voi
     k += b0;
     out = (uint16_t*)out + (int64_t)b0 * f.Hq * HATA_D;
     if (out_f32) out_f32 += (int64_t)b0 * f.Hq * HATA_D;
-    {
-        int dev = 0, cus = 0;
-        a.prefetch = 0;
-        if (hipGetDevice(&dev) == hipSuccess &&
-            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess)
-            a.prefetch = (int64_t)c->n_chunks * f.Hkv * B <= cus ? 1 : 0;  // (measured: pays up to one workgroup per CU)
-    }
+    // small grids (at most one workgroup per CU): the first batch of key codes is fetched ahead
+    a.prefetch = (c->cus > 0 && (int64_t)c->n_chunks * f.Hkv * B <= c->cus) ? 1 : 0;
     a.qcodes = c->qcodes + (int64_t)b0 * f.Hq * c->Wd; a.codes = codes; a.seq_len = seq_len; a.kbud = k;
     a.scores = c->scores + u0 * f.L_cap; a.idx = c->idx + u0 * f.k_max;
     a.chunk_hist = c->chunk_hist + u0 * c->n_chunks * c->NBP;

@@ -44,9 +44,11 @@ struct hata_ctx {
     int keep_scores;         // single-launch step also writes the score array
     int par_merge;           // single-launch step merges the heads of a unit in several workgroups
     int step_mode;           // 0 = single launch when it fits, 3 = always three launches
+    int cus;                 // compute units of the device that was current in hata_create
     int coop_capacity;       // workgroups of the cooperative kernel that can be resident at once (0 = unusable)
     int coop_capacity_paged; // the same for the block-table variant of that kernel
     float* partials;       // [B_max*Hq, max(sparse_splits, dense_splits), d + 2]
+    size_t control_bytes;  // bytes from chunk_info up to the partials: the control words, cleared at creation and after a give-up
 };
 
 namespace hata {

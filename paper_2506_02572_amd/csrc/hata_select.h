@@ -126,7 +126,7 @@ __device__ __forceinline__ void unit_threshold(
     const float low_w = wave_max64(-(float)first_nz);
     if (lane == 63) { S.wtot[wave] = incl_w; S.wlow[wave] = low_w; }
     __syncthreads();
-    HATA_TRACE_AT(10, FUSED && blockIdx.x < 8);
+    HATA_TRACE_AT(26, FUSED);
     {
         const uint32_t w0 = S.wtot[0], w1 = S.wtot[1], w2 = S.wtot[2];
         const uint32_t before = (wave > 0 ? w0 : 0u) + (wave > 1 ? w1 : 0u) + (wave > 2 ? w2 : 0u) + incl_w - local;
@@ -148,7 +148,7 @@ __device__ __forceinline__ void unit_threshold(
     }
     __syncthreads();
     const int T = S.T, need = S.need;
-    HATA_TRACE_AT(11, FUSED && blockIdx.x < 8);
+    HATA_TRACE_AT(27, FUSED);
     // per chunk: keys below T and keys equal to T, from columns [bmin / 8, T / 8] of its row
     auto count_item = [&](const Bins8& v, int c, int col) {
         uint32_t lt = 0;
@@ -194,7 +194,7 @@ __device__ __forceinline__ void unit_threshold(
         }
     }
     __syncthreads();
-    HATA_TRACE_AT(12, FUSED && blockIdx.x < 8);
+    HATA_TRACE_AT(28, FUSED);
     // ordered offsets: ties are granted to chunks in cache order.  One wave: lane l owns chunks
     // [l*cpl, (l+1)*cpl); two wave scans (ties seen so far, then selected so far), no barrier.
     if (tid < 64) {
@@ -234,7 +234,7 @@ __device__ __forceinline__ void unit_threshold(
             eqb += S.c_eq[c];
         }
     }
-    HATA_TRACE_AT(13, FUSED && blockIdx.x < 8);
+    HATA_TRACE_AT(29, FUSED);
     if (tid == 0 && !rec_u) {
         // (write-through: the next launch's workgroups read these)
         st_dev(reinterpret_cast<uint32_t*>(chunk_info_u) + nc * 2 + 0, (uint32_t)keff);

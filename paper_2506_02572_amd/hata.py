@@ -15,7 +15,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libhata.so")
 
 EXPORTS = (
-    "hata_strerror", "hata_workspace_bytes", "hata_create", "hata_destroy", "hata_encode_keys",
+    "hata_strerror", "hata_workspace_bytes", "hata_workspace_bytes_tuned", "hata_create", "hata_create_tuned",
+    "hata_destroy", "hata_encode_keys",
     "hata_prefill_write", "hata_prefill_write_paged", "hata_encode_query", "hata_hamming_score", "hata_topk", "hata_sparse_decode",
     "hata_dense_decode", "hata_decode_step", "hata_decode_step_paged", "hata_step_plan", "hata_step_sub_batches", "hata_set_step_mode", "hata_keep_step_scores", "hata_set_wait_limit",
     "hata_check",
@@ -35,6 +36,11 @@ class hata_config(ctypes.Structure):
         ("kv_stride_b", ctypes.c_int64), ("kv_stride_h", ctypes.c_int64),
         ("kv_stride_n", ctypes.c_int64),
     ]
+
+
+class hata_tuning(ctypes.Structure):
+    _fields_ = [("chunk", ctypes.c_int32), ("attn_rows", ctypes.c_int32), ("par_merge", ctypes.c_int32),
+                ("shared_device", ctypes.c_int32)]
 
 
 _lib = None
@@ -60,6 +66,10 @@ def load_library(build_if_missing: bool = True) -> ctypes.CDLL:
     lib.hata_strerror.argtypes = [ctypes.c_int]
     lib.hata_workspace_bytes.argtypes = [ctypes.POINTER(hata_config), ctypes.POINTER(ctypes.c_size_t)]
     lib.hata_create.argtypes = [ctypes.POINTER(_vp), ctypes.POINTER(hata_config), _vp, ctypes.c_size_t]
+    lib.hata_workspace_bytes_tuned.argtypes = [ctypes.POINTER(hata_config), ctypes.POINTER(hata_tuning),
+                                               ctypes.POINTER(ctypes.c_size_t)]
+    lib.hata_create_tuned.argtypes = [ctypes.POINTER(_vp), ctypes.POINTER(hata_config), ctypes.POINTER(hata_tuning),
+                                      _vp, ctypes.c_size_t]
     lib.hata_destroy.argtypes = [_vp]
     lib.hata_encode_keys.argtypes = [_vp, _vp, _vp, _vp, _vp, _i32, _i32, _vp, _vp]
     lib.hata_prefill_write.argtypes = [_vp, _vp, _vp, _vp, _vp, _i32, _i32, _vp, _vp, _vp, _vp, _vp]
@@ -133,7 +143,8 @@ class Shape:
 class Context:
     """Owns a hata_ctx and the torch-allocated workspace it points into."""
 
-    def __init__(self, B_max, Hq, Hkv, d, r, L_cap, k_max, kv_strides=None, device="cuda:0"):
+    def __init__(self, B_max, Hq, Hkv, d, r, L_cap, k_max, kv_strides=None, device="cuda:0", chunk=0,
+                 attn_rows=0, par_merge=-1, shared_device=False):
         import torch
         lib = load_library()
         if not torch.cuda.is_available():
@@ -142,17 +153,18 @@ class Context:
         if kv_strides is None:
             kv_strides = (Hkv * L_cap * d, L_cap * d, d)
         self.cfg = hata_config(B_max, Hq, Hkv, d, r, L_cap, k_max, *kv_strides)
+        self.tuning = hata_tuning(chunk, attn_rows, par_merge, 1 if shared_device else 0)
         nbytes = ctypes.c_size_t(0)
-        _check(lib.hata_workspace_bytes(ctypes.byref(self.cfg), ctypes.byref(nbytes)),
-               "hata_workspace_bytes")
+        _check(lib.hata_workspace_bytes_tuned(ctypes.byref(self.cfg), ctypes.byref(self.tuning), ctypes.byref(nbytes)),
+               "hata_workspace_bytes_tuned")
         self.device = torch.device(device)
         self.workspace = torch.empty(nbytes.value + 256, dtype=torch.uint8, device=self.device)
         base = self.workspace.data_ptr()
         self._ws_ptr = (base + 255) // 256 * 256
         self._h = ctypes.c_void_p(None)
         with torch.cuda.device(self.device):
-            _check(lib.hata_create(ctypes.byref(self._h), ctypes.byref(self.cfg),
-                                   ctypes.c_void_p(self._ws_ptr), nbytes.value), "hata_create")
+            _check(lib.hata_create_tuned(ctypes.byref(self._h), ctypes.byref(self.cfg), ctypes.byref(self.tuning),
+                                         ctypes.c_void_p(self._ws_ptr), nbytes.value), "hata_create_tuned")
         self.workspace_bytes = nbytes.value
 
     def close(self):

@@ -70,13 +70,13 @@ def check_codes(got: np.ndarray, ref: np.ndarray, near: np.ndarray, what=""):
 class Case:
     """One workload on the device, with its oracle-side twin on the host."""
 
-    def __init__(self, w: synth.Workload, seed: int = synth.DEFAULT_SEED, oracle_codes: bool = True):
+    def __init__(self, w: synth.Workload, seed: int = synth.DEFAULT_SEED, oracle_codes: bool = True, **tuning):
         import torch
         from paper_2506_02572_amd import hata
         self.w = w
         self.inp = synth.generate(w, seed)
         self.scale = 1.0 / math.sqrt(w.d)
-        self.ctx = hata.Context(w.B, w.Hq, w.Hkv, w.d, w.r, w.L_cap, w.k_max)
+        self.ctx = hata.Context(w.B, w.Hq, w.Hkv, w.d, w.r, w.L_cap, w.k_max, **tuning)
         self.K = to_dev(self.inp.K)
         self.V = to_dev(self.inp.V)
         self.W_H = to_dev(self.inp.W_H)
