@@ -56,7 +56,8 @@ typedef enum {
     HATA_EUNSUPPORTED = -2, /* a shape this build has no kernel for */
     HATA_EWORKSPACE = -3,   /* workspace NULL, misaligned or too small */
     HATA_EHIP = -4,         /* a HIP runtime call failed (launch error, no device, ...) */
-    HATA_ETIMEOUT = -5      /* hata_check(): a single-launch decode step gave up its bounded in-kernel wait */
+    HATA_ETIMEOUT = -5,     /* hata_check(): a single-launch decode step gave up its bounded in-kernel wait */
+    HATA_ETOOLARGE = -6     /* hata_sparse_decode_static(): the shape needs more scratch than its static buffer holds */
 } hata_status;
 
 typedef struct {
@@ -154,6 +155,21 @@ int hata_topk(hata_ctx* ctx, const uint16_t* scores, const int32_t* seq_len, con
 int hata_sparse_decode(hata_ctx* ctx, const void* q, const void* K, const void* V,
                        const int32_t* idx, const int32_t* k, int32_t B, float sm_scale,
                        void* out, float* out_f32, void* stream);
+
+/* hata_sparse_decode for callers that cannot allocate device memory or keep a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments
+ * (the shape is passed as the config itself, host pointer; no context), same kernels, same
+ * results bit for bit; the attention partials and their arrival counters live in a buffer that
+ * is part of the library's device image: 8 MiB per device, held until the process ends.
+ * Limit: align256(B_max * Hq * 4) + B_max * Hq * splits * 520 bytes <= 8 MiB, where splits is the
+ * number of row slices the launch plan cuts k_max into (at most 256); larger shapes return
+ * HATA_ETOOLARGE and enqueue nothing.  The call allocates nothing, frees nothing, and only
+ * enqueues kernels (a small fill kernel clears the counters first, so it may be captured).
+ * Every call on a device uses that device's one buffer: calls that overlap in time on one device
+ * (different streams, different threads) race and must be serialised by the caller. */
+int hata_sparse_decode_static(const hata_config* cfg, const void* q, const void* K, const void* V,
+                              const int32_t* idx, const int32_t* k, int32_t B, float sm_scale,
+                              void* out, float* out_f32, void* stream);
 
 /* Dense decode attention over the whole cache (Eq. 1), rows 0 .. seq_len[b]-1: the baseline the
  * sparse path is compared with.  Same numerics and outputs as hata_sparse_decode. */

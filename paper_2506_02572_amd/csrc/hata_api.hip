@@ -1,5 +1,6 @@
 // C-ABI entry points of libhata: argument validation, workspace carving, launch-shape
 // selection and the stage sequence of one decode step (Alg. 3 of the paper).
+#include <mutex>
 #include <new>
 #include <string.h>
 
@@ -19,9 +20,23 @@ extern "C" int hata_debug_trace_reset(void) {
 }
 #endif
 
+// Scratch of hata_sparse_decode_static(): attention partials and their arrival counters for callers
+// that cannot hand over a workspace.  One copy per device the library runs on, held until the
+// process ends.  In host code this name is only a handle for hipGetSymbolAddress(); kernels are
+// given the per-device address looked up below.
+#define HATA_STATIC_SCRATCH_BYTES (8u << 20)
+static __device__ __align__(256) unsigned char scratch[HATA_STATIC_SCRATCH_BYTES];
+
+// fills n words with zero (used instead of a memset node so that the call may be captured in a graph)
+__global__ __launch_bounds__(256) void zero_words_kernel(uint32_t* p, int n) {
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i < n) p[i] = 0u;
+}
+
 namespace {
 
 constexpr size_t kAlign = 256;
+constexpr int kMaxDevices = 64;
 inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
 struct Plan {
@@ -167,6 +182,7 @@ const char* hata_strerror(int status) {
         case HATA_EWORKSPACE: return "workspace missing, misaligned or too small";
         case HATA_EHIP: return "HIP runtime error";
         case HATA_ETIMEOUT: return "a single-launch decode step gave up an in-kernel wait";
+        case HATA_ETOOLARGE: return "shape needs more scratch than the static buffer of the allocation-free entry point holds";
         default: return "unknown status";
     }
 }
@@ -355,6 +371,50 @@ int hata_dense_decode(hata_ctx* ctx, const void* q, const void* K, const void* V
     if (!aligned(q, 16) || !aligned(K, 16) || !aligned(V, 16) || !aligned(out, 2)) return HATA_EINVAL;
     return hip_rc(hata::launch_attention(ctx, 1, q, K, V, nullptr, seq_len, seq_len, B, sm_scale,
                                          out, out_f32, (hipStream_t)stream));
+}
+
+int hata_sparse_decode_static(const hata_config* cfg, const void* q, const void* K, const void* V,
+                              const int32_t* idx, const int32_t* k, int32_t B, float sm_scale, void* out,
+                              float* out_f32, void* stream) {
+    Plan p;
+    int rc = make_plan(cfg, nullptr, &p);
+    if (rc != HATA_OK) return rc;
+    if (B < 1 || B > cfg->B_max) return HATA_EINVAL;
+    if (!q || !K || !V || !idx || !k || !out) return HATA_EINVAL;
+    if (!aligned(q, 16) || !aligned(K, 16) || !aligned(V, 16) || !aligned(out, 2)) return HATA_EINVAL;
+    // layout inside the scratch: [arrival counters of B_max * Hq head tiles][partials]
+    const size_t counter_bytes = align_up((size_t)cfg->B_max * cfg->Hq * 4);
+    const size_t partial_bytes = (size_t)cfg->B_max * cfg->Hq * p.sparse_splits * (128 + 2) * 4;
+    if (counter_bytes + partial_bytes > HATA_STATIC_SCRATCH_BYTES) return HATA_ETOOLARGE;
+    // the device copy of `scratch` that belongs to the current device, looked up once per device
+    static std::mutex mu;
+    static void* dev_ptr[kMaxDevices] = {};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return HATA_EHIP;
+    void* base = nullptr;
+    {
+        std::lock_guard<std::mutex> lock(mu);
+        if (!dev_ptr[dev]) {
+            void* sym = nullptr;
+            if (hipGetSymbolAddress(&sym, HIP_SYMBOL(scratch)) != hipSuccess || !sym) return HATA_EHIP;
+            dev_ptr[dev] = sym;
+        }
+        base = dev_ptr[dev];
+    }
+    hata_ctx c = {};
+    c.cfg = *cfg;
+    c.G = p.G; c.Wd = p.Wd; c.NB = p.NB; c.NBP = p.NBP; c.chunk = p.chunk; c.n_chunks = p.n_chunks; c.HT = p.HT;
+    c.sparse_rows = p.sparse_rows; c.sparse_splits = p.sparse_splits;
+    c.dense_rows = p.dense_rows; c.dense_splits = p.dense_splits;
+    c.attn_counter = (uint32_t*)base;
+    c.partials = (float*)((char*)base + counter_bytes);
+    hipStream_t s = (hipStream_t)stream;
+    // the counters must start at zero whatever an earlier call left behind
+    const int n_cnt = cfg->B_max * cfg->Hq;
+    hipLaunchKernelGGL(zero_words_kernel, dim3((n_cnt + 255) / 256), dim3(256), 0, s, c.attn_counter, n_cnt);
+    if (hipGetLastError() != hipSuccess) return HATA_EHIP;
+    return hip_rc(hata::launch_attention(&c, 0, q, K, V, const_cast<int32_t*>(idx), k, nullptr, B, sm_scale, out,
+                                         out_f32, s));
 }
 
 int hata_decode_step(hata_ctx* ctx, const void* q, const void* K, const void* V, const float* W_H,

@@ -18,7 +18,7 @@ EXPORTS = (
     "hata_strerror", "hata_workspace_bytes", "hata_workspace_bytes_tuned", "hata_create", "hata_create_tuned",
     "hata_destroy", "hata_encode_keys",
     "hata_prefill_write", "hata_prefill_write_paged", "hata_encode_query", "hata_hamming_score", "hata_topk", "hata_sparse_decode",
-    "hata_dense_decode", "hata_decode_step", "hata_decode_step_paged", "hata_step_plan", "hata_step_sub_batches", "hata_set_step_mode", "hata_keep_step_scores", "hata_set_wait_limit",
+    "hata_sparse_decode_static", "hata_dense_decode", "hata_decode_step", "hata_decode_step_paged", "hata_step_plan", "hata_step_sub_batches", "hata_set_step_mode", "hata_keep_step_scores", "hata_set_wait_limit",
     "hata_check",
     "hata_host_device_pointer", "hata_step_buffers",
 )
@@ -79,6 +79,8 @@ def load_library(build_if_missing: bool = True) -> ctypes.CDLL:
     lib.hata_hamming_score.argtypes = [_vp, _vp, _vp, _vp, _i32, _vp, _vp]
     lib.hata_topk.argtypes = [_vp, _vp, _vp, _vp, _i32, _vp, _vp]
     lib.hata_sparse_decode.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _i32, ctypes.c_float, _vp, _vp, _vp]
+    lib.hata_sparse_decode_static.argtypes = [ctypes.POINTER(hata_config), _vp, _vp, _vp, _vp, _vp, _i32,
+                                              ctypes.c_float, _vp, _vp, _vp]
     lib.hata_dense_decode.argtypes = [_vp, _vp, _vp, _vp, _vp, _i32, ctypes.c_float, _vp, _vp, _vp]
     lib.hata_decode_step.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32,
                                      ctypes.c_float, _vp, _vp, _vp]
@@ -212,6 +214,12 @@ class Context:
         _check(load_library().hata_sparse_decode(self._h, _ptr(q), _ptr(K), _ptr(V), _ptr(idx), _ptr(k),
                                                  B, sm_scale, _ptr(out), _ptr(out_f32),
                                                  _stream(stream)), "hata_sparse_decode")
+
+    def hata_sparse_decode_static(self, q, K, V, idx, k, B, sm_scale, out, out_f32=None, stream=None):
+        """The allocation-free variant: uses this context's shape only, not its workspace."""
+        _check(load_library().hata_sparse_decode_static(ctypes.byref(self.cfg), _ptr(q), _ptr(K), _ptr(V), _ptr(idx),
+                                                        _ptr(k), B, sm_scale, _ptr(out), _ptr(out_f32),
+                                                        _stream(stream)), "hata_sparse_decode_static")
 
     def hata_dense_decode(self, q, K, V, seq_len, B, sm_scale, out, out_f32=None, stream=None):
         _check(load_library().hata_dense_decode(self._h, _ptr(q), _ptr(K), _ptr(V), _ptr(seq_len), B,
