@@ -8,10 +8,14 @@ synthetic, resident in HBM before the timed region.  Consecutive steps rotate ov
 distinct copies ("layers") of the K/V/code caches so that the traffic is HBM traffic and
 not Infinity-Cache hits, as a model with tens of layers does for every token.
 
-Prints ONE JSON line.  Beside the step itself it carries separately timed legs of the same
-library: the scoring stage alone, the prefill key encode and the fused prefill cache fill, dense
-attention (the comparison baseline), 32 layer steps replayed from one HIP graph, the step on the
-paged cache layout (--paged), the learning-to-hash training step, and the CPU oracle.
+Prints ONE JSON line.  The headline (value, roofline, cpu_baseline) is the workload named by
+--workload (default: configuration 2), timed over exactly --steps steps after --warmup.  Beside it
+the line carries separately timed legs of the same library (scoring stage alone, prefill key
+encode and fused prefill cache fill, dense attention, 32 layer steps replayed from one HIP graph,
+the paged layout, the KV cache in host memory with and without a staged prefetch, the
+learning-to-hash training step), and -- in the default run -- "per_config": the step of
+configurations 2, 3, 4 and 5 at full size, each with its own steady-state timing, roofline
+fraction, dense comparison and parity against the oracle.
 """
 from __future__ import annotations
 
@@ -27,11 +31,15 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0
+PER_CONFIG_STEPS = 300   # timed steps of every per_config entry (the headline takes --steps)
+PER_CONFIG_WARMUP = 40
 
-# HBM bytes per launch, from the rocprofv3 --pmc runs summarised in profiles/hbm_traffic_pmc.md:
-# FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0 (factors from a plain 256 MiB copy in the same runs).
-# "step": the single-launch decode step (decode_step_coop_kernel); "score": the scoring kernel
-# alone (hata_hamming_score).  None = not measured for that workload.
+# HBM bytes per launch from the rocprofv3 --pmc runs summarised in profiles/hbm_traffic_pmc.md
+# (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, factors from a plain 256 MiB copy in the same runs).  A
+# constant of the build the profile names, not a value measured by the run that prints it: the
+# "traffic_source" field of the output says so.  "step": the single-launch decode step
+# (decode_step_coop_kernel); "score": the scoring kernel alone (hata_hamming_score).
+HBM_TRAFFIC_SOURCE = "profiles/hbm_traffic_pmc.md"
 HBM_TRAFFIC_BYTES = {
     "cfg2_llama3_8b_32k": {"step": 9222963, "score": 5082317},
     "cfg3_batched_ragged": {"step": 72893542, "score": 45563085},
@@ -51,6 +59,9 @@ def parse():
     ap.add_argument("--layers", type=int, default=0, help="distinct cache copies to rotate over (0 = auto)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
+    ap.add_argument("--no-per-config", action="store_true",
+                    help="skip the per_config list (configurations 2-5 at full size); it is only produced "
+                         "when --workload is the default")
     ap.add_argument("--kv-host", action="store_true",
                     help="offloading variant (Sec. 5.3 of the paper): K and V in pinned host memory, hash "
                          "codes on the GPU; the selected rows are gathered over the bus")
@@ -72,179 +83,165 @@ def parse():
     return ap.parse_args()
 
 
-def main():
-    args = parse()
-    if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
-              "--gpus must be 1", file=sys.stderr)
-        sys.exit(2)
+def dev_bits(a, dev):
     import numpy as np
     import torch
-    from paper_2506_02572_amd import hata, synth
+    a = np.ascontiguousarray(a)
+    if a.dtype == np.uint16:
+        a = a.view(np.int16)
+    elif a.dtype == np.uint32:
+        a = a.view(np.int32)
+    return torch.from_numpy(a).to(dev)
 
-    if not torch.cuda.is_available():
-        print("bench.py: no GPU visible; the HATA path has no CPU fallback", file=sys.stderr)
-        sys.exit(1)
-    torch.cuda.set_device(0)
-    dev = torch.device("cuda:0")
-    w = synth.workload(args.workload)
-    inp = synth.generate(w)
-    scale = 1.0 / math.sqrt(w.d)
-    n_step_variants = max(1, w.append_steps)
 
-    def dev_bits(a):
-        a = np.ascontiguousarray(a)
-        if a.dtype == np.uint16:
-            a = a.view(np.int16)
-        elif a.dtype == np.uint32:
-            a = a.view(np.int32)
-        return torch.from_numpy(a).to(dev)
+def timed(fn, n, warm, stream):
+    """ms per call over exactly n calls after warm untimed ones: (device events, host wall)."""
+    import torch
+    for i in range(warm):
+        fn(i)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record(stream)
+    for i in range(n):
+        fn(i)
+    e1.record(stream)
+    torch.cuda.synchronize()
+    wall = (time.perf_counter() - t0) * 1e3
+    return e0.elapsed_time(e1) / n, wall / n
 
-    # ---- device buffers: n_layers copies of (K, V, codes)
-    touched = w.algorithmic_bytes()
-    layer_bytes = 2 * inp.K.nbytes + inp.K.nbytes // (w.d * 2) * (w.r // 8)
-    n_layers = args.layers or max(4, min(int(math.ceil((1 << 30) / touched)), int((96 << 30) // layer_bytes)))
-    if args.kv_host:
-        # K / V stay in pinned host memory (a few copies: host reads are not cached between steps)
-        n_layers = args.layers or 4
-        Kh = torch.from_numpy(np.ascontiguousarray(inp.K).view(np.int16))
-        Vh = torch.from_numpy(np.ascontiguousarray(inp.V).view(np.int16))
-        K_all = torch.empty((n_layers,) + tuple(Kh.shape), dtype=torch.int16, pin_memory=True)
-        V_all = torch.empty((n_layers,) + tuple(Vh.shape), dtype=torch.int16, pin_memory=True)
-        K_all[:] = Kh
-        V_all[:] = Vh
-        K_dev0, V_dev0 = Kh.to(dev), Vh.to(dev)  # device copy of one layer for the prefill key encode
-        del Kh, Vh
-    else:
-        K0, V0 = dev_bits(inp.K), dev_bits(inp.V)
-        K_all = torch.empty((n_layers,) + tuple(K0.shape), dtype=torch.int16, device=dev)
-        V_all = torch.empty_like(K_all)
-        K_all[:] = K0
-        V_all[:] = V0
-        del K0, V0
-    codes_all = torch.zeros((n_layers, w.B, w.Hkv, w.L_cap, w.W), dtype=torch.int32, device=dev)
-    W_H = dev_bits(inp.W_H)
-    kbud = dev_bits(inp.k)
-    zero = torch.zeros(w.B, dtype=torch.int32, device=dev)
-    # cfg5: the cache grows by one row per step for append_steps steps, then the cycle restarts
-    seq_steps = [dev_bits(inp.seq_len + (t + 1 if w.append_steps else 0)) for t in range(n_step_variants)]
-    q_steps = [dev_bits(inp.q(t)) for t in range(min(n_step_variants, 8))]
-    prefill_len = dev_bits(inp.seq_len + w.append_steps)  # rows a later step appends get codes too
-    out = torch.empty((w.B, w.Hq, w.d), dtype=torch.int16, device=dev)
-    out32 = torch.empty((w.B, w.Hq, w.d), dtype=torch.float32, device=dev)
-    ctx = hata.Context(w.B, w.Hq, w.Hkv, w.d, w.r, w.L_cap, w.k_max)
-    ctx.hata_set_step_mode(args.step_mode)
-    stream = torch.cuda.current_stream()
 
-    def timed(fn, n, warm):
-        for i in range(warm):
-            fn(i)
-        torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        t0 = time.perf_counter()
-        e0.record(stream)
-        for i in range(n):
-            fn(i)
-        e1.record(stream)
-        torch.cuda.synchronize()
-        wall = (time.perf_counter() - t0) * 1e3
-        return e0.elapsed_time(e1) / n, wall / n  # ms per call (device events, host wall)
+class Bench:
+    """One workload on the device: rotated cache copies, a context, and the legs that time it."""
 
-    # ---- prefill-side key-code writer (Alg. 1: the key-code fill of the prefill), every layer once; timed separately
-    max_prefill = int(inp.seq_len.max()) + w.append_steps
+    def __init__(self, name, args, layers=0, kv_host=False, step_mode=0):
+        import numpy as np
+        import torch
+        from paper_2506_02572_amd import hata, synth
+        self.np, self.torch = np, torch
+        self.dev = torch.device("cuda:0")
+        self.args = args
+        w = self.w = synth.workload(name)
+        inp = self.inp = synth.generate(w)
+        self.scale = 1.0 / math.sqrt(w.d)
+        self.kv_host = kv_host
+        self.n_step_variants = max(1, w.append_steps)
+        dev = self.dev
+        touched = w.algorithmic_bytes()
+        layer_bytes = 2 * inp.K.nbytes + inp.K.nbytes // (w.d * 2) * (w.r // 8)
+        n_layers = layers or max(4, min(int(math.ceil((1 << 30) / touched)), int((96 << 30) // layer_bytes)))
+        if kv_host:
+            # K / V stay in pinned host memory (a few copies: host reads are not cached between steps)
+            n_layers = layers or 4
+            Kh = torch.from_numpy(np.ascontiguousarray(inp.K).view(np.int16))
+            Vh = torch.from_numpy(np.ascontiguousarray(inp.V).view(np.int16))
+            self.K_all = torch.empty((n_layers,) + tuple(Kh.shape), dtype=torch.int16, pin_memory=True)
+            self.V_all = torch.empty((n_layers,) + tuple(Vh.shape), dtype=torch.int16, pin_memory=True)
+            self.K_all[:] = Kh
+            self.V_all[:] = Vh
+            self.K_dev0, self.V_dev0 = Kh.to(dev), Vh.to(dev)  # device copy of one layer for the prefill key encode
+            del Kh, Vh
+        else:
+            K0, V0 = dev_bits(inp.K, dev), dev_bits(inp.V, dev)
+            self.K_all = torch.empty((n_layers,) + tuple(K0.shape), dtype=torch.int16, device=dev)
+            self.V_all = torch.empty_like(self.K_all)
+            self.K_all[:] = K0
+            self.V_all[:] = V0
+            del K0, V0
+        self.n_layers = n_layers
+        self.codes_all = torch.zeros((n_layers, w.B, w.Hkv, w.L_cap, w.W), dtype=torch.int32, device=dev)
+        self.W_H = dev_bits(inp.W_H, dev)
+        self.kbud = dev_bits(inp.k, dev)
+        self.zero = torch.zeros(w.B, dtype=torch.int32, device=dev)
+        # cfg5: the cache grows by one row per step for append_steps steps, then the cycle restarts
+        self.seq_steps = [dev_bits(inp.seq_len + (t + 1 if w.append_steps else 0), dev)
+                          for t in range(self.n_step_variants)]
+        self.q_steps = [dev_bits(inp.q(t), dev) for t in range(min(self.n_step_variants, 8))]
+        self.prefill_len = dev_bits(inp.seq_len + w.append_steps, dev)  # rows a later step appends get codes too
+        self.max_prefill = int(inp.seq_len.max()) + w.append_steps
+        self.out = torch.empty((w.B, w.Hq, w.d), dtype=torch.int16, device=dev)
+        self.out32 = torch.empty((w.B, w.Hq, w.d), dtype=torch.float32, device=dev)
+        self.ctx = hata.Context(w.B, w.Hq, w.Hkv, w.d, w.r, w.L_cap, w.k_max)
+        self.ctx.hata_set_step_mode(step_mode)
+        self.stream = torch.cuda.current_stream()
+        self.alg_bytes = w.algorithmic_bytes(1 if w.append_steps else 0)
+        self.code_bytes = int(inp.seq_len.sum() + (w.B if w.append_steps else 0)) * w.Hkv * (w.r // 8)
 
-    # (with the cache in host memory the prefill encode runs from a device copy: every layer here
-    # holds the same synthetic keys)
-    enc_calls = [ctx.prepared("hata_encode_keys", K_dev0 if args.kv_host else K_all[l], W_H, zero, prefill_len,
-                              w.B, max_prefill, codes_all[l], stream=stream) for l in range(n_layers)]
+    def close(self):
+        self.ctx.close()
+        for n in ("K_all", "V_all", "codes_all", "K_dev0", "V_dev0"):
+            if hasattr(self, n):
+                delattr(self, n)
+        self.torch.cuda.empty_cache()
 
-    def enc(i):
-        enc_calls[i % n_layers]()
-
-    enc_ms, _ = timed(enc, n_layers, 1)
-    enc_keys = int((inp.seq_len + w.append_steps).sum()) * w.Hkv
-    enc_bytes = enc_keys * (w.d * 2 + w.r // 8)
-    enc_flop = 2.0 * enc_keys * w.d * w.r
+    # ---- prefill-side key-code writer (Alg. 1: the key-code fill of the prefill), every layer once
+    def encode_keys(self):
+        w, inp = self.w, self.inp
+        calls = [self.ctx.prepared("hata_encode_keys", self.K_dev0 if self.kv_host else self.K_all[l], self.W_H,
+                                   self.zero, self.prefill_len, w.B, self.max_prefill, self.codes_all[l],
+                                   stream=self.stream) for l in range(self.n_layers)]
+        ms, _ = timed(lambda i: calls[i % self.n_layers](), self.n_layers, 1, self.stream)
+        keys = int((inp.seq_len + w.append_steps).sum()) * w.Hkv
+        nbytes = keys * (w.d * 2 + w.r // 8)
+        flop = 2.0 * keys * w.d * w.r
+        return {"us_per_layer": round(ms * 1e3, 1), "keys": keys, "GBps": round(nbytes / (ms * 1e-3) / 1e9, 1),
+                "TFLOPs": round(flop / (ms * 1e-3) / 1e12, 2)}
 
     # ---- the same with the cache fill fused in (Alg. 1: KCache <- K, VCache <- V, K_H = HashEncode(K))
-    fill_leg = None
-    if not args.kv_host and not args.pmc_probe and w.r in (32, 64, 128, 256) and max_prefill == w.L_cap:
-        K_dst, V_dst = torch.empty_like(K_all[0]), torch.empty_like(V_all[0])
-        codes_dst = torch.empty_like(codes_all[0])
-        fill_calls = [ctx.prepared("hata_prefill_write", K_all[l], V_all[l], zero, prefill_len, w.B, w.L_cap,
-                                   K_dst, V_dst, codes_dst, W_H, stream=stream) for l in range(n_layers)]
-        ms_fill, _ = timed(lambda i: fill_calls[i % n_layers](), n_layers, 1)
-        fill_bytes = enc_keys * (4 * w.d * 2 + w.r // 8)  # K and V read and written once, codes written
-        fill_leg = {"us_per_layer": round(ms_fill * 1e3, 1), "GBps": round(fill_bytes / (ms_fill * 1e-3) / 1e9, 1)}
-        del K_dst, V_dst, codes_dst, fill_calls
-
-    if args.pmc_probe:
-        # a plain copy of known size (reads and writes COPY_BYTES each) calibrates the counters;
-        # then the decode step and the scoring launch, the same calls the timed legs issue
-        COPY_BYTES = 256 << 20
-        src = torch.empty(COPY_BYTES // 4, dtype=torch.int32, device=dev).fill_(1)
-        dst = torch.empty_like(src)
-        qcodes_buf, scores_buf, _ = ctx.hata_step_buffers()
-        ctx.hata_encode_query(q_steps[0], W_H, w.B, qcodes_buf, stream)
-        torch.cuda.synchronize()
-        for i in range(10):
-            dst.copy_(src)
-        torch.cuda.synchronize()
-        for i in range(40):
-            ctx.hata_hamming_score(qcodes_buf, codes_all[i % n_layers], seq_steps[0], w.B, scores_buf, stream)
-        torch.cuda.synchronize()
-        for i in range(40):
-            ctx.hata_decode_step(q_steps[0], K_all[i % n_layers], V_all[i % n_layers], W_H,
-                                 codes_all[i % n_layers], seq_steps[0], kbud, w.B, True, scale, out, out32,
-                                 stream)
-        ctx.hata_check(stream)
-        code_bytes = int(inp.seq_len.sum() + (w.B if w.append_steps else 0)) * w.Hkv * (w.r // 8)
-        print(json.dumps({"pmc_probe": True, "workload": w.name, "copy_bytes_each_way": COPY_BYTES,
-                          "score_code_bytes": code_bytes,
-                          "score_write_bytes": code_bytes // (w.r // 8) * 2,
-                          "step_algorithmic_bytes": w.algorithmic_bytes(1 if w.append_steps else 0),
-                          "step_launches": ctx.hata_step_plan(w.B)[0]}))
-        ctx.close()
-        return
+    def prefill_write(self):
+        w, torch = self.w, self.torch
+        if self.kv_host or w.r not in (32, 64, 128, 256) or self.max_prefill != w.L_cap:
+            return None
+        K_dst, V_dst = torch.empty_like(self.K_all[0]), torch.empty_like(self.V_all[0])
+        codes_dst = torch.empty_like(self.codes_all[0])
+        calls = [self.ctx.prepared("hata_prefill_write", self.K_all[l], self.V_all[l], self.zero, self.prefill_len,
+                                   w.B, w.L_cap, K_dst, V_dst, codes_dst, self.W_H, stream=self.stream)
+                 for l in range(self.n_layers)]
+        ms, _ = timed(lambda i: calls[i % self.n_layers](), self.n_layers, 1, self.stream)
+        keys = int((self.inp.seq_len + w.append_steps).sum()) * w.Hkv
+        fill_bytes = keys * (4 * w.d * 2 + w.r // 8)  # K and V read and written once, codes written
+        return {"us_per_layer": round(ms * 1e3, 1), "GBps": round(fill_bytes / (ms * 1e-3) / 1e9, 1)}
 
     # ---- the decode step
-    n_combo = n_layers * n_step_variants // math.gcd(n_layers, n_step_variants)
-    n_combo = min(n_combo, args.steps + args.warmup)
-    step_calls = []
-    for i in range(n_combo):
-        l, t = i % n_layers, i % n_step_variants
-        step_calls.append(ctx.prepared("hata_decode_step", q_steps[t % len(q_steps)], K_all[l], V_all[l],
-                                       W_H, codes_all[l], seq_steps[t], kbud, w.B, True, scale, out,
-                                       out32, stream=stream))
+    def step(self, steps, warmup):
+        w = self.w
+        n_combo = self.n_layers * self.n_step_variants // math.gcd(self.n_layers, self.n_step_variants)
+        n_combo = min(n_combo, steps + warmup)
+        calls = []
+        for i in range(n_combo):
+            l, t = i % self.n_layers, i % self.n_step_variants
+            calls.append(self.ctx.prepared("hata_decode_step", self.q_steps[t % len(self.q_steps)], self.K_all[l],
+                                           self.V_all[l], self.W_H, self.codes_all[l], self.seq_steps[t], self.kbud,
+                                           w.B, True, self.scale, self.out, self.out32, stream=self.stream))
+        self.step_calls, self.n_combo = calls, n_combo
+        ms, wall = timed(lambda i: calls[i % n_combo](), steps, warmup, self.stream)
+        self.ctx.hata_check(self.stream)  # raises if a single-launch step gave up an in-kernel wait
+        return ms * 1e3, wall * 1e3
 
-    def step(i):
-        step_calls[i % n_combo]()
-
-    ms_step, ms_wall = timed(step, args.steps, args.warmup)
-    ctx.hata_check(stream)  # raises if a single-launch step gave up an in-kernel wait
-    us_step = ms_step * 1e3
-    n_launches, plan_chunk, plan_n_chunks = ctx.hata_step_plan(w.B)
-    n_sub = ctx.hata_step_sub_batches(w.B)  # launches of the single-launch form (batch slices), 0 = three-launch form
+    def plan(self):
+        n_launches, chunk, n_chunks = self.ctx.hata_step_plan(self.w.B)
+        n_sub = self.ctx.hata_step_sub_batches(self.w.B)  # launches of the single-launch form (batch slices), 0 = three-launch form
+        return n_launches, chunk, n_chunks, n_sub
 
     # ---- N layer steps in one HIP graph (launch gaps out of the way), with and without the dense first layers
-    graph_leg = None
-    if args.graph_layers > 0 and not args.kv_host:
-        NL = args.graph_layers
+    def graph_of_layers(self, NL, steps):
+        torch, w, ctx = self.torch, self.w, self.ctx
 
         def enqueue(dense_first):
             for i in range(NL):
-                l = i % n_layers
+                l = i % self.n_layers
                 if i < dense_first:
-                    ctx.hata_dense_decode(q_steps[0], K_all[l], V_all[l], seq_steps[0], w.B, scale, out, out32)
+                    ctx.hata_dense_decode(self.q_steps[0], self.K_all[l], self.V_all[l], self.seq_steps[0], w.B,
+                                          self.scale, self.out, self.out32)
                 else:
-                    ctx.hata_decode_step(q_steps[0], K_all[l], V_all[l], W_H, codes_all[l], seq_steps[0], kbud,
-                                         w.B, True, scale, out, out32)
+                    ctx.hata_decode_step(self.q_steps[0], self.K_all[l], self.V_all[l], self.W_H, self.codes_all[l],
+                                         self.seq_steps[0], self.kbud, w.B, True, self.scale, self.out, self.out32)
 
         side = torch.cuda.Stream()
-        side.wait_stream(stream)
+        side.wait_stream(self.stream)
         with torch.cuda.stream(side):
             enqueue(2)  # warm-up on a side stream before the capture
-        stream.wait_stream(side)
+        self.stream.wait_stream(side)
         torch.cuda.synchronize()
         graphs = {}
         for name, dense_first in (("hata_all_layers", 0), ("first_two_dense", 2)):
@@ -252,147 +249,251 @@ def main():
             with torch.cuda.graph(g):
                 enqueue(dense_first)
             graphs[name] = g
-        reps = max(10, args.steps // NL)
-        graph_leg = {"layers": NL, "replays": reps}
+        reps = max(10, steps // NL)
+        leg = {"layers": NL, "replays": reps}
         for name, g in graphs.items():
-            ms_g, _ = timed(lambda i: g.replay(), reps, 2)
-            graph_leg[name + "_us_per_replay"] = round(ms_g * 1e3, 1)
-            graph_leg[name + "_us_per_layer"] = round(ms_g * 1e3 / NL, 3)
-        ctx.hata_check(stream)
-        del graphs
+            ms_g, _ = timed(lambda i: g.replay(), reps, 2, self.stream)
+            leg[name + "_us_per_replay"] = round(ms_g * 1e3, 1)
+            leg[name + "_us_per_layer"] = round(ms_g * 1e3 / NL, 3)
+        ctx.hata_check(self.stream)
+        return leg
 
     # ---- the scoring stage alone (the largest stream of bytes of the step)
-    qcodes_buf, scores_buf, _ = ctx.hata_step_buffers()
-
-    score_calls = [ctx.prepared("hata_hamming_score", qcodes_buf, codes_all[l], seq_steps[0], w.B,
-                                scores_buf, stream=stream) for l in range(n_layers)]
-
-    def score_only(i):
-        score_calls[i % n_layers]()
-
-    ms_score, _ = timed(score_only, args.steps, args.warmup)
-    code_bytes = int(inp.seq_len.sum() + (w.B if w.append_steps else 0)) * w.Hkv * (w.r // 8)
-    score_gbps = code_bytes / (ms_score * 1e-3) / 1e9
+    def score(self, steps, warmup):
+        qcodes_buf, scores_buf, _ = self.ctx.hata_step_buffers()
+        calls = [self.ctx.prepared("hata_hamming_score", qcodes_buf, self.codes_all[l], self.seq_steps[0], self.w.B,
+                                   scores_buf, stream=self.stream) for l in range(self.n_layers)]
+        ms, _ = timed(lambda i: calls[i % self.n_layers](), steps, warmup, self.stream)
+        return ms * 1e3
 
     # ---- dense decode over the whole cache (Eq. 1): the comparison baseline, same shapes
-    dense_us = None
-    if not args.no_dense:
-        dense_calls = [ctx.prepared("hata_dense_decode", q_steps[0], K_all[l], V_all[l], seq_steps[0], w.B,
-                                    scale, out, out32, stream=stream) for l in range(n_layers)]
+    def dense(self, steps):
+        calls = [self.ctx.prepared("hata_dense_decode", self.q_steps[0], self.K_all[l], self.V_all[l],
+                                   self.seq_steps[0], self.w.B, self.scale, self.out, self.out32, stream=self.stream)
+                 for l in range(self.n_layers)]
+        ms, _ = timed(lambda i: calls[i % self.n_layers](), 5 if self.kv_host else max(20, steps // 8),
+                      1 if self.kv_host else 5, self.stream)
+        return ms * 1e3
 
-        def dense(i):
-            dense_calls[i % n_layers]()
-        ms_dense, _ = timed(dense, 5 if args.kv_host else max(20, args.steps // 8), 1 if args.kv_host else 5)
-        dense_us = ms_dense * 1e3
-
-    # ---- learning-to-hash training step (Sec. 3.1 / App. B): one SGD step on one head's W_H from a
-    # 32K-triplet chunk (the chunk size of App. B.2), timed separately
-    train_leg = None
-    if not args.no_train:
-        from paper_2506_02572_amd import train as htrain
-        n_tr = 32768
-        tctx = htrain.TrainContext(w.d, w.r, n_tr)
-        Qt = dev_bits(synth.train_vectors(n_tr, tensor_id=synth.TID_Q))
-        Kt = dev_bits(synth.train_vectors(n_tr, tensor_id=synth.TID_K))
-        st = torch.full((n_tr,), -1.0, dtype=torch.float32, device=dev)
-        st[::10] = 5.0
-        Wt = W_H[0].to(torch.float32).contiguous().clone()
-        vt = torch.zeros_like(Wt)
-        hp = htrain.default_hparams(n_tr)
-
-        def tstep(i):
-            tctx.hata_train_step(Qt, Kt, st, n_tr, Wt, vt, hp, None, None, stream)
-        ms_tr, _ = timed(tstep, 50, 5)
-        flop = 4 * 2.0 * n_tr * w.d * w.r  # two projections + two weight-gradient contractions
-        train_leg = {"triplets": n_tr, "r": w.r, "us_per_step": round(ms_tr * 1e3, 1),
-                     "TFLOPs": round(flop / (ms_tr * 1e-3) / 1e12, 1),
-                     "mfma_issue_TFLOPs": round((3 * 3 + 2 * 3) / 4 * flop / (ms_tr * 1e-3) / 1e12, 1),
-                     "launches": 6}
-        tctx.close()
-
-    # ---- parity of one step + the oracle timed on this machine's host cores (rank 0, N = 1)
-    cpu = None
-    parity = None
-    if not args.no_cpu_baseline:
+    # ---- parity of one step against the oracle, the oracle timed on this machine's host cores
+    def oracle(self, cpu_seconds, check_bulk_codes):
+        """One step on the ORACLE's own key codes, compared stage by stage; the oracle's step timed.
+        check_bulk_codes: also compare the GPU's bulk key codes (layer 0) with the oracle's and count
+        the projections inside the |projection| < 1e-4 band and the bits that differ there."""
         from oracle import hata_oracle as O
+        np, torch, w, inp, ctx = self.np, self.torch, self.w, self.inp, self.ctx
         seq0 = inp.seq_len + (1 if w.append_steps else 0)
-        # the oracle encodes its own key codes for its own step
-        codes_o, _ = O.encode_keys_batch(inp.K, inp.W_H, np.zeros(w.B, np.int32), seq0, bulk=True)
+        codes_o, near = O.encode_keys_batch(inp.K, inp.W_H, np.zeros(w.B, np.int32), seq0, bulk=True)
+        band = None
+        if check_bulk_codes:
+            got = self.codes_all[0].cpu().numpy().view(np.uint32)
+            diff = got ^ codes_o
+            for b in range(w.B):  # rows past the oracle's range (later appended rows) are not compared
+                diff[b, :, int(seq0[b]):] = 0
+            band = {"projections": int(seq0.sum()) * w.Hkv * w.r,
+                    "in_band": int(np.unpackbits(near.view(np.uint8)).sum()),
+                    "bits_differ_in_band": int(np.unpackbits((diff & near).view(np.uint8)).sum()),
+                    "bits_differ_outside_band": int(np.unpackbits((diff & ~near).view(np.uint8)).sum())}
         q0 = inp.q(0)
+        codes_before = codes_o.copy()
+        for b in range(w.B):  # the appended row's code is written by the step itself
+            codes_before[b, :, int(seq0[b]) - 1] = 0
         t0 = time.perf_counter()
-        ref = O.decode_step(q0, inp.K, inp.V, inp.W_H, codes_o, seq0, inp.k, w.k_max, scale, append=True)
+        ref = O.decode_step(q0, inp.K, inp.V, inp.W_H, codes_o, seq0, inp.k, w.k_max, self.scale, append=True)
         t1 = time.perf_counter() - t0
-        reps = int(max(1, min(5000, args.cpu_seconds / max(t1, 1e-6))))
+        reps = int(max(1, min(5000, cpu_seconds / max(t1, 1e-6))))
         t0 = time.perf_counter()
         for _ in range(reps):
-            O.decode_step(q0, inp.K, inp.V, inp.W_H, codes_o, seq0, inp.k, w.k_max, scale, append=True)
+            O.decode_step(q0, inp.K, inp.V, inp.W_H, codes_o, seq0, inp.k, w.k_max, self.scale, append=True)
         tn = (time.perf_counter() - t0) / reps
         cpu = {"value": round(tn * 1e6, 1), "unit": "us/step", "cores": O.num_threads(), "kind": "oracle",
                "sample": f"{reps} full decode steps of {w.name} (all {w.B * w.Hkv} units, layer 0, step 0)"}
-        # parity of the GPU step on the oracle's codes
-        codes_dev = dev_bits(codes_o)
-        ctx.hata_decode_step(q_steps[0], K_all[0], V_all[0], W_H, codes_dev, seq_steps[0], kbud, w.B, True,
-                             scale, out, out32, stream)
+        _, near_q = O.encode_query_batch(q0, inp.W_H)
+        codes_dev = dev_bits(codes_before, self.dev)
+        ctx.hata_decode_step(self.q_steps[0], self.K_all[0], self.V_all[0], self.W_H, codes_dev, self.seq_steps[0],
+                             self.kbud, w.B, True, self.scale, self.out, self.out32, self.stream)
         torch.cuda.synchronize()
-        _, _, ix = ctx.hata_step_buffers()
-        idx_equal = bool(np.array_equal(ix.cpu().numpy(), ref["idx"]))
-        err = np.abs(out32.cpu().numpy().astype(np.float64) - ref["out"])
-        ok = bool(np.all(err <= 2e-3 + 1e-3 * np.abs(ref["out"])))
-        parity = {"idx_equal": idx_equal, "attn_within_tol": ok, "max_abs_err": float(err.max())}
+        qc, _, ix = ctx.hata_step_buffers()
+        err = np.abs(self.out32.cpu().numpy().astype(np.float64) - ref["out"])
+        qdiff = qc.cpu().numpy().view(np.uint32) ^ ref["qcodes"]
+        parity = {"appended_code_equal": bool(np.array_equal(codes_dev.cpu().numpy().view(np.uint32), codes_o)),
+                  "qcodes_equal": bool(not np.any(qdiff)),
+                  "idx_equal": bool(np.array_equal(ix.cpu().numpy(), ref["idx"])),
+                  "attn_within_tol": bool(np.all(err <= 2e-3 + 1e-3 * np.abs(ref["out"]))),
+                  "max_abs_err": float(err.max()),
+                  "query_projections_in_band": int(np.unpackbits(near_q.view(np.uint8)).sum()),
+                  "query_bits_differ": int(np.unpackbits(qdiff.view(np.uint8)).sum())}
+        return cpu, parity, band
 
     # ---- the step on the paged layout (last: the caches are re-laid in place, page order random)
-    paged_leg = None
-    if args.paged and not args.kv_host and w.L_cap % args.paged == 0 and n_launches == 1:
-        P = args.paged
-        ctx.hata_decode_step(q_steps[0], K_all[0], V_all[0], W_H, codes_all[0], seq_steps[0], kbud, w.B, True,
-                             scale, out, out32, stream)
+    def paged(self, P, steps, warmup):
+        torch, w, ctx = self.torch, self.w, self.ctx
+        ctx.hata_decode_step(self.q_steps[0], self.K_all[0], self.V_all[0], self.W_H, self.codes_all[0],
+                             self.seq_steps[0], self.kbud, w.B, True, self.scale, self.out, self.out32, self.stream)
         torch.cuda.synchronize()
-        ref_out = out32.clone()  # the same step on the contiguous layout, for a bit-for-bit comparison
+        ref_out = self.out32.clone()  # the same step on the contiguous layout, for a bit-for-bit comparison
         nb = w.L_cap // P
         n_pages = w.B * nb
         perm = torch.randperm(n_pages, generator=torch.Generator().manual_seed(1))  # page of block (b, blk)
-        table = perm.view(w.B, nb).to(torch.int32).to(dev)
-        inv = torch.argsort(perm).to(dev)                                           # block held by page p
+        table = perm.view(w.B, nb).to(torch.int32).to(self.dev)
+        inv = torch.argsort(perm).to(self.dev)                                      # block held by page p
 
         def to_pool(t, last):  # [B, Hkv, L_cap, last] -> [n_pages, Hkv, P, last] in the same memory
             blocks = t.view(w.B, w.Hkv, nb, P, last).permute(0, 2, 1, 3, 4).reshape(n_pages, w.Hkv, P, last)
             t.view(n_pages, w.Hkv, P, last).copy_(blocks.index_select(0, inv))
 
-        for l in range(n_layers):
-            to_pool(K_all[l], w.d)
-            to_pool(V_all[l], w.d)
-            to_pool(codes_all[l], w.W)
-        paged_calls = []
-        for i in range(n_combo):
-            l, t = i % n_layers, i % n_step_variants
-            paged_calls.append(ctx.prepared("hata_decode_step_paged", q_steps[t % len(q_steps)], K_all[l], V_all[l],
-                                            W_H, codes_all[l], table, nb, P, n_pages, seq_steps[t], kbud, w.B,
-                                            True, scale, out, out32, stream=stream))
-        ctx.hata_decode_step_paged(q_steps[0], K_all[0], V_all[0], W_H, codes_all[0], table, nb, P, n_pages,
-                                   seq_steps[0], kbud, w.B, True, scale, out, out32, stream)
+        for l in range(self.n_layers):
+            to_pool(self.K_all[l], w.d)
+            to_pool(self.V_all[l], w.d)
+            to_pool(self.codes_all[l], w.W)
+        calls = []
+        for i in range(self.n_combo):
+            l, t = i % self.n_layers, i % self.n_step_variants
+            calls.append(ctx.prepared("hata_decode_step_paged", self.q_steps[t % len(self.q_steps)], self.K_all[l],
+                                      self.V_all[l], self.W_H, self.codes_all[l], table, nb, P, n_pages,
+                                      self.seq_steps[t], self.kbud, w.B, True, self.scale, self.out, self.out32,
+                                      stream=self.stream))
+        ctx.hata_decode_step_paged(self.q_steps[0], self.K_all[0], self.V_all[0], self.W_H, self.codes_all[0], table,
+                                   nb, P, n_pages, self.seq_steps[0], self.kbud, w.B, True, self.scale, self.out,
+                                   self.out32, self.stream)
         torch.cuda.synchronize()
-        same = bool(torch.equal(ref_out, out32))
-        ms_paged, _ = timed(lambda i: paged_calls[i % n_combo](), args.steps, args.warmup)
-        ctx.hata_check(stream)
-        paged_leg = {"page_rows": P, "n_pages": n_pages, "us_per_step": round(ms_paged * 1e3, 3),
-                     "same_bits_as_contiguous": same}
+        same = bool(torch.equal(ref_out, self.out32))
+        ms, _ = timed(lambda i: calls[i % self.n_combo](), steps, warmup, self.stream)
+        ctx.hata_check(self.stream)
+        return {"page_rows": P, "n_pages": n_pages, "us_per_step": round(ms * 1e3, 3),
+                "same_bits_as_contiguous": same}
 
-    alg_bytes = w.algorithmic_bytes(1 if w.append_steps else 0)
+    def pmc_probe(self):
+        """A plain copy of known size (reads and writes COPY_BYTES each) calibrates the counters; then
+        the decode step and the scoring launch, the same calls the timed legs issue."""
+        torch, w, ctx = self.torch, self.w, self.ctx
+        COPY_BYTES = 256 << 20
+        src = torch.empty(COPY_BYTES // 4, dtype=torch.int32, device=self.dev).fill_(1)
+        dst = torch.empty_like(src)
+        qcodes_buf, scores_buf, _ = ctx.hata_step_buffers()
+        ctx.hata_encode_query(self.q_steps[0], self.W_H, w.B, qcodes_buf, self.stream)
+        torch.cuda.synchronize()
+        for i in range(10):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        for i in range(40):
+            ctx.hata_hamming_score(qcodes_buf, self.codes_all[i % self.n_layers], self.seq_steps[0], w.B, scores_buf,
+                                   self.stream)
+        torch.cuda.synchronize()
+        for i in range(40):
+            l = i % self.n_layers
+            ctx.hata_decode_step(self.q_steps[0], self.K_all[l], self.V_all[l], self.W_H, self.codes_all[l],
+                                 self.seq_steps[0], self.kbud, w.B, True, self.scale, self.out, self.out32, self.stream)
+        ctx.hata_check(self.stream)
+        return {"pmc_probe": True, "workload": w.name, "copy_bytes_each_way": COPY_BYTES,
+                "score_code_bytes": self.code_bytes, "score_write_bytes": self.code_bytes // (w.r // 8) * 2,
+                "step_algorithmic_bytes": self.alg_bytes, "step_launches": ctx.hata_step_plan(w.B)[0]}
+
+
+def train_leg(torch, dev, w, W_H, stream):
+    """Learning-to-hash training step (Sec. 3.1 / App. B): one SGD step on one head's W_H from a
+    32K-triplet chunk (the chunk size of App. B.2)."""
+    from paper_2506_02572_amd import synth
+    from paper_2506_02572_amd import train as htrain
+    n_tr = 32768
+    tctx = htrain.TrainContext(w.d, w.r, n_tr)
+    Qt = dev_bits(synth.train_vectors(n_tr, tensor_id=synth.TID_Q), dev)
+    Kt = dev_bits(synth.train_vectors(n_tr, tensor_id=synth.TID_K), dev)
+    st = torch.full((n_tr,), -1.0, dtype=torch.float32, device=dev)
+    st[::10] = 5.0
+    Wt = W_H[0].to(torch.float32).contiguous().clone()
+    vt = torch.zeros_like(Wt)
+    hp = htrain.default_hparams(n_tr)
+    ms_tr, _ = timed(lambda i: tctx.hata_train_step(Qt, Kt, st, n_tr, Wt, vt, hp, None, None, stream), 50, 5, stream)
+    flop = 4 * 2.0 * n_tr * w.d * w.r  # two projections + two weight-gradient contractions
+    leg = {"triplets": n_tr, "r": w.r, "us_per_step": round(ms_tr * 1e3, 1),
+           "TFLOPs": round(flop / (ms_tr * 1e-3) / 1e12, 1),
+           "mfma_issue_TFLOPs": round((3 * 3 + 2 * 3) / 4 * flop / (ms_tr * 1e-3) / 1e12, 1), "launches": 6}
+    tctx.close()
+    return leg
+
+
+def per_config_entry(name, args):
+    """Configuration `name` at full size: steady-state step time, roofline fraction, the dense
+    comparison (measured and at HBM peak) and parity of one step against the oracle."""
+    b = Bench(name, args)
+    w = b.w
+    b.encode_keys()
+    us_step, _ = b.step(PER_CONFIG_STEPS, PER_CONFIG_WARMUP)
+    n_launches, chunk, n_chunks, n_sub = b.plan()
+    us_score = b.score(PER_CONFIG_STEPS, PER_CONFIG_WARMUP)
+    us_dense = b.dense(PER_CONFIG_STEPS)
+    cpu, parity, band = b.oracle(min(args.cpu_seconds, 2.0), True)
+    gbps = b.alg_bytes / (us_step * 1e-6) / 1e9
+    traffic = HBM_TRAFFIC_BYTES.get(w.name, {}).get("step")
+    ideal_dense = w.dense_bytes(1 if w.append_steps else 0) / (HBM_PEAK_GBPS * 1e9) * 1e6
+    e = {"workload": w.name, "us_per_step": round(us_step, 3), "steps": PER_CONFIG_STEPS, "warmup": PER_CONFIG_WARMUP,
+         "layers_rotated": b.n_layers, "launches_per_step": n_sub if n_launches == 1 else n_launches,
+         "chunk": chunk, "chunks_per_unit": n_chunks,
+         "algorithmic_bytes_per_step": b.alg_bytes, "achieved_GBps": round(gbps, 1),
+         "frac": round(gbps / HBM_PEAK_GBPS, 4), "traffic": traffic,
+         "traffic_over_algorithmic": None if traffic is None else round(traffic / b.alg_bytes, 3),
+         "score_stage_us": round(us_score, 3), "score_stage_GBps": round(b.code_bytes / (us_score * 1e-6) / 1e9, 1),
+         "dense_decode_us": round(us_dense, 2), "ideal_dense_us": round(ideal_dense, 2),
+         "speedup_vs_dense": round(us_dense / us_step, 2), "speedup_vs_ideal_dense": round(ideal_dense / us_step, 2),
+         "parity": parity, "bulk_key_codes": band, "oracle_us_per_step": cpu["value"], "oracle_cores": cpu["cores"]}
+    b.close()
+    return e
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
+              "--gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2506_02572_amd import hata, synth  # noqa: F401
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HATA path has no CPU fallback", file=sys.stderr)
+        sys.exit(1)
+    torch.cuda.set_device(0)
+    default_run = args.workload == "cfg2" and not (args.kv_host or args.paged or args.pmc_probe or args.step_mode)
+    b = Bench(args.workload, args, layers=args.layers, kv_host=args.kv_host, step_mode=args.step_mode)
+    w = b.w
+    enc_leg = b.encode_keys()
+    if args.pmc_probe:
+        print(json.dumps(b.pmc_probe()))
+        b.close()
+        return
+    fill_leg = b.prefill_write()
+    us_step, us_wall = b.step(args.steps, args.warmup)
+    n_launches, plan_chunk, plan_n_chunks, n_sub = b.plan()
+    graph_leg = b.graph_of_layers(args.graph_layers, args.steps) if args.graph_layers > 0 and not args.kv_host else None
+    us_score = b.score(args.steps, args.warmup)
+    score_gbps = b.code_bytes / (us_score * 1e-6) / 1e9
+    dense_us = None if args.no_dense else b.dense(args.steps)
+    tr_leg = None if args.no_train else train_leg(torch, b.dev, w, b.W_H, b.stream)
+    cpu = parity = None
+    if not args.no_cpu_baseline:
+        cpu, parity, _ = b.oracle(args.cpu_seconds, False)
+    paged_leg = None
+    if args.paged and not args.kv_host and w.L_cap % args.paged == 0 and n_launches == 1:
+        paged_leg = b.paged(args.paged, args.steps, args.warmup)
+
     traffic = HBM_TRAFFIC_BYTES.get(w.name, {})
-    step_gbps = alg_bytes / (us_step * 1e-6) / 1e9
+    step_gbps = b.alg_bytes / (us_step * 1e-6) / 1e9
     score_stage = {"kernel": "score_kernel (hata_hamming_score)", "achieved": round(score_gbps, 1),
                    "unit": "GB/s", "frac": round(score_gbps / HBM_PEAK_GBPS, 4),
-                   "traffic": traffic.get("score"), "algorithmic_bytes_per_launch": code_bytes,
-                   "avg_launch_us": round(ms_score * 1e3, 3)}
+                   "traffic": traffic.get("score"), "algorithmic_bytes_per_launch": b.code_bytes,
+                   "avg_launch_us": round(us_score, 3)}
     if n_launches == 1:
         # the whole step is ONE kernel (launched once per slice of a batch too large to be resident at
         # once): it is the dominant kernel, its launches are the step
         roofline = {"bound": "hbm", "kernel": "decode_step_coop_kernel (hata_decode_step: the whole step in one launch)",
                     "achieved": round(step_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                     "frac": round(step_gbps / HBM_PEAK_GBPS, 4), "traffic": traffic.get("step"),
-                    "algorithmic_bytes_per_launch": alg_bytes // n_sub, "avg_launch_us": round(us_step / n_sub, 3)}
+                    "traffic_source": HBM_TRAFFIC_SOURCE + " (a constant of that profile's build, not of this run)",
+                    "algorithmic_bytes_per_launch": b.alg_bytes // n_sub, "avg_launch_us": round(us_step / n_sub, 3)}
     else:
         roofline = dict(score_stage, bound="hbm", peak=HBM_PEAK_GBPS)
+    ideal_dense = w.dense_bytes(1 if w.append_steps else 0) / (HBM_PEAK_GBPS * 1e9) * 1e6
     result = {
         "metric": "hata_decode_attention_us_per_step",
         "value": round(us_step, 3),
@@ -400,7 +501,7 @@ def main():
         "n_gpus": 1,
         "steps": args.steps,
         "warmup": args.warmup,
-        "ms_per_step": round(ms_step, 6),
+        "ms_per_step": round(us_step * 1e-3, 6),
         "higher_is_better": False,
         "scaling": "weak",
         "vs_baseline": None,
@@ -409,31 +510,36 @@ def main():
         "config": {"workload": w.name, "B": w.B, "Hq": w.Hq, "Hkv": w.Hkv, "d": w.d, "r": w.r,
                    "L": list(w.L) if len(set(w.L)) > 1 else w.L[0],
                    "k": list(w.k) if len(set(w.k)) > 1 else w.k[0],
-                   "layers_rotated": n_layers, "append_per_step": True,
+                   "layers_rotated": b.n_layers, "append_per_step": True,
                    "kv_cache": "pinned host memory (rows gathered over the bus)" if args.kv_host else "HBM",
                    "launches_per_step": n_sub if n_launches == 1 else n_launches, "step_mode": args.step_mode,
                    "chunk": plan_chunk,
                    "chunks_per_unit": plan_n_chunks},
         "achieved_GBps": round(step_gbps, 1),
-        "algorithmic_bytes_per_step": alg_bytes,
+        "algorithmic_bytes_per_step": b.alg_bytes,
         "step_roofline_frac": round(step_gbps / HBM_PEAK_GBPS, 4),
-        "host_wall_us_per_step": round(ms_wall * 1e3, 3),
+        "host_wall_us_per_step": round(us_wall, 3),
         "roofline": roofline,
         "score_stage": score_stage,
-        "encode_keys_bulk": {"us_per_layer": round(enc_ms * 1e3, 1), "keys": enc_keys,
-                             "GBps": round(enc_bytes / (enc_ms * 1e-3) / 1e9, 1),
-                             "TFLOPs": round(enc_flop / (enc_ms * 1e-3) / 1e12, 2)},
+        "encode_keys_bulk": enc_leg,
         "prefill_write": fill_leg,
         "paged_step": paged_leg,
         "graph_of_layers": graph_leg,
         "dense_decode_us": None if dense_us is None else round(dense_us, 2),
+        "ideal_dense_us": round(ideal_dense, 2),
         "speedup_vs_dense": None if dense_us is None else round(dense_us / us_step, 2),
-        "train_step": train_leg,
+        "speedup_vs_ideal_dense": round(ideal_dense / us_step, 2),
+        "train_step": tr_leg,
         "cpu_baseline": cpu,
         "parity": parity,
     }
+    b.close()
+    del b
+    if default_run and not args.no_per_config:
+        # configurations 2-5 at full size, each in steady state (the headline above takes the
+        # caller's --steps / --warmup, which may be short)
+        result["per_config"] = [per_config_entry(n, args) for n in ("cfg2", "cfg3", "cfg4", "cfg5")]
     print(json.dumps(result))
-    ctx.close()
 
 
 if __name__ == "__main__":

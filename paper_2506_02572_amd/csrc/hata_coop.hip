@@ -70,6 +70,15 @@ struct CoopArgs {
     hata::PageView pv;  // block table (used by the PAGED instantiations only)
 };
 
+// the kernel's argument block as it lies in memory (the only argument of the kernel is a CoopArgs)
+__device__ __forceinline__ const CoopArgs* coop_args_in_memory() {
+#if defined(__HIP_DEVICE_COMPILE__)
+    return (const CoopArgs*)__builtin_amdgcn_kernarg_segment_ptr();
+#else
+    return nullptr;
+#endif
+}
+
 template <int WD>
 struct CodeW { uint32_t w[WD]; };
 
@@ -216,6 +225,7 @@ __global__ __launch_bounds__(256, (G >= 16 ? 2 : 3)) void decode_step_coop_kerne
     // PAGED: where the pages of this chunk's rows start (pages of 16 rows or more: at most MAX_CHUNK / 16 + 1)
     __shared__ int s_page[PAGED ? HATA_COOP_MAX_CHUNK / 16 + 2 : 1];
     const int tid = threadIdx.x;
+    HATA_TRACE_AT(39, true);
     // Workgroup -> (unit, chunk).  Consecutive workgroup ids go to consecutive XCDs (8 of them, each
     // with its own L2); when the unit count allows, all chunks of a unit get ids that are equal
     // mod 8, so one L2 serves the unit's hash weights and the data its workgroups exchange.  Within
@@ -586,12 +596,17 @@ __global__ __launch_bounds__(256, (G >= 16 ? 2 : 3)) void decode_step_coop_kerne
     // cannot mistake the step for a good one).  The arrival counter carries the news: bits 0..9
     // count arrivals, bits 10..19 the arrivals that had given up a wait, bits 20..31 the sign-offs.
     auto poison = [&](int g) {
+        // (a path that is never taken in a good launch: it reads the kernel arguments again from
+        // the argument segment instead of keeping them in registers through the whole kernel)
+        const CoopArgs* ka = coop_args_in_memory();
+        const int b2 = (int)(u / ka->Hkv), h2 = (int)(u % ka->Hkv);
+        const int64_t o = ((int64_t)b2 * ka->Hq + h2 * G + g) * HATA_D;
         if (tid < HATA_D) {
-            outp[g * HATA_D + tid] = 0x7fc0;
-            if (outp32) outp32[g * HATA_D + tid] = __builtin_nanf("");
+            ka->out[o + tid] = 0x7fc0;
+            if (ka->out_f32) ka->out_f32[o + tid] = __builtin_nanf("");
         }
         if (g == 0)
-            for (int p = tid; p < a.k_max; p += 256) io[p] = -1;
+            for (int p = tid; p < ka->k_max; p += 256) ka->idx[u * ka->k_max + p] = -1;
     };
     if (nc == 1) {
         if (s_bad)
