@@ -39,12 +39,12 @@ PER_CONFIG_WARMUP = 40
 # constant of the build the profile names, not a value measured by the run that prints it: the
 # "traffic_source" field of the output says so.  "step": the single-launch decode step
 # (decode_step_coop_kernel); "score": the scoring kernel alone (hata_hamming_score).
-HBM_TRAFFIC_SOURCE = "profiles/hbm_traffic_pmc.md"
+HBM_TRAFFIC_SOURCE = "profiles/hbm_traffic_pmc.md (library of commit 6927e5d)"
 HBM_TRAFFIC_BYTES = {
-    "cfg2_llama3_8b_32k": {"step": 9222963, "score": 5082317},
-    "cfg3_batched_ragged": {"step": 72893542, "score": 45563085},
-    "cfg4_long_128k_r256": {"step": 48662118, "score": 36862976},
-    "cfg5_gqa8_append": {"step": 59414426, "score": 39123354},
+    "cfg2_llama3_8b_32k": {"step": 9297715, "score": 5082317},
+    "cfg3_batched_ragged": {"step": 72992358, "score": 45563290},
+    "cfg4_long_128k_r256": {"step": 48710246, "score": 36862771},
+    "cfg5_gqa8_append": {"step": 59408077, "score": 39123149},
 }
 
 
@@ -77,6 +77,10 @@ def parse():
                     help="also time the step on the paged (block-table) layout: the caches are re-laid as "
                          "pools of PAGE_ROWS-row pages in a random page order (needs L_cap %% PAGE_ROWS == 0)")
     ap.add_argument("--cpu-seconds", type=float, default=10.0)
+    ap.add_argument("--phase-trace", action="store_true",
+                    help="print the in-kernel timeline of the single-launch step instead of timing it: per "
+                         "checkpoint, when the first / median / last workgroup of the grid passed it.  Needs "
+                         "a tuning build of the library (python paper_2506_02572_amd/build.py --trace)")
     ap.add_argument("--pmc-probe", action="store_true",
                     help="run only a known-size copy kernel, the decode step and the scoring kernel (for "
                          "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs that calibrate and measure HBM traffic)")
@@ -363,6 +367,63 @@ class Bench:
         return {"page_rows": P, "n_pages": n_pages, "us_per_step": round(ms * 1e3, 3),
                 "same_bits_as_contiguous": same}
 
+    # checkpoints of decode_step_coop_kernel (slot = number % 32 of the HATA_TRACE_AT calls in csrc/)
+    PHASES = [(39, "kernel start"), (40, "sequence length known"), (50, "query codes collected"),
+              (41, "chunk scored"), (42, "histogram stores issued"), (43, "histogram stores complete"),
+              (44, "arrived at the unit"), (51, "last arriver: threshold search starts"),
+              (26, "last arriver: unit histogram loaded and scanned"), (27, "last arriver: threshold known"),
+              (28, "last arriver: per-chunk counts"), (29, "last arriver: records published"),
+              (45, "record picked up"), (46, "compaction done"), (47, "attention over own rows done"),
+              (48, "partial emitted"), (54, "merge done (merging workgroups)")]
+
+    def phase_trace(self, launches=16, repeats=10):
+        """Timeline of the single-launch step from a tuning build (-DHATA_TRACE): back-to-back
+        launches over the rotated layers; every workgroup stamps the wall clock at each checkpoint
+        into its own row, the last launch's stamps stay.  Returns, per checkpoint, the time after
+        the first workgroup's start at which the first / 10 % / median / 90 % / last workgroup
+        passed it (median over `repeats` traced launches), in us."""
+        import ctypes
+        from paper_2506_02572_amd import hata
+        np, torch, w, ctx = self.np, self.torch, self.w, self.ctx
+        lib = hata.load_library()
+        if not hasattr(lib, "hata_debug_trace"):
+            raise SystemExit("bench.py --phase-trace needs a tuning build: python paper_2506_02572_amd/build.py --trace")
+        NW = 4096
+        buf = (ctypes.c_ulonglong * (NW * 32))()
+        lib.hata_debug_trace_reset()
+        rows = []
+        for it in range(repeats + 2):
+            for j in range(launches):
+                l = (it + j) % self.n_layers
+                ctx.hata_decode_step(self.q_steps[0], self.K_all[l], self.V_all[l], self.W_H, self.codes_all[l],
+                                     self.seq_steps[0], self.kbud, w.B, True, self.scale, self.out, self.out32,
+                                     self.stream)
+            torch.cuda.synchronize()
+            lib.hata_debug_trace(buf)
+            rows.append(np.frombuffer(buf, dtype=np.uint64).reshape(NW, 32).astype(np.float64).copy())
+        ctx.hata_check(self.stream)
+        table = []
+        for slot, name in self.PHASES:
+            acc, n = [], 0
+            for t in rows[2:]:
+                e = t[:, 39 & 31]
+                newest = e.max()
+                base = e[e >= newest - 200 * 100].min()  # stamps of the last launch: within 200 us of the newest start
+                v = t[:, slot & 31]
+                v = v[v >= base]
+                if v.size == 0:
+                    continue
+                n = int(v.size)
+                acc.append([(x - base) / 100.0 for x in (v.min(), np.percentile(v, 10), np.median(v),
+                                                         np.percentile(v, 90), v.max())])
+            if acc:
+                a = np.median(np.array(acc), axis=0)
+                table.append({"checkpoint": name, "workgroups": n, "first": round(float(a[0]), 2),
+                              "p10": round(float(a[1]), 2), "median": round(float(a[2]), 2),
+                              "p90": round(float(a[3]), 2), "last": round(float(a[4]), 2)})
+        return {"phase_trace": True, "workload": w.name, "unit": "us after the first workgroup's start",
+                "launches_per_sample": launches, "samples": repeats, "checkpoints": table}
+
     def pmc_probe(self):
         """A plain copy of known size (reads and writes COPY_BYTES each) calibrates the counters; then
         the decode step and the scoring launch, the same calls the timed legs issue."""
@@ -460,6 +521,10 @@ def main():
     enc_leg = b.encode_keys()
     if args.pmc_probe:
         print(json.dumps(b.pmc_probe()))
+        b.close()
+        return
+    if args.phase_trace:
+        print(json.dumps(b.phase_trace()))
         b.close()
         return
     fill_leg = b.prefill_write()

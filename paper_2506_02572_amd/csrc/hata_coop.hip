@@ -595,81 +595,83 @@ __global__ __launch_bounds__(256, (G >= 16 ? 2 : 3)) void decode_step_coop_kerne
     // head 0 also sets the unit's index list to -1 (a caller that never calls hata_check() still
     // cannot mistake the step for a good one).  The arrival counter carries the news: bits 0..9
     // count arrivals, bits 10..19 the arrivals that had given up a wait, bits 20..31 the sign-offs.
-    auto poison = [&](int g) {
+    int hw_lo = G, hw_step = 1;  // the heads whose output this workgroup writes: hw_lo, hw_lo + hw_step, ... < G
+    if (nc == 1) {
+        hw_lo = 0;
+    } else {
+        TC(48);
+        wait_stores();
+        __syncthreads();
+        uint32_t* cntp = a.attn_counter + u * HATA_COUNTER_STRIDE;
+        const uint32_t arrival = 1u + (s_bad ? (1u << 10) : 0u);
+        if (a.par_merge) {
+            // Many slices x many heads: every workgroup arrives; the first nm = min(G, nc) workgroups
+            // of the unit wait for all nc arrivals, sign off ("I no longer look at the counter") and
+            // merge one query head each (heads c, c + nm, ...).  Whoever brings the counter to its final
+            // value -- nc arrivals, nm sign-offs -- clears it.
+            const int nm = min(G, nc);
+            auto final_value = [&](uint32_t v) { return (v & 0x3ffu) == (uint32_t)nc && (v >> 20) == (uint32_t)nm; };
+            if (tid == 0) {
+                uint32_t seen = atomicAdd(cntp, arrival) + arrival;
+                if (c >= nm) {
+                    if (final_value(seen)) *cntp = 0;  // (possible only after a merging workgroup gave up its wait)
+                } else {
+                    int budget = a.spin_limit;
+                    while ((seen & 0x3ffu) != (uint32_t)nc) {
+                        if (--budget <= 0) { a.error_word[0] = 1u; s_bad = 1; break; }  // gave up: results invalid
+                        __builtin_amdgcn_s_sleep(1);
+                        seen = __hip_atomic_load(cntp, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    }
+                    if ((seen >> 10) & 0x3ffu) s_bad = 1;  // some workgroup of the unit gave up a wait
+                }
+            }
+            if (c >= nm) return;
+            __syncthreads();
+            // the sign-off goes out now and is looked at after the merge (one lane of the last wave: its
+            // return value queues behind that lane's own partial loads)
+            uint32_t signed_off = 0;
+            if (tid == 255) signed_off = atomicAdd(cntp, 1u << 20) + (1u << 20);
+            float* sm = &S.acc[0][0][0];
+            for (int g = c; g < G; g += nm) {
+                if (g != c) __syncthreads();  // the previous head's use of sm
+                attn_merge_head<16>(sm, part0 + g * head_stride, nc, outp + g * HATA_D, outp32 ? outp32 + g * HATA_D : nullptr);
+            }
+            if (tid == 255 && final_value(signed_off)) *cntp = 0;
+            hw_lo = c;
+            hw_step = nm;
+        } else {
+            if (tid == 0) {
+                const uint32_t done = atomicAdd(cntp, arrival);
+                const int last = ((done & 0x3ffu) == (uint32_t)(nc - 1));
+                if (last) *cntp = 0;
+                if (done >> 10) s_bad = 1;
+                s_flag = last;
+            }
+            __syncthreads();
+            TC(49);
+            if (!s_flag) return;
+            TU(53);
+            attn_merge<G>(S, part0, head_stride, nc, outp, outp32);
+            hw_lo = 0;
+        }
+        TU(54);
+    }
+    if (s_bad) {
         // (a path that is never taken in a good launch: it reads the kernel arguments again from
         // the argument segment instead of keeping them in registers through the whole kernel)
         const CoopArgs* ka = coop_args_in_memory();
-        const int b2 = (int)(u / ka->Hkv), h2 = (int)(u % ka->Hkv);
-        const int64_t o = ((int64_t)b2 * ka->Hq + h2 * G + g) * HATA_D;
-        if (tid < HATA_D) {
-            ka->out[o + tid] = 0x7fc0;
-            if (ka->out_f32) ka->out_f32[o + tid] = __builtin_nanf("");
-        }
-        if (g == 0)
-            for (int p = tid; p < ka->k_max; p += 256) ka->idx[u * ka->k_max + p] = -1;
-    };
-    if (nc == 1) {
-        if (s_bad)
-            for (int g = 0; g < G; ++g) poison(g);
-        return;
-    }
-    TC(48);
-    wait_stores();
-    __syncthreads();
-    uint32_t* cntp = a.attn_counter + u * HATA_COUNTER_STRIDE;
-    const uint32_t arrival = 1u + (s_bad ? (1u << 10) : 0u);
-    if (a.par_merge) {
-        // Many slices x many heads: every workgroup arrives; the first nm = min(G, nc) workgroups
-        // of the unit wait for all nc arrivals, sign off ("I no longer look at the counter") and
-        // merge one query head each (heads c, c + nm, ...).  Whoever brings the counter to its final
-        // value -- nc arrivals, nm sign-offs -- clears it.
-        const int nm = min(G, nc);
-        auto final_value = [&](uint32_t v) { return (v & 0x3ffu) == (uint32_t)nc && (v >> 20) == (uint32_t)nm; };
-        if (tid == 0) {
-            uint32_t seen = atomicAdd(cntp, arrival) + arrival;
-            if (c >= nm) {
-                if (final_value(seen)) *cntp = 0;  // (possible only after a merging workgroup gave up its wait)
-            } else {
-                int budget = a.spin_limit;
-                while ((seen & 0x3ffu) != (uint32_t)nc) {
-                    if (--budget <= 0) { a.error_word[0] = 1u; s_bad = 1; break; }  // gave up: results invalid
-                    __builtin_amdgcn_s_sleep(1);
-                    seen = __hip_atomic_load(cntp, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                }
-                if ((seen >> 10) & 0x3ffu) s_bad = 1;  // some workgroup of the unit gave up a wait
+        const int u32 = (int)u;  // (at most 65535 units)
+        const int b2 = u32 / ka->Hkv, h2 = u32 % ka->Hkv;
+        for (int g = hw_lo; g < G; g += hw_step) {
+            const int64_t o = ((int64_t)b2 * ka->Hq + h2 * G + g) * HATA_D;
+            if (tid < HATA_D) {
+                ka->out[o + tid] = 0x7fc0;
+                if (ka->out_f32) ka->out_f32[o + tid] = __builtin_nanf("");
             }
+            if (g == 0)
+                for (int p = tid; p < ka->k_max; p += 256) ka->idx[u * ka->k_max + p] = -1;
         }
-        if (c >= nm) return;
-        __syncthreads();
-        // the sign-off goes out now and is looked at after the merge (one lane of the last wave: its
-        // return value queues behind that lane's own partial loads)
-        uint32_t signed_off = 0;
-        if (tid == 255) signed_off = atomicAdd(cntp, 1u << 20) + (1u << 20);
-        float* sm = &S.acc[0][0][0];
-        for (int g = c; g < G; g += nm) {
-            if (g != c) __syncthreads();  // the previous head's use of sm
-            attn_merge_head<16>(sm, part0 + g * head_stride, nc, outp + g * HATA_D, outp32 ? outp32 + g * HATA_D : nullptr);
-            if (s_bad) poison(g);
-        }
-        if (tid == 255 && final_value(signed_off)) *cntp = 0;
-        TU(54);
-        return;
     }
-    if (tid == 0) {
-        const uint32_t done = atomicAdd(cntp, arrival);
-        const int last = ((done & 0x3ffu) == (uint32_t)(nc - 1));
-        if (last) *cntp = 0;
-        if (done >> 10) s_bad = 1;
-        s_flag = last;
-    }
-    __syncthreads();
-    TC(49);
-    if (!s_flag) return;
-    TU(53);
-    attn_merge<G>(S, part0, head_stride, nc, outp, outp32);
-    if (s_bad)
-        for (int g = 0; g < G; ++g) poison(g);
-    TU(54);
 #undef TC
 #undef TU
 }

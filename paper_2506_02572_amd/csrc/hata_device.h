@@ -133,7 +133,9 @@ __device__ __forceinline__ uint32_t block_excl_scan_256(uint32_t v, uint32_t* ld
 // WD * (2 NP + 1) operations instead of 2 G WD (36 instead of 64 at G = 8, r = 128).
 template <int WD, int G>
 struct HammingSum {
-    static constexpr bool PLANES = G >= 5;  // below that the direct form is as short
+    // (below five heads the direct form is as short; with 256-bit codes and four heads it needs 32
+    // scalar registers for the query codes against 24 for the planes, and one instruction in eight less)
+    static constexpr bool PLANES = G >= 5 || (G >= 4 && WD >= 8);
     static constexpr int NP = G >= 16 ? 5 : G >= 8 ? 4 : 3;  // G <= 31
     uint32_t d[NP][WD];
     uint32_t c0;
