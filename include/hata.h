@@ -119,6 +119,16 @@ int hata_encode_keys(hata_ctx* ctx, const void* K, const float* W_H,
                      const int32_t* start, const int32_t* n_new, int32_t B, int32_t max_new,
                      uint32_t* codes, void* stream);
 
+/* Prepares the hash weights for the matrix-core key-code writer (the weights of HashEncode, Alg. 2,
+ * are fixed once trained, Sec. 3.1): splits W_H [Hkv, d, r] fp32 into its three bf16 planes, laid out
+ * as the kernel's operand fragments, in the workspace.  Afterwards hata_encode_keys,
+ * hata_prefill_write and hata_prefill_write_paged calls of this context that are given the SAME
+ * pointer W_H read the prepared planes instead of splitting the weights in every workgroup (same
+ * codes, bit for bit).  The caller promises that the tensor at W_H does not change until the next
+ * hata_prepare_weights call of this context; W_H == NULL forgets the prepared tensor.  Enqueues
+ * one small kernel on `stream`; the calls that use the planes must be ordered after it. */
+int hata_prepare_weights(hata_ctx* ctx, const float* W_H, void* stream);
+
 /* Prefill cache fill in one pass (Alg. 1: KCache <- K, VCache <- V, K_H = HashEncode(K)): the rows
  *   K_new[b, h, i, :], V_new[b, h, i, :], i < n_new[b]   (bf16, layout [B, Hkv, max_new, d], contiguous)
  * are written to cache rows start[b] + i of K and V (strides of the context) while their key codes

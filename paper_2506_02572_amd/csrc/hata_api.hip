@@ -41,7 +41,7 @@ inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
 struct Plan {
     int G, Wd, NB, NBP, chunk, n_chunks, HT, sparse_rows, sparse_splits, dense_rows, dense_splits;
-    size_t off_qcodes, off_scores, off_idx, off_hist, off_cinfo, off_uinfo, off_ucnt, off_acnt, off_uflag, off_qrec, off_err, off_uhist, off_partials, total;
+    size_t off_qcodes, off_scores, off_idx, off_hist, off_cinfo, off_uinfo, off_ucnt, off_acnt, off_uflag, off_qrec, off_err, off_uhist, off_partials, off_wplanes, total;
 };
 
 int validate_config(const hata_config* f) {
@@ -124,9 +124,12 @@ int make_plan(const hata_config* f, const hata_tuning* t, Plan* p) {
     p->off_err = o;      o = align_up(o + 4);
     p->off_uhist = o;    o = align_up(o + (size_t)units * p->NB * 4);
     p->off_partials = o; o = align_up(o + (size_t)f->B_max * f->Hq * max_splits * (128 + 2) * 4);
+    p->off_wplanes = o;  o = align_up(o + (size_t)f->Hkv * 3 * 128 * f->r * 2);
     p->total = o;
     return HATA_OK;
 }
+
+inline bool f_has_mfma_width(int r) { return r == 32 || r == 64 || r == 128 || r == 256; }
 
 inline int check_call(const hata_ctx* c, int B) {
     if (!c) return HATA_EINVAL;
@@ -231,6 +234,8 @@ int hata_create_tuned(hata_ctx** ctx_out, const hata_config* cfg, const hata_tun
     c->coop_capacity = 0;
     c->coop_capacity_paged = 0;
     c->partials = (float*)(w + p.off_partials);
+    c->wplanes = (f_has_mfma_width(cfg->r)) ? (void*)(w + p.off_wplanes) : nullptr;
+    c->prepared_W_H = nullptr;
     c->control_bytes = p.off_partials - p.off_cinfo;
     // control words and the self-resetting arrival counters start from zero
     if (hipMemset(c->chunk_info, 0, c->control_bytes) != hipSuccess) {
@@ -281,6 +286,19 @@ int hata_encode_keys(hata_ctx* ctx, const void* K, const float* W_H, const int32
         return hip_rc(hata::launch_encode_vectors(ctx, nullptr, nullptr, K, start, n_new, max_new,
                                                   0, codes, W_H, B, s));
     return hip_rc(hata::launch_encode_bulk(ctx, K, W_H, start, n_new, B, max_new, codes, s));
+}
+
+int hata_prepare_weights(hata_ctx* ctx, const float* W_H, void* stream) {
+    if (!ctx) return HATA_EINVAL;
+    if (!W_H) {  // forget the prepared tensor
+        ctx->prepared_W_H = nullptr;
+        return HATA_OK;
+    }
+    if (!aligned(W_H, 16)) return HATA_EINVAL;
+    if (!ctx->wplanes) return HATA_OK;  // widths without a matrix-core kernel have nothing to prepare
+    if (hata::launch_split_weights(ctx, W_H, (hipStream_t)stream) != hipSuccess) return HATA_EHIP;
+    ctx->prepared_W_H = W_H;
+    return HATA_OK;
 }
 
 int hata_prefill_write(hata_ctx* ctx, const void* K_new, const void* V_new, const int32_t* start,

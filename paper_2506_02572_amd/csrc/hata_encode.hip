@@ -225,11 +225,49 @@ typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
 typedef __attribute__((ext_vector_type(16))) float f32x16_t;
 #define HATA_MFMA_PITCH 136   // LDS row pitch in bf16 elements (272 B: rows shift by 4 banks)
 
-__device__ __forceinline__ uint32_t bf16_rne_bits(float f) { return f32_to_bf16(f); }
 
-template <int R, bool PAGED>
+// Fragment order of the prepared weight planes (hata_prepare_weights): for KV head h, wave w
+// (hash columns 32 w .. 32 w + 31), channel step kk and plane p, the 64 lanes' 16-byte fragments lie
+// one after the other, so a wave fetches a fragment with one coalesced 1 KB load:
+//   uint4 index = (((h * (R / 32) + w) * 8 + kk) * 3 + p) * 64 + lane
+__device__ __forceinline__ void split_weight_pair(float w0, float w1, uint32_t& hi, uint32_t& mid, uint32_t& lo) {
+    uint32_t ph[2], pm[2], pl[2];
+    const float wv2[2] = {w0, w1};
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+        const float wv = wv2[q];
+        ph[q] = f32_to_bf16(wv);
+        const float r1 = wv - __uint_as_float(ph[q] << 16);
+        pm[q] = f32_to_bf16(r1);
+        const float r2 = r1 - __uint_as_float(pm[q] << 16);
+        pl[q] = f32_to_bf16(r2);
+    }
+    hi = ph[0] | (ph[1] << 16);
+    mid = pm[0] | (pm[1] << 16);
+    lo = pl[0] | (pl[1] << 16);
+}
+
+// grid = (R / 32 waves, Hkv); 64 threads: one wave writes its 24 fragments
+__global__ __launch_bounds__(64) void split_weights_kernel(const float* __restrict__ W_H, uint4* __restrict__ planes, int R) {
+    const int lane = threadIdx.x, w = blockIdx.x, h = blockIdx.y;
+    const int m = lane & 31, half = lane >> 5;
+    const float* wp = W_H + (int64_t)h * HATA_D * R + w * 32 + m;
+    uint4* dst = planes + ((int64_t)(h * (R / 32) + w) * 8 * 3) * 64 + lane;
+    for (int kk = 0; kk < 8; ++kk) {
+        uint32_t hi[4], mid[4], lo[4];
+#pragma unroll
+        for (int e2 = 0; e2 < 4; ++e2)
+            split_weight_pair(wp[(int64_t)(kk * 16 + 8 * half + 2 * e2) * R], wp[(int64_t)(kk * 16 + 8 * half + 2 * e2 + 1) * R],
+                              hi[e2], mid[e2], lo[e2]);
+        dst[(kk * 3 + 0) * 64] = make_uint4(hi[0], hi[1], hi[2], hi[3]);
+        dst[(kk * 3 + 1) * 64] = make_uint4(mid[0], mid[1], mid[2], mid[3]);
+        dst[(kk * 3 + 2) * 64] = make_uint4(lo[0], lo[1], lo[2], lo[3]);
+    }
+}
+
+template <int R, bool PAGED, bool PRESPLIT>
 __global__ __launch_bounds__(R * 2) void encode_mfma_kernel(
-    const uint16_t* __restrict__ K, const float* __restrict__ W_H,
+    const uint16_t* __restrict__ K, const float* __restrict__ W_H, const uint4* __restrict__ planes,
     const int32_t* __restrict__ start, const int32_t* __restrict__ n_new,
     uint32_t* __restrict__ codes, int Hkv, int L_cap, int keys_per_wg,
     int64_t sb, int64_t sh, int64_t sn,
@@ -272,35 +310,6 @@ __global__ __launch_bounds__(R * 2) void encode_mfma_kernel(
         return (((int64_t)p * Hkv + h) << pv.shift) + (n & ((1 << pv.shift) - 1));
     };
 
-    // weight fragments: a[plane][kk] holds W_H[h][kk*16 + 8*half + e][32 w + m], e = 0..7
-    bf16x8_t afrag[3][8];
-    {
-        const float* wp = W_H + (int64_t)h * HATA_D * R + w * 32 + m;
-#pragma unroll
-        for (int kk = 0; kk < 8; ++kk) {
-            uint32_t hi[4], mid[4], lo[4];
-#pragma unroll
-            for (int e2 = 0; e2 < 4; ++e2) {
-                uint32_t ph[2], pm[2], pl[2];
-#pragma unroll
-                for (int q = 0; q < 2; ++q) {
-                    const float wv = wp[(int64_t)(kk * 16 + 8 * half + 2 * e2 + q) * R];
-                    ph[q] = bf16_rne_bits(wv);
-                    const float r1 = wv - __uint_as_float(ph[q] << 16);
-                    pm[q] = bf16_rne_bits(r1);
-                    const float r2 = r1 - __uint_as_float(pm[q] << 16);
-                    pl[q] = bf16_rne_bits(r2);
-                }
-                hi[e2] = ph[0] | (ph[1] << 16);
-                mid[e2] = pm[0] | (pm[1] << 16);
-                lo[e2] = pl[0] | (pl[1] << 16);
-            }
-            afrag[0][kk] = __builtin_bit_cast(bf16x8_t, make_uint4(hi[0], hi[1], hi[2], hi[3]));
-            afrag[1][kk] = __builtin_bit_cast(bf16x8_t, make_uint4(mid[0], mid[1], mid[2], mid[3]));
-            afrag[2][kk] = __builtin_bit_cast(bf16x8_t, make_uint4(lo[0], lo[1], lo[2], lo[3]));
-        }
-    }
-
     // stage loader: thread -> (row = it * ROWS_PER_IT + tid / 16, 16-byte piece tid % 16)
     const int lrow = tid >> 4, lsub = tid & 15;
     uint4 pre[NIT];
@@ -327,7 +336,32 @@ __global__ __launch_bounds__(R * 2) void encode_mfma_kernel(
             }
         }
     };
+    // the first stage of keys is on its way while the weight fragments arrive
     load_stage(kb0);
+
+    // weight fragments: a[plane][kk] holds W_H[h][kk*16 + 8*half + e][32 w + m], e = 0..7
+    bf16x8_t afrag[3][8];
+    if constexpr (PRESPLIT) {
+        // prepared once per weight tensor (hata_prepare_weights): 24 coalesced 16-byte loads
+        const uint4* src = planes + ((int64_t)(h * (R / 32) + w) * 8 * 3) * 64 + lane;
+#pragma unroll
+        for (int kk = 0; kk < 8; ++kk)
+#pragma unroll
+            for (int p = 0; p < 3; ++p) afrag[p][kk] = __builtin_bit_cast(bf16x8_t, src[(kk * 3 + p) * 64]);
+    } else {
+        const float* wp = W_H + (int64_t)h * HATA_D * R + w * 32 + m;
+#pragma unroll
+        for (int kk = 0; kk < 8; ++kk) {
+            uint32_t hi[4], mid[4], lo[4];
+#pragma unroll
+            for (int e2 = 0; e2 < 4; ++e2)
+                split_weight_pair(wp[(int64_t)(kk * 16 + 8 * half + 2 * e2) * R],
+                                  wp[(int64_t)(kk * 16 + 8 * half + 2 * e2 + 1) * R], hi[e2], mid[e2], lo[e2]);
+            afrag[0][kk] = __builtin_bit_cast(bf16x8_t, make_uint4(hi[0], hi[1], hi[2], hi[3]));
+            afrag[1][kk] = __builtin_bit_cast(bf16x8_t, make_uint4(mid[0], mid[1], mid[2], mid[3]));
+            afrag[2][kk] = __builtin_bit_cast(bf16x8_t, make_uint4(lo[0], lo[1], lo[2], lo[3]));
+        }
+    }
     for (int k0 = kb0; k0 < kb1; k0 += STAGE) {
         __syncthreads();  // the previous stage has been consumed
 #pragma unroll
@@ -341,26 +375,35 @@ __global__ __launch_bounds__(R * 2) void encode_mfma_kernel(
         for (int t = 0; t < NT; ++t)
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[t][i] = 0.f;
+        // Key fragments come from LDS one channel step ahead: as soon as the three planes of a tile
+        // have been issued for step kk, the tile's fragment for step kk + 1 is requested into the same
+        // registers, so its LDS latency is covered by the nine MFMAs of the other tiles.
+        bf16x8_t bfrag[NT];
+#pragma unroll
+        for (int t = 0; t < NT; ++t)
+            bfrag[t] = *reinterpret_cast<const bf16x8_t*>(&tile[(t * 32 + m) * HATA_MFMA_PITCH + 8 * half]);
 #pragma unroll
         for (int kk = 0; kk < 8; ++kk) {
-            bf16x8_t bfrag[NT];
 #pragma unroll
-            for (int t = 0; t < NT; ++t)
-                bfrag[t] = *reinterpret_cast<const bf16x8_t*>(
-                    &tile[(t * 32 + m) * HATA_MFMA_PITCH + kk * 16 + 8 * half]);
+            for (int t = 0; t < NT; ++t) {
 #pragma unroll
-            for (int p = 0; p < 3; ++p)
-#pragma unroll
-                for (int t = 0; t < NT; ++t)
+                for (int p = 0; p < 3; ++p)
                     acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(afrag[p][kk], bfrag[t], acc[t], 0, 0, 0);
+                if (kk + 1 < 8)
+                    bfrag[t] = *reinterpret_cast<const bf16x8_t*>(
+                        &tile[(t * 32 + m) * HATA_MFMA_PITCH + (kk + 1) * 16 + 8 * half]);
+            }
         }
         // sign bits: this lane holds hash columns 8*(i/4) + 4*half + i%4 of key t*32 + m
 #pragma unroll
         for (int t = 0; t < NT; ++t) {
-            uint32_t word = 0;
+            // (the bit is "projection >= 0": the complement of the sign bit; a sum of exact products
+            // that starts from +0 is never -0)
+            uint32_t neg = 0;
 #pragma unroll
             for (int i = 0; i < 16; ++i)
-                word |= (acc[t][i] >= 0.f ? 1u : 0u) << (8 * (i / 4) + 4 * half + (i % 4));
+                neg |= (__float_as_uint(acc[t][i]) >> 31) << (8 * (i / 4) + (i % 4));
+            uint32_t word = (~neg & 0x0f0f0f0fu) << (4 * half);
             word |= (uint32_t)__shfl_xor((int)word, 32, 64);
             const int key = k0 + t * 32 + m;
             if (half == 0 && key < kb1) {
@@ -418,10 +461,19 @@ hipError_t launch_encode_bulk(const hata_ctx* c, const void* K, const float* W_H
         int kpw = 4096;
         while (kpw > 512 && (int64_t)((max_new + kpw - 1) / kpw) * f.Hkv * B < 512) kpw >>= 1;
         const dim3 grid((max_new + kpw - 1) / kpw, f.Hkv, B);
-#define HATA_LAUNCH_MFMA(R_, P_)                                                                        \
-    hipLaunchKernelGGL((encode_mfma_kernel<R_, P_>), grid, dim3(R_ * 2), 0, s, (const uint16_t*)K, W_H, \
-                       start, n_new, codes, f.Hkv, f.L_cap, kpw, f.kv_stride_b, f.kv_stride_h,          \
-                       f.kv_stride_n, kn, vn, ko, vo, max_new, pv)
+        // the weight planes prepared for exactly this weight tensor, if any (hata_prepare_weights)
+        const uint4* planes = (c->prepared_W_H == W_H && c->wplanes) ? (const uint4*)c->wplanes : nullptr;
+#define HATA_LAUNCH_MFMA(R_, P_)                                                                           \
+    do {                                                                                                   \
+        if (planes)                                                                                        \
+            hipLaunchKernelGGL((encode_mfma_kernel<R_, P_, true>), grid, dim3(R_ * 2), 0, s,               \
+                               (const uint16_t*)K, W_H, planes, start, n_new, codes, f.Hkv, f.L_cap, kpw,  \
+                               f.kv_stride_b, f.kv_stride_h, f.kv_stride_n, kn, vn, ko, vo, max_new, pv);  \
+        else                                                                                               \
+            hipLaunchKernelGGL((encode_mfma_kernel<R_, P_, false>), grid, dim3(R_ * 2), 0, s,              \
+                               (const uint16_t*)K, W_H, planes, start, n_new, codes, f.Hkv, f.L_cap, kpw,  \
+                               f.kv_stride_b, f.kv_stride_h, f.kv_stride_n, kn, vn, ko, vo, max_new, pv);  \
+    } while (0)
         if (pages) {
             if (f.r == 32) HATA_LAUNCH_MFMA(32, true);
             else if (f.r == 64) HATA_LAUNCH_MFMA(64, true);
@@ -441,6 +493,13 @@ hipError_t launch_encode_bulk(const hata_ctx* c, const void* K, const float* W_H
     hipLaunchKernelGGL(encode_bulk_kernel, dim3(tiles, f.Hkv, B), dim3(256), 0, s,
                        (const uint16_t*)K, W_H, start, n_new, codes, f.Hkv, f.r, c->Wd, f.L_cap,
                        f.kv_stride_b, f.kv_stride_h, f.kv_stride_n);
+    return hipGetLastError();
+}
+
+// Split of the fp32 hash weights into three bf16 planes in the fragment order of encode_mfma_kernel
+hipError_t launch_split_weights(const hata_ctx* c, const float* W_H, hipStream_t s) {
+    const hata_config& f = c->cfg;
+    hipLaunchKernelGGL(split_weights_kernel, dim3(f.r / 32, f.Hkv), dim3(64), 0, s, W_H, (uint4*)c->wplanes, f.r);
     return hipGetLastError();
 }
 

@@ -48,6 +48,8 @@ struct hata_ctx {
     int coop_capacity;       // workgroups of the cooperative kernel that can be resident at once (0 = unusable)
     int coop_capacity_paged; // the same for the block-table variant of that kernel
     float* partials;       // [B_max*Hq, max(sparse_splits, dense_splits), d + 2]
+    void* wplanes;               // [Hkv, r/32, 8, 3, 64] 16-byte fragments: the three bf16 planes of the hash weights (prefill key encode)
+    const float* prepared_W_H;   // the weight tensor those planes were made from (nullptr: none)
     size_t control_bytes;  // bytes from chunk_info up to the partials: the control words, cleared at creation and after a give-up
 };
 
@@ -74,6 +76,7 @@ hipError_t launch_encode_bulk(const hata_ctx* c, const void* K, const float* W_H
                               uint32_t* codes, hipStream_t s, const void* K_new = nullptr,
                               const void* V_new = nullptr, void* K_out = nullptr, void* V_out = nullptr,
                               const PageView* pages = nullptr);
+hipError_t launch_split_weights(const hata_ctx* c, const float* W_H, hipStream_t s);
 hipError_t launch_score(const hata_ctx* c, const uint32_t* qcodes, const uint32_t* codes,
                         const int32_t* seq_len, int B, uint16_t* scores, const int32_t* kbud,
                         hipStream_t s);

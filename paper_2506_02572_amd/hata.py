@@ -16,7 +16,7 @@ LIB_PATH = os.path.join(_HERE, "libhata.so")
 
 EXPORTS = (
     "hata_strerror", "hata_workspace_bytes", "hata_workspace_bytes_tuned", "hata_create", "hata_create_tuned",
-    "hata_destroy", "hata_encode_keys",
+    "hata_destroy", "hata_encode_keys", "hata_prepare_weights",
     "hata_prefill_write", "hata_prefill_write_paged", "hata_encode_query", "hata_hamming_score", "hata_topk", "hata_sparse_decode",
     "hata_sparse_decode_static", "hata_dense_decode", "hata_decode_step", "hata_decode_step_paged", "hata_step_plan", "hata_step_sub_batches", "hata_set_step_mode", "hata_keep_step_scores", "hata_set_wait_limit",
     "hata_check",
@@ -72,6 +72,7 @@ def load_library(build_if_missing: bool = True) -> ctypes.CDLL:
                                       _vp, ctypes.c_size_t]
     lib.hata_destroy.argtypes = [_vp]
     lib.hata_encode_keys.argtypes = [_vp, _vp, _vp, _vp, _vp, _i32, _i32, _vp, _vp]
+    lib.hata_prepare_weights.argtypes = [_vp, _vp, _vp]
     lib.hata_prefill_write.argtypes = [_vp, _vp, _vp, _vp, _vp, _i32, _i32, _vp, _vp, _vp, _vp, _vp]
     lib.hata_prefill_write_paged.argtypes = [_vp, _vp, _vp, _vp, _vp, _i32, _i32, _vp, _vp, _vp, _vp, _i32,
                                              _i32, _i32, _vp, _vp]
@@ -185,6 +186,9 @@ class Context:
         _check(load_library().hata_encode_keys(self._h, _ptr(K), _ptr(W_H), _ptr(start), _ptr(n_new),
                                                B, max_new, _ptr(codes), _stream(stream)),
                "hata_encode_keys")
+
+    def hata_prepare_weights(self, W_H, stream=None):
+        _check(load_library().hata_prepare_weights(self._h, _ptr(W_H), _stream(stream)), "hata_prepare_weights")
 
     def hata_prefill_write(self, K_new, V_new, start, n_new, B, max_new, K, V, codes, W_H, stream=None):
         _check(load_library().hata_prefill_write(self._h, _ptr(K_new), _ptr(V_new), _ptr(start), _ptr(n_new),

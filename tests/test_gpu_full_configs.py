@@ -53,6 +53,20 @@ def run_workload(torch, w, steps_to_check, single_launch, dense=True):
     n_proj = int(prefill.sum()) * w.Hkv * w.r
     print(f"[full]   bulk encode: {n_proj} projections, {n_band} inside the band, {n_flip} bits differ there",
           flush=True)
+    # the same with the weight planes prepared once (hata_prepare_weights): identical code words
+    if w.r in (32, 64, 128, 256):
+        codes_p = torch.zeros_like(codes_d)
+        c.ctx.hata_prepare_weights(c.W_H)
+        c.ctx.hata_encode_keys(c.K, c.W_H, c.zero, H.to_dev(prefill), B, int(prefill.max()), codes_p)
+        c.sync()
+        assert torch.equal(codes_p, codes_d), "prepared weight planes give different key codes"
+        # a different tensor at another address must not pick up the prepared planes
+        W2 = (c.W_H.view(torch.float32) * 1.0).clone().view(c.W_H.dtype)
+        codes_p.zero_()
+        c.ctx.hata_encode_keys(c.K, W2, c.zero, H.to_dev(prefill), B, int(prefill.max()), codes_p)
+        c.sync()
+        assert torch.equal(codes_p, codes_d)
+        del codes_p, W2
     # ---- decode steps on the ORACLE's codes (so every later stage is comparable bit for bit)
     codes_h = codes_ref.copy()
     codes_d = H.to_dev(codes_h)
