@@ -48,6 +48,9 @@ HBM_TRAFFIC_BYTES = {
 }
 
 
+GATHER_WGS = 32  # hata_gather_rows from host memory: workgroups with reads outstanding at once
+
+
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -73,6 +76,8 @@ def parse():
     ap.add_argument("--step-mode", type=int, default=0, choices=(0, 1, 3),
                     help="hata_set_step_mode: 0 = single-launch form, a batch too large to be resident in "
                          "slices (default); 1 = the whole batch as one grid; 3 = three-launch form")
+    ap.add_argument("--chunk", type=int, default=0, choices=(0, 1024, 2048, 4096, 8192),
+                    help="hata_tuning.chunk: cached keys per scoring workgroup (0 = the library's choice)")
     ap.add_argument("--paged", type=int, default=0, metavar="PAGE_ROWS",
                     help="also time the step on the paged (block-table) layout: the caches are re-laid as "
                          "pools of PAGE_ROWS-row pages in a random page order (needs L_cap %% PAGE_ROWS == 0)")
@@ -165,7 +170,7 @@ class Bench:
         self.max_prefill = int(inp.seq_len.max()) + w.append_steps
         self.out = torch.empty((w.B, w.Hq, w.d), dtype=torch.int16, device=dev)
         self.out32 = torch.empty((w.B, w.Hq, w.d), dtype=torch.float32, device=dev)
-        self.ctx = hata.Context(w.B, w.Hq, w.Hkv, w.d, w.r, w.L_cap, w.k_max)
+        self.ctx = hata.Context(w.B, w.Hq, w.Hkv, w.d, w.r, w.L_cap, w.k_max, chunk=getattr(args, "chunk", 0))
         self.ctx.hata_set_step_mode(step_mode)
         self.stream = torch.cuda.current_stream()
         # the hash weights are fixed: their bf16 planes for the prefill key encoder are made once
@@ -263,6 +268,80 @@ class Bench:
             leg[name + "_us_per_layer"] = round(ms_g * 1e3 / NL, 3)
         ctx.hata_check(self.stream)
         return leg
+
+    # ---- offloading variant with prefetch (Sec. 5.3): the selected rows of layer l + 1 are fetched from
+    # pinned host memory into a double staging buffer on a second stream while layer l attends
+    def kv_host_prefetch(self, NL, reps, D=3):
+        """Per layer: hata_select_step (codes and q are on the GPU) on the main stream, D - 1 layers
+        ahead of the attention; hata_gather_rows of that layer on the fetch stream (same priority)
+        once the selection is there, into one of D staging buffers; attention over the staged rows on
+        the main stream once the fetch is there.  The queries of all layers are given (synthetic),
+        as they are for every other leg; in a model the query of a layer ahead would come from a
+        speculated projection or from another request in flight.  Returns us per layer, the bus rate
+        of the selected rows, and whether the last layer's output has the bits of attention
+        straight over the host-resident cache."""
+        from paper_2506_02572_amd import hata
+        torch, w, ctx = self.torch, self.w, self.ctx
+        stage_ctx = hata.Context(w.B, w.Hq, w.Hkv, w.d, w.r, w.k_max, w.k_max)
+        iota = torch.arange(w.k_max, dtype=torch.int32, device=self.dev).repeat(w.B, w.Hkv, 1).contiguous()
+        Ks = [torch.zeros((w.B, w.Hkv, w.k_max, w.d), dtype=torch.int16, device=self.dev) for _ in range(D)]
+        Vs = [torch.zeros_like(Ks[0]) for _ in range(D)]
+        idx = [torch.empty((w.B, w.Hkv, w.k_max), dtype=torch.int32, device=self.dev) for _ in range(D)]
+        main, fetch = self.stream, torch.cuda.Stream()
+        selected = [torch.cuda.Event() for _ in range(NL)]
+        fetched = [torch.cuda.Event() for _ in range(NL)]
+        q, seq = self.q_steps[0], self.seq_steps[0]
+        sel, gat, att = [], [], []
+        for l in range(NL):
+            c = l % self.n_layers
+            sel.append(ctx.prepared("hata_select_step", q, None, self.W_H, self.codes_all[c], seq, self.kbud, w.B,
+                                    False, idx[l % D], stream=main))
+            gat.append(ctx.prepared("hata_gather_rows", self.K_all[c], self.V_all[c], idx[l % D], self.kbud, w.B,
+                                    GATHER_WGS, Ks[l % D], Vs[l % D], stream=fetch))
+            att.append(stage_ctx.prepared("hata_sparse_decode", q, Ks[l % D], Vs[l % D], iota, self.kbud, w.B,
+                                          self.scale, self.out, self.out32, stream=main))
+
+        def select_and_fetch(l):
+            # (idx[l % D] and staging buffer l % D were last read by the fetch and the attention of
+            # layer l - D, both complete before this selection runs on the main stream)
+            sel[l]()
+            selected[l].record(main)
+            fetch.wait_event(selected[l])
+            gat[l]()
+            fetched[l].record(fetch)
+
+        def token():
+            for l in range(min(D - 1, NL)):
+                select_and_fetch(l)
+            for l in range(NL):
+                if l + D - 1 < NL:
+                    select_and_fetch(l + D - 1)
+                main.wait_event(fetched[l])
+                att[l]()
+
+        token()
+        torch.cuda.synchronize()
+        staged_out = self.out32.clone()
+        c_last = (NL - 1) % self.n_layers
+        ctx.hata_sparse_decode(q, self.K_all[c_last], self.V_all[c_last], idx[(NL - 1) % D], self.kbud, w.B, self.scale,
+                               self.out, self.out32, stream=main)
+        torch.cuda.synchronize()
+        same = bool(torch.equal(staged_out, self.out32))
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t0 = time.perf_counter()
+        e0.record(main)
+        for _ in range(reps):
+            token()
+        e1.record(main)
+        torch.cuda.synchronize()
+        wall = (time.perf_counter() - t0) * 1e6 / (reps * NL)
+        us = e0.elapsed_time(e1) * 1e3 / (reps * NL)
+        ctx.hata_check(main)
+        row_bytes = int(self.inp.k.sum()) * w.Hkv * 4 * w.d
+        stage_ctx.close()
+        return {"layers": NL, "tokens": reps, "staging_buffers": D, "us_per_layer": round(us, 2),
+                "host_wall_us_per_layer": round(wall, 2), "bus_bytes_per_layer": row_bytes,
+                "bus_GBps": round(row_bytes / (us * 1e-6) / 1e9, 1), "same_bits_as_zero_copy": same}
 
     # ---- the scoring stage alone (the largest stream of bytes of the step)
     def score(self, steps, warmup):
@@ -517,7 +596,7 @@ def main():
         print("bench.py: no GPU visible; the HATA path has no CPU fallback", file=sys.stderr)
         sys.exit(1)
     torch.cuda.set_device(0)
-    default_run = args.workload == "cfg2" and not (args.kv_host or args.paged or args.pmc_probe or args.step_mode)
+    default_run = args.workload == "cfg2" and not (args.kv_host or args.paged or args.pmc_probe or args.step_mode or args.chunk)
     b = Bench(args.workload, args, layers=args.layers, kv_host=args.kv_host, step_mode=args.step_mode)
     w = b.w
     enc_leg = b.encode_keys()
@@ -533,6 +612,7 @@ def main():
     us_step, us_wall = b.step(args.steps, args.warmup)
     n_launches, plan_chunk, plan_n_chunks, n_sub = b.plan()
     graph_leg = b.graph_of_layers(args.graph_layers, args.steps) if args.graph_layers > 0 and not args.kv_host else None
+    prefetch_leg = b.kv_host_prefetch(32, max(3, args.steps // 64)) if args.kv_host else None
     us_score = b.score(args.steps, args.warmup)
     score_gbps = b.code_bytes / (us_score * 1e-6) / 1e9
     dense_us = None if args.no_dense else b.dense(args.steps)
@@ -592,6 +672,7 @@ def main():
         "prefill_write": fill_leg,
         "paged_step": paged_leg,
         "graph_of_layers": graph_leg,
+        "kv_host_prefetch": prefetch_leg,
         "dense_decode_us": None if dense_us is None else round(dense_us, 2),
         "ideal_dense_us": round(ideal_dense, 2),
         "speedup_vs_dense": None if dense_us is None else round(dense_us / us_step, 2),

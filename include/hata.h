@@ -166,6 +166,24 @@ int hata_sparse_decode(hata_ctx* ctx, const void* q, const void* K, const void* 
                        const int32_t* idx, const int32_t* k, int32_t B, float sm_scale,
                        void* out, float* out_f32, void* stream);
 
+/* The gather of Alg. 3 ("K_sparse, V_sparse = Gather(K, V, Idx)") materialised, for the offloading
+ * variant (Sec. 5.3: the KV cache in host memory, the selected rows prefetched over the bus): copies
+ * the selected rows into contiguous staging buffers
+ *   K_stage, V_stage  [B, Hkv, k_max, d] bf16 (device memory, caller-owned):
+ *   K_stage[b, h, t, :] = K[b, h, idx[b, h, t], :]   for t < min(k[b], k_max), likewise V.
+ * K and V follow the context's strides and may be pinned, mapped host memory
+ * (hata_host_device_pointer).  Negative or out-of-range index entries, and rows t past the budget,
+ * leave their staged rows untouched.  Issued on a stream of its own it overlaps other layers'
+ * work; attention over the staged rows is hata_sparse_decode on a context whose cache is the
+ * staging buffer (L_cap = k_max, contiguous strides) with the index list 0, 1, 2, ...
+ * max_workgroups (host value): 0 = one workgroup per block of 64 rows (caches in device memory);
+ * n > 0 = at most n workgroups, each with 32 KB of reads outstanding.  With a cache in host
+ * memory every outstanding read also delays whatever else crosses the bus, the launches of other
+ * streams included: 32 is what kept the bus busy without stalling the other stream on the box
+ * this was measured on. */
+int hata_gather_rows(hata_ctx* ctx, const void* K, const void* V, const int32_t* idx, const int32_t* k,
+                     int32_t B, int32_t max_workgroups, void* K_stage, void* V_stage, void* stream);
+
 /* hata_sparse_decode for callers that cannot allocate device memory or keep a workspace: code
  * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments
  * (the shape is passed as the config itself, host pointer; no context), same kernels, same
@@ -217,6 +235,20 @@ int hata_dense_decode(hata_ctx* ctx, const void* q, const void* K, const void* V
 int hata_decode_step(hata_ctx* ctx, const void* q, const void* K, const void* V, const float* W_H,
                      uint32_t* codes, const int32_t* seq_len, const int32_t* k, int32_t B,
                      int32_t append, float sm_scale, void* out, float* out_f32, void* stream);
+
+/* The selection half of hata_decode_step alone (Alg. 3 from "Update code cache" to "Select
+ * top-k"): the appended key (if `append` != 0; K is read for that row only and may be NULL
+ * otherwise) and the query are hash-encoded, all seq_len[b] codes are scored, and the budget is
+ * selected into
+ *   idx  [B, Hkv, k_max] int32 (caller-owned device memory): ascending cache rows, -1 past the budget.
+ * For the offloading variant (Sec. 5.3), where the selected rows are then fetched with
+ * hata_gather_rows while another layer computes.  ONE launch of the single-launch kernel of
+ * hata_decode_step, stopped after the selection, with the same residency rule, bounded waits and
+ * hata_check() reporting (the lists of a unit whose workgroup gave up are unspecified);
+ * HATA_EUNSUPPORTED for the shapes and batches whose step takes three launches. */
+int hata_select_step(hata_ctx* ctx, const void* q, const void* K, const float* W_H, uint32_t* codes,
+                     const int32_t* seq_len, const int32_t* k, int32_t B, int32_t append, int32_t* idx,
+                     void* stream);
 
 /*
  * Paged (block-table) cache layout: the serving-side layout in which sequences grow page by page

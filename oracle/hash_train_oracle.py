@@ -18,8 +18,10 @@ Function -> passage of the paper:
   recall           overlap of the two index sets / N
 
 Readings (the paper is silent or ambiguous; the HIP path takes the same ones):
-  * the triplets of a batch are independent and shuffled (App. B.1 step 5), so the balance term is
-    taken over the keys of the BATCH: eta * || sum_n h(k_n) ||^2;
+  * the final hashing model sums the balance term per query j: eta * sum_j || sum_i h(k_{j,i}) ||^2.
+    `group[n]` names the query a triplet belongs to and gives exactly that; without it the batch
+    counts as one query (the triplets of a stored batch are shuffled, App. B.1 step 5, and carry
+    no query index): eta * || sum_n h(k_n) ||^2;
   * || W^T W - I || is the Frobenius norm, not squared (the other two terms carry an explicit
     square in the paper, this one does not);
   * the sums are as printed; the optional factors scale_sim / scale_bal multiply the two data
@@ -47,9 +49,28 @@ def relaxed_hash(x: np.ndarray, W: np.ndarray, sigma: float = SIGMA) -> np.ndarr
     return 2.0 / (1.0 + np.exp(-z)) - 1.0
 
 
+def _group_ids(group, n):
+    """Per-triplet query ids as consecutive integers 0 .. n_groups - 1 (None: one query)."""
+    if group is None:
+        return np.zeros(n, dtype=np.int64), 1
+    group = np.asarray(group)
+    assert group.shape == (n,)
+    values, ids = np.unique(group, return_inverse=True)
+    return ids.astype(np.int64), int(values.size)
+
+
+def _group_sums(hk, ids, n_groups):
+    """col[j] = sum of h(k_n) over the triplets of query j."""
+    col = np.zeros((n_groups, hk.shape[1]))
+    for n in range(hk.shape[0]):
+        col[ids[n]] += hk[n]
+    return col
+
+
 def loss_terms(Q, K, s, W, sigma=SIGMA, eps=EPSILON, eta=ETA, lam=LAMBDA,
-               scale_sim=1.0, scale_bal=1.0):
-    """(similarity, balance, uncorrelation) for N triplets (Q[n], K[n], s[n]); W is [d, r]."""
+               scale_sim=1.0, scale_bal=1.0, group=None):
+    """(similarity, balance, uncorrelation) for N triplets (Q[n], K[n], s[n]); W is [d, r];
+    group [N]: the query each triplet belongs to (None: all one query)."""
     Q = np.asarray(Q, np.float64)
     K = np.asarray(K, np.float64)
     s = np.asarray(s, np.float64)
@@ -58,7 +79,8 @@ def loss_terms(Q, K, s, W, sigma=SIGMA, eps=EPSILON, eta=ETA, lam=LAMBDA,
     hk = relaxed_hash(K, W, sigma)
     diff = hq - hk
     l_sim = eps * scale_sim * float(np.sum(s * np.sum(diff * diff, axis=1)))
-    col = np.sum(hk, axis=0)
+    ids, n_groups = _group_ids(group, hk.shape[0])
+    col = _group_sums(hk, ids, n_groups)
     l_bal = eta * scale_bal * float(np.sum(col * col))
     M = W.T @ W - np.eye(W.shape[1])
     l_unc = lam * float(np.sqrt(np.sum(M * M)))
@@ -66,13 +88,13 @@ def loss_terms(Q, K, s, W, sigma=SIGMA, eps=EPSILON, eta=ETA, lam=LAMBDA,
 
 
 def loss_and_grad(Q, K, s, W, sigma=SIGMA, eps=EPSILON, eta=ETA, lam=LAMBDA,
-                  scale_sim=1.0, scale_bal=1.0):
+                  scale_sim=1.0, scale_bal=1.0, group=None):
     """Total loss and dL/dW.
 
     With a = sigma Q W, b = sigma K W, hq = 2 Sigmoid(a) - 1, hk = 2 Sigmoid(b) - 1:
       dh/da = (1 - h^2) / 2
       dL/dhq_n =  2 eps s_n (hq_n - hk_n)
-      dL/dhk_n = -2 eps s_n (hq_n - hk_n) + 2 eta sum_m hk_m
+      dL/dhk_n = -2 eps s_n (hq_n - hk_n) + 2 eta sum_{m in the query of n} hk_m
       dL/dW    = sigma (Q^T dL/da + K^T dL/db) + lam * 2 W (W^T W - I) / ||W^T W - I||_F
     """
     Q = np.asarray(Q, np.float64)
@@ -82,13 +104,14 @@ def loss_and_grad(Q, K, s, W, sigma=SIGMA, eps=EPSILON, eta=ETA, lam=LAMBDA,
     hq = relaxed_hash(Q, W, sigma)
     hk = relaxed_hash(K, W, sigma)
     diff = hq - hk
-    col = np.sum(hk, axis=0)
+    ids, n_groups = _group_ids(group, hk.shape[0])
+    col = _group_sums(hk, ids, n_groups)
     M = W.T @ W - np.eye(W.shape[1])
     fro = float(np.sqrt(np.sum(M * M)))
     loss = (eps * scale_sim * float(np.sum(s * np.sum(diff * diff, axis=1)))
             + eta * scale_bal * float(np.sum(col * col)) + lam * fro)
     d_hq = 2.0 * eps * scale_sim * s[:, None] * diff
-    d_hk = -d_hq + 2.0 * eta * scale_bal * col[None, :]
+    d_hk = -d_hq + 2.0 * eta * scale_bal * col[ids]
     d_a = d_hq * (1.0 - hq * hq) * 0.5
     d_b = d_hk * (1.0 - hk * hk) * 0.5
     grad = sigma * (Q.T @ d_a + K.T @ d_b)

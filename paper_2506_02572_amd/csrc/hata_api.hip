@@ -102,7 +102,10 @@ int make_plan(const hata_config* f, const hata_tuning* t, Plan* p) {
     p->sparse_splits = (f->k_max + rows - 1) / rows;
     if (p->sparse_splits > 256) return HATA_EUNSUPPORTED;  // budget above 65536 rows
     int drows = 4096;
-    while (drows > 512 && attn_units * ((f->L_cap + drows - 1) / drows) < 512) drows >>= 1;
+    // (measured: with few units, 512 workgroups -- more slices make the last workgroup's merge the
+    // long pole, 39 -> 53 us at B = 1, L = 32K; with 32 units and more, 1024: 240 -> 209 us at B = 4, G = 8, L = 64K)
+    const int64_t dense_wgs = attn_units >= 32 ? 1024 : 512;
+    while (drows > 512 && attn_units * ((f->L_cap + drows - 1) / drows) < dense_wgs) drows >>= 1;
     while ((f->L_cap + drows - 1) / drows > 256) drows <<= 1;  // the merge handles <= 256 slices
     p->dense_rows = drows;
     p->dense_splits = (f->L_cap + drows - 1) / drows;
@@ -380,6 +383,16 @@ int hata_sparse_decode(hata_ctx* ctx, const void* q, const void* K, const void* 
                                          sm_scale, out, out_f32, (hipStream_t)stream));
 }
 
+int hata_gather_rows(hata_ctx* ctx, const void* K, const void* V, const int32_t* idx, const int32_t* k,
+                     int32_t B, int32_t max_workgroups, void* K_stage, void* V_stage, void* stream) {
+    int rc = check_call(ctx, B);
+    if (rc != HATA_OK) return rc;
+    if (!K || !V || !idx || !k || !K_stage || !V_stage || max_workgroups < 0) return HATA_EINVAL;
+    if (!aligned(K, 16) || !aligned(V, 16) || !aligned(K_stage, 16) || !aligned(V_stage, 16) || !aligned(idx, 4))
+        return HATA_EINVAL;
+    return hip_rc(hata::launch_gather_rows(ctx, K, V, idx, k, B, max_workgroups, K_stage, V_stage, (hipStream_t)stream));
+}
+
 int hata_dense_decode(hata_ctx* ctx, const void* q, const void* K, const void* V,
                       const int32_t* seq_len, int32_t B, float sm_scale, void* out, float* out_f32,
                       void* stream) {
@@ -468,6 +481,26 @@ int hata_decode_step(hata_ctx* ctx, const void* q, const void* K, const void* V,
     if (e != hipSuccess) return HATA_EHIP;
     // TopK(S, N) compaction fused with the attention over the selected rows (gather fused too)
     e = hata::launch_attention(ctx, 2, q, K, V, ctx->idx, k, seq_len, B, sm_scale, out, out_f32, s);
+    return hip_rc(e);
+}
+
+int hata_select_step(hata_ctx* ctx, const void* q, const void* K, const float* W_H, uint32_t* codes,
+                     const int32_t* seq_len, const int32_t* k, int32_t B, int32_t append, int32_t* idx,
+                     void* stream) {
+    int rc = check_call(ctx, B);
+    if (rc != HATA_OK) return rc;
+    if (!q || !W_H || !codes || !seq_len || !k || !idx || (append && !K)) return HATA_EINVAL;
+    if (!aligned(q, 16) || !aligned(K, 16) || !aligned(codes, 16) || !aligned(W_H, 16) || !aligned(idx, 4))
+        return HATA_EINVAL;
+    const int ns = coop_sub_batches(ctx, B, false);
+    if (ns == 0) return HATA_EUNSUPPORTED;
+    hipError_t e = hipSuccess;
+    for (int i = 0; i < ns && e == hipSuccess; ++i) {
+        const int b0 = (int)((int64_t)i * B / ns), b1 = (int)((int64_t)(i + 1) * B / ns);
+        e = hata::launch_coop_step(ctx, q, K, nullptr, W_H, codes, append, seq_len, k, b1 - b0, 0.f, nullptr,
+                                   nullptr, (hipStream_t)stream, nullptr, b0, idx);
+    }
+    if (e == hipErrorNotSupported) return HATA_EUNSUPPORTED;
     return hip_rc(e);
 }
 

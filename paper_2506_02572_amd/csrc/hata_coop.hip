@@ -67,6 +67,7 @@ struct CoopArgs {
     int keep_scores;  // also write the score array (a by-product the kernel itself never reads back)
     int par_merge;    // the heads of a unit are merged side by side by several of its workgroups
     int cmajor;       // workgroup order: chunk-major (every unit's chunk 0 first) instead of unit-major
+    int select_only;  // stop after the index lists are written (no attention, no output)
     hata::PageView pv;  // block table (used by the PAGED instantiations only)
 };
 
@@ -379,7 +380,7 @@ __global__ __launch_bounds__(256, (G >= 16 ? 2 : 3)) void decode_step_coop_kerne
         for (int i = tid; i < G * WD; i += 256) a.qcodes[((int64_t)b * a.Hq + hq0) * WD + i] = s_codes[i];
     if (own && tid < WD) a.codes[cache_row(L - 1) * WD + tid] = s_codes[G * WD + tid];
     if (base >= L) {  // empty sequence: nothing selected, zero output
-        for (int i = tid; i < G * HATA_D; i += 256) {
+        for (int i = tid; i < (a.select_only ? 0 : G * HATA_D); i += 256) {
             outp[i] = 0;
             if (outp32) outp32[i] = 0.f;
         }
@@ -573,6 +574,13 @@ __global__ __launch_bounds__(256, (G >= 16 ? 2 : 3)) void decode_step_coop_kerne
     }
     __syncthreads();
     TC(46);
+    if (a.select_only) {
+        // (a workgroup that gave up a wait poisons the unit's list as far as it can: peers that did
+        // not give up may still write their slices afterwards, hata_check() reports the step)
+        if (s_bad)
+            for (int p = tid; p < a.k_max; p += 256) io[p] = -1;
+        return;
+    }
     // ---- 4. attention over the rows this chunk contributes
     if constexpr (PAGED) {  // rows of the pools (the host has checked that their count fits an int)
         auto row_of = [&](int row) { return (int)cache_row(base + (int)s_sc[row]); };
@@ -723,7 +731,7 @@ int coop_capacity(const hata_ctx* c, bool paged) {
 hipError_t launch_coop_step(hata_ctx* c, const void* q, const void* K, const void* V,
                             const float* W_H, uint32_t* codes, int append, const int32_t* seq_len,
                             const int32_t* k, int B, float sm_scale, void* out, float* out_f32, hipStream_t s,
-                            const PageView* pages, int b0) {
+                            const PageView* pages, int b0, int32_t* idx_only) {
     const hata_config& f = c->cfg;
     const void* fn = coop_kernel_for(c->Wd, c->G, pages != nullptr);
     if (!fn || c->chunk > HATA_COOP_MAX_CHUNK) return hipErrorNotSupported;
@@ -733,6 +741,7 @@ hipError_t launch_coop_step(hata_ctx* c, const void* q, const void* K, const voi
     a.spin_limit = c->spin_limit > 0 ? c->spin_limit : HATA_COOP_SPIN_LIMIT;
     a.keep_scores = c->keep_scores;
     a.par_merge = c->par_merge;
+    a.select_only = idx_only ? 1 : 0;
     // chunk-major order needs the whole grid resident (an oversubscribed grid relies on a unit's
     // workgroups having neighbouring indices)
     a.cmajor = (c->step_mode != 1) ? 1 : 0;
@@ -749,12 +758,12 @@ hipError_t launch_coop_step(hata_ctx* c, const void* q, const void* K, const voi
     }
     seq_len += b0;
     k += b0;
-    out = (uint16_t*)out + (int64_t)b0 * f.Hq * HATA_D;
+    if (out) out = (uint16_t*)out + (int64_t)b0 * f.Hq * HATA_D;
     if (out_f32) out_f32 += (int64_t)b0 * f.Hq * HATA_D;
     // small grids (at most one workgroup per CU): the first batch of key codes is fetched ahead
     a.prefetch = (c->cus > 0 && (int64_t)c->n_chunks * f.Hkv * B <= c->cus) ? 1 : 0;
     a.qcodes = c->qcodes + (int64_t)b0 * f.Hq * c->Wd; a.codes = codes; a.seq_len = seq_len; a.kbud = k;
-    a.scores = c->scores + u0 * f.L_cap; a.idx = c->idx + u0 * f.k_max;
+    a.scores = c->scores + u0 * f.L_cap; a.idx = (idx_only ? idx_only : c->idx) + u0 * f.k_max;
     a.chunk_hist = c->chunk_hist + u0 * c->n_chunks * c->NBP;
     a.chunk_info = c->chunk_info + u0 * (c->n_chunks + 1) * 2; a.unit_info = c->unit_info + u0 * 2;
     a.unit_counter = c->unit_counter + u0 * HATA_COUNTER_STRIDE;

@@ -88,12 +88,18 @@ hipError_t launch_attention(const hata_ctx* c, int mode, const void* q, const vo
                             const int32_t* seq_len, int B, float sm_scale, void* out,
                             float* out_f32, hipStream_t s);
 
+hipError_t launch_gather_rows(const hata_ctx* c, const void* K, const void* V, const int32_t* idx,
+                              const int32_t* k, int B, int max_workgroups, void* K_stage, void* V_stage,
+                              hipStream_t s);
+
 // encode + score + select + attend in one cooperative launch; returns hipErrorNotSupported if
 // this shape has no cooperative kernel
 hipError_t launch_coop_step(hata_ctx* c, const void* q, const void* K, const void* V,
                             const float* W_H, uint32_t* codes, int append, const int32_t* seq_len,
                             const int32_t* k, int B, float sm_scale, void* out, float* out_f32, hipStream_t s,
-                            const PageView* pages = nullptr, int b0 = 0);
+                            const PageView* pages = nullptr, int b0 = 0, int32_t* idx_only = nullptr);
+// (idx_only != nullptr: the launch stops once the index lists are written, into idx_only
+// [B, Hkv, k_max] instead of the workspace; V, out and out_f32 are not touched)
 int coop_capacity(const hata_ctx* c, bool paged);
 
 }  // namespace hata

@@ -18,7 +18,7 @@ EXPORTS = (
     "hata_strerror", "hata_workspace_bytes", "hata_workspace_bytes_tuned", "hata_create", "hata_create_tuned",
     "hata_destroy", "hata_encode_keys", "hata_prepare_weights",
     "hata_prefill_write", "hata_prefill_write_paged", "hata_encode_query", "hata_hamming_score", "hata_topk", "hata_sparse_decode",
-    "hata_sparse_decode_static", "hata_dense_decode", "hata_decode_step", "hata_decode_step_paged", "hata_step_plan", "hata_step_sub_batches", "hata_set_step_mode", "hata_keep_step_scores", "hata_set_wait_limit",
+    "hata_sparse_decode_static", "hata_gather_rows", "hata_dense_decode", "hata_decode_step", "hata_select_step", "hata_decode_step_paged", "hata_step_plan", "hata_step_sub_batches", "hata_set_step_mode", "hata_keep_step_scores", "hata_set_wait_limit",
     "hata_check",
     "hata_host_device_pointer", "hata_step_buffers",
 )
@@ -82,7 +82,9 @@ def load_library(build_if_missing: bool = True) -> ctypes.CDLL:
     lib.hata_sparse_decode.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _i32, ctypes.c_float, _vp, _vp, _vp]
     lib.hata_sparse_decode_static.argtypes = [ctypes.POINTER(hata_config), _vp, _vp, _vp, _vp, _vp, _i32,
                                               ctypes.c_float, _vp, _vp, _vp]
+    lib.hata_gather_rows.argtypes = [_vp, _vp, _vp, _vp, _vp, _i32, _i32, _vp, _vp, _vp]
     lib.hata_dense_decode.argtypes = [_vp, _vp, _vp, _vp, _vp, _i32, ctypes.c_float, _vp, _vp, _vp]
+    lib.hata_select_step.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _vp, _vp]
     lib.hata_decode_step.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32,
                                      ctypes.c_float, _vp, _vp, _vp]
     lib.hata_decode_step_paged.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _vp, _vp,
@@ -225,6 +227,10 @@ class Context:
                                                         _ptr(k), B, sm_scale, _ptr(out), _ptr(out_f32),
                                                         _stream(stream)), "hata_sparse_decode_static")
 
+    def hata_gather_rows(self, K, V, idx, k, B, max_workgroups, K_stage, V_stage, stream=None):
+        _check(load_library().hata_gather_rows(self._h, _ptr(K), _ptr(V), _ptr(idx), _ptr(k), B, max_workgroups,
+                                               _ptr(K_stage), _ptr(V_stage), _stream(stream)), "hata_gather_rows")
+
     def hata_dense_decode(self, q, K, V, seq_len, B, sm_scale, out, out_f32=None, stream=None):
         _check(load_library().hata_dense_decode(self._h, _ptr(q), _ptr(K), _ptr(V), _ptr(seq_len), B,
                                                 sm_scale, _ptr(out), _ptr(out_f32), _stream(stream)),
@@ -236,6 +242,11 @@ class Context:
                                                _ptr(codes), _ptr(seq_len), _ptr(k), B,
                                                1 if append else 0, sm_scale, _ptr(out),
                                                _ptr(out_f32), _stream(stream)), "hata_decode_step")
+
+    def hata_select_step(self, q, K, W_H, codes, seq_len, k, B, append, idx, stream=None):
+        _check(load_library().hata_select_step(self._h, _ptr(q), _ptr(K), _ptr(W_H), _ptr(codes), _ptr(seq_len),
+                                               _ptr(k), B, 1 if append else 0, _ptr(idx), _stream(stream)),
+               "hata_select_step")
 
     def hata_decode_step_paged(self, q, K_pool, V_pool, W_H, codes_pool, block_table, max_blocks,
                                page_rows, n_pages, seq_len, k, B, append, sm_scale, out, out_f32=None,

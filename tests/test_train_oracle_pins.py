@@ -104,6 +104,77 @@ def test_gradient_matches_torch_autograd():
     assert np.allclose(got_g, Wt.grad.numpy(), rtol=1e-10, atol=1e-13)
 
 
+def test_per_query_balance_closed_form_and_invariants():
+    # two queries with one key each, d = r = 1: eta (h(k1)^2 + h(k2)^2) per query against
+    # eta (h(k1) + h(k2))^2 when the batch counts as one query
+    k1, k2, w, sig, eta = 0.9, -1.7, 1.3, 0.5, 2.0
+    h1, h2 = math.tanh(sig * k1 * w / 2), math.tanh(sig * k2 * w / 2)
+    args = ([[0.0], [0.0]], [[k1], [k2]], [0.0, 0.0], [[w]], sig, 0.0, eta, 0.0)
+    assert math.isclose(T.loss_terms(*args, group=[0, 1])[1], eta * (h1 * h1 + h2 * h2), rel_tol=1e-14)
+    assert math.isclose(T.loss_terms(*args)[1], eta * (h1 + h2) ** 2, rel_tol=1e-14)
+    assert math.isclose(T.loss_terms(*args, group=[5, 5])[1], eta * (h1 + h2) ** 2, rel_tol=1e-14)
+    Q, K, s, W = small_problem(8, n=30)
+    # one group for everything is the ungrouped form; the names of the groups do not matter, nor
+    # does the order of the triplets
+    g = np.array([0] * 7 + [1] * 12 + [2] * 11)
+    one = T.loss_and_grad(Q, K, s, W)
+    same = T.loss_and_grad(Q, K, s, W, group=np.full(30, 3))
+    assert one[0] == same[0] and np.array_equal(one[1], same[1])
+    a = T.loss_and_grad(Q, K, s, W, group=g)
+    b = T.loss_and_grad(Q, K, s, W, group=np.array([9, 4, 7])[g])
+    assert math.isclose(a[0], b[0], rel_tol=1e-14) and np.allclose(a[1], b[1], rtol=1e-12, atol=1e-15)
+    perm = np.random.default_rng(9).permutation(30)
+    c = T.loss_and_grad(Q[perm], K[perm], s[perm], W, group=g[perm])
+    assert math.isclose(a[0], c[0], rel_tol=1e-13) and np.allclose(a[1], c[1], rtol=1e-11, atol=1e-14)
+    # the per-query balance term is the sum of the balance terms of the queries taken alone, and
+    # it differs from the whole-batch form by the cross terms between queries
+    parts = sum(T.loss_terms(Q[g == j], K[g == j], s[g == j], W)[1] for j in range(3))
+    assert math.isclose(T.loss_terms(Q, K, s, W, group=g)[1], parts, rel_tol=1e-13)
+    assert abs(T.loss_terms(Q, K, s, W, group=g)[1] - T.loss_terms(Q, K, s, W)[1]) > 1e-3
+    # every query made of (k, -k) pairs: its bit sums cancel
+    K2 = np.concatenate([K, -K])
+    assert T.loss_terms(np.concatenate([Q, Q]), K2, np.concatenate([s, s]), W, group=np.concatenate([g, g]))[1] < 1e-28
+
+
+@pytest.mark.parametrize("which", ["bal", "all"])
+def test_per_query_gradient_matches_central_finite_differences(which):
+    Q, K, s, W = small_problem(10, n=26)
+    g = np.array([0] * 11 + [1] * 15)  # two queries
+    kw = dict(sigma=0.4, eps=0.01 if which == "all" else 0.0, eta=2.0, lam=1.0 if which == "all" else 0.0,
+              scale_sim=0.7, scale_bal=0.3, group=g)
+    _, grad = T.loss_and_grad(Q, K, s, W, **kw)
+    num = np.zeros_like(W)
+    h = 1e-6
+    for i in range(W.shape[0]):
+        for j in range(W.shape[1]):
+            Wp, Wm = W.copy(), W.copy()
+            Wp[i, j] += h
+            Wm[i, j] -= h
+            num[i, j] = (sum(T.loss_terms(Q, K, s, Wp, **kw)) - sum(T.loss_terms(Q, K, s, Wm, **kw))) / (2 * h)
+    assert np.max(np.abs(grad - num)) <= 1e-7 * max(1.0, float(np.max(np.abs(num))))
+    assert float(np.max(np.abs(num))) > 1e-4
+    # and it is not the gradient of the whole-batch form
+    kw0 = dict(kw, group=None)
+    assert np.max(np.abs(grad - T.loss_and_grad(Q, K, s, W, **kw0)[1])) > 1e-4
+
+
+def test_per_query_gradient_matches_torch_autograd():
+    torch = pytest.importorskip("torch")
+    Q, K, s, W = small_problem(11, n=40, d=8, r=7)
+    g = np.array([2] * 9 + [0] * 17 + [1] * 14)
+    Wt = torch.tensor(W, dtype=torch.float64, requires_grad=True)
+    Qt, Kt, st = (torch.tensor(a, dtype=torch.float64) for a in (Q, K, s))
+    hq = 2 * torch.sigmoid(T.SIGMA * Qt @ Wt) - 1
+    hk = 2 * torch.sigmoid(T.SIGMA * Kt @ Wt) - 1
+    bal = sum((hk[torch.tensor(g == j)].sum(0) ** 2).sum() for j in range(3))
+    loss = (T.EPSILON * (st * ((hq - hk) ** 2).sum(1)).sum() + T.ETA * bal
+            + T.LAMBDA * torch.linalg.matrix_norm(Wt.T @ Wt - torch.eye(7, dtype=torch.float64)))
+    loss.backward()
+    got_l, got_g = T.loss_and_grad(Q, K, s, W, group=g)
+    assert math.isclose(got_l, float(loss.detach()), rel_tol=1e-12)
+    assert np.allclose(got_g, Wt.grad.numpy(), rtol=1e-10, atol=1e-13)
+
+
 def test_sgd_step_matches_torch_optimizer():
     torch = pytest.importorskip("torch")
     rng = np.random.default_rng(5)
