@@ -1,8 +1,10 @@
 // Learning-to-hash trainer: one SGD step on the hash weights of one attention head (Sec. 3.1 of
 // the paper, the final multi-query hashing model; App. B.2 for the optimiser).
 //
-//   L = c_sim sum_n s_n ||h(q_n) - h(k_n)||^2 + c_bal ||sum_n h(k_n)||^2 + lam ||W^T W - I||_F,
-//   h(x) = 2 Sigmoid(sigma x W) - 1 = tanh(sigma x W / 2)
+//   L = c_sim sum_n s_n ||h(q_n) - h(k_n)||^2 + c_bal sum_j ||sum_{n in query j} h(k_n)||^2
+//       + lam ||W^T W - I||_F,      h(x) = 2 Sigmoid(sigma x W) - 1 = tanh(sigma x W / 2)
+// (the balance term per query j, as the final hashing model prints it: the triplets of a query fill
+// whole blocks of TR_ROWS rows and every block names its query; without names the batch is one query)
 //
 // The two projections X W ([n,128] x [128,r]) and the weight-gradient contraction X^T dZ
 // ([128,n] x [n,r]) are dense contractions and run on MFMA (v_mfma_f32_32x32x16_bf16).  q and k are
@@ -11,8 +13,9 @@
 //
 // Launches of a step:
 //   1. train_colsum_kernel   h(k) of every key -> per-workgroup column sums (the balance term
-//                            couples every row to sum_n h(k_n), so that sum comes first);
-//      train_colreduce_kernel adds them up
+//                            couples every row to the sum of h(k) over its query, so those sums
+//                            come first);
+//      train_colreduce_kernel adds them up per query
 //   2. train_grad_kernel     forward of q and k again, dL/dz elementwise in the MFMA result
 //                            registers, then X^T dZ with those registers as the B operand (the
 //                            contraction index -- the row -- may be enumerated in any order, so the
@@ -30,7 +33,8 @@ struct hata_train_ctx {
     hata_train_config cfg;
     int n_wgs_max;
     float* colsum_part;  // [n_wgs_max, r]
-    float* colsum;       // [r]  sum_n h(k_n)
+    float* colsum;       // [queries (<= n_wgs_max), r]  sum of h(k_n) over the triplets of a query
+    double* scores;      // [n_max] qk scores of the label builder
     float* dw_part;      // [n_wgs_max, d, r]
     float* loss_part;    // [column groups (<= 2), n_wgs_max]
     float* P;            // [r, r]
@@ -136,29 +140,38 @@ __global__ __launch_bounds__((R < 128 ? R : 128) * 2) void train_colsum_kernel(
     if (half == 0) colsum_part[(int64_t)blockIdx.x * R + col] = cs;
 }
 
-// sum of the per-workgroup column sums: one workgroup per hash column
+// the query a block of TR_ROWS triplets belongs to (no names: everything is query 0; a name outside
+// [0, n_groups) counts as the nearest valid one, so no access leaves the arrays)
+__device__ __forceinline__ int block_query(const int32_t* __restrict__ block_group, int wg, int n_groups) {
+    return block_group ? clampi(block_group[wg], 0, n_groups - 1) : 0;
+}
+
+// sum of the per-workgroup column sums of one query: one workgroup per (hash column, query)
 __global__ __launch_bounds__(256) void train_colreduce_kernel(const float* __restrict__ colsum_part, int r,
-                                                              int n_wgs, float* __restrict__ colsum) {
+                                                              int n_wgs, const int32_t* __restrict__ block_group,
+                                                              int n_groups, float* __restrict__ colsum) {
     __shared__ float red[4];
-    const int j = blockIdx.x, tid = threadIdx.x;
+    const int j = blockIdx.x, q = blockIdx.y, tid = threadIdx.x;
     float acc = 0.f;
-    for (int g = tid; g < n_wgs; g += 256) acc += colsum_part[(int64_t)g * r + j];
+    for (int g = tid; g < n_wgs; g += 256)
+        if (block_query(block_group, g, n_groups) == q) acc += colsum_part[(int64_t)g * r + j];
     acc = wave_sum64(acc);
     if ((tid & 63) == 0) red[tid >> 6] = acc;
     __syncthreads();
-    if (tid == 0) colsum[j] = red[0] + red[1] + red[2] + red[3];
+    if (tid == 0) colsum[(int64_t)q * r + j] = red[0] + red[1] + red[2] + red[3];
 }
 
 template <int R>
 __global__ __launch_bounds__((R < 128 ? R : 128) * 2) void train_grad_kernel(
     const uint16_t* __restrict__ Q, const uint16_t* __restrict__ K, const float* __restrict__ s,
     const float* __restrict__ W, int n, float sigma, float c_sim2, float c_bal2,
-    const float* __restrict__ colsum, float* __restrict__ dw_part, float* __restrict__ loss_part) {
+    const float* __restrict__ colsum, const int32_t* __restrict__ block_group, int n_groups,
+    float* __restrict__ dw_part, float* __restrict__ loss_part) {
     constexpr int THREADS = (R < 128 ? R : 128) * 2;
     __shared__ __attribute__((aligned(16))) uint16_t tile_q[TR_ROWS * TR_PITCH];
     __shared__ __attribute__((aligned(16))) uint16_t tile_k[TR_ROWS * TR_PITCH];
     __shared__ float s_lab[TR_ROWS];
-    __shared__ float s_col[R];          // sum_n h(k_n) per hash column
+    __shared__ float s_col[R];          // sum of h(k_n) over this block's query, per hash column
     __shared__ float s_loss[THREADS / 64];
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int m = lane & 31, half = lane >> 5;
@@ -166,7 +179,8 @@ __global__ __launch_bounds__((R < 128 ? R : 128) * 2) void train_grad_kernel(
     const int col = blockIdx.y * 128 + w * 32 + m;
     tr_bf16x8_t wfrag[3][8];
     load_weight_planes<R>(W, col, half, wfrag);
-    for (int j = tid; j < R; j += THREADS) s_col[j] = colsum[j];
+    const float* colsum_q = colsum + (int64_t)block_query(block_group, blockIdx.x, n_groups) * R;
+    for (int j = tid; j < R; j += THREADS) s_col[j] = colsum_q[j];
     for (int i = tid; i < TR_ROWS; i += THREADS) s_lab[i] = (row0 + i < n) ? s[row0 + i] : 0.f;
     stage_rows<THREADS>(Q, row0, n, tile_q);
     stage_rows<THREADS>(K, row0, n, tile_k);
@@ -282,7 +296,7 @@ __global__ __launch_bounds__(256) void train_gram_kernel(const float* __restrict
 __global__ __launch_bounds__(256) void train_assemble_kernel(
     const float* __restrict__ W, int r, int n_wgs, float sigma, float lam, float c_sim, float c_bal,
     const float* __restrict__ dw_part, const float* __restrict__ P, const float* __restrict__ fro_part,
-    const float* __restrict__ colsum, const float* __restrict__ loss_part,
+    const float* __restrict__ colsum, int n_groups, const float* __restrict__ loss_part,
     float* __restrict__ G, float* __restrict__ grad, float* __restrict__ loss) {
     __shared__ float s_fro;
     __shared__ float red[4];
@@ -334,7 +348,7 @@ __global__ __launch_bounds__(256) void train_assemble_kernel(
         // similarity: sum of the workgroup partials; balance: squared norm of the column sums
         float ls = 0.f, lb = 0.f;
         for (int wg = tid; wg < n_wgs * ((r + 127) / 128); wg += 256) ls += loss_part[wg];
-        for (int j = tid; j < r; j += 256) lb = fmaf(colsum[j], colsum[j], lb);
+        for (int j = tid; j < r * n_groups; j += 256) lb = fmaf(colsum[j], colsum[j], lb);
         ls = wave_sum64(ls);
         lb = wave_sum64(lb);
         __syncthreads();
@@ -349,6 +363,54 @@ __global__ __launch_bounds__(256) void train_assemble_kernel(
             loss[1] = c_bal * (red[0] + red[1] + red[2] + red[3]);
             loss[2] = lam * fro;
         }
+    }
+}
+
+// Label builder (App. B.1, steps 3-4).  qk scores of one query against m keys, in fp64 (every product
+// of two bf16 values is exact there): a row per 16 lanes, 8 channels per lane.
+__global__ __launch_bounds__(256) void train_scores_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ K,
+                                                           int m, double* __restrict__ scores) {
+    const int sub = threadIdx.x & 15;
+    const int row = blockIdx.x * 16 + (threadIdx.x >> 4);
+    double acc = 0.0;
+    if (row < m) {
+        const uint4 kv = *reinterpret_cast<const uint4*>(K + (int64_t)row * HATA_D + sub * 8);
+        const uint4 qv = *reinterpret_cast<const uint4*>(q + sub * 8);
+        const uint32_t kw[4] = {kv.x, kv.y, kv.z, kv.w}, qw[4] = {qv.x, qv.y, qv.z, qv.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            acc = fma((double)bf16_lo(kw[i]), (double)bf16_lo(qw[i]), acc);
+            acc = fma((double)bf16_hi(kw[i]), (double)bf16_hi(qw[i]), acc);
+        }
+    }
+    // sum over the 16 lanes of the row, in a fixed order
+#pragma unroll
+    for (int o = 8; o >= 1; o >>= 1) acc += __shfl_xor(acc, o, 16);
+    if (row < m && sub == 0) scores[row] = acc;
+}
+
+// rank of every pair by counting (pairs with a larger score, or an equal score and a lower index,
+// come first); the first n_pos ranks get 20 .. 1 in equal steps, the others -1
+__global__ __launch_bounds__(256) void train_labels_kernel(const double* __restrict__ scores, int m, int n_pos,
+                                                           float* __restrict__ s) {
+    __shared__ double tile[256];
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    const double mine = i < m ? scores[i] : 0.0;
+    int rank = 0;
+    for (int j0 = 0; j0 < m; j0 += 256) {
+        __syncthreads();
+        tile[threadIdx.x] = (j0 + threadIdx.x < m) ? scores[j0 + threadIdx.x] : 0.0;
+        __syncthreads();
+        const int nj = min(256, m - j0);
+        for (int j = 0; j < nj; ++j) {
+            const double o = tile[j];
+            rank += (o > mine || (o == mine && j0 + j < i)) ? 1 : 0;
+        }
+    }
+    if (i < m) {
+        float lab = -1.f;
+        if (rank < n_pos) lab = (float)(n_pos == 1 ? 20.0 : 20.0 - 19.0 * (double)rank / (double)(n_pos - 1));
+        s[i] = lab;
     }
 }
 
@@ -369,7 +431,7 @@ __global__ __launch_bounds__(256) void train_update_kernel(float* __restrict__ W
 namespace {
 constexpr size_t kAlignT = 256;
 inline size_t align_up_t(size_t x) { return (x + kAlignT - 1) / kAlignT * kAlignT; }
-struct TrainPlan { int n_wgs_max; size_t off_colsum, off_cs, off_dw, off_loss, off_P, off_fro, off_G, total; };
+struct TrainPlan { int n_wgs_max; size_t off_colsum, off_cs, off_dw, off_loss, off_P, off_fro, off_G, off_scores, total; };
 int make_train_plan(const hata_train_config* f, TrainPlan* p) {
     if (!f) return HATA_EINVAL;
     if (f->n_max < 1) return HATA_EINVAL;
@@ -379,12 +441,13 @@ int make_train_plan(const hata_train_config* f, TrainPlan* p) {
     if (p->n_wgs_max > 65535) return HATA_EUNSUPPORTED;
     size_t o = 0;
     p->off_colsum = o; o = align_up_t(o + (size_t)p->n_wgs_max * f->r * 4);
-    p->off_cs = o;     o = align_up_t(o + (size_t)f->r * 4);
+    p->off_cs = o;     o = align_up_t(o + (size_t)p->n_wgs_max * f->r * 4);
     p->off_dw = o;     o = align_up_t(o + (size_t)p->n_wgs_max * f->d * f->r * 4);
     p->off_loss = o;   o = align_up_t(o + (size_t)p->n_wgs_max * 2 * 4);
     p->off_P = o;      o = align_up_t(o + (size_t)f->r * f->r * 4);
     p->off_fro = o;    o = align_up_t(o + (size_t)f->r * 4);
     p->off_G = o;      o = align_up_t(o + (size_t)f->d * f->r * 4);
+    p->off_scores = o; o = align_up_t(o + (size_t)f->n_max * 8);
     p->total = o;
     return HATA_OK;
 }
@@ -421,6 +484,7 @@ int hata_train_create(hata_train_ctx** ctx_out, const hata_train_config* cfg, vo
     c->P = (float*)(w + p.off_P);
     c->fro_part = (float*)(w + p.off_fro);
     c->G = (float*)(w + p.off_G);
+    c->scores = (double*)(w + p.off_scores);
     *ctx_out = c;
     return HATA_OK;
 }
@@ -431,10 +495,12 @@ int hata_train_destroy(hata_train_ctx* ctx) {
 }
 
 int hata_train_step(hata_train_ctx* ctx, const void* Q, const void* K, const float* s, int32_t n,
-                    float* W, float* v, const hata_train_hparams* hp, float* grad, float* loss,
-                    void* stream) {
+                    const int32_t* block_query, int32_t n_queries, float* W, float* v,
+                    const hata_train_hparams* hp, float* grad, float* loss, void* stream) {
     if (!ctx || !Q || !K || !s || !W || !v || !hp) return HATA_EINVAL;
     if (n < 1 || n > ctx->cfg.n_max) return HATA_EINVAL;
+    if (!block_query) n_queries = 1;
+    if (n_queries < 1 || n_queries > (n + TR_ROWS - 1) / TR_ROWS || ((uintptr_t)block_query % 4)) return HATA_EINVAL;
     if (((uintptr_t)Q % 16) || ((uintptr_t)K % 16) || ((uintptr_t)W % 16) || ((uintptr_t)v % 4) || ((uintptr_t)s % 4))
         return HATA_EINVAL;
     hipStream_t st = (hipStream_t)stream;
@@ -446,11 +512,12 @@ int hata_train_step(hata_train_ctx* ctx, const void* Q, const void* K, const flo
 #define HATA_TRAIN_LAUNCH(RR)                                                                          \
     hipLaunchKernelGGL((hata::train_colsum_kernel<RR>), dim3(n_wgs, (RR + 127) / 128),                 \
                        dim3((RR < 128 ? RR : 128) * 2), 0, st, k, W, n, hp->sigma, ctx->colsum_part);  \
-    hipLaunchKernelGGL(hata::train_colreduce_kernel, dim3(RR), dim3(256), 0, st, ctx->colsum_part, RR, \
-                       n_wgs, ctx->colsum);                                                            \
+    hipLaunchKernelGGL(hata::train_colreduce_kernel, dim3(RR, n_queries), dim3(256), 0, st,            \
+                       ctx->colsum_part, RR, n_wgs, block_query, n_queries, ctx->colsum);              \
     hipLaunchKernelGGL((hata::train_grad_kernel<RR>), dim3(n_wgs, (RR + 127) / 128),                   \
                        dim3((RR < 128 ? RR : 128) * 2), 0, st, q, k, s, W, n, hp->sigma,               \
-                       2.f * c_sim, 2.f * c_bal, ctx->colsum, ctx->dw_part, ctx->loss_part)
+                       2.f * c_sim, 2.f * c_bal, ctx->colsum, block_query, n_queries, ctx->dw_part,     \
+                       ctx->loss_part)
     switch (r) {
         case 32: HATA_TRAIN_LAUNCH(32); break;
         case 64: HATA_TRAIN_LAUNCH(64); break;
@@ -462,9 +529,23 @@ int hata_train_step(hata_train_ctx* ctx, const void* Q, const void* K, const flo
     const int count = ctx->cfg.d * r;
     hipLaunchKernelGGL(hata::train_assemble_kernel, dim3((count + 63) / 64), dim3(256), 0, st, W, r,
                        n_wgs, hp->sigma, hp->lam, c_sim, c_bal, ctx->dw_part, ctx->P, ctx->fro_part,
-                       ctx->colsum, ctx->loss_part, ctx->G, grad, loss);
+                       ctx->colsum, n_queries, ctx->loss_part, ctx->G, grad, loss);
     hipLaunchKernelGGL(hata::train_update_kernel, dim3((count + 255) / 256), dim3(256), 0, st, W, v,
                        ctx->G, count, hp->lr, hp->momentum, hp->weight_decay);
+    return hipGetLastError() == hipSuccess ? HATA_OK : HATA_EHIP;
+}
+
+int hata_train_make_labels(hata_train_ctx* ctx, const void* q, const void* K, int32_t m, float* s,
+                           void* stream) {
+    if (!ctx || !q || !K || !s) return HATA_EINVAL;
+    if (m < 1 || m > ctx->cfg.n_max) return HATA_EINVAL;
+    if (((uintptr_t)q % 16) || ((uintptr_t)K % 16) || ((uintptr_t)s % 4)) return HATA_EINVAL;
+    hipStream_t st = (hipStream_t)stream;
+    int n_pos = m / 10;
+    if (n_pos < 1) n_pos = 1;
+    hipLaunchKernelGGL(hata::train_scores_kernel, dim3((m + 15) / 16), dim3(256), 0, st, (const uint16_t*)q,
+                       (const uint16_t*)K, m, ctx->scores);
+    hipLaunchKernelGGL(hata::train_labels_kernel, dim3((m + 255) / 256), dim3(256), 0, st, ctx->scores, m, n_pos, s);
     return hipGetLastError() == hipSuccess ? HATA_OK : HATA_EHIP;
 }
 

@@ -228,6 +228,25 @@ def train_vectors(n: int, d: int = 128, latent: int = 8, seed: int = DEFAULT_SEE
     return round_to_bf16_bits(x.astype(np.float32))
 
 
+def massive_direction_vectors(n_keys: int, n_queries: int, d: int = 128, signal: int = 64, massive: int = 4,
+                              massive_scale: float = 20.0, noise: float = 0.1, query_scale: float = 4.0,
+                              seed: int = DEFAULT_SEED):
+    """Stand-in for the q / k vectors of a head whose keys carry a few directions of very large
+    magnitude that the queries ignore (LLM keys show such massive, query-irrelevant components; here
+    they are rotated away from the channel axes).  In a seeded orthonormal basis, keys have unit
+    variance on `signal` directions, `massive_scale` on `massive` further ones and `noise`
+    everywhere; queries live on the signal directions (plus the noise) and are scaled to a norm like
+    the keys'.  Returns bf16 bit patterns (K [n_keys, d], Q [n_queries, d])."""
+    basis, _ = np.linalg.qr(fill_f32(seed, TID_MISC + 80, (d, d), 1.0).astype(np.float64))
+    S, M = basis[:, :signal], basis[:, signal:signal + massive]
+    zk = fill_f32(seed, TID_K + 96, (n_keys, signal), 1.0).astype(np.float64)
+    mk = fill_f32(seed, TID_K + 112, (n_keys, massive), massive_scale).astype(np.float64)
+    K = zk @ S.T + mk @ M.T + fill_f32(seed, TID_K + 128, (n_keys, d), noise)
+    zq = fill_f32(seed, TID_Q + 96, (n_queries, signal), 1.0).astype(np.float64)
+    Q = query_scale * (zq @ S.T + fill_f32(seed, TID_Q + 128, (n_queries, d), noise))
+    return round_to_bf16_bits(K.astype(np.float32)), round_to_bf16_bits(Q.astype(np.float32))
+
+
 def outlier_scales(w: Workload, seed: int) -> np.ndarray:
     """Per-(KV head, channel) scale: ``n_outlier`` distinct channels per head get
     ``outlier_scale``; drawn with a partial Fisher-Yates shuffle of the channel ids."""

@@ -1,18 +1,19 @@
 """Thin ctypes binding of the learning-to-hash trainer in ``libhata.so`` (C ABI declared in
-``include/hata_train.h``), plus the host-side construction of training triplets.
+``include/hata_train.h``).
 
-Argument marshalling only for the training step: the loss, its gradient and the optimiser run in
-the HIP kernels.  torch allocates device memory and supplies the stream.  No CPU fallback.
+Argument marshalling only: the loss, its gradient, the optimiser and the construction of the
+training labels run in the HIP kernels.  torch allocates device memory and supplies the stream.
+No CPU fallback.
 """
 from __future__ import annotations
 
 import ctypes
 
-import numpy as np
-
 from . import hata as _hata
 
-EXPORTS = ("hata_train_workspace_bytes", "hata_train_create", "hata_train_destroy", "hata_train_step")
+EXPORTS = ("hata_train_workspace_bytes", "hata_train_create", "hata_train_destroy", "hata_train_step",
+           "hata_train_make_labels")
+BLOCK = 128  # HATA_TRAIN_BLOCK: triplets per block of the per-query balance term
 
 
 class hata_train_config(ctypes.Structure):
@@ -41,7 +42,9 @@ def _lib():
         lib.hata_train_workspace_bytes.argtypes = [ctypes.POINTER(hata_train_config), ctypes.POINTER(ctypes.c_size_t)]
         lib.hata_train_create.argtypes = [ctypes.POINTER(vp), ctypes.POINTER(hata_train_config), vp, ctypes.c_size_t]
         lib.hata_train_destroy.argtypes = [vp]
-        lib.hata_train_step.argtypes = [vp, vp, vp, vp, i32, vp, vp, ctypes.POINTER(hata_train_hparams), vp, vp, vp]
+        lib.hata_train_step.argtypes = [vp, vp, vp, vp, i32, vp, i32, vp, vp, ctypes.POINTER(hata_train_hparams),
+                                        vp, vp, vp]
+        lib.hata_train_make_labels.argtypes = [vp, vp, vp, i32, vp, vp]
         for n in EXPORTS:
             getattr(lib, n).restype = ctypes.c_int
         _bound = True
@@ -78,23 +81,13 @@ class TrainContext:
         except Exception:
             pass
 
-    def hata_train_step(self, Q, K, s, n, W, v, hp: hata_train_hparams, grad=None, loss=None, stream=None):
+    def hata_train_step(self, Q, K, s, n, W, v, hp: hata_train_hparams, grad=None, loss=None, stream=None,
+                        block_query=None, n_queries=1):
         _hata._check(_lib().hata_train_step(self._h, _hata._ptr(Q), _hata._ptr(K), _hata._ptr(s), n,
-                                            _hata._ptr(W), _hata._ptr(v), ctypes.byref(hp),
-                                            _hata._ptr(grad), _hata._ptr(loss), _hata._stream(stream)),
-                     "hata_train_step")
+                                            _hata._ptr(block_query), n_queries, _hata._ptr(W), _hata._ptr(v),
+                                            ctypes.byref(hp), _hata._ptr(grad), _hata._ptr(loss),
+                                            _hata._stream(stream)), "hata_train_step")
 
-
-def make_triplets(q: np.ndarray, K: np.ndarray):
-    """Training triplets of one sampled query against its causal keys (App. B.1 steps 2-5):
-    qk scores, the best tenth labelled 20 .. 1 in equal steps, the others -1.
-    q [d], K [m, d] as float arrays; returns (Q [m, d] = q repeated, K, s [m] float32)."""
-    q = np.asarray(q, dtype=np.float64)
-    K = np.asarray(K, dtype=np.float64)
-    m = K.shape[0]
-    scores = K @ q
-    ranking = np.lexsort((np.arange(m), -scores))  # best score first, earlier key first on ties
-    n_pos = max(1, m // 10)
-    s = np.full(m, -1.0, dtype=np.float32)
-    s[ranking[:n_pos]] = 20.0 if n_pos == 1 else np.linspace(20.0, 1.0, n_pos, dtype=np.float64).astype(np.float32)
-    return np.broadcast_to(q, (m, q.shape[0])).copy(), K, s
+    def hata_train_make_labels(self, q, K, m, s, stream=None):
+        _hata._check(_lib().hata_train_make_labels(self._h, _hata._ptr(q), _hata._ptr(K), m, _hata._ptr(s),
+                                                   _hata._stream(stream)), "hata_train_make_labels")

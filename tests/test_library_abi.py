@@ -43,7 +43,7 @@ def test_trainer_symbols_are_exported_and_bound():
     assert lib.hata_train_workspace_bytes(None, ctypes.byref(n)) == -1
     h = ctypes.c_void_p()
     assert lib.hata_train_create(ctypes.byref(h), ctypes.byref(train.hata_train_config(128, 128, 10)), None, 0) == -3
-    assert lib.hata_train_step(None, None, None, None, 1, None, None, None, None, None, None) == -1
+    assert lib.hata_train_step(None, None, None, None, 1, None, 1, None, None, None, None, None, None) == -1
     assert lib.hata_train_destroy(None) == 0
 
 
