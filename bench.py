@@ -89,6 +89,9 @@ def parse():
     ap.add_argument("--pmc-probe", action="store_true",
                     help="run only a known-size copy kernel, the decode step and the scoring kernel (for "
                          "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs that calibrate and measure HBM traffic)")
+    ap.add_argument("--overlap-probe", action="store_true",
+                    help="run only hata_probe_mfma_stream: a loop of bf16 matrix-core instructions, a 1 GiB "
+                         "read, and both in one launch, timed with events (do the two overlap on this device?)")
     return ap.parse_args()
 
 
@@ -532,6 +535,41 @@ class Bench:
                 "step_algorithmic_bytes": self.alg_bytes, "step_launches": ctx.hata_step_plan(w.B)[0]}
 
 
+def overlap_probe(torch, gib=1, reps=5):
+    """Times hata_probe_mfma_stream in its three modes on bf16 N(0,1) data: the matrix-core loop alone
+    (sized to take about as long as the read), the read alone, and both in one launch."""
+    from paper_2506_02572_amd import hata
+    dev = torch.device("cuda:0")
+    buf = torch.randn((gib << 30) // 2, dtype=torch.bfloat16, device=dev).view(torch.int16)
+    stream = torch.cuda.current_stream()
+
+    def run(mode, iters):
+        best = None
+        for _ in range(reps):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            hata.hata_probe_mfma_stream(buf, iters, mode, stream)
+            e1.record(stream)
+            e1.synchronize()
+            t = e0.elapsed_time(e1) * 1e3
+            best = t if best is None else min(best, t)
+        return best
+
+    us_mem = run(2, 0)
+    iters = 256
+    us_mfma = run(1, iters)
+    iters = max(16, int(iters * us_mem / us_mfma))  # a matrix-core loop about as long as the read
+    us_mfma = run(1, iters)
+    us_both = run(3, iters)
+    n_mfma = 16 * iters  # per wave = per SIMD (one matrix-core wave per SIMD on 256 CUs)
+    return {"overlap_probe": True, "bytes_read": buf.numel() * 2, "mfma_per_simd": n_mfma,
+            "stream_only_us": round(us_mem, 1), "stream_only_TBps": round(buf.numel() * 2 / us_mem / 1e6, 2),
+            "mfma_only_us": round(us_mfma, 1),
+            "mfma_only_TFLOPs": round(2.0 * 32 * 32 * 16 * n_mfma * 1024 / us_mfma / 1e6, 1),
+            "both_us": round(us_both, 1), "sum_of_parts_us": round(us_mem + us_mfma, 1),
+            "max_of_parts_us": round(max(us_mem, us_mfma), 1)}
+
+
 def train_leg(torch, dev, w, W_H, stream):
     """Learning-to-hash training step (Sec. 3.1 / App. B): one SGD step on one head's W_H from a
     32K-triplet chunk (the chunk size of App. B.2)."""
@@ -596,6 +634,9 @@ def main():
         print("bench.py: no GPU visible; the HATA path has no CPU fallback", file=sys.stderr)
         sys.exit(1)
     torch.cuda.set_device(0)
+    if args.overlap_probe:
+        print(json.dumps(overlap_probe(torch)))
+        return
     default_run = args.workload == "cfg2" and not (args.kv_host or args.paged or args.pmc_probe or args.step_mode or args.chunk)
     b = Bench(args.workload, args, layers=args.layers, kv_host=args.kv_host, step_mode=args.step_mode)
     w = b.w

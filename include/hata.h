@@ -339,6 +339,15 @@ int hata_host_device_pointer(void* host, void** dev_out);
  * for B_max); valid until the workspace is released.  Any output pointer may be NULL. */
 int hata_step_buffers(hata_ctx* ctx, uint32_t** qcodes, uint16_t** scores, int32_t** idx);
 
+/* Diagnostic (no part of the method; used by bench.py --overlap-probe): one launch of 256 workgroups
+ * in which four waves per workgroup issue mfma_iters x 16 bf16 matrix-core instructions on operands
+ * taken from the first 10 KB of buf (mode bit 0) and four waves read the workgroup's 1/256 share of
+ * buf [bytes] with 16-byte loads (mode bit 1).  buf: device memory, 16-byte aligned, at least 4 MiB,
+ * read only; fill it with values like the workload's (the matrix cores' rate depends on them).  The
+ * caller times mode 1, mode 2 and mode 3 to see whether the two overlap on the device at hand.
+ * Returns HATA_EINVAL for bad arguments; enqueues on `stream` and returns. */
+int hata_probe_mfma_stream(const void* buf, size_t bytes, int32_t mfma_iters, int32_t mode, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -10,7 +10,7 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libhata.so")
 OBJ = os.path.join(HERE, "_build")
 SOURCES = ["hata_api.hip", "hata_encode.hip", "hata_score.hip", "hata_topk.hip", "hata_attn.hip", "hata_gather.hip", "hata_coop.hip",
-           "hata_train.hip"]
+           "hata_train.hip", "hata_probe.hip"]
 HEADERS = ["hata_device.h", "hata_internal.h", "hata_select.h", "hata_trace.h", "hata_attn_core.h", os.path.join("..", "..", "include", "hata.h"),
            os.path.join("..", "..", "include", "hata_train.h")]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")

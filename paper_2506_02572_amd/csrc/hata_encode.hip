@@ -414,6 +414,226 @@ __global__ __launch_bounds__(R * 2) void encode_mfma_kernel(
     }
 }
 
+// ---- key encode with fp16 weight planes -------------------------------------------------------
+// The projection for keys that already lie in a contiguous cache (no fused fill), with weights
+// prepared by hata_prepare_weights.  Two things differ from encode_mfma_kernel.
+//
+// (1) Two fp16 planes instead of three bf16 planes.  With realistic operand values the matrix cores
+// of the whole chip sustain about 55 cycles per v_mfma_f32_32x32x16 and SIMD, not 32 (measured with a
+// loop of nothing but MFMAs: the rate depends on the values, i.e. on power), and the three-plane kernel's
+// stage loop runs at exactly that rate -- so what shortens the kernel is fewer MFMAs.  Per hash-column
+// tile (32 columns) the weights are scaled by a power of two S so that max |W S| < 2^14 (signs and
+// therefore code bits are unchanged), hi = fp16(W S), lo = fp16(W S - hi): |W S - hi - lo| <= 2^-22 |W S|.
+// A bf16 key channel converts to fp16 exactly for 2^-14 <= |x| <= 65504 (eight significant bits);
+// smaller values lose at most 2^-25 absolutely, larger ones saturate at 65504.  Every product of two
+// fp16 values is exact in the fp32 accumulator.  The projection therefore differs from the exact one by
+// at most 2^-22 * sum_c |x_c W_c| (about 5e-6 for the workloads here) plus the fp32 summation error the
+// bf16 form has as well: far inside the band of 1e-4 in which code bits may differ from an exact evaluation.
+//
+// (2) The key rows are staged by the memory pipeline itself: global_load_lds_dwordx4 moves 16 bytes
+// per lane from memory straight into LDS (lane l of a wave lands at the instruction's LDS base + 16 l),
+// so a stage costs no registers and several stages can be on their way while one is being multiplied.
+// A workgroup cycles through DMA_NBUF tiles of DMA_STAGE keys: in turn s it waits for tile s, passes the
+// one barrier of the turn, requests tile s + DMA_NBUF - 1 into the buffer that turn s - 1 has just
+// finished with, and multiplies tile s.
+// LDS tile: row r at byte 256 r, unpadded; its 16-byte piece c sits in slot c ^ (r & 15), which makes
+// the operand reads (32 rows, one piece index) conflict-free.  A lane of a DMA instruction therefore
+// fetches piece slot ^ (row & 15) of its row: 16 lanes still read one whole 256-byte row.
+// Every wave converts the key fragments it reads to fp16 itself (three VALU instructions per dword, in
+// the shadow of the MFMAs).  The code words of a stage go through a small LDS array and leave as
+// 16-byte stores one turn later.
+typedef __attribute__((ext_vector_type(8))) _Float16 f16x8_t;
+typedef __attribute__((ext_vector_type(2))) __fp16 fp16x2_t;
+#define DMA_STAGE 64
+#define DMA_NBUF 4
+
+// Fragment order of the fp16 planes: for KV head h, wave w (hash columns 32 w .. 32 w + 31), channel
+// step kk and plane p (0 = hi, 1 = lo) the 64 lanes' 16-byte fragments lie one after the other:
+//   uint4 index = (((h * (R / 32) + w) * 8 + kk) * 2 + p) * 64 + lane
+// grid = (R / 32, Hkv); 64 threads: one wave scales and splits its 32 columns
+__global__ __launch_bounds__(64) void split_weights_f16_kernel(const float* __restrict__ W_H, uint4* __restrict__ planes, int R) {
+    const int lane = threadIdx.x, w = blockIdx.x, h = blockIdx.y;
+    const int m = lane & 31, half = lane >> 5;
+    const float* wp = W_H + (int64_t)h * HATA_D * R + w * 32 + m;
+    float wv[8][8];
+    float mx = 0.f;
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            wv[kk][e] = wp[(int64_t)(kk * 16 + 8 * half + e) * R];
+            mx = fmaxf(mx, fabsf(wv[kk][e]));  // (fmaxf drops NaN)
+        }
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 64));
+    int ex = 14;  // scale 1 for an all-zero or non-finite tile
+    if (mx > 0.f && mx < __builtin_inff()) (void)frexpf(mx, &ex);  // mx = f 2^ex, 0.5 <= f < 1
+    const int sh = 14 - ex;                                        // max |W| 2^sh < 2^14
+    uint4* dst = planes + ((int64_t)(h * (R / 32) + w) * 8 * 2) * 64 + lane;
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk) {
+        f16x8_t hi, lo;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const float ws = ldexpf(wv[kk][e], sh);
+            hi[e] = (_Float16)ws;                 // round to nearest even
+            lo[e] = (_Float16)(ws - (float)hi[e]);  // (the difference is exact in fp32)
+        }
+        dst[(kk * 2 + 0) * 64] = __builtin_bit_cast(uint4, hi);
+        dst[(kk * 2 + 1) * 64] = __builtin_bit_cast(uint4, lo);
+    }
+}
+
+// eight bf16 values (one 16-byte operand fragment) -> fp16
+__device__ __forceinline__ f16x8_t bf16x8_to_f16(const uint4 v) {
+    const uint32_t x[4] = {v.x, v.y, v.z, v.w};
+    uint32_t o[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+        o[i] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(bf16_lo(x[i]), bf16_hi(x[i])));
+    return __builtin_bit_cast(f16x8_t, make_uint4(o[0], o[1], o[2], o[3]));
+}
+
+template <int R>
+__global__ __launch_bounds__(R * 2) void encode_dma_kernel(
+    const uint16_t* __restrict__ K, const uint4* __restrict__ planes,
+    const int32_t* __restrict__ start, const int32_t* __restrict__ n_new, uint32_t* __restrict__ codes,
+    int Hkv, int L_cap, int keys_per_wg, int64_t sb, int64_t sh, int64_t sn) {
+    constexpr int WAVES = R / 32, WD = R / 32;
+    constexpr int NT = DMA_STAGE / 32;                 // 32-key MFMA tiles per stage
+    constexpr int INSTR = DMA_STAGE / (WAVES * 4);     // DMA instructions per wave and stage (4 rows each)
+    static_assert(INSTR >= 1 && INSTR * WAVES * 4 == DMA_STAGE, "a stage is a whole number of DMA instructions per wave");
+    __shared__ __attribute__((aligned(16))) uint4 tile[DMA_NBUF][DMA_STAGE * 16];
+    __shared__ __attribute__((aligned(16))) uint32_t cbuf[2][DMA_STAGE * WD];
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int m = lane & 31, half = lane >> 5;
+    const int h = blockIdx.y, b = blockIdx.z;
+    const int first = start[b];
+    const int cnt = min(n_new[b], L_cap - first);
+    const int kb0 = blockIdx.x * keys_per_wg;
+    if (first < 0 || kb0 >= cnt) return;
+    const int kb1 = min(kb0 + keys_per_wg, cnt);
+    const int64_t u = (int64_t)b * Hkv + h;
+    const uint16_t* Kb = K + b * sb + h * sh + (int64_t)first * sn;
+    uint32_t* cb = codes + (u * L_cap + first) * WD;
+    const int n_stages = (kb1 - kb0 + DMA_STAGE - 1) / DMA_STAGE;
+
+    // rows past the end of the range are fetched from the range's last row (valid memory; their code
+    // words are never stored)
+    const int drow = lane >> 4, dslot = lane & 15;
+    auto request = [&](int s) {
+        const int k0 = kb0 + s * DMA_STAGE;
+        uint4* dst = &tile[s % DMA_NBUF][0];
+#pragma unroll
+        for (int it = 0; it < INSTR; ++it) {
+            const int r0 = (it * WAVES + w) * 4;
+            const int row = r0 + drow;
+            const int key = min(k0 + row, kb1 - 1);
+            const uint16_t* g = Kb + (int64_t)key * sn + ((dslot ^ (row & 15)) * 8);
+            // (written as an instruction: given the compiler's builtin for it, every later LDS read is
+            // made to wait for ALL requests outstanding, which is the one thing this kernel must not do;
+            // the waits are the explicit ones in the stage loop)
+            const uint32_t lds_base = __builtin_amdgcn_readfirstlane(
+                (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)(dst + r0 * 16));
+            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+                         :: "s"(lds_base), "v"(g) : "memory", "m0");
+        }
+    };
+    // weight fragments first (they are needed for as long as the kernel runs), then the first tiles
+    f16x8_t afrag[2][8];
+    {
+        const uint4* src = planes + ((int64_t)(h * (R / 32) + w) * 8 * 2) * 64 + lane;
+#pragma unroll
+        for (int kk = 0; kk < 8; ++kk)
+#pragma unroll
+            for (int p = 0; p < 2; ++p) afrag[p][kk] = __builtin_bit_cast(f16x8_t, src[(kk * 2 + p) * 64]);
+    }
+#pragma unroll
+    for (int s = 0; s < DMA_NBUF - 1; ++s)
+        if (s < n_stages) request(s);
+    // the weight fragments are there before the loop starts (said explicitly, or the compiler guards
+    // their every use inside the loop with a count of outstanding loads that fits the first turn only)
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
+
+    // 16-byte pieces of the previous stage's code words that this thread stores (none for most threads)
+    constexpr int CODE_VEC = DMA_STAGE * WD / 4;
+    auto flush_codes = [&](int s) {  // code words of stage s, staged in cbuf[s & 1]
+        const int k0 = kb0 + s * DMA_STAGE;
+        if constexpr (WD >= 4) {  // (a key's code is 16 bytes or more: every piece is aligned)
+            if (tid < CODE_VEC && k0 + (tid * 4) / WD < kb1)
+                reinterpret_cast<uint4*>(cb + (int64_t)k0 * WD)[tid] = reinterpret_cast<const uint4*>(&cbuf[s & 1][0])[tid];
+        } else {
+            if (tid < DMA_STAGE * WD && k0 + tid / WD < kb1) cb[(int64_t)k0 * WD + tid] = cbuf[s & 1][tid];
+        }
+    };
+    for (int s = 0; s < n_stages; ++s) {
+        // tile s has landed once at most the requests made after it are outstanding: those of the
+        // DMA_NBUF - 2 tiles that follow (stores of code words, if any, only make this wait longer)
+        if (s + DMA_NBUF - 2 < n_stages) __builtin_amdgcn_s_waitcnt(0x0F70 | (((DMA_NBUF - 2) * INSTR) & 15) | ((((DMA_NBUF - 2) * INSTR) >> 4) << 14));
+        else __builtin_amdgcn_s_waitcnt(0x0F70);
+        __syncthreads();  // every wave's part of tile s is there; everybody is done with tile s - 1
+        if (s + DMA_NBUF - 1 < n_stages) request(s + DMA_NBUF - 1);
+        if (s > 0) flush_codes(s - 1);
+        const uint4* tl = &tile[s % DMA_NBUF][0];
+        f32x16_t acc[NT];
+#pragma unroll
+        for (int t = 0; t < NT; ++t)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[t][i] = 0.f;
+        // Key fragments: the raw bf16 pieces are read from LDS two channel steps ahead and converted one
+        // step ahead, so that neither the LDS latency nor the conversion stands in front of an MFMA (the
+        // scheduler is told to keep the steps apart: left alone it moves each read down to its first use)
+        auto piece = [&](int kk, int t) { return tl[(t * 32 + m) * 16 + ((2 * kk + half) ^ (m & 15))]; };
+        uint4 raw[NT];
+        f16x8_t bcur[NT], bnext[NT];
+#pragma unroll
+        for (int t = 0; t < NT; ++t) raw[t] = piece(0, t);
+#pragma unroll
+        for (int t = 0; t < NT; ++t) bcur[t] = bf16x8_to_f16(raw[t]);
+#pragma unroll
+        for (int t = 0; t < NT; ++t) raw[t] = piece(1, t);
+#pragma unroll
+        for (int kk = 0; kk < 8; ++kk) {
+            __builtin_amdgcn_sched_barrier(0);
+            if (kk + 1 < 8) {
+#pragma unroll
+                for (int t = 0; t < NT; ++t) bnext[t] = bf16x8_to_f16(raw[t]);
+            }
+            if (kk + 2 < 8) {
+#pragma unroll
+                for (int t = 0; t < NT; ++t) raw[t] = piece(kk + 2, t);
+            }
+#pragma unroll
+            for (int p = 0; p < 2; ++p)
+#pragma unroll
+                for (int t = 0; t < NT; ++t)
+                    acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_f16(afrag[p][kk], bcur[t], acc[t], 0, 0, 0);
+            // one MFMA, then a quarter of the step's conversions in its shadow
+#pragma unroll
+            for (int q = 0; q < 2 * NT; ++q) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);           // MFMA
+                __builtin_amdgcn_sched_group_barrier(0x002, 12 / 2, 0);      // VALU
+            }
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int t = 0; t < NT; ++t) bcur[t] = bnext[t];
+        }
+        // sign bits: this lane holds hash columns 8*(i/4) + 4*half + i%4 of key t*32 + m
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+            uint32_t neg = 0;
+#pragma unroll
+            for (int i = 0; i < 16; ++i)
+                neg |= (__float_as_uint(acc[t][i]) >> 31) << (8 * (i / 4) + (i % 4));
+            uint32_t word = (~neg & 0x0f0f0f0fu) << (4 * half);
+            word |= (uint32_t)__shfl_xor((int)word, 32, 64);
+            if (half == 0) cbuf[s & 1][(t * 32 + m) * WD + w] = word;
+        }
+    }
+    __syncthreads();
+    flush_codes(n_stages - 1);
+}
+
 hipError_t launch_encode_vectors(const hata_ctx* c, const void* q, uint32_t* qcodes,
                                  const void* K, const int32_t* start, const int32_t* n_new,
                                  int max_new, int from_seq_len, uint32_t* codes,
@@ -463,6 +683,19 @@ hipError_t launch_encode_bulk(const hata_ctx* c, const void* K, const float* W_H
         const dim3 grid((max_new + kpw - 1) / kpw, f.Hkv, B);
         // the weight planes prepared for exactly this weight tensor, if any (hata_prepare_weights)
         const uint4* planes = (c->prepared_W_H == W_H && c->wplanes) ? (const uint4*)c->wplanes : nullptr;
+        if (!kn && !pages && planes) {
+            // keys already in a contiguous cache, weights prepared: the fp16-plane kernel
+            const uint4* p16 = planes + (size_t)f.Hkv * 3 * 128 * f.r * 2 / 16;
+#define HATA_LAUNCH_DMA(R_)                                                                                   \
+    hipLaunchKernelGGL((encode_dma_kernel<R_>), grid, dim3(R_ * 2), 0, s, (const uint16_t*)K, p16, start, n_new, \
+                       codes, f.Hkv, f.L_cap, kpw, f.kv_stride_b, f.kv_stride_h, f.kv_stride_n)
+            if (f.r == 32) HATA_LAUNCH_DMA(32);
+            else if (f.r == 64) HATA_LAUNCH_DMA(64);
+            else if (f.r == 128) HATA_LAUNCH_DMA(128);
+            else HATA_LAUNCH_DMA(256);
+#undef HATA_LAUNCH_DMA
+            return hipGetLastError();
+        }
 #define HATA_LAUNCH_MFMA(R_, P_)                                                                           \
     do {                                                                                                   \
         if (planes)                                                                                        \
@@ -497,9 +730,13 @@ hipError_t launch_encode_bulk(const hata_ctx* c, const void* K, const float* W_H
 }
 
 // Split of the fp32 hash weights into three bf16 planes in the fragment order of encode_mfma_kernel
+// and into two scaled fp16 planes in the fragment order of encode_dma_kernel
 hipError_t launch_split_weights(const hata_ctx* c, const float* W_H, hipStream_t s) {
     const hata_config& f = c->cfg;
     hipLaunchKernelGGL(split_weights_kernel, dim3(f.r / 32, f.Hkv), dim3(64), 0, s, W_H, (uint4*)c->wplanes, f.r);
+    // the two fp16 planes lie behind the three bf16 planes
+    hipLaunchKernelGGL(split_weights_f16_kernel, dim3(f.r / 32, f.Hkv), dim3(64), 0, s, W_H,
+                       (uint4*)c->wplanes + (size_t)f.Hkv * 3 * 128 * f.r * 2 / 16, f.r);
     return hipGetLastError();
 }
 

@@ -20,7 +20,7 @@ EXPORTS = (
     "hata_prefill_write", "hata_prefill_write_paged", "hata_encode_query", "hata_hamming_score", "hata_topk", "hata_sparse_decode",
     "hata_sparse_decode_static", "hata_gather_rows", "hata_dense_decode", "hata_decode_step", "hata_select_step", "hata_decode_step_paged", "hata_step_plan", "hata_step_sub_batches", "hata_set_step_mode", "hata_keep_step_scores", "hata_set_wait_limit",
     "hata_check",
-    "hata_host_device_pointer", "hata_step_buffers",
+    "hata_host_device_pointer", "hata_step_buffers", "hata_probe_mfma_stream",
 )
 
 
@@ -97,6 +97,7 @@ def load_library(build_if_missing: bool = True) -> ctypes.CDLL:
     lib.hata_check.argtypes = [_vp, _vp]
     lib.hata_host_device_pointer.argtypes = [_vp, ctypes.POINTER(_vp)]
     lib.hata_step_buffers.argtypes = [_vp, ctypes.POINTER(_vp), ctypes.POINTER(_vp), ctypes.POINTER(_vp)]
+    lib.hata_probe_mfma_stream.argtypes = [_vp, ctypes.c_size_t, _i32, _i32, _vp]
     for name in EXPORTS:
         if name != "hata_strerror":
             getattr(lib, name).restype = ctypes.c_int
@@ -321,3 +322,9 @@ class Context:
         return (view(qc, s.B_max * s.Hq * Wd * 4, torch.int32, (s.B_max, s.Hq, Wd)),
                 view(sc, s.B_max * s.Hkv * s.L_cap * 2, torch.int16, (s.B_max, s.Hkv, s.L_cap)),
                 view(ix, s.B_max * s.Hkv * s.k_max * 4, torch.int32, (s.B_max, s.Hkv, s.k_max)))
+
+
+def hata_probe_mfma_stream(buf, mfma_iters, mode, stream=None):
+    """Diagnostic launch (see include/hata.h): mode bit 0 = matrix-core waves, bit 1 = streaming waves."""
+    _check(load_library().hata_probe_mfma_stream(_ptr(buf), buf.numel() * buf.element_size(), int(mfma_iters),
+                                                 int(mode), _stream(stream)), "hata_probe_mfma_stream")

@@ -53,13 +53,18 @@ def run_workload(torch, w, steps_to_check, single_launch, dense=True):
     n_proj = int(prefill.sum()) * w.Hkv * w.r
     print(f"[full]   bulk encode: {n_proj} projections, {n_band} inside the band, {n_flip} bits differ there",
           flush=True)
-    # the same with the weight planes prepared once (hata_prepare_weights): identical code words
+    # the same with the weight planes prepared once (hata_prepare_weights): the key-code writer then
+    # runs its fp16-plane form, whose bits may differ from the exact evaluation inside the band only
     if w.r in (32, 64, 128, 256):
         codes_p = torch.zeros_like(codes_d)
         c.ctx.hata_prepare_weights(c.W_H)
         c.ctx.hata_encode_keys(c.K, c.W_H, c.zero, H.to_dev(prefill), B, int(prefill.max()), codes_p)
         c.sync()
-        assert torch.equal(codes_p, codes_d), "prepared weight planes give different key codes"
+        diff_p = H.to_host(codes_p, np.uint32) ^ codes_ref
+        assert not np.any(diff_p & ~near), "key codes from prepared weight planes differ outside the band"
+        print(f"[full]   bulk encode, prepared planes: {int(np.unpackbits(diff_p.view(np.uint8)).sum())} bits "
+              f"differ inside the band", flush=True)
+        del diff_p
         # a different tensor at another address must not pick up the prepared planes
         W2 = (c.W_H.view(torch.float32) * 1.0).clone().view(c.W_H.dtype)
         codes_p.zero_()
