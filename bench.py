@@ -76,7 +76,7 @@ def parse():
     ap.add_argument("--step-mode", type=int, default=0, choices=(0, 1, 3),
                     help="hata_set_step_mode: 0 = single-launch form, a batch too large to be resident in "
                          "slices (default); 1 = the whole batch as one grid; 3 = three-launch form")
-    ap.add_argument("--chunk", type=int, default=0, choices=(0, 1024, 2048, 4096, 8192),
+    ap.add_argument("--chunk", type=int, default=0, choices=(0, 1024, 2048, 4096, 8192, 16384, 32768),
                     help="hata_tuning.chunk: cached keys per scoring workgroup (0 = the library's choice)")
     ap.add_argument("--paged", type=int, default=0, metavar="PAGE_ROWS",
                     help="also time the step on the paged (block-table) layout: the caches are re-laid as "

@@ -90,7 +90,10 @@ int hata_create(hata_ctx** ctx_out, const hata_config* cfg, void* workspace, siz
  * shapes; tests of the batch slicing on small inputs; a device that is not the caller's alone).
  * A zero-initialised struct, or a NULL pointer, means "all defaults". */
 typedef struct {
-    int32_t chunk;         /* cached keys per scoring workgroup: 0 = default, else 1024, 2048, 4096 or 8192 */
+    int32_t chunk;         /* cached keys per scoring workgroup: 0 = default (the single-launch step then picks, per
+                            * call, the size that needs the fewest launches for the batch), else 1024, 2048,
+                            * 4096 or 8192 for every kernel, or 16384 / 32768 for the single-launch step alone
+                            * (contiguous caches only; the other kernels keep their default) */
     int32_t attn_rows;     /* selected rows per attention workgroup of the three-launch form: 0 = default, else a power of two in 16..256 */
     int32_t par_merge;     /* single-launch form, merge of a unit's partials: -1 = default, 0 = by the last workgroup to arrive, 1 = a query head per workgroup */
     int32_t shared_device; /* != 0: other work may run on the device beside the step, so the context starts in step mode 3 (see hata_set_step_mode) */
@@ -284,8 +287,8 @@ int hata_prefill_write_paged(hata_ctx* ctx, const void* K_new, const void* V_new
 
 /* Host-side query of how hata_decode_step() runs a batch of B sequences; nothing is enqueued.
  * *n_launches: 1 (single-launch form) or 3 (three-launch form); *chunk: cached keys per scoring
- * workgroup; *n_chunks: scoring workgroups per (sequence, KV head).  Any output pointer (host)
- * may be NULL. */
+ * workgroup for a batch of this size; *n_chunks: scoring workgroups per (sequence, KV head).  Any
+ * output pointer (host) may be NULL. */
 int hata_step_plan(const hata_ctx* ctx, int32_t B, int32_t* n_launches, int32_t* chunk, int32_t* n_chunks);
 
 /* A batch with more (sequence, KV head) units than one launch can keep resident still runs in the

@@ -40,7 +40,7 @@ constexpr int kMaxDevices = 64;
 inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
 struct Plan {
-    int G, Wd, NB, NBP, chunk, n_chunks, HT, sparse_rows, sparse_splits, dense_rows, dense_splits;
+    int G, Wd, NB, NBP, chunk, n_chunks, coop_chunk, HT, sparse_rows, sparse_splits, dense_rows, dense_splits;
     size_t off_qcodes, off_scores, off_idx, off_hist, off_cinfo, off_uinfo, off_ucnt, off_acnt, off_uflag, off_qrec, off_err, off_uhist, off_partials, off_wplanes, total;
 };
 
@@ -78,14 +78,22 @@ int make_plan(const hata_config* f, const hata_tuning* t, Plan* p) {
     int chunk = 4096;
     while (chunk > 1024 && units * ((f->L_cap + chunk / 2 - 1) / (chunk / 2)) <= max_wgs) chunk >>= 1;
     while (chunk < 8192 && (f->L_cap + chunk - 1) / chunk > 1024) chunk <<= 1;
+    // the single-launch step can give a workgroup more keys than the other kernels' chunk (its scores
+    // stay in LDS, up to 32768 of them): fewer workgroups per unit, fewer exchanges between them
+    int coop_chunk = 0;
     if (t && t->chunk != 0) {  // the caller's choice (launch-shape sweeps, tests of the batch slicing)
         const int v = t->chunk;
-        if (!(v == 1024 || v == 2048 || v == 4096 || v == 8192) || (f->L_cap + v - 1) / v > 1024) return HATA_EINVAL;
-        chunk = v;
+        if (v == 16384 || v == 32768) {
+            coop_chunk = v;  // the single-launch step only; the other kernels keep the choice made above
+        } else {
+            if (!(v == 1024 || v == 2048 || v == 4096 || v == 8192) || (f->L_cap + v - 1) / v > 1024) return HATA_EINVAL;
+            chunk = v;
+        }
     }
     p->chunk = chunk;
     p->n_chunks = (f->L_cap + chunk - 1) / chunk;
     if (p->n_chunks > 1024) return HATA_EUNSUPPORTED;  // L_cap above 8M rows
+    p->coop_chunk = (t && t->chunk != 0) ? (coop_chunk > chunk ? coop_chunk : chunk) : 0;  // 0: chosen per call
     const int G = p->G;
     // (16 heads as two tiles of 8: measured faster than one tile of 16 for the stand-alone kernels)
     p->HT = (G % 8 == 0) ? 8 : (G % 5 == 0) ? 5 : (G % 4 == 0) ? 4 : (G % 2 == 0) ? 2 : 1;
@@ -144,20 +152,31 @@ inline int check_call(const hata_ctx* c, int B) {
 // Single-launch form of the step: the number of launches a batch of B sequences is cut into -- every
 // launch must be resident as a whole, so a batch with more (sequence, KV head) units than that
 // allows goes in equal slices, one launch each -- or 0 when the form is not available.
-inline int coop_sub_batches(const hata_ctx* c, int B, bool paged) {
-    if (c->step_mode == 3 || c->n_chunks > 256) return 0;
-    const int cap = paged ? c->coop_capacity_paged : c->coop_capacity;
-    const int64_t per_seq = (int64_t)c->n_chunks * c->cfg.Hkv;
-    if (cap <= 0 || per_seq > cap) return 0;
-    // the whole batch in one grid, whatever its size, if the workgroups of the units that are at
-    // work together -- eight units interleaved when their number is a multiple of eight, else
-    // one -- fit the device at once; otherwise in slices, as in mode 0
-    if (c->step_mode == 1) {
-        const int64_t span = ((int64_t)B * c->cfg.Hkv % 8 == 0 ? 8 : 1) * (int64_t)c->n_chunks;
-        if (span <= cap) return 1;
+inline int coop_sub_batches(const hata_ctx* c, int B, bool paged, int* chunk_out = nullptr) {
+    if (c->step_mode == 3) return 0;
+    // paged caches and the oversubscribed grid of mode 1 use the first size only
+    const int n_opts = (paged || c->step_mode == 1) ? 1 : c->coop_opts;
+    int best = 0, best_chunk = 0;
+    for (int o = 0; o < n_opts; ++o) {
+        const int chunk = c->coop_opt_chunk[o];
+        const int n_chunks = (c->cfg.L_cap + chunk - 1) / chunk;
+        const int cap = paged ? c->coop_capacity_paged : c->coop_opt_cap[o];
+        const int64_t per_seq = (int64_t)n_chunks * c->cfg.Hkv;
+        if (n_chunks > 256 || cap <= 0 || per_seq > cap) continue;
+        int ns;
+        // mode 1: the whole batch in one grid, whatever its size, if the workgroups of the units that
+        // are at work together -- eight units interleaved when their number is a multiple of eight,
+        // else one -- fit the device at once; otherwise in slices, as in mode 0
+        if (c->step_mode == 1 && ((int64_t)B * c->cfg.Hkv % 8 == 0 ? 8 : 1) * (int64_t)n_chunks <= cap) {
+            ns = 1;
+        } else {
+            const int per_launch = (int)(cap / per_seq);
+            ns = (B + per_launch - 1) / per_launch;
+        }
+        if (best == 0 || ns < best) { best = ns; best_chunk = chunk; }
     }
-    const int per_launch = (int)(cap / per_seq);
-    return (B + per_launch - 1) / per_launch;
+    if (chunk_out) *chunk_out = best_chunk;
+    return best;
 }
 inline bool aligned(const void* p, size_t a) { return ((uintptr_t)p % a) == 0; }
 
@@ -234,7 +253,7 @@ int hata_create_tuned(hata_ctx** ctx_out, const hata_config* cfg, const hata_tun
     c->coop_qrec = (unsigned long long*)(w + p.off_qrec);
     c->error_word = (uint32_t*)(w + p.off_err);
     c->epoch = 0;
-    c->coop_capacity = 0;
+    c->coop_opts = 0;
     c->coop_capacity_paged = 0;
     c->partials = (float*)(w + p.off_partials);
     c->wplanes = (f_has_mfma_width(cfg->r)) ? (void*)(w + p.off_wplanes) : nullptr;
@@ -251,8 +270,20 @@ int hata_create_tuned(hata_ctx** ctx_out, const hata_config* cfg, const hata_tun
     if (hipGetDevice(&dev) != hipSuccess ||
         hipDeviceGetAttribute(&c->cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
         c->cus = 0;
-    c->coop_capacity = hata::coop_capacity(c, false);
-    c->coop_capacity_paged = hata::coop_capacity(c, true);
+    // Chunk sizes of the single-launch step.  The caller's, if one was given; else the plan's and,
+    // for batches too large to be resident at that size, up to three larger ones: with 16384 keys
+    // per workgroup B = 32 at L = 32K is ONE resident launch of 512 workgroups instead of two of 1024
+    // (measured 58 against 75 us), while small batches are fastest at the plan's size.
+    if (p.coop_chunk) {
+        c->coop_opts = 1;
+        c->coop_opt_chunk[0] = p.coop_chunk;
+    } else {
+        c->coop_opt_chunk[c->coop_opts++] = p.chunk;
+        for (int v = 8192; v <= 32768 && c->coop_opts < 4; v <<= 1)
+            if (v > p.chunk && v < 2 * cfg->L_cap) c->coop_opt_chunk[c->coop_opts++] = v;
+    }
+    for (int o = 0; o < c->coop_opts; ++o) c->coop_opt_cap[o] = hata::coop_capacity(c, false, c->coop_opt_chunk[o]);
+    c->coop_capacity_paged = hata::coop_capacity(c, true, c->coop_opt_chunk[0]);
     // a device shared with other work cannot promise that a whole grid is resident: three launches
     c->step_mode = (tuning && tuning->shared_device) ? 3 : 0;
     c->spin_limit = 0;
@@ -461,12 +492,13 @@ int hata_decode_step(hata_ctx* ctx, const void* q, const void* K, const void* V,
     // Cooperative path: encoding, scoring, selection and attention in ONE launch (workgroups of a
     // unit wait for the unit's threshold inside the kernel), when every workgroup can be resident
     // at once.
-    if (const int ns = coop_sub_batches(ctx, B, false)) {
+    int step_chunk = 0;
+    if (const int ns = coop_sub_batches(ctx, B, false, &step_chunk)) {
         hipError_t e = hipSuccess;
         for (int i = 0; i < ns && e == hipSuccess; ++i) {
             const int b0 = (int)((int64_t)i * B / ns), b1 = (int)((int64_t)(i + 1) * B / ns);
             e = hata::launch_coop_step(ctx, q, K, V, W_H, codes, append, seq_len, k, b1 - b0, sm_scale, out,
-                                       out_f32, s, nullptr, b0);
+                                       out_f32, s, step_chunk, nullptr, b0);
         }
         if (e == hipSuccess) return HATA_OK;
         if (e != hipErrorNotSupported) return HATA_EHIP;  // (not supported: no kernel for this shape, nothing was launched)
@@ -492,13 +524,14 @@ int hata_select_step(hata_ctx* ctx, const void* q, const void* K, const float* W
     if (!q || !W_H || !codes || !seq_len || !k || !idx || (append && !K)) return HATA_EINVAL;
     if (!aligned(q, 16) || !aligned(K, 16) || !aligned(codes, 16) || !aligned(W_H, 16) || !aligned(idx, 4))
         return HATA_EINVAL;
-    const int ns = coop_sub_batches(ctx, B, false);
+    int step_chunk = 0;
+    const int ns = coop_sub_batches(ctx, B, false, &step_chunk);
     if (ns == 0) return HATA_EUNSUPPORTED;
     hipError_t e = hipSuccess;
     for (int i = 0; i < ns && e == hipSuccess; ++i) {
         const int b0 = (int)((int64_t)i * B / ns), b1 = (int)((int64_t)(i + 1) * B / ns);
         e = hata::launch_coop_step(ctx, q, K, nullptr, W_H, codes, append, seq_len, k, b1 - b0, 0.f, nullptr,
-                                   nullptr, (hipStream_t)stream, nullptr, b0, idx);
+                                   nullptr, (hipStream_t)stream, step_chunk, nullptr, b0, idx);
     }
     if (e == hipErrorNotSupported) return HATA_EUNSUPPORTED;
     return hip_rc(e);
@@ -521,14 +554,15 @@ int hata_decode_step_paged(hata_ctx* ctx, const void* q, const void* K_pool, con
     // the block table is read by the single-launch kernel only
     const int mode = ctx->step_mode;
     ctx->step_mode = 0;  // (hata_set_step_mode does not apply here)
-    const int ns = coop_sub_batches(ctx, B, true);
+    int step_chunk = 0;
+    const int ns = coop_sub_batches(ctx, B, true, &step_chunk);
     ctx->step_mode = mode;
     if (ns == 0) return HATA_EUNSUPPORTED;
     hipError_t e = hipSuccess;
     for (int i = 0; i < ns && e == hipSuccess; ++i) {
         const int b0 = (int)((int64_t)i * B / ns), b1 = (int)((int64_t)(i + 1) * B / ns);
         e = hata::launch_coop_step(ctx, q, K_pool, V_pool, W_H, codes_pool, append, seq_len, k, b1 - b0, sm_scale,
-                                   out, out_f32, (hipStream_t)stream, &pv, b0);
+                                   out, out_f32, (hipStream_t)stream, step_chunk, &pv, b0);
     }
     if (e == hipErrorNotSupported) return HATA_EUNSUPPORTED;
     return hip_rc(e);
@@ -537,9 +571,12 @@ int hata_decode_step_paged(hata_ctx* ctx, const void* q, const void* K_pool, con
 int hata_step_plan(const hata_ctx* ctx, int32_t B, int32_t* n_launches, int32_t* chunk, int32_t* n_chunks) {
     int rc = check_call(ctx, B);
     if (rc != HATA_OK) return rc;
-    if (n_launches) *n_launches = coop_sub_batches(ctx, B, false) ? 1 : 3;
-    if (chunk) *chunk = ctx->chunk;
-    if (n_chunks) *n_chunks = ctx->n_chunks;
+    int step_chunk = 0;
+    const bool single = coop_sub_batches(ctx, B, false, &step_chunk) != 0;
+    if (!single) step_chunk = ctx->chunk;
+    if (n_launches) *n_launches = single ? 1 : 3;
+    if (chunk) *chunk = step_chunk;
+    if (n_chunks) *n_chunks = (ctx->cfg.L_cap + step_chunk - 1) / step_chunk;
     return HATA_OK;
 }
 

@@ -31,7 +31,9 @@
 
 namespace hata {
 
-#define HATA_COOP_MAX_CHUNK 4096
+#define HATA_COOP_MAX_CHUNK 32768        // keys per workgroup: their scores stay in LDS (2 bytes each)
+#define HATA_COOP_MAX_CHUNK_PAGED 4096   // block-table variant (its page starts are staged in LDS per chunk)
+#define HATA_COOP_SUB 4096               // keys the ordered compaction takes per turn (16 per thread)
 #define HATA_COOP_SPIN_LIMIT (1 << 18)  // default bound of every in-kernel wait (polls, ~0.1 us apart at least)
 
 struct CoopArgs {
@@ -204,10 +206,21 @@ __device__ __forceinline__ void coop_encode_vec(const float* __restrict__ Wh, co
 
 // WD in {1, 2, 4, 8} (r = 32, 64, 128, 256); G in {1, 2, 4, 5, 8, 16} (all heads of the group in one
 // attention tile; 16 only up to r = 128: one wave collects the G * WD <= 64 query code words)
-template <int WD, int G, bool PAGED>
-__global__ __launch_bounds__(256, (G >= 16 ? 2 : 3)) void decode_step_coop_kernel(const CoopArgs a) {
+// BIG: chunks of more than HATA_COOP_SUB keys (the ordered compaction then takes several turns; kept
+// out of the other instantiation, where the loop's scalar registers push some shapes into spills)
+// (registers: at least three workgroups per CU, two with sixteen heads; at r = 256 also at most
+// three -- with the scores in dynamic LDS the compiler would otherwise squeeze that form into the
+// registers of a fourth, which costs it 1.3 us; the narrower forms fit four as they are, and a batch of
+// 128 units at 4096 keys per chunk needs the four)
+template <int WD, int G, bool PAGED, bool BIG = false>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu((G >= 16 ? 2 : 3), (WD >= 8 ? 3 : 4))))
+void decode_step_coop_kernel(const CoopArgs a) {
+    static_assert(!(PAGED && BIG), "the block-table variant keeps to small chunks");
     static_assert(G * WD <= 64, "query code words of a unit are collected by one wave");
-    extern __shared__ uint32_t hist[];  // NB words: chunk histogram, later the unit's total
+    // dynamic LDS: the chunk's scores (2 bytes per key; later the selected rows as offsets in the
+    // chunk) at a fixed address, then NB words of histogram (the chunk's, later the unit's total)
+    extern __shared__ __attribute__((aligned(16))) uint16_t s_sc[];
+    uint32_t* const hist = reinterpret_cast<uint32_t*>(s_sc + a.chunk);
     constexpr bool MFMA = G >= 4;  // matrix-core form of the attention core
     // the threshold search (last arriver only) is over before the attention stages V tiles
     __shared__ __attribute__((aligned(16))) union {
@@ -216,15 +229,14 @@ __global__ __launch_bounds__(256, (G >= 16 ? 2 : 3)) void decode_step_coop_kerne
     } U;
     ThresholdLds& TS = U.ts;
     __shared__ __attribute__((aligned(16))) AttnLds<G> S;
-    __shared__ __attribute__((aligned(16))) uint16_t s_sc[HATA_COOP_MAX_CHUNK];  // chunk scores, later the selected rows (offsets in the chunk)
-    __shared__ uint32_t scan4[4];
+    __shared__ uint32_t scan4[2][4];
     __shared__ int s_flag;
     __shared__ uint32_t s_rec[2];
     __shared__ int s_low;  // lowest score of this chunk
     __shared__ int s_bad;  // this workgroup gave up a wait: the unit's outputs are invalid
     __shared__ uint32_t s_codes[(G + 1) * WD];  // codes of the G query heads and of the appended key
     // PAGED: where the pages of this chunk's rows start (pages of 16 rows or more: at most MAX_CHUNK / 16 + 1)
-    __shared__ int s_page[PAGED ? HATA_COOP_MAX_CHUNK / 16 + 2 : 1];
+    __shared__ int s_page[PAGED ? HATA_COOP_MAX_CHUNK_PAGED / 16 + 2 : 1];
     const int tid = threadIdx.x;
     HATA_TRACE_AT(39, true);
     // Workgroup -> (unit, chunk).  Consecutive workgroup ids go to consecutive XCDs (8 of them, each
@@ -505,8 +517,8 @@ __global__ __launch_bounds__(256, (G >= 16 ? 2 : 3)) void decode_step_coop_kerne
     }
     __syncthreads();
     TC(45);
-    const int off = clampi((int)(s_rec[0] >> 13), 0, a.k_max);
-    const int cnt = clampi((int)(s_rec[0] & 0x1fffu), 0, min(a.chunk, a.k_max - off));
+    const int off = clampi((int)(s_rec[0] >> 16), 0, a.k_max);
+    const int cnt = clampi((int)(s_rec[0] & 0xffffu), 0, min(a.chunk, a.k_max - off));
     const int take = (int)(s_rec[1] >> 13);
     const int T = (int)(s_rec[1] & 0x1fffu);
 
@@ -515,61 +527,74 @@ __global__ __launch_bounds__(256, (G >= 16 ? 2 : 3)) void decode_step_coop_kerne
     if (c == 0)
         for (int p = keff + tid; p < a.k_max; p += 256) io[p] = -1;
     {
-        const int kpt = a.chunk / 256;  // consecutive keys per thread
-        const int n_first = tid * kpt;  // offset in the chunk
-        // this thread's scores (kpt <= 16 consecutive uint16), read once with 8-byte LDS loads
-        uint32_t sv[16];
+        // HATA_COOP_SUB keys per turn (the whole chunk in one turn up to that size): a thread takes
+        // kpt <= 16 consecutive keys of the turn's block; lt_run / eq_run count the keys below / at the
+        // threshold in the blocks before.  The row list overwrites the scores from the front: a
+        // turn writes below the end of its own block, which every thread has read by then.
+        uint32_t lt_run = 0, eq_run = 0;
+        for (int sb0 = 0; sb0 < (BIG ? end - base : 1); sb0 += HATA_COOP_SUB) {  // (one turn unless BIG)
+            const int kpt = min(a.chunk, HATA_COOP_SUB) / 256;  // consecutive keys per thread
+            const int n_first = sb0 + tid * kpt;  // offset in the chunk
+            // this thread's scores (kpt <= 16 consecutive uint16), read once with 8-byte LDS loads
+            uint32_t sv[16];
 #pragma unroll
-        for (int i4 = 0; i4 < 4; ++i4) {
-            if (i4 * 4 < kpt) {
-                const uint2 v = *reinterpret_cast<const uint2*>(&s_sc[n_first + i4 * 4]);
-                sv[4 * i4 + 0] = v.x & 0xffffu; sv[4 * i4 + 1] = v.x >> 16;
-                sv[4 * i4 + 2] = v.y & 0xffffu; sv[4 * i4 + 3] = v.y >> 16;
-            } else {
-                sv[4 * i4 + 0] = sv[4 * i4 + 1] = sv[4 * i4 + 2] = sv[4 * i4 + 3] = 0xffffffffu;
-            }
-        }
-        // bit i of m_lt / m_eq: key i of this thread is live and scores below / exactly the threshold
-        const int nlive = clampi(end - base - n_first, 0, kpt);
-        const uint32_t live = (1u << nlive) - 1u;  // (nlive <= 16)
-        uint32_t m_lt = 0, m_eq = 0;
-#pragma unroll
-        for (int i4 = 0; i4 < 4; ++i4) {
-            if (i4 * 4 < kpt) {
-#pragma unroll
-                for (int i = 4 * i4; i < 4 * i4 + 4; ++i) {
-                    m_lt |= ((int)sv[i] < T ? 1u : 0u) << i;
-                    m_eq |= ((int)sv[i] == T ? 1u : 0u) << i;
+            for (int i4 = 0; i4 < 4; ++i4) {
+                if (i4 * 4 < kpt) {
+                    const uint2 v = *reinterpret_cast<const uint2*>(&s_sc[n_first + i4 * 4]);
+                    sv[4 * i4 + 0] = v.x & 0xffffu; sv[4 * i4 + 1] = v.x >> 16;
+                    sv[4 * i4 + 2] = v.y & 0xffffu; sv[4 * i4 + 3] = v.y >> 16;
+                } else {
+                    sv[4 * i4 + 0] = sv[4 * i4 + 1] = sv[4 * i4 + 2] = sv[4 * i4 + 3] = 0xffffffffu;
                 }
             }
-        }
-        m_lt &= live;
-        m_eq &= live;
-        const uint32_t lt = __popc(m_lt), eq = __popc(m_eq);
-        // block-wide exclusive scan of (lt, eq) with ONE barrier, which also marks the point where
-        // every thread has read its scores, so that s_sc can become the row list
-        const uint32_t mine = lt | (eq << 16);
-        const uint32_t incl = wave_incl_scan(mine);
-        if ((tid & 63) == 63) scan4[tid >> 6] = incl;
-        __syncthreads();
-        const int wv = tid >> 6;
-        const uint32_t before = (wv > 0 ? scan4[0] : 0u) + (wv > 1 ? scan4[1] : 0u) + (wv > 2 ? scan4[2] : 0u) + incl - mine;
-        const uint32_t lt_b = before & 0xffffu, eq_b = before >> 16;
-        // ties go to the lowest rows: this thread keeps the first `avail` of its keys at the threshold
-        const uint32_t ties_before = min(eq_b, (uint32_t)take);  // ties taken by the threads before this one
-        const uint32_t avail = min(eq, (uint32_t)take - ties_before);
-        uint32_t keep = m_eq;
-        while ((uint32_t)__popc(keep) > avail) keep &= ~(0x80000000u >> __clz(keep));  // drop the highest row
-        uint32_t sel = m_lt | keep;
-        uint32_t r = lt_b + ties_before;  // local rank of the thread's first selected key
-        while (sel) {  // (a thread holds k / L of its keys on average: mostly zero or one turn)
-            const int i = __ffs(sel) - 1;
-            sel &= sel - 1;
-            if (r < (uint32_t)cnt) {
-                s_sc[r] = (uint16_t)(n_first + i);
-                io[off + r] = base + n_first + i;
+            // bit i of m_lt / m_eq: key i of this thread is live and scores below / exactly the threshold
+            const int nlive = clampi(end - base - n_first, 0, kpt);
+            const uint32_t live = (1u << nlive) - 1u;  // (nlive <= 16)
+            uint32_t m_lt = 0, m_eq = 0;
+#pragma unroll
+            for (int i4 = 0; i4 < 4; ++i4) {
+                if (i4 * 4 < kpt) {
+#pragma unroll
+                    for (int i = 4 * i4; i < 4 * i4 + 4; ++i) {
+                        m_lt |= ((int)sv[i] < T ? 1u : 0u) << i;
+                        m_eq |= ((int)sv[i] == T ? 1u : 0u) << i;
+                    }
+                }
             }
-            ++r;
+            m_lt &= live;
+            m_eq &= live;
+            const uint32_t lt = __popc(m_lt), eq = __popc(m_eq);
+            // block-wide exclusive scan of (lt, eq) with ONE barrier, which also marks the point where
+            // every thread has read its scores, so that s_sc can become the row list (two sets of
+            // wave totals, used in turn: a thread may still read one while the next turn fills the other)
+            uint32_t* sc4 = scan4[(sb0 / HATA_COOP_SUB) & 1];
+            const uint32_t mine = lt | (eq << 16);
+            const uint32_t incl = wave_incl_scan(mine);
+            if ((tid & 63) == 63) sc4[tid >> 6] = incl;
+            __syncthreads();
+            const int wv = tid >> 6;
+            const uint32_t w0 = sc4[0], w1 = sc4[1], w2 = sc4[2], w3 = sc4[3];
+            const uint32_t before = (wv > 0 ? w0 : 0u) + (wv > 1 ? w1 : 0u) + (wv > 2 ? w2 : 0u) + incl - mine;
+            const uint32_t lt_b = lt_run + (before & 0xffffu), eq_b = eq_run + (before >> 16);
+            const uint32_t total = w0 + w1 + w2 + w3;
+            lt_run += total & 0xffffu;
+            eq_run += total >> 16;
+            // ties go to the lowest rows: this thread keeps the first `avail` of its keys at the threshold
+            const uint32_t ties_before = min(eq_b, (uint32_t)take);  // ties taken by the threads before this one
+            const uint32_t avail = min(eq, (uint32_t)take - ties_before);
+            uint32_t keep = m_eq;
+            while ((uint32_t)__popc(keep) > avail) keep &= ~(0x80000000u >> __clz(keep));  // drop the highest row
+            uint32_t sel = m_lt | keep;
+            uint32_t r = lt_b + ties_before;  // local rank of the thread's first selected key
+            while (sel) {  // (a thread holds k / L of its keys on average: mostly zero or one turn)
+                const int i = __ffs(sel) - 1;
+                sel &= sel - 1;
+                if (r < (uint32_t)cnt) {
+                    s_sc[r] = (uint16_t)(n_first + i);
+                    io[off + r] = base + n_first + i;
+                }
+                ++r;
+            }
         }
     }
     __syncthreads();
@@ -685,56 +710,68 @@ __global__ __launch_bounds__(256, (G >= 16 ? 2 : 3)) void decode_step_coop_kerne
 }
 
 template <int WD, int G>
-static const void* coop_fn(bool paged) {
-    return paged ? (const void*)&decode_step_coop_kernel<WD, G, true> : (const void*)&decode_step_coop_kernel<WD, G, false>;
+static const void* coop_fn(bool paged, bool big) {
+    if (paged) return big ? nullptr : (const void*)&decode_step_coop_kernel<WD, G, true, false>;
+    return big ? (const void*)&decode_step_coop_kernel<WD, G, false, true> : (const void*)&decode_step_coop_kernel<WD, G, false, false>;
 }
 
-static const void* coop_kernel_for(int Wd, int G, bool paged) {
+static const void* coop_kernel_for(int Wd, int G, bool paged, bool big) {
     switch (Wd * 100 + G) {
-        case 101: return coop_fn<1, 1>(paged);
-        case 102: return coop_fn<1, 2>(paged);
-        case 104: return coop_fn<1, 4>(paged);
-        case 105: return coop_fn<1, 5>(paged);
-        case 108: return coop_fn<1, 8>(paged);
-        case 116: return coop_fn<1, 16>(paged);
-        case 216: return coop_fn<2, 16>(paged);
-        case 416: return coop_fn<4, 16>(paged);
-        case 201: return coop_fn<2, 1>(paged);
-        case 202: return coop_fn<2, 2>(paged);
-        case 204: return coop_fn<2, 4>(paged);
-        case 205: return coop_fn<2, 5>(paged);
-        case 208: return coop_fn<2, 8>(paged);
-        case 401: return coop_fn<4, 1>(paged);
-        case 402: return coop_fn<4, 2>(paged);
-        case 404: return coop_fn<4, 4>(paged);
-        case 405: return coop_fn<4, 5>(paged);
-        case 408: return coop_fn<4, 8>(paged);
-        case 801: return coop_fn<8, 1>(paged);
-        case 802: return coop_fn<8, 2>(paged);
-        case 804: return coop_fn<8, 4>(paged);
-        case 805: return coop_fn<8, 5>(paged);
-        case 808: return coop_fn<8, 8>(paged);
+        case 101: return coop_fn<1, 1>(paged, big);
+        case 102: return coop_fn<1, 2>(paged, big);
+        case 104: return coop_fn<1, 4>(paged, big);
+        case 105: return coop_fn<1, 5>(paged, big);
+        case 108: return coop_fn<1, 8>(paged, big);
+        case 116: return coop_fn<1, 16>(paged, big);
+        case 216: return coop_fn<2, 16>(paged, big);
+        case 416: return coop_fn<4, 16>(paged, big);
+        case 201: return coop_fn<2, 1>(paged, big);
+        case 202: return coop_fn<2, 2>(paged, big);
+        case 204: return coop_fn<2, 4>(paged, big);
+        case 205: return coop_fn<2, 5>(paged, big);
+        case 208: return coop_fn<2, 8>(paged, big);
+        case 401: return coop_fn<4, 1>(paged, big);
+        case 402: return coop_fn<4, 2>(paged, big);
+        case 404: return coop_fn<4, 4>(paged, big);
+        case 405: return coop_fn<4, 5>(paged, big);
+        case 408: return coop_fn<4, 8>(paged, big);
+        case 801: return coop_fn<8, 1>(paged, big);
+        case 802: return coop_fn<8, 2>(paged, big);
+        case 804: return coop_fn<8, 4>(paged, big);
+        case 805: return coop_fn<8, 5>(paged, big);
+        case 808: return coop_fn<8, 8>(paged, big);
         default: return nullptr;
     }
 }
 
+// chunk sizes the kernel is built for, and the width of the {offset, count} record word
+static bool coop_shape_ok(const hata_ctx* c, bool paged, int chunk) {
+    return chunk >= 256 && chunk % 256 == 0 && chunk <= (paged ? HATA_COOP_MAX_CHUNK_PAGED : HATA_COOP_MAX_CHUNK) &&
+           c->cfg.k_max <= 65535;
+}
+static size_t coop_dynamic_lds(const hata_ctx* c, int chunk) { return (size_t)chunk * 2 + (size_t)c->NB * 4; }
+
 // how many workgroups of this context's cooperative kernel fit on the device at once
-int coop_capacity(const hata_ctx* c, bool paged) {
-    const void* fn = coop_kernel_for(c->Wd, c->G, paged);
-    if (!fn || c->chunk > HATA_COOP_MAX_CHUNK) return 0;
+int coop_capacity(const hata_ctx* c, bool paged, int chunk) {
+    const void* fn = coop_kernel_for(c->Wd, c->G, paged, chunk > HATA_COOP_SUB);
+    if (!fn || !coop_shape_ok(c, paged, chunk)) return 0;
     int per_cu = 0;
     if (c->cus <= 0) return 0;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, 256, (size_t)c->NB * 4) != hipSuccess) return 0;
+    const size_t lds = coop_dynamic_lds(c, chunk);
+    // (more than 64 KB of dynamic LDS has to be asked for)
+    if (lds > 65536 && hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) return 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, 256, lds) != hipSuccess) return 0;
     return per_cu * c->cus;
 }
 
 hipError_t launch_coop_step(hata_ctx* c, const void* q, const void* K, const void* V,
                             const float* W_H, uint32_t* codes, int append, const int32_t* seq_len,
                             const int32_t* k, int B, float sm_scale, void* out, float* out_f32, hipStream_t s,
-                            const PageView* pages, int b0, int32_t* idx_only) {
+                            int chunk, const PageView* pages, int b0, int32_t* idx_only) {
     const hata_config& f = c->cfg;
-    const void* fn = coop_kernel_for(c->Wd, c->G, pages != nullptr);
-    if (!fn || c->chunk > HATA_COOP_MAX_CHUNK) return hipErrorNotSupported;
+    const void* fn = coop_kernel_for(c->Wd, c->G, pages != nullptr, chunk > HATA_COOP_SUB);
+    if (!fn || !coop_shape_ok(c, pages != nullptr, chunk) || chunk < c->chunk) return hipErrorNotSupported;
+    const int n_chunks = (f.L_cap + chunk - 1) / chunk;  // (the workspace regions are sized for c->n_chunks >= n_chunks)
     CoopArgs a;
     a.q = (const uint16_t*)q; a.K = (const uint16_t*)K; a.V = (const uint16_t*)V;
     a.W_H = W_H; a.append = append;
@@ -761,27 +798,27 @@ hipError_t launch_coop_step(hata_ctx* c, const void* q, const void* K, const voi
     if (out) out = (uint16_t*)out + (int64_t)b0 * f.Hq * HATA_D;
     if (out_f32) out_f32 += (int64_t)b0 * f.Hq * HATA_D;
     // small grids (at most one workgroup per CU): the first batch of key codes is fetched ahead
-    a.prefetch = (c->cus > 0 && (int64_t)c->n_chunks * f.Hkv * B <= c->cus) ? 1 : 0;
+    a.prefetch = (c->cus > 0 && (int64_t)n_chunks * f.Hkv * B <= c->cus) ? 1 : 0;
     a.qcodes = c->qcodes + (int64_t)b0 * f.Hq * c->Wd; a.codes = codes; a.seq_len = seq_len; a.kbud = k;
     a.scores = c->scores + u0 * f.L_cap; a.idx = (idx_only ? idx_only : c->idx) + u0 * f.k_max;
-    a.chunk_hist = c->chunk_hist + u0 * c->n_chunks * c->NBP;
-    a.chunk_info = c->chunk_info + u0 * (c->n_chunks + 1) * 2; a.unit_info = c->unit_info + u0 * 2;
+    a.chunk_hist = c->chunk_hist + u0 * n_chunks * c->NBP;
+    a.chunk_info = c->chunk_info + u0 * (n_chunks + 1) * 2; a.unit_info = c->unit_info + u0 * 2;
     a.unit_counter = c->unit_counter + u0 * HATA_COUNTER_STRIDE;
-    a.unit_hist = c->unit_hist + u0 * c->NB; a.rec = c->coop_rec + u0 * c->n_chunks * HATA_REC_STRIDE;
-    a.qrec = c->coop_qrec + u0 * c->n_chunks * c->G * c->Wd;
+    a.unit_hist = c->unit_hist + u0 * c->NB; a.rec = c->coop_rec + u0 * n_chunks * HATA_REC_STRIDE;
+    a.qrec = c->coop_qrec + u0 * n_chunks * c->G * c->Wd;
     a.attn_counter = c->attn_counter + u0 * HATA_COUNTER_STRIDE;
     a.error_word = c->error_word;
-    a.partials = c->partials + (int64_t)b0 * f.Hq * c->n_chunks * HATA_PSTRIDE;
+    a.partials = c->partials + (int64_t)b0 * f.Hq * n_chunks * HATA_PSTRIDE;
     a.out = (uint16_t*)out; a.out_f32 = out_f32;
-    a.Hq = f.Hq; a.Hkv = f.Hkv; a.L_cap = f.L_cap; a.k_max = f.k_max; a.chunk = c->chunk;
-    a.n_chunks = c->n_chunks; a.NB = c->NB; a.NBP = c->NBP; a.units = f.Hkv * B;
+    a.Hq = f.Hq; a.Hkv = f.Hkv; a.L_cap = f.L_cap; a.k_max = f.k_max; a.chunk = chunk;
+    a.n_chunks = n_chunks; a.NB = c->NB; a.NBP = c->NBP; a.units = f.Hkv * B;
     a.sb = f.kv_stride_b; a.sh = f.kv_stride_h; a.sn = f.kv_stride_n;
     a.scale_log2 = sm_scale * 1.4426950408889634f;
     c->epoch += 1;
     if (c->epoch == 0) c->epoch = 1;  // 0 is the cleared state of the flags
     a.epoch = c->epoch;
     void* args[] = {(void*)&a};
-    return hipLaunchKernel(fn, dim3((unsigned)(c->n_chunks * f.Hkv * B)), dim3(256), args, (size_t)c->NB * 4, s);
+    return hipLaunchKernel(fn, dim3((unsigned)(n_chunks * f.Hkv * B)), dim3(256), args, coop_dynamic_lds(c, chunk), s);
 }
 
 }  // namespace hata

@@ -22,6 +22,10 @@ struct hata_ctx {
     int chunk;        // cached keys handled by one scoring / selection workgroup
     int n_chunks;     // ceil(L_cap / chunk)
     int HT;           // query heads of a group handled together by one attention workgroup
+    // keys per workgroup the single-launch step may use (ascending; [0] = chunk unless the caller fixed
+    // another size) and how many of its workgroups are resident at once with each (0 = unusable); a
+    // call takes the size that needs the fewest launches for its batch, the smallest such
+    int coop_opts, coop_opt_chunk[4], coop_opt_cap[4];
     int sparse_rows;  // selected rows per attention workgroup
     int sparse_splits;
     int dense_rows;   // cache rows per dense-attention workgroup
@@ -45,8 +49,7 @@ struct hata_ctx {
     int par_merge;           // single-launch step merges the heads of a unit in several workgroups
     int step_mode;           // 0 = single launch when it fits, 3 = always three launches
     int cus;                 // compute units of the device that was current in hata_create
-    int coop_capacity;       // workgroups of the cooperative kernel that can be resident at once (0 = unusable)
-    int coop_capacity_paged; // the same for the block-table variant of that kernel
+    int coop_capacity_paged; // resident workgroups of the block-table variant of the single-launch kernel (chunk coop_opt_chunk[0]; 0 = unusable)
     float* partials;       // [B_max*Hq, max(sparse_splits, dense_splits), d + 2]
     void* wplanes;               // [Hkv, r/32, 8, 3, 64] 16-byte fragments: the three bf16 planes of the hash weights (prefill key encode)
     const float* prepared_W_H;   // the weight tensor those planes were made from (nullptr: none)
@@ -97,9 +100,10 @@ hipError_t launch_gather_rows(const hata_ctx* c, const void* K, const void* V, c
 hipError_t launch_coop_step(hata_ctx* c, const void* q, const void* K, const void* V,
                             const float* W_H, uint32_t* codes, int append, const int32_t* seq_len,
                             const int32_t* k, int B, float sm_scale, void* out, float* out_f32, hipStream_t s,
-                            const PageView* pages = nullptr, int b0 = 0, int32_t* idx_only = nullptr);
-// (idx_only != nullptr: the launch stops once the index lists are written, into idx_only
-// [B, Hkv, k_max] instead of the workspace; V, out and out_f32 are not touched)
-int coop_capacity(const hata_ctx* c, bool paged);
+                            int chunk, const PageView* pages = nullptr, int b0 = 0, int32_t* idx_only = nullptr);
+// (chunk: keys per workgroup, one of the context's coop_opt_chunk; idx_only != nullptr: the launch
+// stops once the index lists are written, into idx_only [B, Hkv, k_max] instead of the workspace;
+// V, out and out_f32 are not touched)
+int coop_capacity(const hata_ctx* c, bool paged, int chunk);
 
 }  // namespace hata

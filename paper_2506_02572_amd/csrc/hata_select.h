@@ -222,10 +222,11 @@ __device__ __forceinline__ void unit_threshold(
                 st_dev(reinterpret_cast<uint32_t*>(chunk_info_u) + c * 2 + 1, take);
             } else {
                 // two self-validating words per chunk (each carries the launch epoch in its upper
-                // half, so a waiting workgroup needs no separate flag): {off, selected count} and
-                // {ties granted, T}
+                // half, so a waiting workgroup needs no separate flag): {off, selected count}, 16 bits
+                // each (the caller runs this form only for budgets below 65536 rows), and
+                // {ties granted, T}, 19 and 13 bits
                 const uint32_t cnt_c = S.c_lt[c] + take;
-                __hip_atomic_store(rec_u + HATA_REC_STRIDE * c, ((unsigned long long)epoch << 32) | (off << 13) | cnt_c,
+                __hip_atomic_store(rec_u + HATA_REC_STRIDE * c, ((unsigned long long)epoch << 32) | (off << 16) | cnt_c,
                                    __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 __hip_atomic_store(rec_u + HATA_REC_STRIDE * c + 1, ((unsigned long long)epoch << 32) | (take << 13) | (uint32_t)T,
                                    __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);

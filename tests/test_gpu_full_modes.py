@@ -39,24 +39,34 @@ def test_batch_32_at_32k_in_slices_and_as_one_grid(torch_mod):
     out = c.empty((B, w.Hq, w.d), torch.int16)
     out32 = c.empty((B, w.Hq, w.d), torch.float32)
     qd = H.to_dev(q)
-    for mode, want_sub in ((0, None), (1, 1)):
-        c.ctx.hata_set_step_mode(mode)
-        n_sub = c.ctx.hata_step_sub_batches(B)
-        assert c.ctx.hata_step_plan(B)[0] == 1, "the step is expected in its single-launch form"
-        if mode == 0:
-            assert n_sub >= 2, "a batch of 32 at 32K does not fit one resident launch"
+    from paper_2506_02572_amd import hata
+    # three forms of the same step: the library's own choice (a larger chunk, so that the whole batch
+    # is one resident launch), one oversubscribed grid at the plan's chunk (mode 1), and -- on a second
+    # context whose chunk is fixed at 4096 keys -- the batch in slices, one resident launch each
+    ctx_sliced = hata.Context(w.B, w.Hq, w.Hkv, w.d, w.r, w.L_cap, w.k_max, chunk=4096)
+    for name, ctx, mode in (("own choice", c.ctx, 0), ("one oversubscribed grid", c.ctx, 1), ("slices", ctx_sliced, 0)):
+        ctx.hata_set_step_mode(mode)
+        n_sub = ctx.hata_step_sub_batches(B)
+        n_launches, chunk, n_chunks = ctx.hata_step_plan(B)
+        assert n_launches == 1, "the step is expected in its single-launch form"
+        if name == "own choice":
+            assert n_sub == 1 and chunk > 4096, "a batch of 32 at 32K is one resident launch at a larger chunk"
+        elif name == "slices":
+            assert n_sub >= 2 and chunk == 4096, "a batch of 32 at 32K does not fit one resident launch at 4096 keys"
         else:
-            assert n_sub == want_sub
+            assert n_sub == 1
         codes_d = H.to_dev(c.codes_ref)
         out32.zero_()
-        c.ctx.hata_decode_step(qd, c.K, c.V, c.W_H, codes_d, c.seq_len, c.k, B, True, c.scale, out, out32)
-        c.ctx.hata_check()
-        qc, _, ix = c.ctx.hata_step_buffers()
-        assert np.array_equal(H.to_host(codes_d, np.uint32), codes_h), f"mode {mode}: code cache"
-        assert np.array_equal(H.to_host(qc, np.uint32), ref["qcodes"]), f"mode {mode}: query codes"
-        assert np.array_equal(H.to_host(ix), ref["idx"]), f"mode {mode}: index lists"
-        e = H.check_attention(H.to_host(out32), H.to_host(out, np.uint16), ref["out"], f"mode {mode}")
-        print(f"[modes] b32_32k mode {mode}: {n_sub} launch(es), idx exact, attention max abs {e[0]:.2e}", flush=True)
+        ctx.hata_decode_step(qd, c.K, c.V, c.W_H, codes_d, c.seq_len, c.k, B, True, c.scale, out, out32)
+        ctx.hata_check()
+        qc, _, ix = ctx.hata_step_buffers()
+        assert np.array_equal(H.to_host(codes_d, np.uint32), codes_h), f"{name}: code cache"
+        assert np.array_equal(H.to_host(qc, np.uint32), ref["qcodes"]), f"{name}: query codes"
+        assert np.array_equal(H.to_host(ix), ref["idx"]), f"{name}: index lists"
+        e = H.check_attention(H.to_host(out32), H.to_host(out, np.uint16), ref["out"], name)
+        print(f"[modes] b32_32k, {name}: {n_sub} launch(es), chunk {chunk} x {n_chunks}, idx exact, "
+              f"attention max abs {e[0]:.2e}", flush=True)
+    ctx_sliced.close()
     c.ctx.close()
 
 
