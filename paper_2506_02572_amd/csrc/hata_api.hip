@@ -135,7 +135,7 @@ int make_plan(const hata_config* f, const hata_tuning* t, Plan* p) {
     p->off_err = o;      o = align_up(o + 4);
     p->off_uhist = o;    o = align_up(o + (size_t)units * p->NB * 4);
     p->off_partials = o; o = align_up(o + (size_t)f->B_max * f->Hq * max_splits * (128 + 2) * 4);
-    p->off_wplanes = o;  o = align_up(o + (size_t)f->Hkv * (3 + 2) * 128 * f->r * 2);  // three bf16 planes, two fp16 planes
+    p->off_wplanes = o;  o = align_up(o + (size_t)f->Hkv * 2 * 128 * f->r * 2);  // two fp16 planes
     p->total = o;
     return HATA_OK;
 }

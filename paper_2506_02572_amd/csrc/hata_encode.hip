@@ -226,10 +226,7 @@ typedef __attribute__((ext_vector_type(16))) float f32x16_t;
 #define HATA_MFMA_PITCH 136   // LDS row pitch in bf16 elements (272 B: rows shift by 4 banks)
 
 
-// Fragment order of the prepared weight planes (hata_prepare_weights): for KV head h, wave w
-// (hash columns 32 w .. 32 w + 31), channel step kk and plane p, the 64 lanes' 16-byte fragments lie
-// one after the other, so a wave fetches a fragment with one coalesced 1 KB load:
-//   uint4 index = (((h * (R / 32) + w) * 8 + kk) * 3 + p) * 64 + lane
+// fp32 weight pair -> the three bf16 planes (hi, mid, lo) whose sum is the weight exactly; two weights per dword
 __device__ __forceinline__ void split_weight_pair(float w0, float w1, uint32_t& hi, uint32_t& mid, uint32_t& lo) {
     uint32_t ph[2], pm[2], pl[2];
     const float wv2[2] = {w0, w1};
@@ -247,24 +244,21 @@ __device__ __forceinline__ void split_weight_pair(float w0, float w1, uint32_t& 
     lo = pl[0] | (pl[1] << 16);
 }
 
-// grid = (R / 32 waves, Hkv); 64 threads: one wave writes its 24 fragments
-__global__ __launch_bounds__(64) void split_weights_kernel(const float* __restrict__ W_H, uint4* __restrict__ planes, int R) {
-    const int lane = threadIdx.x, w = blockIdx.x, h = blockIdx.y;
-    const int m = lane & 31, half = lane >> 5;
-    const float* wp = W_H + (int64_t)h * HATA_D * R + w * 32 + m;
-    uint4* dst = planes + ((int64_t)(h * (R / 32) + w) * 8 * 3) * 64 + lane;
-    for (int kk = 0; kk < 8; ++kk) {
-        uint32_t hi[4], mid[4], lo[4];
+typedef __attribute__((ext_vector_type(8))) _Float16 f16x8_t;
+
+// eight bf16 values (one 16-byte operand fragment) -> fp16
+__device__ __forceinline__ f16x8_t bf16x8_to_f16(const uint4 v) {
+    const uint32_t x[4] = {v.x, v.y, v.z, v.w};
+    uint32_t o[4];
 #pragma unroll
-        for (int e2 = 0; e2 < 4; ++e2)
-            split_weight_pair(wp[(int64_t)(kk * 16 + 8 * half + 2 * e2) * R], wp[(int64_t)(kk * 16 + 8 * half + 2 * e2 + 1) * R],
-                              hi[e2], mid[e2], lo[e2]);
-        dst[(kk * 3 + 0) * 64] = make_uint4(hi[0], hi[1], hi[2], hi[3]);
-        dst[(kk * 3 + 1) * 64] = make_uint4(mid[0], mid[1], mid[2], mid[3]);
-        dst[(kk * 3 + 2) * 64] = make_uint4(lo[0], lo[1], lo[2], lo[3]);
-    }
+    for (int i = 0; i < 4; ++i)
+        o[i] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(bf16_lo(x[i]), bf16_hi(x[i])));
+    return __builtin_bit_cast(f16x8_t, make_uint4(o[0], o[1], o[2], o[3]));
 }
 
+// PRESPLIT: the weights come from the planes hata_prepare_weights made, and they are the two scaled
+// fp16 planes described at encode_dma_kernel below (two MFMAs per fragment instead of three; the key
+// fragments are converted to fp16 on their way from LDS)
 template <int R, bool PAGED, bool PRESPLIT>
 __global__ __launch_bounds__(R * 2) void encode_mfma_kernel(
     const uint16_t* __restrict__ K, const float* __restrict__ W_H, const uint4* __restrict__ planes,
@@ -340,14 +334,15 @@ __global__ __launch_bounds__(R * 2) void encode_mfma_kernel(
     load_stage(kb0);
 
     // weight fragments: a[plane][kk] holds W_H[h][kk*16 + 8*half + e][32 w + m], e = 0..7
-    bf16x8_t afrag[3][8];
+    bf16x8_t afrag[PRESPLIT ? 1 : 3][PRESPLIT ? 1 : 8];
+    f16x8_t afrag16[PRESPLIT ? 2 : 1][PRESPLIT ? 8 : 1];
     if constexpr (PRESPLIT) {
-        // prepared once per weight tensor (hata_prepare_weights): 24 coalesced 16-byte loads
-        const uint4* src = planes + ((int64_t)(h * (R / 32) + w) * 8 * 3) * 64 + lane;
+        // prepared once per weight tensor (hata_prepare_weights): 16 coalesced 16-byte loads
+        const uint4* src = planes + ((int64_t)(h * (R / 32) + w) * 8 * 2) * 64 + lane;
 #pragma unroll
         for (int kk = 0; kk < 8; ++kk)
 #pragma unroll
-            for (int p = 0; p < 3; ++p) afrag[p][kk] = __builtin_bit_cast(bf16x8_t, src[(kk * 3 + p) * 64]);
+            for (int p = 0; p < 2; ++p) afrag16[p][kk] = __builtin_bit_cast(f16x8_t, src[(kk * 2 + p) * 64]);
     } else {
         const float* wp = W_H + (int64_t)h * HATA_D * R + w * 32 + m;
 #pragma unroll
@@ -378,19 +373,26 @@ __global__ __launch_bounds__(R * 2) void encode_mfma_kernel(
         // Key fragments come from LDS one channel step ahead: as soon as the three planes of a tile
         // have been issued for step kk, the tile's fragment for step kk + 1 is requested into the same
         // registers, so its LDS latency is covered by the nine MFMAs of the other tiles.
-        bf16x8_t bfrag[NT];
+        uint4 bfrag[NT];
 #pragma unroll
         for (int t = 0; t < NT; ++t)
-            bfrag[t] = *reinterpret_cast<const bf16x8_t*>(&tile[(t * 32 + m) * HATA_MFMA_PITCH + 8 * half]);
+            bfrag[t] = *reinterpret_cast<const uint4*>(&tile[(t * 32 + m) * HATA_MFMA_PITCH + 8 * half]);
 #pragma unroll
         for (int kk = 0; kk < 8; ++kk) {
 #pragma unroll
             for (int t = 0; t < NT; ++t) {
+                if constexpr (PRESPLIT) {
+                    const f16x8_t b16 = bf16x8_to_f16(bfrag[t]);
 #pragma unroll
-                for (int p = 0; p < 3; ++p)
-                    acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(afrag[p][kk], bfrag[t], acc[t], 0, 0, 0);
+                    for (int p = 0; p < 2; ++p)
+                        acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_f16(afrag16[p][kk], b16, acc[t], 0, 0, 0);
+                } else {
+#pragma unroll
+                    for (int p = 0; p < 3; ++p)
+                        acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(afrag[p][kk], __builtin_bit_cast(bf16x8_t, bfrag[t]), acc[t], 0, 0, 0);
+                }
                 if (kk + 1 < 8)
-                    bfrag[t] = *reinterpret_cast<const bf16x8_t*>(
+                    bfrag[t] = *reinterpret_cast<const uint4*>(
                         &tile[(t * 32 + m) * HATA_MFMA_PITCH + (kk + 1) * 16 + 8 * half]);
             }
         }
@@ -442,8 +444,6 @@ __global__ __launch_bounds__(R * 2) void encode_mfma_kernel(
 // Every wave converts the key fragments it reads to fp16 itself (three VALU instructions per dword, in
 // the shadow of the MFMAs).  The code words of a stage go through a small LDS array and leave as
 // 16-byte stores one turn later.
-typedef __attribute__((ext_vector_type(8))) _Float16 f16x8_t;
-typedef __attribute__((ext_vector_type(2))) __fp16 fp16x2_t;
 #define DMA_STAGE 64
 #define DMA_NBUF 4
 
@@ -482,16 +482,6 @@ __global__ __launch_bounds__(64) void split_weights_f16_kernel(const float* __re
         dst[(kk * 2 + 0) * 64] = __builtin_bit_cast(uint4, hi);
         dst[(kk * 2 + 1) * 64] = __builtin_bit_cast(uint4, lo);
     }
-}
-
-// eight bf16 values (one 16-byte operand fragment) -> fp16
-__device__ __forceinline__ f16x8_t bf16x8_to_f16(const uint4 v) {
-    const uint32_t x[4] = {v.x, v.y, v.z, v.w};
-    uint32_t o[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-        o[i] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(bf16_lo(x[i]), bf16_hi(x[i])));
-    return __builtin_bit_cast(f16x8_t, make_uint4(o[0], o[1], o[2], o[3]));
 }
 
 template <int R>
@@ -684,8 +674,8 @@ hipError_t launch_encode_bulk(const hata_ctx* c, const void* K, const float* W_H
         // the weight planes prepared for exactly this weight tensor, if any (hata_prepare_weights)
         const uint4* planes = (c->prepared_W_H == W_H && c->wplanes) ? (const uint4*)c->wplanes : nullptr;
         if (!kn && !pages && planes) {
-            // keys already in a contiguous cache, weights prepared: the fp16-plane kernel
-            const uint4* p16 = planes + (size_t)f.Hkv * 3 * 128 * f.r * 2 / 16;
+            // keys already in a contiguous cache, weights prepared: the kernel that stages with LDS-direct loads
+            const uint4* p16 = planes;
 #define HATA_LAUNCH_DMA(R_)                                                                                   \
     hipLaunchKernelGGL((encode_dma_kernel<R_>), grid, dim3(R_ * 2), 0, s, (const uint16_t*)K, p16, start, n_new, \
                        codes, f.Hkv, f.L_cap, kpw, f.kv_stride_b, f.kv_stride_h, f.kv_stride_n)
@@ -729,14 +719,10 @@ hipError_t launch_encode_bulk(const hata_ctx* c, const void* K, const float* W_H
     return hipGetLastError();
 }
 
-// Split of the fp32 hash weights into three bf16 planes in the fragment order of encode_mfma_kernel
-// and into two scaled fp16 planes in the fragment order of encode_dma_kernel
+// Split of the fp32 hash weights into two scaled fp16 planes in the operand-fragment order of the key encoders
 hipError_t launch_split_weights(const hata_ctx* c, const float* W_H, hipStream_t s) {
     const hata_config& f = c->cfg;
-    hipLaunchKernelGGL(split_weights_kernel, dim3(f.r / 32, f.Hkv), dim3(64), 0, s, W_H, (uint4*)c->wplanes, f.r);
-    // the two fp16 planes lie behind the three bf16 planes
-    hipLaunchKernelGGL(split_weights_f16_kernel, dim3(f.r / 32, f.Hkv), dim3(64), 0, s, W_H,
-                       (uint4*)c->wplanes + (size_t)f.Hkv * 3 * 128 * f.r * 2 / 16, f.r);
+    hipLaunchKernelGGL(split_weights_f16_kernel, dim3(f.r / 32, f.Hkv), dim3(64), 0, s, W_H, (uint4*)c->wplanes, f.r);
     return hipGetLastError();
 }
 

@@ -51,7 +51,7 @@ struct hata_ctx {
     int cus;                 // compute units of the device that was current in hata_create
     int coop_capacity_paged; // resident workgroups of the block-table variant of the single-launch kernel (chunk coop_opt_chunk[0]; 0 = unusable)
     float* partials;       // [B_max*Hq, max(sparse_splits, dense_splits), d + 2]
-    void* wplanes;               // [Hkv, r/32, 8, 3, 64] 16-byte fragments: the three bf16 planes of the hash weights (prefill key encode)
+    void* wplanes;               // [Hkv, r/32, 8, 2, 64] 16-byte fragments: the two scaled fp16 planes of the hash weights (prefill key encode)
     const float* prepared_W_H;   // the weight tensor those planes were made from (nullptr: none)
     size_t control_bytes;  // bytes from chunk_info up to the partials: the control words, cleared at creation and after a give-up
 };
