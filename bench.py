@@ -39,12 +39,12 @@ PER_CONFIG_WARMUP = 40
 # constant of the build the profile names, not a value measured by the run that prints it: the
 # "traffic_source" field of the output says so.  "step": the single-launch decode step
 # (decode_step_coop_kernel); "score": the scoring kernel alone (hata_hamming_score).
-HBM_TRAFFIC_SOURCE = "profiles/hbm_traffic_pmc.md (library of commit 6927e5d)"
+HBM_TRAFFIC_SOURCE = "profiles/hbm_traffic_pmc.md (library of commit acbc27c)"
 HBM_TRAFFIC_BYTES = {
-    "cfg2_llama3_8b_32k": {"step": 9297715, "score": 5082317},
-    "cfg3_batched_ragged": {"step": 72992358, "score": 45563290},
-    "cfg4_long_128k_r256": {"step": 48710246, "score": 36862771},
-    "cfg5_gqa8_append": {"step": 59408077, "score": 39123149},
+    "cfg2_llama3_8b_32k": {"step": 9268838, "score": 5082317},
+    "cfg3_batched_ragged": {"step": 72980173, "score": 45563290},
+    "cfg4_long_128k_r256": {"step": 48689152, "score": 36881408},
+    "cfg5_gqa8_append": {"step": 59384730, "score": 39123149},
 }
 
 

@@ -123,13 +123,18 @@ int hata_encode_keys(hata_ctx* ctx, const void* K, const float* W_H,
                      uint32_t* codes, void* stream);
 
 /* Prepares the hash weights for the matrix-core key-code writer (the weights of HashEncode, Alg. 2,
- * are fixed once trained, Sec. 3.1): splits W_H [Hkv, d, r] fp32 into its three bf16 planes, laid out
- * as the kernel's operand fragments, in the workspace.  Afterwards hata_encode_keys,
- * hata_prefill_write and hata_prefill_write_paged calls of this context that are given the SAME
- * pointer W_H read the prepared planes instead of splitting the weights in every workgroup (same
- * codes, bit for bit).  The caller promises that the tensor at W_H does not change until the next
- * hata_prepare_weights call of this context; W_H == NULL forgets the prepared tensor.  Enqueues
- * one small kernel on `stream`; the calls that use the planes must be ordered after it. */
+ * are fixed once trained, Sec. 3.1): W_H [Hkv, d, r] fp32 becomes two fp16 planes per tile of 32 hash
+ * columns -- hi = fp16(W S), lo = fp16(W S - hi), S a power of two that brings the tile's largest
+ * weight below 2^14, so no sign changes -- laid out as the kernels' operand fragments, in the workspace.
+ * Afterwards hata_encode_keys, hata_prefill_write and hata_prefill_write_paged calls of this context
+ * that are given the SAME pointer W_H read the prepared planes instead of splitting the weights into
+ * three bf16 planes in every workgroup: two matrix-core instructions per fragment instead of three.
+ * The prepared form evaluates the projection to within 2^-22 of sum_c |K_c W_c| (about 5e-6 here), so,
+ * like the unprepared form, its code bits can differ from an exact evaluation only where |projection|
+ * is below about 1e-4; inside that band the two forms need not agree with each other.  The caller
+ * promises that the tensor at W_H does not change until the next hata_prepare_weights call of this
+ * context; W_H == NULL forgets the prepared tensor.  Enqueues one small kernel on `stream`; the calls
+ * that use the planes must be ordered after it. */
 int hata_prepare_weights(hata_ctx* ctx, const float* W_H, void* stream);
 
 /* Prefill cache fill in one pass (Alg. 1: KCache <- K, VCache <- V, K_H = HashEncode(K)): the rows
