@@ -427,3 +427,40 @@ def test_batch_larger_than_one_launch_runs_in_sub_batches(torch_mod):
     assert np.array_equal(H.to_host(c.ctx.hata_step_buffers()[2]), ref["idx"])
     assert torch.equal(out32, first)
     c.ctx.close()
+
+
+@pytest.mark.parametrize("chunk", [8192, 16384, 32768])
+def test_step_with_large_chunks_ties_across_compaction_turns(torch_mod, chunk):
+    """Single-launch step with more than 4096 keys per workgroup (the ordered compaction then runs in
+    turns of 4096 keys): two-valued scores, so that the threshold's ties span turns and chunks, budgets
+    above 4096 and above 8191 selected rows per chunk, ragged lengths incl. one row past a turn boundary."""
+    torch = torch_mod
+    from paper_2506_02572_amd import hata
+    w = synth.Workload("bigchunk", 3, 8, 2, 128, 128, (20000, 13000, 4097), (9000, 5000, 4097), 4, 8.0,
+                       L_cap=20000, k_max=9000)
+    inp = synth.generate(w, seed=91)
+    scale = 1.0 / math.sqrt(w.d)
+    q = inp.q(0)
+    seq = inp.seq_len.copy()
+    rng = np.random.default_rng(92)
+    two = rng.integers(0, 2 ** 32, size=(2, w.W), dtype=np.uint64).astype(np.uint32)
+    pick = rng.integers(0, 2, size=(w.B, w.Hkv, w.L_cap))
+    codes_h = two[pick]  # every key carries one of two codes: its score takes one of two values
+    assert codes_h.shape == (w.B, w.Hkv, w.L_cap, w.W)
+    ctx = hata.Context(w.B, w.Hq, w.Hkv, w.d, w.r, w.L_cap, w.k_max, chunk=chunk)
+    n_launches, got_chunk, n_chunks = ctx.hata_step_plan(w.B)
+    assert n_launches == 1 and got_chunk == chunk and n_chunks == (w.L_cap + chunk - 1) // chunk
+    K, V, WH = H.to_dev(inp.K), H.to_dev(inp.V), H.to_dev(inp.W_H)
+    out = torch.empty((w.B, w.Hq, w.d), dtype=torch.int16, device="cuda")
+    out32 = torch.empty((w.B, w.Hq, w.d), dtype=torch.float32, device="cuda")
+    codes_d = H.to_dev(codes_h)
+    ref = O.decode_step(q, inp.K, inp.V, inp.W_H, codes_h.copy(), seq, inp.k, w.k_max, scale, append=False)
+    for rep in range(2):  # twice: the control words must be back in their cleared state
+        out32.zero_()
+        ctx.hata_decode_step(H.to_dev(q), K, V, WH, codes_d, H.to_dev(seq), H.to_dev(inp.k), w.B, False,
+                             scale, out, out32)
+        ctx.hata_check()
+        _, _, ix = ctx.hata_step_buffers()
+        assert np.array_equal(H.to_host(ix), ref["idx"]), f"chunk {chunk}, call {rep}: index lists"
+        H.check_attention(H.to_host(out32), H.to_host(out, np.uint16), ref["out"], f"chunk {chunk}")
+    ctx.close()
