@@ -33,7 +33,7 @@ namespace hata {
 
 #define HATA_COOP_MAX_CHUNK 32768        // keys per workgroup: their scores stay in LDS (2 bytes each)
 #define HATA_COOP_MAX_CHUNK_PAGED 4096   // block-table variant (its page starts are staged in LDS per chunk)
-#define HATA_COOP_SUB 4096               // keys the ordered compaction takes per turn (16 per thread)
+#define HATA_COOP_SUB 4096               // chunks above this size run the BIG instantiation (more than 16 keys per thread in the compaction)
 #define HATA_COOP_SPIN_LIMIT (1 << 18)  // default bound of every in-kernel wait (polls, ~0.1 us apart at least)
 
 struct CoopArgs {
@@ -206,8 +206,8 @@ __device__ __forceinline__ void coop_encode_vec(const float* __restrict__ Wh, co
 
 // WD in {1, 2, 4, 8} (r = 32, 64, 128, 256); G in {1, 2, 4, 5, 8, 16} (all heads of the group in one
 // attention tile; 16 only up to r = 128: one wave collects the G * WD <= 64 query code words)
-// BIG: chunks of more than HATA_COOP_SUB keys (the ordered compaction then takes several turns; kept
-// out of the other instantiation, where the loop's scalar registers push some shapes into spills)
+// BIG: chunks of more than HATA_COOP_SUB keys (a thread of the ordered compaction then holds up to 128
+// keys as eight mask words; kept out of the other instantiation, whose registers are tighter)
 // (registers: at least three workgroups per CU, two with sixteen heads; at r = 256 also at most
 // three -- with the scores in dynamic LDS the compiler would otherwise squeeze that form into the
 // registers of a fourth, which costs it 1.3 us; the narrower forms fit four as they are, and a batch of
@@ -229,7 +229,7 @@ void decode_step_coop_kernel(const CoopArgs a) {
     } U;
     ThresholdLds& TS = U.ts;
     __shared__ __attribute__((aligned(16))) AttnLds<G> S;
-    __shared__ uint32_t scan4[2][4];
+    __shared__ uint32_t scan4[4];
     __shared__ int s_flag;
     __shared__ uint32_t s_rec[2];
     __shared__ int s_low;  // lowest score of this chunk
@@ -526,75 +526,125 @@ void decode_step_coop_kernel(const CoopArgs a) {
     int32_t* io = a.idx + u * a.k_max;
     if (c == 0)
         for (int p = keff + tid; p < a.k_max; p += 256) io[p] = -1;
-    {
-        // HATA_COOP_SUB keys per turn (the whole chunk in one turn up to that size): a thread takes
-        // kpt <= 16 consecutive keys of the turn's block; lt_run / eq_run count the keys below / at the
-        // threshold in the blocks before.  The row list overwrites the scores from the front: a
-        // turn writes below the end of its own block, which every thread has read by then.
-        uint32_t lt_run = 0, eq_run = 0;
-        for (int sb0 = 0; sb0 < (BIG ? end - base : 1); sb0 += HATA_COOP_SUB) {  // (one turn unless BIG)
-            const int kpt = min(a.chunk, HATA_COOP_SUB) / 256;  // consecutive keys per thread
-            const int n_first = sb0 + tid * kpt;  // offset in the chunk
-            // this thread's scores (kpt <= 16 consecutive uint16), read once with 8-byte LDS loads
-            uint32_t sv[16];
+    if constexpr (BIG) {
+        // chunks of 8192 .. 32768 keys: a thread takes kpt = 32 .. 128 consecutive keys, 16 at a time
+        // (bits 0..15 of mk[g]: key below the threshold, bits 16..31: key at the threshold), then ONE
+        // block-wide scan; the totals stay below 65536, so the packed (lt, eq) pair still fits
+        const int kpt = a.chunk / 256;
+        const int n_first = tid * kpt;  // offset in the chunk
+        uint32_t mk[8];
+        uint32_t lt = 0, eq = 0;
 #pragma unroll
-            for (int i4 = 0; i4 < 4; ++i4) {
-                if (i4 * 4 < kpt) {
-                    const uint2 v = *reinterpret_cast<const uint2*>(&s_sc[n_first + i4 * 4]);
-                    sv[4 * i4 + 0] = v.x & 0xffffu; sv[4 * i4 + 1] = v.x >> 16;
-                    sv[4 * i4 + 2] = v.y & 0xffffu; sv[4 * i4 + 3] = v.y >> 16;
-                } else {
-                    sv[4 * i4 + 0] = sv[4 * i4 + 1] = sv[4 * i4 + 2] = sv[4 * i4 + 3] = 0xffffffffu;
+        for (int g = 0; g < 8; ++g) {
+            mk[g] = 0;
+            if (g * 16 < kpt) {
+                const uint4 v0 = *reinterpret_cast<const uint4*>(&s_sc[n_first + g * 16]);
+                const uint4 v1 = *reinterpret_cast<const uint4*>(&s_sc[n_first + g * 16 + 8]);
+                const uint32_t w8[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
+                uint32_t m_lt = 0, m_eq = 0;
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const int sc = (int)((i & 1) ? (w8[i >> 1] >> 16) : (w8[i >> 1] & 0xffffu));
+                    m_lt |= (sc < T ? 1u : 0u) << i;
+                    m_eq |= (sc == T ? 1u : 0u) << i;
                 }
+                const int nlive = clampi(end - base - n_first - g * 16, 0, 16);
+                const uint32_t live = (1u << nlive) - 1u;
+                m_lt &= live;
+                m_eq &= live;
+                mk[g] = m_lt | (m_eq << 16);
+                lt += __popc(m_lt);
+                eq += __popc(m_eq);
             }
-            // bit i of m_lt / m_eq: key i of this thread is live and scores below / exactly the threshold
-            const int nlive = clampi(end - base - n_first, 0, kpt);
-            const uint32_t live = (1u << nlive) - 1u;  // (nlive <= 16)
-            uint32_t m_lt = 0, m_eq = 0;
+        }
+        const uint32_t mine = lt | (eq << 16);
+        const uint32_t incl = wave_incl_scan(mine);
+        if ((tid & 63) == 63) scan4[tid >> 6] = incl;
+        __syncthreads();  // (every thread has read its scores: s_sc becomes the row list)
+        const int wv = tid >> 6;
+        const uint32_t before = (wv > 0 ? scan4[0] : 0u) + (wv > 1 ? scan4[1] : 0u) + (wv > 2 ? scan4[2] : 0u) + incl - mine;
+        const uint32_t lt_b = before & 0xffffu, eq_b = before >> 16;
+        // ties go to the lowest rows: this thread may keep `ties_left` of its keys at the threshold
+        const uint32_t ties_before = min(eq_b, (uint32_t)take);
+        uint32_t ties_left = (uint32_t)take - ties_before;
+        uint32_t r = lt_b + ties_before;  // local rank of the thread's first selected key
 #pragma unroll
-            for (int i4 = 0; i4 < 4; ++i4) {
-                if (i4 * 4 < kpt) {
-#pragma unroll
-                    for (int i = 4 * i4; i < 4 * i4 + 4; ++i) {
-                        m_lt |= ((int)sv[i] < T ? 1u : 0u) << i;
-                        m_eq |= ((int)sv[i] == T ? 1u : 0u) << i;
+        for (int g = 0; g < 8; ++g) {
+            if (g * 16 < kpt) {
+                uint32_t keep = mk[g] >> 16;
+                const uint32_t avail = min((uint32_t)__popc(keep), ties_left);
+                while ((uint32_t)__popc(keep) > avail) keep &= ~(0x80000000u >> __clz(keep));  // drop the highest row
+                ties_left -= avail;
+                uint32_t sel = (mk[g] & 0xffffu) | keep;
+                while (sel) {
+                    const int i = __ffs(sel) - 1;
+                    sel &= sel - 1;
+                    if (r < (uint32_t)cnt) {
+                        s_sc[r] = (uint16_t)(n_first + g * 16 + i);
+                        io[off + r] = base + n_first + g * 16 + i;
                     }
+                    ++r;
                 }
             }
-            m_lt &= live;
-            m_eq &= live;
-            const uint32_t lt = __popc(m_lt), eq = __popc(m_eq);
-            // block-wide exclusive scan of (lt, eq) with ONE barrier, which also marks the point where
-            // every thread has read its scores, so that s_sc can become the row list (two sets of
-            // wave totals, used in turn: a thread may still read one while the next turn fills the other)
-            uint32_t* sc4 = scan4[(sb0 / HATA_COOP_SUB) & 1];
-            const uint32_t mine = lt | (eq << 16);
-            const uint32_t incl = wave_incl_scan(mine);
-            if ((tid & 63) == 63) sc4[tid >> 6] = incl;
-            __syncthreads();
-            const int wv = tid >> 6;
-            const uint32_t w0 = sc4[0], w1 = sc4[1], w2 = sc4[2], w3 = sc4[3];
-            const uint32_t before = (wv > 0 ? w0 : 0u) + (wv > 1 ? w1 : 0u) + (wv > 2 ? w2 : 0u) + incl - mine;
-            const uint32_t lt_b = lt_run + (before & 0xffffu), eq_b = eq_run + (before >> 16);
-            const uint32_t total = w0 + w1 + w2 + w3;
-            lt_run += total & 0xffffu;
-            eq_run += total >> 16;
-            // ties go to the lowest rows: this thread keeps the first `avail` of its keys at the threshold
-            const uint32_t ties_before = min(eq_b, (uint32_t)take);  // ties taken by the threads before this one
-            const uint32_t avail = min(eq, (uint32_t)take - ties_before);
-            uint32_t keep = m_eq;
-            while ((uint32_t)__popc(keep) > avail) keep &= ~(0x80000000u >> __clz(keep));  // drop the highest row
-            uint32_t sel = m_lt | keep;
-            uint32_t r = lt_b + ties_before;  // local rank of the thread's first selected key
-            while (sel) {  // (a thread holds k / L of its keys on average: mostly zero or one turn)
-                const int i = __ffs(sel) - 1;
-                sel &= sel - 1;
-                if (r < (uint32_t)cnt) {
-                    s_sc[r] = (uint16_t)(n_first + i);
-                    io[off + r] = base + n_first + i;
-                }
-                ++r;
+        }
+    } else {
+        // chunks of up to HATA_COOP_SUB keys: a thread takes kpt <= 16 consecutive keys
+        const int kpt = a.chunk / 256;  // consecutive keys per thread
+        const int n_first = tid * kpt;  // offset in the chunk
+        // this thread's scores (kpt <= 16 consecutive uint16), read once with 8-byte LDS loads
+        uint32_t sv[16];
+#pragma unroll
+        for (int i4 = 0; i4 < 4; ++i4) {
+            if (i4 * 4 < kpt) {
+                const uint2 v = *reinterpret_cast<const uint2*>(&s_sc[n_first + i4 * 4]);
+                sv[4 * i4 + 0] = v.x & 0xffffu; sv[4 * i4 + 1] = v.x >> 16;
+                sv[4 * i4 + 2] = v.y & 0xffffu; sv[4 * i4 + 3] = v.y >> 16;
+            } else {
+                sv[4 * i4 + 0] = sv[4 * i4 + 1] = sv[4 * i4 + 2] = sv[4 * i4 + 3] = 0xffffffffu;
             }
+        }
+        // bit i of m_lt / m_eq: key i of this thread is live and scores below / exactly the threshold
+        const int nlive = clampi(end - base - n_first, 0, kpt);
+        const uint32_t live = (1u << nlive) - 1u;  // (nlive <= 16)
+        uint32_t m_lt = 0, m_eq = 0;
+#pragma unroll
+        for (int i4 = 0; i4 < 4; ++i4) {
+            if (i4 * 4 < kpt) {
+#pragma unroll
+                for (int i = 4 * i4; i < 4 * i4 + 4; ++i) {
+                    m_lt |= ((int)sv[i] < T ? 1u : 0u) << i;
+                    m_eq |= ((int)sv[i] == T ? 1u : 0u) << i;
+                }
+            }
+        }
+        m_lt &= live;
+        m_eq &= live;
+        const uint32_t lt = __popc(m_lt), eq = __popc(m_eq);
+        // block-wide exclusive scan of (lt, eq) with ONE barrier, which also marks the point where
+        // every thread has read its scores, so that s_sc can become the row list
+        uint32_t* sc4 = scan4;
+        const uint32_t mine = lt | (eq << 16);
+        const uint32_t incl = wave_incl_scan(mine);
+        if ((tid & 63) == 63) sc4[tid >> 6] = incl;
+        __syncthreads();
+        const int wv = tid >> 6;
+        const uint32_t before = (wv > 0 ? sc4[0] : 0u) + (wv > 1 ? sc4[1] : 0u) + (wv > 2 ? sc4[2] : 0u) + incl - mine;
+        const uint32_t lt_b = before & 0xffffu, eq_b = before >> 16;
+        // ties go to the lowest rows: this thread keeps the first `avail` of its keys at the threshold
+        const uint32_t ties_before = min(eq_b, (uint32_t)take);  // ties taken by the threads before this one
+        const uint32_t avail = min(eq, (uint32_t)take - ties_before);
+        uint32_t keep = m_eq;
+        while ((uint32_t)__popc(keep) > avail) keep &= ~(0x80000000u >> __clz(keep));  // drop the highest row
+        uint32_t sel = m_lt | keep;
+        uint32_t r = lt_b + ties_before;  // local rank of the thread's first selected key
+        while (sel) {  // (a thread holds k / L of its keys on average: mostly zero or one turn)
+            const int i = __ffs(sel) - 1;
+            sel &= sel - 1;
+            if (r < (uint32_t)cnt) {
+                s_sc[r] = (uint16_t)(n_first + i);
+                io[off + r] = base + n_first + i;
+            }
+            ++r;
         }
     }
     __syncthreads();
