@@ -221,10 +221,12 @@ int hata_dense_decode(hata_ctx* ctx, const void* q, const void* K, const void* V
  * (see hata_step_buffers).
  *
  * Launches (see hata_step_plan): for r in {32, 64, 128, 256} and Hq/Hkv in {1, 2, 4, 5, 8}, or 16
- * with r <= 128, when the workgroups of at least one sequence can be resident on the device at once,
- * the step is ONE kernel launch (one per slice of a batch too large to be resident as a whole:
- * hata_step_sub_batches) whose
- * workgroups hand the query codes, the selection threshold and the attention partials to each
+ * with r <= 128, a budget k_max of at most 65535 rows, and when the workgroups of at least one sequence
+ * can be resident on the device at once,
+ * the step is ONE kernel launch whose workgroups each take a chunk of 1024 to 32768 cached keys of
+ * one (sequence, KV head) unit -- per call the chunk size that lets the fewest resident launches
+ * cover the batch, the smallest such; a batch too large to be resident even at the largest chunk
+ * goes as one launch per slice of it: hata_step_sub_batches, hata_step_plan -- and hand the query codes, the selection threshold and the attention partials to each
  * other through the workspace, waiting for one another inside the kernel.  Every such wait is
  * bounded: a workgroup that gives up raises a flag in the workspace and runs to its end; the
  * outputs of every (sequence, KV head) unit one of whose workgroups gave up are then overwritten
