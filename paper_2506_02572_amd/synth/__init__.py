@@ -195,6 +195,8 @@ SWEEP = {
     "budget0p4_32k": Workload("budget0p4_32k", 1, 32, 8, 128, 128, (32768,), (128,), 4, 8.0),
     "budget3p13_32k": Workload("budget3p13_32k", 1, 32, 8, 128, 128, (32768,), (1024,), 4, 8.0),
     "ctx256k": Workload("ctx256k", 1, 32, 8, 128, 128, (262144,), (4096,), 4, 8.0, append_steps=2),
+    # the shape the paper's headline ratio is quoted on (Sec. 5.3: batch 8 at 32K tokens, budget 1.56 %)
+    "b8_32k": Workload("b8_32k", 8, 32, 8, 128, 128, (32768,) * 8, (512,) * 8, 4, 8.0),
     # a serving-size batch: more (sequence, KV head) units than one launch can keep resident
     "b32_32k": Workload("b32_32k", 32, 32, 8, 128, 128, (32768,) * 32, (512,) * 32, 4, 8.0),
     "b64_32k": Workload("b64_32k", 64, 32, 8, 128, 128, (32768,) * 64, (512,) * 64, 4, 8.0),

@@ -47,3 +47,7 @@ def test_budgets_0p4_and_3p13_percent(torch_mod):
 
 def test_context_256k_with_append(torch_mod):
     run_workload(torch_mod, synth.SWEEP["ctx256k"], {0, 1}, True)
+
+
+def test_batch_8_at_32k_the_papers_headline_shape(torch_mod):
+    run_workload(torch_mod, synth.SWEEP["b8_32k"], {0}, True)
