@@ -154,13 +154,13 @@ inline int check_call(const hata_ctx* c, int B) {
 // allows goes in equal slices, one launch each -- or 0 when the form is not available.
 inline int coop_sub_batches(const hata_ctx* c, int B, bool paged, int* chunk_out = nullptr) {
     if (c->step_mode == 3) return 0;
-    // paged caches and the oversubscribed grid of mode 1 use the first size only
-    const int n_opts = (paged || c->step_mode == 1) ? 1 : c->coop_opts;
+    // the oversubscribed grid of mode 1 uses the first size only
+    const int n_opts = c->step_mode == 1 ? 1 : c->coop_opts;
     int best = 0, best_chunk = 0;
     for (int o = 0; o < n_opts; ++o) {
         const int chunk = c->coop_opt_chunk[o];
         const int n_chunks = (c->cfg.L_cap + chunk - 1) / chunk;
-        const int cap = paged ? c->coop_capacity_paged : c->coop_opt_cap[o];
+        const int cap = paged ? c->coop_opt_cap_paged[o] : c->coop_opt_cap[o];
         const int64_t per_seq = (int64_t)n_chunks * c->cfg.Hkv;
         if (n_chunks > 256 || cap <= 0 || per_seq > cap) continue;
         int ns;
@@ -254,7 +254,6 @@ int hata_create_tuned(hata_ctx** ctx_out, const hata_config* cfg, const hata_tun
     c->error_word = (uint32_t*)(w + p.off_err);
     c->epoch = 0;
     c->coop_opts = 0;
-    c->coop_capacity_paged = 0;
     c->partials = (float*)(w + p.off_partials);
     c->wplanes = (f_has_mfma_width(cfg->r)) ? (void*)(w + p.off_wplanes) : nullptr;
     c->prepared_W_H = nullptr;
@@ -282,8 +281,10 @@ int hata_create_tuned(hata_ctx** ctx_out, const hata_config* cfg, const hata_tun
         for (int v = 8192; v <= 32768 && c->coop_opts < 4; v <<= 1)
             if (v > p.chunk && v < 2 * cfg->L_cap) c->coop_opt_chunk[c->coop_opts++] = v;
     }
-    for (int o = 0; o < c->coop_opts; ++o) c->coop_opt_cap[o] = hata::coop_capacity(c, false, c->coop_opt_chunk[o]);
-    c->coop_capacity_paged = hata::coop_capacity(c, true, c->coop_opt_chunk[0]);
+    for (int o = 0; o < c->coop_opts; ++o) {
+        c->coop_opt_cap[o] = hata::coop_capacity(c, false, c->coop_opt_chunk[o]);
+        c->coop_opt_cap_paged[o] = hata::coop_capacity(c, true, c->coop_opt_chunk[o]);
+    }
     // a device shared with other work cannot promise that a whole grid is resident: three launches
     c->step_mode = (tuning && tuning->shared_device) ? 3 : 0;
     c->spin_limit = 0;

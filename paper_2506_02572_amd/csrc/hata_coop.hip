@@ -32,7 +32,6 @@
 namespace hata {
 
 #define HATA_COOP_MAX_CHUNK 32768        // keys per workgroup: their scores stay in LDS (2 bytes each)
-#define HATA_COOP_MAX_CHUNK_PAGED 4096   // block-table variant (its page starts are staged in LDS per chunk)
 #define HATA_COOP_SUB 4096               // chunks above this size run the BIG instantiation (more than 16 keys per thread in the compaction)
 #define HATA_COOP_SPIN_LIMIT (1 << 18)  // default bound of every in-kernel wait (polls, ~0.1 us apart at least)
 
@@ -215,7 +214,6 @@ __device__ __forceinline__ void coop_encode_vec(const float* __restrict__ Wh, co
 template <int WD, int G, bool PAGED, bool BIG = false>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu((G >= 16 ? 2 : 3), (WD >= 8 ? 3 : 4))))
 void decode_step_coop_kernel(const CoopArgs a) {
-    static_assert(!(PAGED && BIG), "the block-table variant keeps to small chunks");
     static_assert(G * WD <= 64, "query code words of a unit are collected by one wave");
     // dynamic LDS: the chunk's scores (2 bytes per key; later the selected rows as offsets in the
     // chunk) at a fixed address, then NB words of histogram (the chunk's, later the unit's total)
@@ -235,8 +233,8 @@ void decode_step_coop_kernel(const CoopArgs a) {
     __shared__ int s_low;  // lowest score of this chunk
     __shared__ int s_bad;  // this workgroup gave up a wait: the unit's outputs are invalid
     __shared__ uint32_t s_codes[(G + 1) * WD];  // codes of the G query heads and of the appended key
-    // PAGED: where the pages of this chunk's rows start (pages of 16 rows or more: at most MAX_CHUNK / 16 + 1)
-    __shared__ int s_page[PAGED ? HATA_COOP_MAX_CHUNK_PAGED / 16 + 2 : 1];
+    // PAGED: where the pages of this chunk's rows start (pages of 16 rows or more: at most chunk / 16 + 1)
+    __shared__ int s_page[PAGED ? (BIG ? HATA_COOP_MAX_CHUNK : HATA_COOP_SUB) / 16 + 2 : 1];
     const int tid = threadIdx.x;
     HATA_TRACE_AT(39, true);
     // Workgroup -> (unit, chunk).  Consecutive workgroup ids go to consecutive XCDs (8 of them, each
@@ -761,7 +759,7 @@ void decode_step_coop_kernel(const CoopArgs a) {
 
 template <int WD, int G>
 static const void* coop_fn(bool paged, bool big) {
-    if (paged) return big ? nullptr : (const void*)&decode_step_coop_kernel<WD, G, true, false>;
+    if (paged) return big ? (const void*)&decode_step_coop_kernel<WD, G, true, true> : (const void*)&decode_step_coop_kernel<WD, G, true, false>;
     return big ? (const void*)&decode_step_coop_kernel<WD, G, false, true> : (const void*)&decode_step_coop_kernel<WD, G, false, false>;
 }
 
@@ -796,7 +794,7 @@ static const void* coop_kernel_for(int Wd, int G, bool paged, bool big) {
 
 // chunk sizes the kernel is built for, and the width of the {offset, count} record word
 static bool coop_shape_ok(const hata_ctx* c, bool paged, int chunk) {
-    return chunk >= 256 && chunk % 256 == 0 && chunk <= (paged ? HATA_COOP_MAX_CHUNK_PAGED : HATA_COOP_MAX_CHUNK) &&
+    return chunk >= 256 && chunk % 256 == 0 && chunk <= HATA_COOP_MAX_CHUNK &&
            c->cfg.k_max <= 65535;
 }
 static size_t coop_dynamic_lds(const hata_ctx* c, int chunk) { return (size_t)chunk * 2 + (size_t)c->NB * 4; }

@@ -49,7 +49,7 @@ struct hata_ctx {
     int par_merge;           // single-launch step merges the heads of a unit in several workgroups
     int step_mode;           // 0 = single launch when it fits, 3 = always three launches
     int cus;                 // compute units of the device that was current in hata_create
-    int coop_capacity_paged; // resident workgroups of the block-table variant of the single-launch kernel (chunk coop_opt_chunk[0]; 0 = unusable)
+    int coop_opt_cap_paged[4];  // the same for the block-table variant of the kernel
     float* partials;       // [B_max*Hq, max(sparse_splits, dense_splits), d + 2]
     void* wplanes;               // [Hkv, r/32, 8, 2, 64] 16-byte fragments: the two scaled fp16 planes of the hash weights (prefill key encode)
     const float* prepared_W_H;   // the weight tensor those planes were made from (nullptr: none)

@@ -68,13 +68,20 @@ def gather(pool, table, blocks, page_rows, shape, fill):
     (2048, ("g8_r256", 2, 16, 2, 256, (7000, 4097), (512, 100), 8192)),
     (64, ("g1_r64", 2, 4, 4, 64, (2500, 900), (128, 128), 4096)),
     (512, ("g16_r128", 1, 32, 2, 128, (6000,), (300,), 8192)),
+    # more than 4096 keys per workgroup (the chunk fixed through hata_tuning): up to 2049 page starts per chunk
+    (16, ("g4_r128_chunk8k", 2, 8, 2, 128, (20000, 9001), (6000, 300), 20480, 8192)),
+    (256, ("g4_r128_chunk16k", 2, 8, 2, 128, (20000, 9001), (6000, 300), 20480, 16384)),
+    (16, ("g8_r256_chunk32k", 1, 16, 2, 256, (30001,), (9000,), 32768, 32768)),
 ])
 def test_paged_decode_step_matches_the_oracle_and_the_contiguous_step(torch_mod, page_rows, shape):
     torch = torch_mod
     from paper_2506_02572_amd import hata
-    name, B, Hq, Hkv, r, lens, ks, L_cap = shape
+    name, B, Hq, Hkv, r, lens, ks, L_cap = shape[:8]
+    chunk = shape[8] if len(shape) > 8 else 0
     w = synth.Workload(name, B, Hq, Hkv, 128, r, lens, ks, 4, 8.0, L_cap=L_cap, k_max=min(L_cap, max(ks)))
-    c = H.Case(w, seed=9 + page_rows)
+    c = H.Case(w, seed=9 + page_rows, chunk=chunk)
+    if chunk:
+        assert c.ctx.hata_step_plan(B)[:2] == (1, chunk)
     rng = np.random.default_rng(page_rows)
     seq = c.inp.seq_len
     table, max_blocks, n_pages, blocks = make_table(rng, seq, page_rows)
