@@ -177,7 +177,7 @@ class Bench:
         self.ctx = hata.Context(w.B, w.Hq, w.Hkv, w.d, w.r, w.L_cap, w.k_max, chunk=getattr(args, "chunk", 0))
         self.ctx.hata_set_step_mode(step_mode)
         self.stream = torch.cuda.current_stream()
-        # the hash weights are fixed: their bf16 planes for the prefill key encoder are made once
+        # the hash weights are fixed: their fp16 planes for the prefill key encoder are made once
         self.ctx.hata_prepare_weights(self.W_H, self.stream)
         self.alg_bytes = w.algorithmic_bytes(1 if w.append_steps else 0)
         self.code_bytes = int(inp.seq_len.sum() + (w.B if w.append_steps else 0)) * w.Hkv * (w.r // 8)
