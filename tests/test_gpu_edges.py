@@ -464,3 +464,15 @@ def test_step_with_large_chunks_ties_across_compaction_turns(torch_mod, chunk):
         assert np.array_equal(H.to_host(ix), ref["idx"]), f"chunk {chunk}, call {rep}: index lists"
         H.check_attention(H.to_host(out32), H.to_host(out, np.uint16), ref["out"], f"chunk {chunk}")
     ctx.close()
+
+
+def test_overlap_probe_runs_in_its_three_modes(torch_mod):
+    torch = torch_mod
+    from paper_2506_02572_amd import hata
+    buf = torch.randn((8 << 20) // 2, dtype=torch.bfloat16, device="cuda").view(torch.int16)
+    for mode in (1, 2, 3):
+        hata.hata_probe_mfma_stream(buf, 4, mode)
+    torch.cuda.synchronize()
+    with pytest.raises(hata.HataError):
+        hata.hata_probe_mfma_stream(buf[: 1 << 20], 4, 3)  # 2 MiB: below the probe's minimum
+

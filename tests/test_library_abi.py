@@ -96,3 +96,13 @@ def test_binding_has_no_cpu_fallback():
         pytest.skip("GPU present")
     with pytest.raises(hata.HataError):
         hata.Context(1, 32, 8, 128, 128, 2048, 128)
+
+
+def test_probe_rejects_bad_arguments_without_a_device():
+    lib = hata.load_library()
+    assert lib.hata_probe_mfma_stream(None, 1 << 30, 16, 3, None) == -1      # no buffer
+    assert lib.hata_probe_mfma_stream(ctypes.c_void_p(4096), 1 << 20, 16, 3, None) == -1   # below 4 MiB
+    assert lib.hata_probe_mfma_stream(ctypes.c_void_p(4096 + 8), 1 << 30, 16, 3, None) == -1  # misaligned
+    assert lib.hata_probe_mfma_stream(ctypes.c_void_p(4096), 1 << 30, 16, 0, None) == -1   # no mode bit
+    assert lib.hata_probe_mfma_stream(ctypes.c_void_p(4096), 1 << 30, -1, 3, None) == -1
+
