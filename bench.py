@@ -10,7 +10,8 @@ not Infinity-Cache hits, as a model with tens of layers does for every token.
 
 Prints ONE JSON line.  The headline (value, roofline, cpu_baseline) is the workload named by
 --workload (default: configuration 2), timed over exactly --steps steps after --warmup.  Beside it
-the line carries separately timed legs of the same library (scoring stage alone, prefill key
+the line carries separately timed legs of the same library (the four stage entry points of the step
+each alone -- "stages_alone": query encode, Hamming scoring, top-k, sparse attention --, prefill key
 encode and fused prefill cache fill, dense attention, 32 layer steps replayed from one HIP graph,
 the paged layout, the KV cache in host memory with and without a staged prefetch, the
 learning-to-hash training step), and -- in the default run -- "per_config": the step of
@@ -355,6 +356,31 @@ class Bench:
         ms, _ = timed(lambda i: calls[i % self.n_layers](), steps, warmup, self.stream)
         return ms * 1e3
 
+    # ---- the four stage entry points of Alg. 3, each alone (the step fuses them; these are the
+    # stand-alone kernels behind hata_encode_query / hata_hamming_score / hata_topk / hata_sparse_decode)
+    def stages(self, steps, warmup):
+        w, ctx = self.w, self.ctx
+        qcodes_buf, scores_buf, idx_buf = ctx.hata_step_buffers()
+        seq, q = self.seq_steps[0], self.q_steps[0]
+        enc = ctx.prepared("hata_encode_query", q, self.W_H, w.B, qcodes_buf, stream=self.stream)
+        us_enc = timed(lambda i: enc(), steps, warmup, self.stream)[0] * 1e3
+        us_score = self.score(steps, warmup)   # leaves the scores of the last layer's codes (all layers hold the same codes)
+        topk = ctx.prepared("hata_topk", scores_buf, seq, self.kbud, w.B, idx_buf, stream=self.stream)
+        us_topk = timed(lambda i: topk(), steps, warmup, self.stream)[0] * 1e3
+        att = [ctx.prepared("hata_sparse_decode", q, self.K_all[l], self.V_all[l], idx_buf, self.kbud, w.B, self.scale,
+                            self.out, self.out32, stream=self.stream) for l in range(self.n_layers)]
+        us_att = timed(lambda i: att[i % self.n_layers](), steps, warmup, self.stream)[0] * 1e3
+        rows = int(self.np.minimum(self.inp.k, self.inp.seq_len).sum()) * w.Hkv
+        att_bytes = rows * 2 * w.d * 2 + 2 * w.B * w.Hq * w.d * 2
+        score_bytes = self.code_bytes
+
+        def bw(nbytes, us):
+            return {"us": round(us, 3), "algorithmic_bytes": nbytes, "GBps": round(nbytes / (us * 1e-6) / 1e9, 1),
+                    "frac": round(nbytes / (us * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4)}
+
+        return {"encode_query_us": round(us_enc, 3), "hamming_score": bw(score_bytes, us_score),
+                "topk_us": round(us_topk, 3), "sparse_decode": bw(att_bytes, us_att)}
+
     # ---- dense decode over the whole cache (Eq. 1): the comparison baseline, same shapes
     def dense(self, steps):
         calls = [self.ctx.prepared("hata_dense_decode", self.q_steps[0], self.K_all[l], self.V_all[l],
@@ -602,7 +628,8 @@ def per_config_entry(name, args):
     b.encode_keys()
     us_step, _ = b.step(PER_CONFIG_STEPS, PER_CONFIG_WARMUP)
     n_launches, chunk, n_chunks, n_sub = b.plan()
-    us_score = b.score(PER_CONFIG_STEPS, PER_CONFIG_WARMUP)
+    stages = b.stages(PER_CONFIG_STEPS, PER_CONFIG_WARMUP)
+    us_score = stages["hamming_score"]["us"]
     us_dense = b.dense(PER_CONFIG_STEPS)
     cpu, parity, band = b.oracle(min(args.cpu_seconds, 2.0), True)
     gbps = b.alg_bytes / (us_step * 1e-6) / 1e9
@@ -615,6 +642,7 @@ def per_config_entry(name, args):
          "frac": round(gbps / HBM_PEAK_GBPS, 4), "traffic": traffic,
          "traffic_over_algorithmic": None if traffic is None else round(traffic / b.alg_bytes, 3),
          "score_stage_us": round(us_score, 3), "score_stage_GBps": round(b.code_bytes / (us_score * 1e-6) / 1e9, 1),
+         "stages_alone": stages,
          "dense_decode_us": round(us_dense, 2), "ideal_dense_us": round(ideal_dense, 2),
          "speedup_vs_dense": round(us_dense / us_step, 2), "speedup_vs_ideal_dense": round(ideal_dense / us_step, 2),
          "parity": parity, "bulk_key_codes": band, "oracle_us_per_step": cpu["value"], "oracle_cores": cpu["cores"]}
@@ -655,7 +683,8 @@ def main():
     n_launches, plan_chunk, plan_n_chunks, n_sub = b.plan()
     graph_leg = b.graph_of_layers(args.graph_layers, args.steps) if args.graph_layers > 0 and not args.kv_host else None
     prefetch_leg = b.kv_host_prefetch(32, max(3, args.steps // 64)) if args.kv_host else None
-    us_score = b.score(args.steps, args.warmup)
+    stages_alone = None if args.kv_host else b.stages(args.steps, args.warmup)
+    us_score = stages_alone["hamming_score"]["us"] if stages_alone else b.score(args.steps, args.warmup)
     score_gbps = b.code_bytes / (us_score * 1e-6) / 1e9
     dense_us = None if args.no_dense else b.dense(args.steps)
     tr_leg = None if args.no_train else train_leg(torch, b.dev, w, b.W_H, b.stream)
@@ -710,6 +739,7 @@ def main():
         "host_wall_us_per_step": round(us_wall, 3),
         "roofline": roofline,
         "score_stage": score_stage,
+        "stages_alone": stages_alone,
         "encode_keys_bulk": enc_leg,
         "prefill_write": fill_leg,
         "paged_step": paged_leg,

@@ -98,8 +98,11 @@ int make_plan(const hata_config* f, const hata_tuning* t, Plan* p) {
     // (16 heads as two tiles of 8: measured faster than one tile of 16 for the stand-alone kernels)
     p->HT = (G % 8 == 0) ? 8 : (G % 5 == 0) ? 5 : (G % 4 == 0) ? 4 : (G % 2 == 0) ? 2 : 1;
     const int64_t attn_units = units * (G / p->HT);
+    // selected rows per attention workgroup: halved from 256 towards 512 workgroups, but not below 64
+    // (measured with hata_sparse_decode alone: at B = 1 slices of 16-32 rows cost more in partials and
+    // merge than they gain in parallelism -- cfg 2 10.0 us at 16 rows, 8.0 at 64; cfg 4 18.7 at 32, 10.8 at 64)
     int rows = 256;
-    while (rows > 16 && attn_units * ((f->k_max + rows - 1) / rows) < 512) rows >>= 1;
+    while (rows > 64 && attn_units * ((f->k_max + rows - 1) / rows) < 512) rows >>= 1;
     if (t && t->attn_rows != 0) {
         const int v = t->attn_rows;
         if (v < 16 || v > 256 || (v & (v - 1)) != 0) return HATA_EINVAL;

@@ -245,6 +245,49 @@ __device__ __forceinline__ void unit_threshold(
     }
 }
 
+// LDS histogram (NB words) -> the chunk's row of uint16 counts, two bins per write-through store
+__device__ __forceinline__ void write_chunk_hist(uint16_t* hp, const uint32_t* hist, int NB, int NBP) {
+    uint32_t* hp32 = reinterpret_cast<uint32_t*>(hp);
+    for (int i = threadIdx.x; i < NBP / 2; i += 256) {
+        const uint32_t lo = (2 * i < NB) ? hist[2 * i] : 0u;
+        const uint32_t hi = (2 * i + 1 < NB) ? hist[2 * i + 1] : 0u;
+        st_dev(hp32 + i, lo | (hi << 16));
+    }
+}
+
+// Tail of a scoring workgroup in the fused step: publish the chunk histogram, count the unit's
+// finished chunks, and let the last one compute the unit's threshold.  `hist` (NB words of LDS)
+// is reused as the total histogram.
+__device__ __forceinline__ void finish_unit(
+    int64_t u, int nc, int keff, const uint16_t* __restrict__ chunk_hist_u, int NB, int NBP,
+    int n_chunks, int32_t* __restrict__ chunk_info, int32_t* __restrict__ unit_info,
+    uint32_t* __restrict__ unit_counter, uint32_t* __restrict__ unit_hist, uint32_t* hist,
+    ThresholdLds& S, int* flag) {
+    HATA_TRACE_AT(2, u == 0);
+    // add this chunk's histogram to the unit's total (only occupied bins)
+    for (int i = threadIdx.x; i < NB; i += 256) {
+        const uint32_t hv = hist[i];
+        if (hv) atomicAdd(&unit_hist[u * NB + i], hv);
+    }
+    HATA_TRACE_AT(3, u == 0);
+    wait_stores();    // this thread's write-through stores and atomics have completed
+    HATA_TRACE_AT(4, u == 0);
+    __syncthreads();  // ... and so have those of the whole workgroup
+    if (threadIdx.x == 0) {
+        const uint32_t done = atomicAdd(&unit_counter[u], 1u);
+        const int last = (done == (uint32_t)(nc - 1));
+        if (last) unit_counter[u] = 0;  // ready for the next launch
+        *flag = last;
+    }
+    __syncthreads();
+    if (!*flag) return;
+    HATA_TRACE_AT(5, u == 0);
+    // the other workgroups' histograms are read with device-coherent loads
+    unit_threshold<true>(chunk_hist_u, unit_hist + u * NB, nc, keff, NB, NBP, chunk_info + u * (n_chunks + 1) * 2,
+                   unit_info + u * 2, hist, S);
+    HATA_TRACE_AT(6, u == 0);
+}
+
 // Ordered compaction of one whole chunk of 256 * KPT consecutive keys [n0, n0 + 256*KPT) by 256
 // threads (KPT consecutive keys each, all score loads in flight together).  For every selected
 // key, emit(pos, n) is called with pos = its position in the unit's index list.
