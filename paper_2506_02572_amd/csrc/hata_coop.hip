@@ -490,7 +490,7 @@ void decode_step_coop_kernel(const CoopArgs a) {
     else attn_load_q<G>(a.q + ((int64_t)b * a.Hq + hq0) * HATA_D, qr);
     if (s_flag) {
         TU(51);
-        unit_threshold<true, (G * WD * 32) / 256 + 1>(a.chunk_hist + u * a.n_chunks * a.NBP, a.unit_hist + u * a.NB, nc, keff,
+        unit_threshold<(G * WD * 32) / 256 + 1>(a.chunk_hist + u * a.n_chunks * a.NBP, a.unit_hist + u * a.NB, nc, keff,
                              a.NB, a.NBP, ci_u, a.unit_info + u * 2, hist, TS, rec_u, a.epoch,
                              s_low < a.NB ? s_low : -1);
         TU(52);

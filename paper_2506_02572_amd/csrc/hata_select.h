@@ -29,10 +29,9 @@ struct ThresholdLds {
 //   unit_info[u]       = {T, keff}: keys with score < T are all selected, keff = min(k, L)
 //   chunk_info[u][c]   = {first output position of chunk c, ties (score == T) chunk c may take},
 //                        c = 0 .. nc (entry nc = {keff, 0} closes the list)
-// from the nc chunk histograms of the unit (`hp`, pitch NBP, uint16 counts) and -- FUSED -- the
-// unit's total histogram `unit_hist` (NB words) that the scoring workgroups of this launch
-// accumulated with atomics; it is read with device-coherent loads and cleared for the next
-// launch.  Not FUSED: the total is summed from the chunk rows.  `tot` is unused.
+// from the nc chunk histograms of the unit (`hp`, pitch NBP, uint16 counts) and the unit's total
+// histogram `unit_hist` (NB words) that the workgroups of this launch accumulated with atomics; it
+// is read with device-coherent loads and cleared for the next launch.  `tot` is unused.
 // Must be called by all 256 threads.
 //
 // Only the few 8-bin columns between the lowest occupied score and T matter for the per-chunk
@@ -57,7 +56,7 @@ __device__ __forceinline__ uint32_t bin_of(const Bins8& v, int e) {
     return (e & 1) ? (w >> 16) : (w & 0xffffu);
 }
 
-template <bool FUSED, int MAXSEG = 17>
+template <int MAXSEG = 17>
 __device__ __forceinline__ void unit_threshold(
     const uint16_t* __restrict__ hp, uint32_t* __restrict__ unit_hist_u, int nc, int keff, int NB,
     int NBP, int32_t* __restrict__ chunk_info_u, int32_t* __restrict__ unit_info_u, uint32_t* tot,
@@ -78,10 +77,10 @@ __device__ __forceinline__ void unit_threshold(
     // fetched together with the unit histogram and used if they turn out to cover the range
     // (3 columns below: the unit's lowest score is a little lower than one chunk's).
     constexpr int SPEC_COLS = 8, SPEC_IT = 4;
-    const bool spec = FUSED && spec_bmin >= 0 && nc * SPEC_COLS <= 256 * SPEC_IT && NBP / 8 >= SPEC_COLS;
+    const bool spec = spec_bmin >= 0 && nc * SPEC_COLS <= 256 * SPEC_IT && NBP / 8 >= SPEC_COLS;
     const int colA = spec ? min(max(spec_bmin / 8 - 3, 0), NBP / 8 - SPEC_COLS) : 0;
     Bins8 sx[SPEC_IT];
-    if constexpr (FUSED) {
+    {
 #pragma unroll
         for (int j = 0; j < MAXSEG; ++j)  // clamped index: unconditional loads
             if (j < seg)
@@ -104,14 +103,6 @@ __device__ __forceinline__ void unit_threshold(
                 x[j] = 0;
             }
         }
-    } else {
-#pragma unroll
-        for (int j = 0; j < MAXSEG; ++j) x[j] = 0;
-        for (int c = 0; c < nc; ++c) {
-#pragma unroll
-            for (int j = 0; j < MAXSEG; ++j)
-                if (j < seg && s0 + j < NB) x[j] += hp[(int64_t)c * NBP + s0 + j];
-        }
     }
     uint32_t local = 0;
     int first_nz = NB;
@@ -126,7 +117,7 @@ __device__ __forceinline__ void unit_threshold(
     const float low_w = wave_max64(-(float)first_nz);
     if (lane == 63) { S.wtot[wave] = incl_w; S.wlow[wave] = low_w; }
     __syncthreads();
-    HATA_TRACE_AT(26, FUSED);
+    HATA_TRACE_AT(26, true);
     {
         const uint32_t w0 = S.wtot[0], w1 = S.wtot[1], w2 = S.wtot[2];
         const uint32_t before = (wave > 0 ? w0 : 0u) + (wave > 1 ? w1 : 0u) + (wave > 2 ? w2 : 0u) + incl_w - local;
@@ -148,7 +139,7 @@ __device__ __forceinline__ void unit_threshold(
     }
     __syncthreads();
     const int T = S.T, need = S.need;
-    HATA_TRACE_AT(27, FUSED);
+    HATA_TRACE_AT(27, true);
     // per chunk: keys below T and keys equal to T, from columns [bmin / 8, T / 8] of its row
     auto count_item = [&](const Bins8& v, int c, int col) {
         uint32_t lt = 0;
@@ -181,7 +172,7 @@ __device__ __forceinline__ void unit_threshold(
             for (int j = 0; j < 4; ++j) {
                 const int i = min(i0 + j * 256, items - 1);
                 const int c = i / ncols, col = col0 + (i - c * ncols);
-                x[j] = load_bins8<FUSED>(hp + (int64_t)c * NBP + col * 8);
+                x[j] = load_bins8<true>(hp + (int64_t)c * NBP + col * 8);
             }
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
@@ -194,7 +185,7 @@ __device__ __forceinline__ void unit_threshold(
         }
     }
     __syncthreads();
-    HATA_TRACE_AT(28, FUSED);
+    HATA_TRACE_AT(28, true);
     // ordered offsets: ties are granted to chunks in cache order.  One wave: lane l owns chunks
     // [l*cpl, (l+1)*cpl); two wave scans (ties seen so far, then selected so far), no barrier.
     if (tid < 64) {
@@ -235,7 +226,7 @@ __device__ __forceinline__ void unit_threshold(
             eqb += S.c_eq[c];
         }
     }
-    HATA_TRACE_AT(29, FUSED);
+    HATA_TRACE_AT(29, true);
     if (tid == 0 && !rec_u) {
         // (write-through: the next launch's workgroups read these)
         st_dev(reinterpret_cast<uint32_t*>(chunk_info_u) + nc * 2 + 0, (uint32_t)keff);
@@ -283,7 +274,7 @@ __device__ __forceinline__ void finish_unit(
     if (!*flag) return;
     HATA_TRACE_AT(5, u == 0);
     // the other workgroups' histograms are read with device-coherent loads
-    unit_threshold<true>(chunk_hist_u, unit_hist + u * NB, nc, keff, NB, NBP, chunk_info + u * (n_chunks + 1) * 2,
+    unit_threshold(chunk_hist_u, unit_hist + u * NB, nc, keff, NB, NBP, chunk_info + u * (n_chunks + 1) * 2,
                    unit_info + u * 2, hist, S);
     HATA_TRACE_AT(6, u == 0);
 }
