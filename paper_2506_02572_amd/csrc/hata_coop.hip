@@ -8,7 +8,9 @@
 //   1. scores its chunk of cached key codes (as score_kernel does), keeps the scores in LDS,
 //      publishes the chunk histogram and adds it to the unit histogram, then ARRIVES at the unit;
 //   2. the last workgroup of the unit to arrive computes the unit's threshold and the ordered
-//      chunk offsets (unit_threshold) and publishes an epoch flag; the others WAIT for that flag;
+//      chunk offsets (unit_threshold) and publishes an epoch flag; the others WAIT for that flag --
+//      and meanwhile list their chunk's candidates (the keys up to a score taken from the chunk's own
+//      histogram), so that the selection is a filter over a short list once the threshold is there;
 //   3. compacts its own chunk (ordered, from the LDS scores) -- writing its part of Idx -- and
 //      attends over exactly the rows it selected, for all query heads of the group;
 //   4. writes its partial (max, sum, weighted V) and arrives; the first min(G, nc) workgroups of the
@@ -495,6 +497,75 @@ void decode_step_coop_kernel(const CoopArgs a) {
                              s_low < a.NB ? s_low : -1);
         TU(52);
     }
+    // While the unit's threshold is on its way (the last arriver computes it, everybody else would only
+    // wait): an ordered list of the chunk's CANDIDATES, the keys up to a score Tc chosen from the chunk's
+    // own histogram so that the list holds about twice the chunk's share of the budget.  If the unit's
+    // threshold turns out to be at most Tc -- the rule -- the selection is a filter over this short
+    // list instead of a pass over the whole chunk.  The list lives where the last arriver keeps its
+    // threshold search and the attention later stages V (neither is in use by this workgroup now).
+    constexpr int CAND_MAX = 1024;
+    uint32_t* const s_cand = reinterpret_cast<uint32_t*>(&U);
+    __shared__ int s_Tc, s_ncand;
+    if constexpr (!BIG) {
+        if (tid == 0) { s_Tc = -1; s_ncand = 0; }
+        if (!s_flag) {
+            const int n_keys = end - base;
+            const int want = min(n_keys, (int)(((int64_t)keff * n_keys + L - 1) / L) * 2 + 64);
+            // smallest score whose inclusive count reaches `want`: thread t owns seg consecutive bins
+            const int seg = (a.NB + 255) / 256;
+            uint32_t loc = 0;
+            for (int j = 0; j < seg; ++j) loc += (tid * seg + j < a.NB) ? hist[tid * seg + j] : 0u;
+            const uint32_t incl = wave_incl_scan(loc);
+            if ((tid & 63) == 63) scan4[tid >> 6] = incl;
+            __syncthreads();
+            const int wv = tid >> 6;
+            uint32_t run = (wv > 0 ? scan4[0] : 0u) + (wv > 1 ? scan4[1] : 0u) + (wv > 2 ? scan4[2] : 0u) + incl - loc;
+            if (run < (uint32_t)want && run + loc >= (uint32_t)want) {
+                for (int j = 0; j < seg; ++j) {
+                    const uint32_t hv = (tid * seg + j < a.NB) ? hist[tid * seg + j] : 0u;
+                    if (run < (uint32_t)want && run + hv >= (uint32_t)want) { s_Tc = tid * seg + j; s_ncand = (int)(run + hv); }
+                    run += hv;
+                }
+            }
+            __syncthreads();
+            const int Tc = s_Tc;
+            if (Tc >= 0 && s_ncand <= CAND_MAX) {
+                const int kpt = a.chunk / 256;
+                const int n_first = tid * kpt;
+                uint32_t sv[16];
+#pragma unroll
+                for (int i4 = 0; i4 < 4; ++i4) {
+                    if (i4 * 4 < kpt) {
+                        const uint2 v = *reinterpret_cast<const uint2*>(&s_sc[n_first + i4 * 4]);
+                        sv[4 * i4 + 0] = v.x & 0xffffu; sv[4 * i4 + 1] = v.x >> 16;
+                        sv[4 * i4 + 2] = v.y & 0xffffu; sv[4 * i4 + 3] = v.y >> 16;
+                    } else {
+                        sv[4 * i4 + 0] = sv[4 * i4 + 1] = sv[4 * i4 + 2] = sv[4 * i4 + 3] = 0xffffffffu;
+                    }
+                }
+                const int nlive = clampi(end - base - n_first, 0, kpt);
+                uint32_t m_c = 0;
+#pragma unroll
+                for (int i = 0; i < 16; ++i) m_c |= ((int)sv[i] <= Tc ? 1u : 0u) << i;
+                m_c &= (1u << nlive) - 1u;
+                const uint32_t cn = __popc(m_c);
+                const uint32_t cincl = wave_incl_scan(cn);
+                __syncthreads();  // (scan4 is free again)
+                if ((tid & 63) == 63) scan4[tid >> 6] = cincl;
+                __syncthreads();
+                uint32_t r = (wv > 0 ? scan4[0] : 0u) + (wv > 1 ? scan4[1] : 0u) + (wv > 2 ? scan4[2] : 0u) + cincl - cn;
+                while (m_c) {
+                    const int i = __ffs(m_c) - 1;
+                    m_c &= m_c - 1;
+                    if (r < (uint32_t)CAND_MAX) s_cand[r] = (uint32_t)(n_first + i) | (sv[i] << 16);
+                    ++r;
+                }
+            } else if (tid == 0) {
+                s_Tc = -1;
+            }
+        }
+        __syncthreads();
+    }
     // every workgroup (the last arriver too) picks up its chunk's record: two words that carry
     // this launch's epoch once the threshold of the unit has been published
     if (tid == 0) {
@@ -584,6 +655,44 @@ void decode_step_coop_kernel(const CoopArgs a) {
                     ++r;
                 }
             }
+        }
+    } else if (s_Tc >= 0 && (T <= s_Tc || cnt == 0)) {
+        // the candidate list covers the selection: a thread filters up to four consecutive candidates
+        const int n_cand = s_ncand;
+        const int cpt = (n_cand + 255) / 256;  // <= 4
+        const int j0 = tid * cpt;
+        uint32_t cw[4];
+        uint32_t m_lt = 0, m_eq = 0;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            cw[i] = (i < cpt && j0 + i < n_cand) ? s_cand[j0 + i] : 0xffff0000u;
+            const int sc = (int)(cw[i] >> 16);
+            const bool live = i < cpt && j0 + i < n_cand;
+            m_lt |= (live && sc < T ? 1u : 0u) << i;
+            m_eq |= (live && sc == T ? 1u : 0u) << i;
+        }
+        const uint32_t lt = __popc(m_lt), eq = __popc(m_eq);
+        const uint32_t mine = lt | (eq << 16);
+        const uint32_t incl = wave_incl_scan(mine);
+        if ((tid & 63) == 63) scan4[tid >> 6] = incl;
+        __syncthreads();
+        const int wv = tid >> 6;
+        const uint32_t before = (wv > 0 ? scan4[0] : 0u) + (wv > 1 ? scan4[1] : 0u) + (wv > 2 ? scan4[2] : 0u) + incl - mine;
+        const uint32_t lt_b = before & 0xffffu, eq_b = before >> 16;
+        const uint32_t ties_before = min(eq_b, (uint32_t)take);
+        const uint32_t avail = min(eq, (uint32_t)take - ties_before);
+        uint32_t keep = m_eq;
+        while ((uint32_t)__popc(keep) > avail) keep &= ~(0x80000000u >> __clz(keep));
+        uint32_t sel = m_lt | keep;
+        uint32_t r = lt_b + ties_before;
+        while (sel) {
+            const int i = __ffs(sel) - 1;
+            sel &= sel - 1;
+            if (r < (uint32_t)cnt) {
+                s_sc[r] = (uint16_t)(cw[i] & 0xffffu);
+                io[off + r] = base + (int)(cw[i] & 0xffffu);
+            }
+            ++r;
         }
     } else {
         // chunks of up to HATA_COOP_SUB keys: a thread takes kpt <= 16 consecutive keys
