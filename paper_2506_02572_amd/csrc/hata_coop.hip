@@ -506,7 +506,7 @@ void decode_step_coop_kernel(const CoopArgs a) {
     constexpr int CAND_MAX = 1024;
     uint32_t* const s_cand = reinterpret_cast<uint32_t*>(&U);
     __shared__ int s_Tc, s_ncand;
-    if constexpr (!BIG) {
+    {
         if (tid == 0) { s_Tc = -1; s_ncand = 0; }
         if (!s_flag) {
             const int n_keys = end - base;
@@ -530,35 +530,76 @@ void decode_step_coop_kernel(const CoopArgs a) {
             __syncthreads();
             const int Tc = s_Tc;
             if (Tc >= 0 && s_ncand <= CAND_MAX) {
-                const int kpt = a.chunk / 256;
-                const int n_first = tid * kpt;
-                uint32_t sv[16];
+                if constexpr (BIG) {
+                    // (16 keys at a time, as the one-pass compaction of these chunks below)
+                    const int kpt = a.chunk / 256;
+                    const int n_first = tid * kpt;
+                    uint32_t mc[8];
+                    uint32_t cn = 0;
 #pragma unroll
-                for (int i4 = 0; i4 < 4; ++i4) {
-                    if (i4 * 4 < kpt) {
-                        const uint2 v = *reinterpret_cast<const uint2*>(&s_sc[n_first + i4 * 4]);
-                        sv[4 * i4 + 0] = v.x & 0xffffu; sv[4 * i4 + 1] = v.x >> 16;
-                        sv[4 * i4 + 2] = v.y & 0xffffu; sv[4 * i4 + 3] = v.y >> 16;
-                    } else {
-                        sv[4 * i4 + 0] = sv[4 * i4 + 1] = sv[4 * i4 + 2] = sv[4 * i4 + 3] = 0xffffffffu;
+                    for (int g = 0; g < 8; ++g) {
+                        mc[g] = 0;
+                        if (g * 16 < kpt) {
+                            const uint4 v0 = *reinterpret_cast<const uint4*>(&s_sc[n_first + g * 16]);
+                            const uint4 v1 = *reinterpret_cast<const uint4*>(&s_sc[n_first + g * 16 + 8]);
+                            const uint32_t w8[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
+                            uint32_t m = 0;
+#pragma unroll
+                            for (int i = 0; i < 16; ++i) {
+                                const int sc = (int)((i & 1) ? (w8[i >> 1] >> 16) : (w8[i >> 1] & 0xffffu));
+                                m |= (sc <= Tc ? 1u : 0u) << i;
+                            }
+                            const int nlive = clampi(end - base - n_first - g * 16, 0, 16);
+                            mc[g] = m & ((1u << nlive) - 1u);
+                            cn += __popc(mc[g]);
+                        }
                     }
-                }
-                const int nlive = clampi(end - base - n_first, 0, kpt);
-                uint32_t m_c = 0;
+                    const uint32_t cincl = wave_incl_scan(cn);
+                    __syncthreads();  // (scan4 is free again)
+                    if ((tid & 63) == 63) scan4[tid >> 6] = cincl;
+                    __syncthreads();
+                    uint32_t r = (wv > 0 ? scan4[0] : 0u) + (wv > 1 ? scan4[1] : 0u) + (wv > 2 ? scan4[2] : 0u) + cincl - cn;
 #pragma unroll
-                for (int i = 0; i < 16; ++i) m_c |= ((int)sv[i] <= Tc ? 1u : 0u) << i;
-                m_c &= (1u << nlive) - 1u;
-                const uint32_t cn = __popc(m_c);
-                const uint32_t cincl = wave_incl_scan(cn);
-                __syncthreads();  // (scan4 is free again)
-                if ((tid & 63) == 63) scan4[tid >> 6] = cincl;
-                __syncthreads();
-                uint32_t r = (wv > 0 ? scan4[0] : 0u) + (wv > 1 ? scan4[1] : 0u) + (wv > 2 ? scan4[2] : 0u) + cincl - cn;
-                while (m_c) {
-                    const int i = __ffs(m_c) - 1;
-                    m_c &= m_c - 1;
-                    if (r < (uint32_t)CAND_MAX) s_cand[r] = (uint32_t)(n_first + i) | (sv[i] << 16);
-                    ++r;
+                    for (int g = 0; g < 8; ++g) {
+                        uint32_t m = mc[g];
+                        while (m) {
+                            const int n = n_first + g * 16 + __ffs(m) - 1;
+                            m &= m - 1;
+                            if (r < (uint32_t)CAND_MAX) s_cand[r] = (uint32_t)n | ((uint32_t)s_sc[n] << 16);
+                            ++r;
+                        }
+                    }
+                } else {
+                    const int kpt = a.chunk / 256;
+                    const int n_first = tid * kpt;
+                    uint32_t sv[16];
+#pragma unroll
+                    for (int i4 = 0; i4 < 4; ++i4) {
+                        if (i4 * 4 < kpt) {
+                            const uint2 v = *reinterpret_cast<const uint2*>(&s_sc[n_first + i4 * 4]);
+                            sv[4 * i4 + 0] = v.x & 0xffffu; sv[4 * i4 + 1] = v.x >> 16;
+                            sv[4 * i4 + 2] = v.y & 0xffffu; sv[4 * i4 + 3] = v.y >> 16;
+                        } else {
+                            sv[4 * i4 + 0] = sv[4 * i4 + 1] = sv[4 * i4 + 2] = sv[4 * i4 + 3] = 0xffffffffu;
+                        }
+                    }
+                    const int nlive = clampi(end - base - n_first, 0, kpt);
+                    uint32_t m_c = 0;
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) m_c |= ((int)sv[i] <= Tc ? 1u : 0u) << i;
+                    m_c &= (1u << nlive) - 1u;
+                    const uint32_t cn = __popc(m_c);
+                    const uint32_t cincl = wave_incl_scan(cn);
+                    __syncthreads();  // (scan4 is free again)
+                    if ((tid & 63) == 63) scan4[tid >> 6] = cincl;
+                    __syncthreads();
+                    uint32_t r = (wv > 0 ? scan4[0] : 0u) + (wv > 1 ? scan4[1] : 0u) + (wv > 2 ? scan4[2] : 0u) + cincl - cn;
+                    while (m_c) {
+                        const int i = __ffs(m_c) - 1;
+                        m_c &= m_c - 1;
+                        if (r < (uint32_t)CAND_MAX) s_cand[r] = (uint32_t)(n_first + i) | (sv[i] << 16);
+                        ++r;
+                    }
                 }
             } else if (tid == 0) {
                 s_Tc = -1;
@@ -595,7 +636,45 @@ void decode_step_coop_kernel(const CoopArgs a) {
     int32_t* io = a.idx + u * a.k_max;
     if (c == 0)
         for (int p = keff + tid; p < a.k_max; p += 256) io[p] = -1;
-    if constexpr (BIG) {
+    if (s_Tc >= 0 && (T <= s_Tc || cnt == 0)) {
+        // the candidate list covers the selection: a thread filters up to four consecutive candidates
+        const int n_cand = s_ncand;
+        const int cpt = (n_cand + 255) / 256;  // <= 4
+        const int j0 = tid * cpt;
+        uint32_t cw[4];
+        uint32_t m_lt = 0, m_eq = 0;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            cw[i] = (i < cpt && j0 + i < n_cand) ? s_cand[j0 + i] : 0xffff0000u;
+            const int sc = (int)(cw[i] >> 16);
+            const bool live = i < cpt && j0 + i < n_cand;
+            m_lt |= (live && sc < T ? 1u : 0u) << i;
+            m_eq |= (live && sc == T ? 1u : 0u) << i;
+        }
+        const uint32_t lt = __popc(m_lt), eq = __popc(m_eq);
+        const uint32_t mine = lt | (eq << 16);
+        const uint32_t incl = wave_incl_scan(mine);
+        if ((tid & 63) == 63) scan4[tid >> 6] = incl;
+        __syncthreads();
+        const int wv = tid >> 6;
+        const uint32_t before = (wv > 0 ? scan4[0] : 0u) + (wv > 1 ? scan4[1] : 0u) + (wv > 2 ? scan4[2] : 0u) + incl - mine;
+        const uint32_t lt_b = before & 0xffffu, eq_b = before >> 16;
+        const uint32_t ties_before = min(eq_b, (uint32_t)take);
+        const uint32_t avail = min(eq, (uint32_t)take - ties_before);
+        uint32_t keep = m_eq;
+        while ((uint32_t)__popc(keep) > avail) keep &= ~(0x80000000u >> __clz(keep));
+        uint32_t sel = m_lt | keep;
+        uint32_t r = lt_b + ties_before;
+        while (sel) {
+            const int i = __ffs(sel) - 1;
+            sel &= sel - 1;
+            if (r < (uint32_t)cnt) {
+                s_sc[r] = (uint16_t)(cw[i] & 0xffffu);
+                io[off + r] = base + (int)(cw[i] & 0xffffu);
+            }
+            ++r;
+        }
+    } else if constexpr (BIG) {
         // chunks of 8192 .. 32768 keys: a thread takes kpt = 32 .. 128 consecutive keys, 16 at a time
         // (bits 0..15 of mk[g]: key below the threshold, bits 16..31: key at the threshold), then ONE
         // block-wide scan; the totals stay below 65536, so the packed (lt, eq) pair still fits
@@ -655,44 +734,6 @@ void decode_step_coop_kernel(const CoopArgs a) {
                     ++r;
                 }
             }
-        }
-    } else if (s_Tc >= 0 && (T <= s_Tc || cnt == 0)) {
-        // the candidate list covers the selection: a thread filters up to four consecutive candidates
-        const int n_cand = s_ncand;
-        const int cpt = (n_cand + 255) / 256;  // <= 4
-        const int j0 = tid * cpt;
-        uint32_t cw[4];
-        uint32_t m_lt = 0, m_eq = 0;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            cw[i] = (i < cpt && j0 + i < n_cand) ? s_cand[j0 + i] : 0xffff0000u;
-            const int sc = (int)(cw[i] >> 16);
-            const bool live = i < cpt && j0 + i < n_cand;
-            m_lt |= (live && sc < T ? 1u : 0u) << i;
-            m_eq |= (live && sc == T ? 1u : 0u) << i;
-        }
-        const uint32_t lt = __popc(m_lt), eq = __popc(m_eq);
-        const uint32_t mine = lt | (eq << 16);
-        const uint32_t incl = wave_incl_scan(mine);
-        if ((tid & 63) == 63) scan4[tid >> 6] = incl;
-        __syncthreads();
-        const int wv = tid >> 6;
-        const uint32_t before = (wv > 0 ? scan4[0] : 0u) + (wv > 1 ? scan4[1] : 0u) + (wv > 2 ? scan4[2] : 0u) + incl - mine;
-        const uint32_t lt_b = before & 0xffffu, eq_b = before >> 16;
-        const uint32_t ties_before = min(eq_b, (uint32_t)take);
-        const uint32_t avail = min(eq, (uint32_t)take - ties_before);
-        uint32_t keep = m_eq;
-        while ((uint32_t)__popc(keep) > avail) keep &= ~(0x80000000u >> __clz(keep));
-        uint32_t sel = m_lt | keep;
-        uint32_t r = lt_b + ties_before;
-        while (sel) {
-            const int i = __ffs(sel) - 1;
-            sel &= sel - 1;
-            if (r < (uint32_t)cnt) {
-                s_sc[r] = (uint16_t)(cw[i] & 0xffffu);
-                io[off + r] = base + (int)(cw[i] & 0xffffu);
-            }
-            ++r;
         }
     } else {
         // chunks of up to HATA_COOP_SUB keys: a thread takes kpt <= 16 consecutive keys
