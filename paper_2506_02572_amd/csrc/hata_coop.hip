@@ -166,6 +166,22 @@ __device__ __forceinline__ void coop_encode_load(const float* __restrict__ Wh,
 #pragma unroll
     for (int j = 0; j < EncodeLoads<WD>::NW; ++j) e.w[j] = *reinterpret_cast<const float4*>(wp + (int64_t)j * R);
 }
+// the channels of x alone (for a further vector once the weight part is in registers: NW == CP)
+template <int WD>
+__device__ __forceinline__ void coop_encode_load_x(const uint16_t* __restrict__ x, uint32_t* xw) {
+    constexpr int R = WD * 32, CG = R / 16, P = 64 / CG, CP = HATA_D / P;
+    const int p = (threadIdx.x & 63) / CG;
+    if constexpr (CP == 4) {
+        const uint2 v = *reinterpret_cast<const uint2*>(x + p * CP);
+        xw[0] = v.x; xw[1] = v.y;
+    } else {
+#pragma unroll
+        for (int i = 0; i < CP / 8; ++i) {
+            const uint4 v = reinterpret_cast<const uint4*>(x + p * CP)[i];
+            xw[4 * i] = v.x; xw[4 * i + 1] = v.y; xw[4 * i + 2] = v.z; xw[4 * i + 3] = v.w;
+        }
+    }
+}
 template <int WD>
 __device__ __forceinline__ void coop_encode_vec(const float* __restrict__ Wh, const EncodeLoads<WD>& e,
                                                 uint32_t* s_word) {
@@ -347,19 +363,53 @@ void decode_step_coop_kernel(const CoopArgs a) {
                             << a.pv.shift;
         }
         __syncthreads();
-        for (int v = c; v < G; v += max(nc, 1)) {
-            if (!EARLY || v != c) coop_encode_load<WD>(Wh, qv + v * HATA_D, el);
-            coop_encode_vec<WD>(Wh, el, &s_codes[v * WD]);
+        auto publish = [&](int v) {
             __syncthreads();
             for (int i = tid; i < WD * max(nc, 1); i += 256)
                 __hip_atomic_store(qrec_u + (i / WD) * (G * WD) + v * WD + i % WD,
                                    ((unsigned long long)a.epoch << 32) | s_codes[v * WD + i % WD],
                                    __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        }
-        if (own) {
-            coop_encode_load<WD>(Wh, PAGED ? a.K + cache_row(L - 1) * HATA_D
-                                           : a.K + b * a.sb + h * a.sh + (int64_t)(L - 1) * a.sn, el);
-            coop_encode_vec<WD>(Wh, el, &s_codes[G * WD]);
+        };
+        const uint16_t* kx = !own ? nullptr
+                             : PAGED ? a.K + cache_row(L - 1) * HATA_D
+                                     : a.K + b * a.sb + h * a.sh + (int64_t)(L - 1) * a.sn;
+        if constexpr (BIG && EncodeLoads<WD>::NW == EncodeLoads<WD>::CP) {
+            // Large chunks mean few chunks per unit, so a workgroup has several vectors to encode (fewer
+            // chunks than heads in the group, and the appended key on top).  The lane's weight part stays
+            // in registers (r <= 128): the workgroup loads the weights once, and the channels of the
+            // NEXT vector while it works on the current one.
+            // Items: query vectors c, c + nc, ... < G, then the appended key (index G) if it is ours.
+            const int stepv = max(nc, 1);
+            int v = c < G ? c : (own ? G : G + 1);
+            if (v <= G && !(EARLY && c < G)) coop_encode_load<WD>(Wh, v < G ? qv + v * HATA_D : kx, el);
+#pragma clang loop unroll(disable)
+            while (v <= G) {
+                const int vn = v == G ? G + 1 : (v + stepv < G ? v + stepv : (own ? G : G + 1));
+                uint32_t xn[EncodeLoads<WD>::CP / 2];
+                if (vn <= G) coop_encode_load_x<WD>(vn < G ? qv + vn * HATA_D : kx, xn);
+                // (the weights are loop-invariant: without this the compiler keeps their fp64 conversions,
+                // twice the registers, across the loop)
+#pragma unroll
+                for (int j = 0; j < EncodeLoads<WD>::NW; ++j)
+                    asm volatile("" : "+v"(el.w[j].x), "+v"(el.w[j].y), "+v"(el.w[j].z), "+v"(el.w[j].w));
+                coop_encode_vec<WD>(Wh, el, &s_codes[v * WD]);
+                if (v < G) publish(v);
+                if (vn <= G) {
+#pragma unroll
+                    for (int i = 0; i < EncodeLoads<WD>::CP / 2; ++i) el.xw[i] = xn[i];
+                }
+                v = vn;
+            }
+        } else {
+            for (int v = c; v < G; v += max(nc, 1)) {
+                if (!EARLY || v != c) coop_encode_load<WD>(Wh, qv + v * HATA_D, el);
+                coop_encode_vec<WD>(Wh, el, &s_codes[v * WD]);
+                publish(v);
+            }
+            if (own) {
+                coop_encode_load<WD>(Wh, kx, el);
+                coop_encode_vec<WD>(Wh, el, &s_codes[G * WD]);
+            }
         }
         // Small grids (at most one workgroup per CU: the step is a chain of latencies, not a stream):
         // the first batch of the chunk's key codes is fetched while the query codes are collected.
