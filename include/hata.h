@@ -95,7 +95,7 @@ typedef struct {
                             * 4096 or 8192 for every kernel, or 16384 / 32768 for the single-launch step alone
                             * (the other kernels keep their default) */
     int32_t attn_rows;     /* selected rows per attention workgroup of the three-launch form: 0 = default, else a power of two in 16..256 */
-    int32_t par_merge;     /* single-launch form, merge of a unit's partials: -1 = default, 0 = by the last workgroup to arrive, 1 = a query head per workgroup */
+    int32_t par_merge;     /* single-launch form, merge of a unit's partials: -1 = default, 0 = by the last workgroup to arrive, 1 = a query head per workgroup (taken for launches with more than four chunks per unit; the default when a group has two heads or more) */
     int32_t shared_device; /* != 0: other work may run on the device beside the step, so the context starts in step mode 3 (see hata_set_step_mode) */
 } hata_tuning;
 

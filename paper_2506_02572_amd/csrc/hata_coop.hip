@@ -1025,7 +1025,10 @@ hipError_t launch_coop_step(hata_ctx* c, const void* q, const void* K, const voi
     a.W_H = W_H; a.append = append;
     a.spin_limit = c->spin_limit > 0 ? c->spin_limit : HATA_COOP_SPIN_LIMIT;
     a.keep_scores = c->keep_scores;
-    a.par_merge = c->par_merge;
+    // side-by-side merging pays with many slices per unit; with up to four, the workgroups that would
+    // wait for the unit's last partial only add a hand-off, and the unit's last arriver merges all heads
+    // (measured at L = 32K: B = 32 at two slices 55.1 -> 54.1 us, at four 73.1 -> 72.7, eight: no difference)
+    a.par_merge = c->par_merge && n_chunks > 4;
     a.select_only = idx_only ? 1 : 0;
     // chunk-major order needs the whole grid resident (an oversubscribed grid relies on a unit's
     // workgroups having neighbouring indices)
