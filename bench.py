@@ -41,12 +41,13 @@ PER_CONFIG_WARMUP = 40
 # constant of the build the profile names, not a value measured by the run that prints it: the
 # "traffic_source" field of the output says so.  "step": the single-launch decode step
 # (decode_step_coop_kernel); "score": the scoring kernel alone (hata_hamming_score).
-HBM_TRAFFIC_SOURCE = "profiles/hbm_traffic_pmc.md (library of commit 27b79d8)"
+HBM_TRAFFIC_SOURCE = "profiles/hbm_traffic_pmc.md (library of commit 27b79d8; b32_32k: e4b3f88)"
 HBM_TRAFFIC_BYTES = {
     "cfg2_llama3_8b_32k": {"step": 9348096, "score": 5082317},
     "cfg3_batched_ragged": {"step": 73044890, "score": 45608141},
     "cfg4_long_128k_r256": {"step": 48791552, "score": 36881203},
     "cfg5_gqa8_append": {"step": 59498394, "score": 39123354},
+    "b32_32k": {"step": 209088922, "score": 153628262},
 }
 
 
